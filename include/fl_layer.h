@@ -1,0 +1,158 @@
+/*
+ * fl_layer.h -- C ABI of the MI355X-native Transformer encoder layer.
+ *
+ * One encoder layer's forward and backward pass, executed the way the paper's
+ * tensor / autograd stack dispatches it (Flashlight, arXiv 2201.12465):
+ * a module's forward() calls tensor primitives (Section 4.1.1, Section 4.2
+ * "Neural Network Primitives"), each call is recorded on a dynamic tape together
+ * with a gradient function (Section 4.2 "Automatic Differentiation", the
+ * cosine-operator listing), backward() replays the tape in reverse, and every
+ * intermediate buffer comes from a caching memory manager (Section 4.1.2 and its
+ * CachingMemoryManager listing; Section 5.2.2).  Here all of it is native to one
+ * gfx950 GPU: hand-written HIP kernels behind the calls below.
+ *
+ * Conventions
+ *   - All pointers named X, Y, dY, dX, params.*, grads.*, lengths are DEVICE
+ *     pointers owned by the caller.  Config / stats / handle pointers are HOST.
+ *   - Activations are contiguous row-major [B, T, d_model].  Weights are
+ *     [out, in] row-major, y = x W^T + b.  Wqkv = rows [Wq; Wk; Wv] ([3D, D]);
+ *     head h owns columns h*dh .. (h+1)*dh of each D-wide slab (dh = D / heads).
+ *   - Element type of every activation, parameter and gradient is `dtype`
+ *     (FL_F32: float; FL_BF16: bfloat16 storage, fp32 accumulation and fp32
+ *     softmax / LayerNorm statistics).  Device pointers must be 16-byte aligned.
+ *   - `hip_stream` is the caller's hipStream_t (0 = the null stream).  Every
+ *     kernel is enqueued there; forward/backward never synchronise the device.
+ *   - Every call returns fl_status_t; no exception or abort crosses this ABI.
+ *     fl_last_error() returns a thread-local message for the last failure.
+ *     After an error outputs are unspecified; the handle stays destroyable.
+ *   - A handle is not thread-safe; distinct handles may be used from distinct
+ *     threads.  The caching allocator is process-wide and locked internally.
+ */
+#ifndef FL_LAYER_H
+#define FL_LAYER_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fl_layer fl_layer_t; /* opaque: tape + saved activations */
+
+typedef enum {
+  FL_OK = 0,
+  FL_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, B > max_B, T > max_T, D % heads != 0 */
+  FL_ERR_UNSUPPORTED = 2, /* shape outside what the kernels handle, misaligned pointer */
+  FL_ERR_OOM = 3,         /* device allocation failed (handle stays usable)            */
+  FL_ERR_DEVICE = 4,      /* a HIP call failed                                         */
+  FL_ERR_STATE = 5        /* backward without a recorded forward, or on another stream */
+} fl_status_t;
+
+typedef enum { FL_F32 = 0, FL_BF16 = 1 } fl_dtype_t;
+typedef enum { FL_ACT_RELU = 0, FL_ACT_GELU = 1 } fl_act_t; /* GELU = exact erf form */
+typedef enum { FL_NORM_POST = 0, FL_NORM_PRE = 1 } fl_norm_t;
+
+/* Host struct.  Supported shapes: d_model % 8 == 0, d_ffn % 8 == 0,
+ * head size dh = d_model / n_heads with dh % 16 == 0 and dh <= 256,
+ * d_model <= 8192.  ln_eps <= 0 selects the default 1e-5. */
+typedef struct {
+  int32_t max_B, max_T, d_model, n_heads, d_ffn;
+  fl_act_t act;
+  fl_norm_t norm;
+  fl_dtype_t dtype;
+  float ln_eps;
+} fl_layer_config_t;
+
+/* Host structs of device pointers; all 12 must be non-null.  Parameters are
+ * read during forward AND backward and are never copied: keep them unchanged
+ * between a forward and its backward. */
+typedef struct {
+  const void *Wqkv, *bqkv, *Wo, *bo, *W1, *b1, *W2, *b2, *ln1_g, *ln1_b, *ln2_g, *ln2_b;
+} fl_layer_params_t;
+typedef struct {
+  void *Wqkv, *bqkv, *Wo, *bo, *W1, *b1, *W2, *b2, *ln1_g, *ln1_b, *ln2_g, *ln2_b;
+} fl_layer_grads_t;
+
+/* Creates a layer (the paper's Module, Section 4.2).  Allocates no device memory. */
+fl_status_t fl_layer_create(const fl_layer_config_t *cfg, fl_layer_t **out);
+
+/* Forward pass (Module::forward, Section 4.2 / the Dropout-module listing's
+ * forward()): records one tape node per fused operator.
+ *   post-LN:  Y1 = LN1(X + Attn(X)),  Y = LN2(Y1 + FFN(Y1))
+ *   pre-LN :  R1 = X + Attn(LN1(X)),  Y = R1 + FFN(LN2(R1))
+ *   Attn(x) = softmax(mask(QK^T / sqrt(dh))) V Wo^T + bo,  FFN(x) = act(x W1^T + b1) W2^T + b2.
+ * X [B,T,D] is read here and again by backward (it is not copied: keep it
+ * unchanged until backward has been enqueued and has run).  `lengths` is a
+ * device int32[B] of key-padding lengths (key j of sequence b is masked iff
+ * j >= lengths[b]; 1 <= lengths[b] <= T is a precondition, not checked) or
+ * NULL for no mask.  Y [B,T,D] is written.  Any earlier recording on the handle
+ * is discarded and its buffers go back to the cache. */
+fl_status_t fl_layer_forward(fl_layer_t *layer, const fl_layer_params_t *params, const void *X,
+                             const int32_t *lengths, int32_t B, int32_t T, void *Y, void *hip_stream);
+
+/* Backward pass (Variable::backward(), Section 4.2; the training-loop listing's
+ * loss.backward()): replays the tape of the last forward in reverse order.
+ * dY [B,T,D] is the upstream gradient; dX [B,T,D] and all 12 gradient tensors
+ * are OVERWRITTEN (each parameter is used once per layer, so this equals the
+ * paper's addGrad after zeroGrad).  `params` must hold the same values as in
+ * the forward call.  Saved activations are released to the cache as their
+ * nodes are replayed; a second backward without a new forward is FL_ERR_STATE. */
+fl_status_t fl_layer_backward(fl_layer_t *layer, const fl_layer_params_t *params, const void *dY,
+                              void *dX, fl_layer_grads_t *grads, void *hip_stream);
+
+/* Releases the handle and returns its buffers to the cache.  NULL is a no-op. */
+fl_status_t fl_layer_destroy(fl_layer_t *layer);
+
+/* Thread-local text of the last error returned on this thread ("" if none). */
+const char *fl_last_error(void);
+
+/* Caching device allocator telemetry (Section 4.1.2; Section 5.2.2 describes
+ * size-bucketed caches, block splitting and allocation telemetry).
+ * backing_mallocs / backing_bytes: calls to and bytes obtained from the device
+ * allocator so far; cache_hits / cache_misses: requests served from / not from
+ * cached blocks; live_bytes: bytes handed out now; peak_bytes: its maximum;
+ * cached_bytes: bytes held in free blocks; split_count: blocks split so far. */
+typedef struct {
+  uint64_t backing_mallocs, backing_bytes, cache_hits, cache_misses;
+  uint64_t live_bytes, peak_bytes, cached_bytes, split_count;
+} fl_alloc_stats_t;
+fl_status_t fl_alloc_get_stats(fl_alloc_stats_t *out);
+
+/* Returns every cached (free) slab to the device.  Synchronises the device. */
+fl_status_t fl_alloc_trim(void);
+
+/* Blocks larger than `bytes` are never split to serve a smaller request
+ * (Section 5.2.2: restricting the splitting of large cache blocks reduced
+ * fragmentation).  0 restores the default (no limit). */
+fl_status_t fl_alloc_set_split_limit(uint64_t bytes);
+
+/* ---- per-kernel timing telemetry (host-side; used by the benchmark) -------------
+ * While enabled, launches of the selected kernel classes are bracketed by HIP
+ * events on the caller's stream.  fl_prof_collect() synchronises those events
+ * and fills `out` (host array of `cap` entries) with one entry per kernel class
+ * seen: launches, total milliseconds, algorithmic flops and bytes summed over
+ * the launches.  Returns the number of entries through *n. */
+typedef enum {
+  FL_K_GEMM_NT = 0,   /* y = x W^T (+bias, +activation, +residual)           */
+  FL_K_GEMM_NN = 1,   /* dx = dy W (+activation derivative, +skip gradient)  */
+  FL_K_GEMM_TN = 2,   /* dW = dy^T x (split over the token dimension)        */
+  FL_K_SPLITK_REDUCE = 3,
+  FL_K_ATTN_FWD = 4,
+  FL_K_ATTN_BWD = 5,
+  FL_K_LN_FWD = 6,
+  FL_K_LN_BWD = 7,
+  FL_K_COLSUM = 8,    /* bias gradients and second-stage column reductions   */
+  FL_K_CLASS_COUNT = 9
+} fl_kernel_class_t;
+typedef struct {
+  int32_t kernel_class;
+  int32_t launches;
+  double total_ms, flops, bytes;
+} fl_prof_entry_t;
+fl_status_t fl_prof_enable(uint32_t class_mask); /* bit i = class i; 0 disables and drops pending events */
+fl_status_t fl_prof_collect(fl_prof_entry_t *out, int32_t cap, int32_t *n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FL_LAYER_H */
