@@ -54,7 +54,7 @@ typedef enum { FL_NORM_POST = 0, FL_NORM_PRE = 1 } fl_norm_t;
 
 /* Host struct.  Supported shapes: d_model % 8 == 0, d_ffn % 8 == 0,
  * head size dh = d_model / n_heads with dh % 16 == 0 and dh <= 256,
- * d_model <= 8192.  ln_eps <= 0 selects the default 1e-5. */
+ * d_model <= 4096.  ln_eps <= 0 selects the default 1e-5. */
 typedef struct {
   int32_t max_B, max_T, d_model, n_heads, d_ffn;
   fl_act_t act;

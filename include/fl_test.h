@@ -1,0 +1,72 @@
+/*
+ * fl_test.h -- test-only entry points of the library.
+ *
+ * Each hot-path kernel on its own (so that a parity test can compare it with the
+ * matching step of the CPU oracle), the caching allocator over a caller-supplied
+ * backing store, and the tape with stub operators (so that the host logic can be
+ * tested without a GPU).  Nothing here is needed to run a layer.
+ *
+ * dtype is fl_dtype_t.  Pointers named A, B, C, x, y, ... are DEVICE pointers,
+ * 16-byte aligned; hip_stream is a hipStream_t.  Return value: fl_status_t
+ * (0 = ok; fl_last_error() has the message).  Nothing synchronises.
+ */
+#ifndef FL_TEST_H
+#define FL_TEST_H
+#include <stddef.h>
+#include <stdint.h>
+#include "fl_layer.h"
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* C[M,N] = sum_k A(m,k) B(n,k) with the epilogue of the layer's GEMMs, in this order:
+ * v += bias[n]; preact = v; v = act(v) (1 relu, 2 gelu); v += residual; v *= act'(aux)
+ * (dact 1: aux > 0, dact 2: GELU derivative at aux).  a_kc: A is [M,K] (k contiguous) else
+ * [K,M]; b_kc: B is [N,K] else [K,N].  splits: 0 = library's choice, 1 = none, >1 = that many
+ * k-ranges (then `partial` must hold splits*M*N floats and the epilogue must be empty).
+ * This is the matmul primitive of the paper's tensor interface (Section 4.1.1). */
+int32_t fl_test_gemm(int32_t dtype, int32_t a_kc, int32_t b_kc, const void *A, const void *B, void *C, int32_t M,
+                     int32_t N, int32_t K, const void *bias, const void *residual, int32_t act, void *preact,
+                     int32_t dact, const void *aux, int32_t splits, float *partial, void *hip_stream);
+int32_t fl_test_gemm_splits(int32_t dtype, int32_t M, int32_t N, int32_t K);
+
+/* LayerNorm (a normalisation primitive, Section 4.2) over the last dimension of x[M,D]. */
+int32_t fl_test_layernorm_fwd(int32_t dtype, const void *x, const void *gamma, const void *beta, float eps, int32_t M,
+                              int32_t D, void *y, float *mean, float *rstd, void *hip_stream);
+int32_t fl_test_layernorm_bwd_ws_floats(int32_t M, int32_t D);
+/* dx = LN'(dy) (+ add if non-null); dgamma, dbeta; dxsum (may be NULL) = column sums of dx. */
+int32_t fl_test_layernorm_bwd(int32_t dtype, const void *dy, const void *x, const float *mean, const float *rstd,
+                              const void *gamma, const void *add, int32_t M, int32_t D, void *dx, void *dgamma,
+                              void *dbeta, void *dxsum, float *ws, void *hip_stream);
+
+/* out[n] = sum_m in[m,n]: the bias gradient of a linear layer. */
+int64_t fl_test_colsum_ws_floats(int32_t M, int32_t N);
+int32_t fl_test_colsum(int32_t dtype, const void *in, int32_t M, int32_t N, float *ws, void *out, void *hip_stream);
+
+/* Masked scaled-dot-product attention on qkv[B*T, 3*H*dh]; lse and delta are fp32 [B,H,T]. */
+int32_t fl_test_attention_fwd(int32_t dtype, const void *qkv, const int32_t *lengths, int32_t B, int32_t T, int32_t H,
+                              int32_t dh, void *o, float *lse, void *hip_stream);
+int32_t fl_test_attention_bwd(int32_t dtype, const void *qkv, const void *o, const void *dout, const float *lse,
+                              const int32_t *lengths, int32_t B, int32_t T, int32_t H, int32_t dh, void *dqkv,
+                              float *delta, void *hip_stream);
+
+/* The caching allocator (Section 4.1.2, Section 5.2.2) over a HOST-side backing store:
+ * the two callbacks stand in for the device allocator; pointers are never dereferenced. */
+typedef int (*fl_test_backing_malloc_fn)(void **ptr, size_t bytes); /* 0 = ok */
+typedef int (*fl_test_backing_free_fn)(void *ptr);
+void *fl_test_alloc_create(fl_test_backing_malloc_fn m, fl_test_backing_free_fn f);
+void fl_test_alloc_destroy(void *a);
+void *fl_test_alloc_alloc(void *a, uint64_t bytes, const void *stream);
+int32_t fl_test_alloc_release(void *a, void *ptr);
+void fl_test_alloc_trim(void *a);
+void fl_test_alloc_set_split_limit(void *a, uint64_t bytes);
+void fl_test_alloc_stats(void *a, fl_alloc_stats_t *out);
+
+/* The tape (Section 4.2) with stub gradient functions: see the definition for the arguments. */
+int32_t fl_test_tape_replay(int32_t n, const int32_t *in0, const int32_t *in1, int32_t n_input_slots, int32_t fail_at,
+                            int32_t *order, int32_t *n_ran, int32_t *first_consumer, int32_t n_slots);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,193 @@
+"""ctypes binding of libflmi355.so: same names as include/fl_layer.h and
+include/fl_test.h, argument marshalling only.  Every computation runs in the
+library's HIP kernels; there is no fallback: if the library is missing, loading
+raises.
+
+Device buffers are passed as integers (addresses) or as objects with a
+``data_ptr()`` method (torch tensors); streams as integers (``hipStream_t``).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libflmi355.so")
+
+FL_OK, FL_ERR_INVALID_ARG, FL_ERR_UNSUPPORTED, FL_ERR_OOM, FL_ERR_DEVICE, FL_ERR_STATE = range(6)
+FL_F32, FL_BF16 = 0, 1
+FL_ACT_RELU, FL_ACT_GELU = 0, 1
+FL_NORM_POST, FL_NORM_PRE = 0, 1
+PARAM_FIELDS = ("Wqkv", "bqkv", "Wo", "bo", "W1", "b1", "W2", "b2", "ln1_g", "ln1_b", "ln2_g", "ln2_b")
+KERNEL_CLASSES = ("gemm_nt", "gemm_nn", "gemm_tn", "splitk_reduce", "attn_fwd", "attn_bwd",
+                  "ln_fwd", "ln_bwd", "colsum")
+
+
+class FlError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"fl status {status}: {message}")
+        self.status = status
+
+
+class fl_layer_config_t(C.Structure):
+    _fields_ = [("max_B", C.c_int32), ("max_T", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
+                ("d_ffn", C.c_int32), ("act", C.c_int), ("norm", C.c_int), ("dtype", C.c_int),
+                ("ln_eps", C.c_float)]
+
+
+class fl_layer_params_t(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in PARAM_FIELDS]
+
+
+class fl_layer_grads_t(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in PARAM_FIELDS]
+
+
+class fl_alloc_stats_t(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in ("backing_mallocs", "backing_bytes", "cache_hits", "cache_misses",
+                                           "live_bytes", "peak_bytes", "cached_bytes", "split_count")]
+
+    def as_dict(self):
+        return {n: int(getattr(self, n)) for n, _ in self._fields_}
+
+
+class fl_prof_entry_t(C.Structure):
+    _fields_ = [("kernel_class", C.c_int32), ("launches", C.c_int32), ("total_ms", C.c_double),
+                ("flops", C.c_double), ("bytes", C.c_double)]
+
+
+BACKING_MALLOC = C.CFUNCTYPE(C.c_int, C.POINTER(C.c_void_p), C.c_size_t)
+BACKING_FREE = C.CFUNCTYPE(C.c_int, C.c_void_p)
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads the library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: run `python -m paper_2201_12465_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, u64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_float
+        sig = {
+            "fl_layer_create": (C.c_int, [C.POINTER(fl_layer_config_t), C.POINTER(vp)]),
+            "fl_layer_forward": (C.c_int, [vp, C.POINTER(fl_layer_params_t), vp, vp, i32, i32, vp, vp]),
+            "fl_layer_backward": (C.c_int, [vp, C.POINTER(fl_layer_params_t), vp, vp, C.POINTER(fl_layer_grads_t), vp]),
+            "fl_layer_destroy": (C.c_int, [vp]),
+            "fl_last_error": (C.c_char_p, []),
+            "fl_alloc_get_stats": (C.c_int, [C.POINTER(fl_alloc_stats_t)]),
+            "fl_alloc_trim": (C.c_int, []),
+            "fl_alloc_set_split_limit": (C.c_int, [u64]),
+            "fl_prof_enable": (C.c_int, [C.c_uint32]),
+            "fl_prof_collect": (C.c_int, [C.POINTER(fl_prof_entry_t), i32, C.POINTER(i32)]),
+            "fl_test_gemm": (i32, [i32, i32, i32, vp, vp, vp, i32, i32, i32, vp, vp, i32, vp, i32, vp, i32, vp, vp]),
+            "fl_test_gemm_splits": (i32, [i32, i32, i32, i32]),
+            "fl_test_layernorm_fwd": (i32, [i32, vp, vp, vp, f32, i32, i32, vp, vp, vp, vp]),
+            "fl_test_layernorm_bwd_ws_floats": (i32, [i32, i32]),
+            "fl_test_layernorm_bwd": (i32, [i32, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp]),
+            "fl_test_colsum_ws_floats": (i64, [i32, i32]),
+            "fl_test_colsum": (i32, [i32, vp, i32, i32, vp, vp, vp]),
+            "fl_test_attention_fwd": (i32, [i32, vp, vp, i32, i32, i32, i32, vp, vp, vp]),
+            "fl_test_attention_bwd": (i32, [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]),
+            "fl_test_alloc_create": (vp, [BACKING_MALLOC, BACKING_FREE]),
+            "fl_test_alloc_destroy": (None, [vp]),
+            "fl_test_alloc_alloc": (vp, [vp, u64, vp]),
+            "fl_test_alloc_release": (i32, [vp, vp]),
+            "fl_test_alloc_trim": (None, [vp]),
+            "fl_test_alloc_set_split_limit": (None, [vp, u64]),
+            "fl_test_alloc_stats": (None, [vp, C.POINTER(fl_alloc_stats_t)]),
+            "fl_test_tape_replay": (i32, [i32, C.POINTER(i32), C.POINTER(i32), i32, i32, C.POINTER(i32),
+                                          C.POINTER(i32), C.POINTER(i32), i32]),
+        }
+        for name, (res, args) in sig.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def ptr(x) -> int | None:
+    if x is None:
+        return None
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    return int(x)
+
+
+def check(status: int) -> None:
+    if status != FL_OK:
+        raise FlError(status, lib().fl_last_error().decode())
+
+
+def _pack(struct_type, tensors: dict):
+    s = struct_type()
+    for n in PARAM_FIELDS:
+        setattr(s, n, ptr(tensors[n]))
+    return s
+
+
+class Layer:
+    """Thin handle wrapper: create / forward / backward / destroy."""
+
+    def __init__(self, max_B, max_T, d_model, n_heads, d_ffn, act="relu", norm="post", dtype="f32", ln_eps=1e-5):
+        cfg = fl_layer_config_t(max_B, max_T, d_model, n_heads, d_ffn,
+                                {"relu": FL_ACT_RELU, "gelu": FL_ACT_GELU}[act],
+                                {"post": FL_NORM_POST, "pre": FL_NORM_PRE}[norm],
+                                {"f32": FL_F32, "bf16": FL_BF16}[dtype], ln_eps)
+        self._h = C.c_void_p()
+        check(lib().fl_layer_create(C.byref(cfg), C.byref(self._h)))
+
+    def forward(self, params: dict, X, lengths, B: int, T: int, Y, stream: int = 0) -> None:
+        p = _pack(fl_layer_params_t, params)
+        check(lib().fl_layer_forward(self._h, C.byref(p), ptr(X), ptr(lengths), B, T, ptr(Y), stream))
+
+    def backward(self, params: dict, dY, dX, grads: dict, stream: int = 0) -> None:
+        p = _pack(fl_layer_params_t, params)
+        g = _pack(fl_layer_grads_t, grads)
+        check(lib().fl_layer_backward(self._h, C.byref(p), ptr(dY), ptr(dX), C.byref(g), stream))
+
+    def destroy(self) -> None:
+        if self._h:
+            check(lib().fl_layer_destroy(self._h))
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def alloc_stats() -> dict:
+    s = fl_alloc_stats_t()
+    check(lib().fl_alloc_get_stats(C.byref(s)))
+    return s.as_dict()
+
+
+def alloc_trim() -> None:
+    check(lib().fl_alloc_trim())
+
+
+def alloc_set_split_limit(nbytes: int) -> None:
+    check(lib().fl_alloc_set_split_limit(nbytes))
+
+
+def prof_enable(classes=None) -> None:
+    """classes: iterable of names from KERNEL_CLASSES, "all", or None/empty to disable."""
+    mask = 0
+    if classes == "all":
+        mask = (1 << len(KERNEL_CLASSES)) - 1
+    elif classes:
+        for c in classes:
+            mask |= 1 << KERNEL_CLASSES.index(c)
+    check(lib().fl_prof_enable(mask))
+
+
+def prof_collect() -> dict:
+    arr = (fl_prof_entry_t * len(KERNEL_CLASSES))()
+    n = C.c_int32(0)
+    check(lib().fl_prof_collect(arr, len(KERNEL_CLASSES), C.byref(n)))
+    return {KERNEL_CLASSES[arr[i].kernel_class]: {"launches": arr[i].launches, "total_ms": arr[i].total_ms,
+                                                  "flops": arr[i].flops, "bytes": arr[i].bytes}
+            for i in range(n.value)}

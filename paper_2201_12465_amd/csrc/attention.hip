@@ -1,0 +1,272 @@
+// Masked scaled-dot-product attention, forward and backward, with the score and
+// probability matrices kept on chip (never written to HBM).
+//
+// In the paper's terms this is a chain of tensor primitives -- two matmuls, a
+// scale, a max/exp/sum softmax (Section 4.1.1) -- fused into one operator with a
+// hand-written gradient function (Section 4.2; Section 5.2.1 "pre-fused gradient
+// computation for common sequences").  The softmax is computed online over key
+// tiles of 64 (running row maximum and row sum), so any sequence length fits;
+// masked keys (j >= length) are simply never visited, which gives them
+// probability exactly 0.  The backward pass recomputes the probabilities from
+// the saved log-sum-exp:  P = exp(S - LSE), dV = P^T dO, dP = dO V^T,
+// dS = P (dP - delta), delta_i = sum_d dO_i O_i, dQ = dS K / sqrt(dh),
+// dK = dS^T Q / sqrt(dh).
+//
+// This file holds the general kernels (any element type, fp32 arithmetic on the
+// vector ALUs): one wavefront per query row (forward, dQ) or per key row (dK, dV).
+#include "devutil.h"
+#include "kernels.h"
+
+namespace fl {
+namespace {
+
+constexpr int ROWS_PER_WG = 16;  // rows a workgroup of 4 waves walks (4 per wave)
+constexpr int MAX_DH = 256;
+
+template <typename T>
+__device__ __forceinline__ float dot_row(const float *__restrict__ s, const T *__restrict__ g, int dh) {
+  constexpr int VEC = Elem<T>::VEC;
+  float a = 0.f;
+  for (int d = 0; d < dh; d += VEC) {
+    float v[VEC];
+    VecIO<T, VEC>::load(g + d, v);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) a += s[d + e] * v[e];
+  }
+  return a;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void attn_fwd_rows(const T *__restrict__ qkv, const int32_t *__restrict__ lengths,
+                                                     int Tn, int H, int dh, float scale, T *__restrict__ o,
+                                                     float *__restrict__ lse) {
+  __shared__ float sq[4][MAX_DH];
+  __shared__ float sp[4][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int D = H * dh, ld = 3 * D;
+  const int len = lengths ? lengths[b] : Tn;
+  const T *base = qkv + (size_t)b * Tn * ld;
+  for (int r = 0; r < ROWS_PER_WG / 4; ++r) {
+    const int iw = blockIdx.x * ROWS_PER_WG + r * 4 + wave;
+    const bool active = iw < Tn;
+    const int i = active ? iw : Tn - 1;
+    __syncthreads();
+    for (int d = lane; d < dh; d += 64) sq[wave][d] = to_f32(base[(size_t)i * ld + h * dh + d]) * scale;
+    __syncthreads();
+    float mrun = -INFINITY, lrun = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int j0 = 0; j0 < len; j0 += 64) {
+      const int j = j0 + lane;
+      float s = -INFINITY;
+      if (j < len) s = dot_row<T>(sq[wave], base + (size_t)j * ld + D + h * dh, dh);
+      const float mnew = fmaxf(mrun, wave_max(s));
+      const float p = j < len ? __expf(s - mnew) : 0.f;
+      const float corr = __expf(mrun - mnew);
+      lrun = lrun * corr + wave_sum(p);
+      mrun = mnew;
+      sp[wave][lane] = p;
+      __syncthreads();
+      const int nj = min(64, len - j0);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) acc[c] *= corr;
+      for (int jj = 0; jj < nj; ++jj) {
+        const float pj = sp[wave][jj];
+        const T *vrow = base + (size_t)(j0 + jj) * ld + 2 * D + h * dh;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const int d = lane + 64 * c;
+          if (d < dh) acc[c] += pj * to_f32(vrow[d]);
+        }
+      }
+      __syncthreads();
+    }
+    if (active) {
+      const float inv = 1.0f / lrun;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int d = lane + 64 * c;
+        if (d < dh) o[((size_t)b * Tn + i) * D + h * dh + d] = from_f32<T>(acc[c] * inv);
+      }
+      if (lane == 0) lse[((size_t)b * H + h) * Tn + i] = mrun + __logf(lrun);
+    }
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void attn_bwd_dq_rows(const T *__restrict__ qkv, const T *__restrict__ o,
+                                                        const T *__restrict__ dout, const float *__restrict__ lse,
+                                                        const int32_t *__restrict__ lengths, int Tn, int H, int dh,
+                                                        float scale, T *__restrict__ dqkv,
+                                                        float *__restrict__ delta) {
+  __shared__ float sq[4][MAX_DH];
+  __shared__ float sdo[4][MAX_DH];
+  __shared__ float sp[4][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int D = H * dh, ld = 3 * D;
+  const int len = lengths ? lengths[b] : Tn;
+  const T *base = qkv + (size_t)b * Tn * ld;
+  for (int r = 0; r < ROWS_PER_WG / 4; ++r) {
+    const int iw = blockIdx.x * ROWS_PER_WG + r * 4 + wave;
+    const bool active = iw < Tn;
+    const int i = active ? iw : Tn - 1;
+    const size_t orow = ((size_t)b * Tn + i) * D + h * dh;
+    __syncthreads();
+    float dl = 0.f;
+    for (int d = lane; d < dh; d += 64) {
+      sq[wave][d] = to_f32(base[(size_t)i * ld + h * dh + d]) * scale;
+      const float g = to_f32(dout[orow + d]);
+      sdo[wave][d] = g;
+      dl += g * to_f32(o[orow + d]);
+    }
+    dl = wave_sum(dl);
+    const float L = lse[((size_t)b * H + h) * Tn + i];
+    if (active && lane == 0) delta[((size_t)b * H + h) * Tn + i] = dl;
+    __syncthreads();
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int j0 = 0; j0 < len; j0 += 64) {
+      const int j = j0 + lane;
+      float ds = 0.f;
+      if (j < len) {
+        const float s = dot_row<T>(sq[wave], base + (size_t)j * ld + D + h * dh, dh);
+        const float dp = dot_row<T>(sdo[wave], base + (size_t)j * ld + 2 * D + h * dh, dh);
+        ds = __expf(s - L) * (dp - dl);
+      }
+      sp[wave][lane] = ds;
+      __syncthreads();
+      const int nj = min(64, len - j0);
+      for (int jj = 0; jj < nj; ++jj) {
+        const float dj = sp[wave][jj];
+        const T *krow = base + (size_t)(j0 + jj) * ld + D + h * dh;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const int d = lane + 64 * c;
+          if (d < dh) acc[c] += dj * to_f32(krow[d]);
+        }
+      }
+      __syncthreads();
+    }
+    if (active) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int d = lane + 64 * c;
+        if (d < dh) dqkv[((size_t)b * Tn + i) * ld + h * dh + d] = from_f32<T>(acc[c] * scale);
+      }
+    }
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void attn_bwd_dkv_rows(const T *__restrict__ qkv, const T *__restrict__ dout,
+                                                         const float *__restrict__ lse,
+                                                         const float *__restrict__ delta,
+                                                         const int32_t *__restrict__ lengths, int Tn, int H, int dh,
+                                                         float scale, T *__restrict__ dqkv) {
+  __shared__ float sk[4][MAX_DH];
+  __shared__ float sv[4][MAX_DH];
+  __shared__ float sp[4][64];
+  __shared__ float sds[4][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int D = H * dh, ld = 3 * D;
+  const int len = lengths ? lengths[b] : Tn;
+  const T *base = qkv + (size_t)b * Tn * ld;
+  for (int r = 0; r < ROWS_PER_WG / 4; ++r) {
+    const int jw = blockIdx.x * ROWS_PER_WG + r * 4 + wave;
+    const bool active = jw < Tn;
+    const int j = active ? jw : Tn - 1;
+    const bool masked = j >= len;
+    __syncthreads();
+    for (int d = lane; d < dh; d += 64) {
+      sk[wave][d] = to_f32(base[(size_t)j * ld + D + h * dh + d]) * scale;
+      sv[wave][d] = to_f32(base[(size_t)j * ld + 2 * D + h * dh + d]);
+    }
+    __syncthreads();
+    float ak[4] = {0.f, 0.f, 0.f, 0.f}, av[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int i0 = 0; i0 < Tn; i0 += 64) {
+      const int i = i0 + lane;
+      float p = 0.f, ds = 0.f;
+      if (i < Tn && !masked) {
+        const float s = dot_row<T>(sk[wave], base + (size_t)i * ld + h * dh, dh);
+        const float dp = dot_row<T>(sv[wave], dout + ((size_t)b * Tn + i) * D + h * dh, dh);
+        const size_t st = ((size_t)b * H + h) * Tn + i;
+        p = __expf(s - lse[st]);
+        ds = p * (dp - delta[st]);
+      }
+      sp[wave][lane] = p;
+      sds[wave][lane] = ds;
+      __syncthreads();
+      const int ni = min(64, Tn - i0);
+      for (int ii = 0; ii < ni; ++ii) {
+        const float pi = sp[wave][ii], di = sds[wave][ii];
+        const T *qrow = base + (size_t)(i0 + ii) * ld + h * dh;
+        const T *grow = dout + ((size_t)b * Tn + i0 + ii) * D + h * dh;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const int d = lane + 64 * c;
+          if (d < dh) {
+            av[c] += pi * to_f32(grow[d]);
+            ak[c] += di * to_f32(qrow[d]);
+          }
+        }
+      }
+      __syncthreads();
+    }
+    if (active) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int d = lane + 64 * c;
+        if (d < dh) {
+          dqkv[((size_t)b * Tn + j) * ld + D + h * dh + d] = from_f32<T>(masked ? 0.f : ak[c] * scale);
+          dqkv[((size_t)b * Tn + j) * ld + 2 * D + h * dh + d] = from_f32<T>(masked ? 0.f : av[c]);
+        }
+      }
+    }
+  }
+}
+
+bool attn_shape_ok(int B, int T, int H, int dh) {
+  return B >= 1 && T >= 1 && H >= 1 && dh >= 16 && dh % 16 == 0 && dh <= MAX_DH && H <= 65535 && B <= 65535;
+}
+
+}  // namespace
+
+hipError_t launch_attention_fwd(int dt, const void *qkv, const int32_t *lengths, int B, int T, int H, int dh, void *o,
+                                float *lse, hipStream_t stream) {
+  if (!qkv || !o || !lse || !attn_shape_ok(B, T, H, dh)) return hipErrorInvalidValue;
+  const float scale = 1.0f / sqrtf((float)dh);
+  dim3 grid((T + ROWS_PER_WG - 1) / ROWS_PER_WG, H, B), block(256);
+  if (dt == DT_F32)
+    hipLaunchKernelGGL(attn_fwd_rows<float>, grid, block, 0, stream, static_cast<const float *>(qkv), lengths, T, H,
+                       dh, scale, static_cast<float *>(o), lse);
+  else
+    hipLaunchKernelGGL(attn_fwd_rows<bf16_t>, grid, block, 0, stream, static_cast<const bf16_t *>(qkv), lengths, T, H,
+                       dh, scale, static_cast<bf16_t *>(o), lse);
+  return hipGetLastError();
+}
+
+hipError_t launch_attention_bwd(int dt, const void *qkv, const void *o, const void *do_, const float *lse,
+                                const int32_t *lengths, int B, int T, int H, int dh, void *dqkv, float *delta,
+                                hipStream_t stream) {
+  if (!qkv || !o || !do_ || !lse || !dqkv || !delta || !attn_shape_ok(B, T, H, dh)) return hipErrorInvalidValue;
+  const float scale = 1.0f / sqrtf((float)dh);
+  dim3 grid((T + ROWS_PER_WG - 1) / ROWS_PER_WG, H, B), block(256);
+  if (dt == DT_F32) {
+    hipLaunchKernelGGL(attn_bwd_dq_rows<float>, grid, block, 0, stream, static_cast<const float *>(qkv),
+                       static_cast<const float *>(o), static_cast<const float *>(do_), lse, lengths, T, H, dh, scale,
+                       static_cast<float *>(dqkv), delta);
+    hipLaunchKernelGGL(attn_bwd_dkv_rows<float>, grid, block, 0, stream, static_cast<const float *>(qkv),
+                       static_cast<const float *>(do_), lse, delta, lengths, T, H, dh, scale,
+                       static_cast<float *>(dqkv));
+  } else {
+    hipLaunchKernelGGL(attn_bwd_dq_rows<bf16_t>, grid, block, 0, stream, static_cast<const bf16_t *>(qkv),
+                       static_cast<const bf16_t *>(o), static_cast<const bf16_t *>(do_), lse, lengths, T, H, dh,
+                       scale, static_cast<bf16_t *>(dqkv), delta);
+    hipLaunchKernelGGL(attn_bwd_dkv_rows<bf16_t>, grid, block, 0, stream, static_cast<const bf16_t *>(qkv),
+                       static_cast<const bf16_t *>(do_), lse, delta, lengths, T, H, dh, scale,
+                       static_cast<bf16_t *>(dqkv));
+  }
+  return hipGetLastError();
+}
+
+}  // namespace fl

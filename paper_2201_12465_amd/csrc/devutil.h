@@ -1,0 +1,82 @@
+// Device-side helpers shared by the kernels: element types, 16-byte vector
+// access, bf16 <-> fp32 conversion, wavefront reductions (64 lanes).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+namespace fl {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+template <typename T> struct Elem;
+template <> struct Elem<float> { static constexpr int VEC = 4; };   // elements per 16 bytes
+template <> struct Elem<bf16_t> { static constexpr int VEC = 8; };
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return static_cast<float>(v); }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return static_cast<bf16_t>(v); }  // RNE
+
+// Loads / stores of N consecutive elements as fp32 (N*sizeof(T) bytes, naturally aligned).
+template <typename T, int N> struct VecIO;
+template <> struct VecIO<float, 4> {
+  static __device__ __forceinline__ void load(const float *p, float *v) {
+    float4 t = *reinterpret_cast<const float4 *>(p);
+    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+  }
+  static __device__ __forceinline__ void store(float *p, const float *v) {
+    *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  }
+};
+template <> struct VecIO<bf16_t, 4> {
+  static __device__ __forceinline__ void load(const bf16_t *p, float *v) {
+    bf16x4_t t = *reinterpret_cast<const bf16x4_t *>(p);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = static_cast<float>(t[i]);
+  }
+  static __device__ __forceinline__ void store(bf16_t *p, const float *v) {
+    bf16x4_t t;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) t[i] = static_cast<bf16_t>(v[i]);
+    *reinterpret_cast<bf16x4_t *>(p) = t;
+  }
+};
+template <> struct VecIO<bf16_t, 8> {
+  static __device__ __forceinline__ void load(const bf16_t *p, float *v) {
+    bf16x8_t t = *reinterpret_cast<const bf16x8_t *>(p);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = static_cast<float>(t[i]);
+  }
+  static __device__ __forceinline__ void store(bf16_t *p, const float *v) {
+    bf16x8_t t;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) t[i] = static_cast<bf16_t>(v[i]);
+    *reinterpret_cast<bf16x8_t *>(p) = t;
+  }
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+__device__ __forceinline__ float gelu_f(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_grad_f(float u) {
+  float cdf = 0.5f * (1.0f + erff(u * 0.70710678118654752f));
+  float pdf = 0.39894228040143268f * __expf(-0.5f * u * u);
+  return cdf + u * pdf;
+}
+
+}  // namespace fl

@@ -1,0 +1,80 @@
+// Launchers of the gfx950 kernels.  Every launcher validates what its kernel and
+// grid assume, enqueues on `stream`, never synchronises, and returns hipError_t.
+// Element type: dt = 0 -> float, 1 -> bfloat16 (storage; all arithmetic in fp32).
+#pragma once
+#include <hip/hip_runtime_api.h>
+#include <cstddef>
+#include <cstdint>
+
+namespace fl {
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+static inline size_t dt_size(int dt) { return dt == DT_F32 ? 4 : 2; }
+
+// ---------------------------------------------------------------------------
+// GEMM  C[M,N] = sum_k A(m,k) * B(n,k), fp32 accumulation on MFMA.
+//   a_kc:  A(m,k) = A[m*lda + k]  (k contiguous)   else  A[k*lda + m]
+//   b_kc:  B(n,k) = B[n*ldb + k]  (k contiguous)   else  B[k*ldb + n]
+// so  y = x W^T is (a_kc, b_kc);  dx = dy W is (a_kc, !b_kc);  dW = dy^T x is
+// (!a_kc, !b_kc) with k running over tokens.
+// Epilogue, in this order, on v = accumulator:
+//   v += bias[n];  preact[m,n] = v (if preact);  v = act(v);  v += residual[m,n];
+//   v *= act'(aux[m,n]) (dact: 1 = aux > 0, 2 = exact-GELU derivative at aux);  C[m,n] = v
+// With splits > 1 (k is cut into `splits` ranges) the raw partial sums go to
+// `partial` (fp32 [splits][M][N]) and the epilogue must be empty; the caller then
+// runs reduce_partials.
+// Requirements (checked): N % 8 == 0; the contiguous dimension of each operand
+// % 8 == 0; lda/ldb/ldc % 8 == 0; pointers 16-byte aligned.
+struct GemmArgs {
+  const void *A = nullptr, *B = nullptr;
+  void *C = nullptr;
+  int M = 0, N = 0, K = 0, lda = 0, ldb = 0, ldc = 0;
+  bool a_kc = true, b_kc = true;
+  const void *bias = nullptr, *residual = nullptr, *aux = nullptr;
+  void *preact = nullptr;
+  int act = 0, dact = 0;
+  float *partial = nullptr;
+  int splits = 1;
+};
+hipError_t launch_gemm(int dt, const GemmArgs &a, hipStream_t stream);
+// Number of k-ranges launch_gemm should use so that a small output still fills the chip.
+int gemm_pick_splits(int dt, int M, int N, int K);
+
+// out_s[n] = sum_p partial[p*stride + s*seglen + n]  for s < nseg (<= 3), n < seglen;
+// out_s has element type dt.  seglen % 4 == 0.
+hipError_t launch_reduce_partials(int dt, const float *partial, int P, size_t stride, size_t seglen,
+                                  int nseg, void *out0, void *out1, void *out2, hipStream_t stream);
+
+// Column sums of in[M,N] (type dt) -> out[N] (type dt); ws must hold colsum_ws_floats(M,N) floats.
+size_t colsum_ws_floats(int M, int N);
+hipError_t launch_colsum(int dt, const void *in, int M, int N, float *ws, void *out, hipStream_t stream);
+
+// ---------------------------------------------------------------------------
+// LayerNorm over the last dimension D of x[M,D] (biased variance, eps inside the
+// square root).  Forward writes y and the per-row mean / reciprocal std (fp32).
+// D % 8 == 0, D <= 4096.
+hipError_t launch_layernorm_fwd(int dt, const void *x, const void *gamma, const void *beta, float eps,
+                                int M, int D, void *y, float *mean, float *rstd, hipStream_t stream);
+// Backward:  g = dy*gamma;  dx = rstd*(g - mean_D(g) - xhat*mean_D(g*xhat)) (+ add[m,:] if add);
+// partial sums over rows of dy*xhat, dy and the final dx go to ws
+// ([ln_bwd_parts(M, D)][3][D] floats); reduce_partials turns them into dgamma, dbeta
+// and (if wanted) the bias gradient of the producer of x.
+int ln_bwd_parts(int M, int D);
+hipError_t launch_layernorm_bwd(int dt, const void *dy, const void *x, const float *mean, const float *rstd,
+                                const void *gamma, const void *add, int M, int D, void *dx, float *ws,
+                                hipStream_t stream);
+
+// ---------------------------------------------------------------------------
+// Masked scaled-dot-product attention on the fused projection buffer
+// qkv[B*T, 3D] (q | k | v slabs, head h = columns h*dh..).  lengths: device
+// int32[B] or nullptr.  Forward writes o[B*T, D] and lse[B,H,T] (log-sum-exp of
+// the scaled, masked scores; fp32).  dh % 16 == 0, dh <= 256.
+hipError_t launch_attention_fwd(int dt, const void *qkv, const int32_t *lengths, int B, int T, int H, int dh,
+                                void *o, float *lse, hipStream_t stream);
+// Backward: dqkv[B*T, 3D] from do_[B*T, D]; delta is fp32 scratch [B,H,T]
+// (delta_i = sum_d dO_i O_i).  Rows of dk, dv at masked keys are written as 0.
+hipError_t launch_attention_bwd(int dt, const void *qkv, const void *o, const void *do_, const float *lse,
+                                const int32_t *lengths, int B, int T, int H, int dh, void *dqkv, float *delta,
+                                hipStream_t stream);
+
+}  // namespace fl

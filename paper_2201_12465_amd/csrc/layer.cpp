@@ -1,0 +1,740 @@
+// Encoder-layer orchestration and the C ABI declared in include/fl_layer.h.
+//
+// forward() is the paper's Module::forward (Section 4.2): it runs the fused
+// operators in order, takes every intermediate buffer from the caching allocator
+// (Section 4.1.2) and records one tape node per operator.  backward() is the
+// paper's Variable::backward(): the tape is replayed in reverse and each node's
+// gradient function adds into its inputs' gradients (Section 4.2, the
+// cosine-operator listing).  Adding is fused into the producing kernel's
+// epilogue wherever two gradient contributions meet (the residual connections),
+// and requests attached to a slot let the kernel that finishes a gradient also
+// apply the activation derivative or emit a bias gradient (Section 5.2.1,
+// pre-fused gradient computation for common sequences).
+#include <hip/hip_runtime_api.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "../../include/fl_layer.h"
+#include "allocator.h"
+#include "kernels.h"
+#include "runtime.h"
+#include "tape.h"
+
+using namespace fl;
+
+// ------------------------------------------------------------------ errors
+namespace {
+thread_local char g_err[512] = "";
+}
+namespace fl {
+int set_error(int code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+}  // namespace fl
+
+// ------------------------------------------------------------------ allocator instance
+namespace {
+int hip_backing_malloc(void **p, size_t bytes) {
+  hipError_t e = hipMalloc(p, bytes);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();  // clear the sticky out-of-memory code
+    *p = nullptr;
+    return 1;
+  }
+  return 0;
+}
+int hip_backing_free(void *p) { return hipFree(p) == hipSuccess ? 0 : 1; }
+}  // namespace
+namespace fl {
+CachingAllocator &device_allocator() {
+  static CachingAllocator *a = new CachingAllocator(hip_backing_malloc, hip_backing_free);  // never destroyed
+  return *a;
+}
+}  // namespace fl
+
+// ------------------------------------------------------------------ per-kernel timing
+namespace {
+struct ProfEvent {
+  hipEvent_t a, b;
+  int cls;
+  double flops, bytes;
+};
+struct Prof {
+  std::mutex mu;
+  uint32_t mask = 0;
+  std::vector<ProfEvent> pending;
+  std::vector<hipEvent_t> pool;
+  hipEvent_t get() {
+    if (!pool.empty()) {
+      hipEvent_t e = pool.back();
+      pool.pop_back();
+      return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+};
+Prof &prof() {
+  static Prof *p = new Prof();
+  return *p;
+}
+}  // namespace
+
+namespace fl {
+// Runs `launch` (which enqueues one kernel class on `s`), bracketed by events when that class is selected.
+template <typename F>
+hipError_t timed(int cls, double flops, double bytes, hipStream_t s, F &&launch) {
+  Prof &P = prof();
+  if (!(P.mask & (1u << cls))) return launch();
+  std::lock_guard<std::mutex> g(P.mu);
+  ProfEvent ev{P.get(), P.get(), cls, flops, bytes};
+  if (!ev.a || !ev.b) return hipErrorOutOfMemory;
+  hipError_t e = hipEventRecord(ev.a, s);
+  if (e != hipSuccess) return e;
+  e = launch();
+  if (e != hipSuccess) return e;
+  e = hipEventRecord(ev.b, s);
+  if (e != hipSuccess) return e;
+  P.pending.push_back(ev);
+  return hipSuccess;
+}
+}  // namespace fl
+
+// ------------------------------------------------------------------ the layer
+enum ParamId { P_WQKV, P_BQKV, P_WO, P_BO, P_W1, P_B1, P_W2, P_B2, P_LN1G, P_LN1B, P_LN2G, P_LN2B, P_COUNT };
+enum OpId { OP_LINEAR = 1, OP_ATTN = 2, OP_LN = 3 };
+
+struct fl_layer {
+  fl_layer_config_t cfg;
+  float eps;
+  int dt;
+  Tape tape;
+  // state of the recorded forward
+  int B = 0, T = 0, M = 0;
+  hipStream_t stream = nullptr;
+  const int32_t *lengths = nullptr;
+  int slot_x = -1, slot_y = -1;
+  // valid during backward
+  const void *params[P_COUNT];
+  void *grads[P_COUNT];
+};
+
+namespace {
+
+#define FL_HIP(expr)                                                                      \
+  do {                                                                                    \
+    hipError_t e_ = (expr);                                                               \
+    if (e_ != hipSuccess)                                                                 \
+      return set_error(e_ == hipErrorInvalidValue ? FL_ERR_UNSUPPORTED : FL_ERR_DEVICE,   \
+                       "%s failed: %s", #expr, hipGetErrorString(e_));                    \
+  } while (0)
+#define FL_TRY(expr)        \
+  do {                      \
+    int rc_ = (expr);       \
+    if (rc_) return rc_;    \
+  } while (0)
+
+Buf *buf_new(size_t bytes, hipStream_t s) {
+  void *p = device_allocator().alloc(bytes, s);
+  if (!p) return nullptr;
+  Buf *b = new (std::nothrow) Buf();
+  if (!b) {
+    device_allocator().release(p);
+    return nullptr;
+  }
+  b->ptr = p;
+  b->bytes = bytes;
+  b->refs = 1;
+  return b;
+}
+void buf_unref(Buf *&b) {
+  if (b && --b->refs == 0) {
+    device_allocator().release(b->ptr);
+    delete b;
+  }
+  b = nullptr;
+}
+// Scratch that lives for the kernels enqueued in one scope: released to the cache at scope
+// exit, which is safe because the cache only hands it out again for later work on this stream.
+struct Scratch {
+  Buf *b = nullptr;
+  ~Scratch() { buf_unref(b); }
+  int get(size_t bytes, hipStream_t s) {
+    b = buf_new(bytes, s);
+    return b ? 0 : set_error(FL_ERR_OOM, "device allocation of %zu bytes failed", bytes);
+  }
+  float *f32() { return static_cast<float *>(b->ptr); }
+};
+
+void release_tape(fl_layer *L) {
+  for (Slot &s : L->tape.slots) {
+    buf_unref(s.value_buf);
+    buf_unref(s.grad_buf);
+  }
+  for (Node &n : L->tape.nodes)
+    for (Buf *&b : n.saved) buf_unref(b);
+  L->tape.clear();
+}
+
+size_t esize(const fl_layer *L) { return dt_size(L->dt); }
+
+// Replaces a slot's accumulated gradient.
+void set_grad(Slot &s, void *ptr, Buf *buf) {
+  buf_unref(s.grad_buf);
+  s.grad = ptr;
+  s.grad_buf = buf;
+}
+
+// ---- gradient functions ---------------------------------------------------------------
+
+struct LinearShape {
+  int w, b;  // parameter ids
+};
+const LinearShape kLinear[4] = {{P_WQKV, P_BQKV}, {P_WO, P_BO}, {P_W1, P_B1}, {P_W2, P_B2}};
+
+// y = x W^T + b (+act) (+residual):  db = colsum(gy), dW = gy^T x, dx += gy W, dresidual += gy.
+int linear_backward(void *ctx, Tape *tape, const Node *n) {
+  fl_layer *L = static_cast<fl_layer *>(ctx);
+  const int self = tape->index_of(n);
+  hipStream_t st = L->stream;
+  Slot &ys = tape->slots[n->out];
+  const int M = n->rows, K = n->n_in, N = n->n_out, dt = L->dt;
+  const size_t e = esize(L);
+  if (!ys.grad) return set_error(FL_ERR_STATE, "linear node %d: no gradient reached its output", self);
+  if (ys.xform != XF_NONE && !ys.xform_done)
+    return set_error(FL_ERR_STATE, "linear node %d: activation derivative was not applied upstream", self);
+  const void *gy = ys.grad;
+  const void *W = L->params[kLinear[n->param].w];
+  // bias gradient, unless the kernel that finished gy already produced it
+  if (!ys.colsum_done) {
+    Scratch ws;
+    FL_TRY(ws.get(colsum_ws_floats(M, N) * sizeof(float), st));
+    FL_HIP(timed(FL_K_COLSUM, 0, (double)M * N * e, st,
+                 [&] { return launch_colsum(dt, gy, M, N, ws.f32(), L->grads[kLinear[n->param].b], st); }));
+  }
+  // weight gradient: dW[N,K] = sum_m gy[m,n] x[m,k]
+  {
+    GemmArgs a;
+    a.A = gy; a.lda = N; a.a_kc = false;
+    a.B = n->s0; a.ldb = K; a.b_kc = false;
+    a.M = N; a.N = K; a.K = M;
+    a.C = L->grads[kLinear[n->param].w]; a.ldc = K;
+    a.splits = gemm_pick_splits(dt, a.M, a.N, a.K);
+    const double fl = 2.0 * M * N * K, by = ((double)M * N + (double)M * K + (double)N * K) * e;
+    if (a.splits > 1) {
+      Scratch ws;
+      FL_TRY(ws.get((size_t)a.splits * N * K * sizeof(float), st));
+      a.partial = ws.f32();
+      FL_HIP(timed(FL_K_GEMM_TN, fl, by, st, [&] { return launch_gemm(dt, a, st); }));
+      FL_HIP(timed(FL_K_SPLITK_REDUCE, 0, (double)(a.splits * 4 + e) * N * K, st, [&] {
+        return launch_reduce_partials(dt, ws.f32(), a.splits, (size_t)N * K, (size_t)N * K, 1, a.C, nullptr, nullptr, st);
+      }));
+    } else {
+      FL_HIP(timed(FL_K_GEMM_TN, fl, by, st, [&] { return launch_gemm(dt, a, st); }));
+    }
+  }
+  // input gradient: dx[M,K] = gy W (+ what other consumers of x already contributed)
+  {
+    Slot &xs = tape->slots[n->in0];
+    const bool fin = tape->finishes(self, n->in0);
+    GemmArgs a;
+    a.A = gy; a.lda = N; a.a_kc = true;
+    a.B = W; a.ldb = K; a.b_kc = false;
+    a.M = M; a.N = K; a.K = N; a.ldc = K;
+    a.residual = xs.grad;
+    if (fin && xs.xform != XF_NONE) {
+      a.dact = xs.xform;
+      a.aux = xs.xform_aux;
+    }
+    Buf *nb = nullptr;
+    if (fin && xs.grad_dst) {
+      a.C = xs.grad_dst;
+    } else {
+      nb = buf_new((size_t)M * K * e, st);
+      if (!nb) return set_error(FL_ERR_OOM, "device allocation of %zu bytes failed", (size_t)M * K * e);
+      a.C = nb->ptr;
+    }
+    hipError_t he = timed(FL_K_GEMM_NN, 2.0 * M * N * K, ((double)M * N + (double)M * K + (double)N * K) * e, st,
+                          [&] { return launch_gemm(dt, a, st); });
+    if (he != hipSuccess) {
+      buf_unref(nb);
+      FL_HIP(he);
+    }
+    set_grad(xs, a.C, nb);
+    if (a.dact) xs.xform_done = true;
+  }
+  // residual input: the identity branch passes gy through unchanged
+  if (n->in1 >= 0) {
+    Slot &rs = tape->slots[n->in1];
+    if (rs.grad || tape->finishes(self, n->in1))
+      return set_error(FL_ERR_UNSUPPORTED, "linear node %d: residual gradient would need a separate add", self);
+    rs.grad = ys.grad;
+    rs.grad_buf = ys.grad_buf;
+    if (rs.grad_buf) rs.grad_buf->refs++;
+  }
+  set_grad(ys, nullptr, nullptr);
+  buf_unref(ys.value_buf);
+  for (Buf *b : n->saved) {
+    Buf *t = b;
+    buf_unref(t);
+  }
+  const_cast<Node *>(n)->saved[0] = const_cast<Node *>(n)->saved[1] = const_cast<Node *>(n)->saved[2] = nullptr;
+  return 0;
+}
+
+int attention_backward(void *ctx, Tape *tape, const Node *n) {
+  fl_layer *L = static_cast<fl_layer *>(ctx);
+  const int self = tape->index_of(n);
+  hipStream_t st = L->stream;
+  Slot &os = tape->slots[n->out], &qs = tape->slots[n->in0];
+  const int D = L->cfg.d_model, H = L->cfg.n_heads, dh = D / H, M = L->M;
+  const size_t e = esize(L);
+  if (!os.grad) return set_error(FL_ERR_STATE, "attention node %d: no gradient reached its output", self);
+  if (qs.grad || !tape->finishes(self, n->in0) || qs.xform != XF_NONE)
+    return set_error(FL_ERR_UNSUPPORTED, "attention node %d: its input must have no other consumer", self);
+  Buf *nb = buf_new((size_t)M * 3 * D * e, st);
+  if (!nb) return set_error(FL_ERR_OOM, "device allocation of %zu bytes failed", (size_t)M * 3 * D * e);
+  Scratch delta;
+  int rc = delta.get((size_t)L->B * H * L->T * sizeof(float), st);
+  if (rc) {
+    buf_unref(nb);
+    return rc;
+  }
+  const double fl = 10.0 * D * L->T * (double)M, by = 8.0 * M * D * e + 8.0 * L->B * H * L->T;
+  hipError_t he = timed(FL_K_ATTN_BWD, fl, by, st, [&] {
+    return launch_attention_bwd(L->dt, qs.value, os.value, os.grad, static_cast<const float *>(n->s0), L->lengths,
+                                L->B, L->T, H, dh, nb->ptr, delta.f32(), st);
+  });
+  if (he != hipSuccess) {
+    buf_unref(nb);
+    FL_HIP(he);
+  }
+  set_grad(qs, nb->ptr, nb);
+  set_grad(os, nullptr, nullptr);
+  buf_unref(os.value_buf);
+  Buf *t = n->saved[0];
+  buf_unref(t);
+  const_cast<Node *>(n)->saved[0] = nullptr;
+  return 0;
+}
+
+int layernorm_backward(void *ctx, Tape *tape, const Node *n) {
+  fl_layer *L = static_cast<fl_layer *>(ctx);
+  const int self = tape->index_of(n);
+  hipStream_t st = L->stream;
+  Slot &ys = tape->slots[n->out], &xs = tape->slots[n->in0];
+  const int D = L->cfg.d_model, M = L->M, dt = L->dt;
+  const size_t e = esize(L);
+  if (!ys.grad) return set_error(FL_ERR_STATE, "layernorm node %d: no gradient reached its output", self);
+  const bool fin = tape->finishes(self, n->in0);
+  if (fin && xs.xform != XF_NONE)
+    return set_error(FL_ERR_UNSUPPORTED, "layernorm node %d: cannot apply an activation derivative", self);
+  const int gi = n->param == 0 ? P_LN1G : P_LN2G, bi = n->param == 0 ? P_LN1B : P_LN2B;
+  const int parts = ln_bwd_parts(M, D);
+  Scratch ws;
+  FL_TRY(ws.get((size_t)parts * 3 * D * sizeof(float), st));
+  Buf *nb = nullptr;
+  void *dst;
+  if (fin && xs.grad_dst) {
+    dst = xs.grad_dst;
+  } else {
+    nb = buf_new((size_t)M * D * e, st);
+    if (!nb) return set_error(FL_ERR_OOM, "device allocation of %zu bytes failed", (size_t)M * D * e);
+    dst = nb->ptr;
+  }
+  const float *mean = static_cast<const float *>(n->s0);
+  const double by = (double)M * D * e * (xs.grad ? 4 : 3) + 8.0 * M;
+  hipError_t he = timed(FL_K_LN_BWD, 0, by, st, [&] {
+    return launch_layernorm_bwd(dt, ys.grad, xs.value, mean, mean + M, L->params[gi], xs.grad, M, D, dst, ws.f32(), st);
+  });
+  if (he != hipSuccess) {
+    buf_unref(nb);
+    FL_HIP(he);
+  }
+  set_grad(xs, dst, nb);
+  const bool want_bias = fin && xs.colsum_param >= 0;
+  FL_HIP(timed(FL_K_COLSUM, 0, (double)parts * 3 * D * 4, st, [&] {
+    return launch_reduce_partials(dt, ws.f32(), parts, (size_t)3 * D, (size_t)D, want_bias ? 3 : 2, L->grads[gi],
+                                  L->grads[bi], want_bias ? L->grads[xs.colsum_param] : nullptr, st);
+  }));
+  if (want_bias) xs.colsum_done = true;
+  set_grad(ys, nullptr, nullptr);
+  buf_unref(ys.value_buf);
+  Buf *t = n->saved[0];
+  buf_unref(t);
+  const_cast<Node *>(n)->saved[0] = nullptr;
+  return 0;
+}
+
+// ---- forward operators (each enqueues its kernel and records its node) ------------------
+
+// y = x W^T + b, optional activation (records the request for its derivative on y) and residual.
+int op_linear(fl_layer *L, int lin, int xslot, int rslot, int act, int K, int N, void *y_ext, int *yslot) {
+  Tape &tp = L->tape;
+  hipStream_t st = L->stream;
+  const int M = L->M, dt = L->dt;
+  const size_t e = esize(L);
+  Buf *yb = nullptr, *ub = nullptr;
+  void *y = y_ext;
+  if (!y) {
+    yb = buf_new((size_t)M * N * e, st);
+    if (!yb) return set_error(FL_ERR_OOM, "device allocation of %zu bytes failed", (size_t)M * N * e);
+    y = yb->ptr;
+  }
+  GemmArgs a;
+  a.A = tp.slots[xslot].value; a.lda = K; a.a_kc = true;
+  a.B = L->params[kLinear[lin].w]; a.ldb = K; a.b_kc = true;
+  a.M = M; a.N = N; a.K = K; a.C = y; a.ldc = N;
+  a.bias = L->params[kLinear[lin].b];
+  a.act = act;
+  if (rslot >= 0) a.residual = tp.slots[rslot].value;
+  if (act == XF_GELU) {  // the derivative needs the pre-activation
+    ub = buf_new((size_t)M * N * e, st);
+    if (!ub) {
+      buf_unref(yb);
+      return set_error(FL_ERR_OOM, "device allocation of %zu bytes failed", (size_t)M * N * e);
+    }
+    a.preact = ub->ptr;
+  }
+  hipError_t he = timed(FL_K_GEMM_NT, 2.0 * M * N * K, ((double)M * N + (double)M * K + (double)N * K) * e, st,
+                        [&] { return launch_gemm(dt, a, st); });
+  if (he != hipSuccess) {
+    buf_unref(yb);
+    buf_unref(ub);
+    FL_HIP(he);
+  }
+  const int ys = tp.new_slot();
+  Slot &s = tp.slots[ys];
+  s.value = y;
+  s.value_buf = yb;
+  s.colsum_param = kLinear[lin].b;
+  if (act != XF_NONE) {
+    s.xform = act;
+    s.xform_aux = act == XF_GELU ? ub->ptr : y;  // ReLU: the output's sign is the pre-activation's
+  }
+  Node n;
+  n.backward = linear_backward;
+  n.op = OP_LINEAR;
+  n.in0 = xslot; n.in1 = rslot; n.out = ys; n.param = lin;
+  n.s0 = tp.slots[xslot].value;
+  n.saved[0] = ub;
+  n.rows = M; n.n_in = K; n.n_out = N;
+  tp.record(n);
+  *yslot = ys;
+  return 0;
+}
+
+int op_attention(fl_layer *L, int qslot, int *oslot) {
+  Tape &tp = L->tape;
+  hipStream_t st = L->stream;
+  const int D = L->cfg.d_model, H = L->cfg.n_heads, dh = D / H, M = L->M;
+  const size_t e = esize(L);
+  Buf *ob = buf_new((size_t)M * D * e, st);
+  Buf *lb = buf_new((size_t)L->B * H * L->T * sizeof(float), st);
+  if (!ob || !lb) {
+    buf_unref(ob);
+    buf_unref(lb);
+    return set_error(FL_ERR_OOM, "device allocation for attention output failed");
+  }
+  const double fl = 4.0 * D * L->T * (double)M, by = 4.0 * M * D * e + 4.0 * L->B * H * L->T;
+  hipError_t he = timed(FL_K_ATTN_FWD, fl, by, st, [&] {
+    return launch_attention_fwd(L->dt, tp.slots[qslot].value, L->lengths, L->B, L->T, H, dh, ob->ptr,
+                                static_cast<float *>(lb->ptr), st);
+  });
+  if (he != hipSuccess) {
+    buf_unref(ob);
+    buf_unref(lb);
+    FL_HIP(he);
+  }
+  const int os = tp.new_slot();
+  tp.slots[os].value = ob->ptr;
+  tp.slots[os].value_buf = ob;
+  Node n;
+  n.backward = attention_backward;
+  n.op = OP_ATTN;
+  n.in0 = qslot; n.out = os;
+  n.s0 = lb->ptr;
+  n.saved[0] = lb;
+  n.rows = M;
+  tp.record(n);
+  *oslot = os;
+  return 0;
+}
+
+int op_layernorm(fl_layer *L, int which, int xslot, void *y_ext, int *yslot) {
+  Tape &tp = L->tape;
+  hipStream_t st = L->stream;
+  const int D = L->cfg.d_model, M = L->M;
+  const size_t e = esize(L);
+  Buf *yb = nullptr;
+  void *y = y_ext;
+  if (!y) {
+    yb = buf_new((size_t)M * D * e, st);
+    if (!yb) return set_error(FL_ERR_OOM, "device allocation of %zu bytes failed", (size_t)M * D * e);
+    y = yb->ptr;
+  }
+  Buf *sb = buf_new((size_t)2 * M * sizeof(float), st);
+  if (!sb) {
+    buf_unref(yb);
+    return set_error(FL_ERR_OOM, "device allocation for LayerNorm statistics failed");
+  }
+  float *mean = static_cast<float *>(sb->ptr);
+  const int gi = which == 0 ? P_LN1G : P_LN2G, bi = which == 0 ? P_LN1B : P_LN2B;
+  hipError_t he = timed(FL_K_LN_FWD, 0, 2.0 * M * D * e + 8.0 * M, st, [&] {
+    return launch_layernorm_fwd(L->dt, tp.slots[xslot].value, L->params[gi], L->params[bi], L->eps, M, D, y, mean,
+                                mean + M, st);
+  });
+  if (he != hipSuccess) {
+    buf_unref(yb);
+    buf_unref(sb);
+    FL_HIP(he);
+  }
+  const int ys = tp.new_slot();
+  tp.slots[ys].value = y;
+  tp.slots[ys].value_buf = yb;
+  Node n;
+  n.backward = layernorm_backward;
+  n.op = OP_LN;
+  n.in0 = xslot; n.out = ys; n.param = which;
+  n.s0 = mean;
+  n.saved[0] = sb;
+  n.rows = M;
+  tp.record(n);
+  *yslot = ys;
+  return 0;
+}
+
+void load_params(fl_layer *L, const fl_layer_params_t *p) {
+  const void *v[P_COUNT] = {p->Wqkv, p->bqkv, p->Wo, p->bo, p->W1, p->b1, p->W2, p->b2,
+                            p->ln1_g, p->ln1_b, p->ln2_g, p->ln2_b};
+  memcpy(L->params, v, sizeof(v));
+}
+
+int check_ptrs(const void *const *v, int n, const char *what) {
+  for (int i = 0; i < n; ++i) {
+    if (!v[i]) return set_error(FL_ERR_INVALID_ARG, "%s: pointer %d is null", what, i);
+    if (reinterpret_cast<uintptr_t>(v[i]) & 15)
+      return set_error(FL_ERR_UNSUPPORTED, "%s: pointer %d is not 16-byte aligned", what, i);
+  }
+  return 0;
+}
+
+int forward_impl(fl_layer *L, const fl_layer_params_t *params, const void *X, const int32_t *lengths, int B, int T,
+                 void *Y, hipStream_t st) {
+  const fl_layer_config_t &c = L->cfg;
+  if (B < 1 || T < 1 || B > c.max_B || T > c.max_T)
+    return set_error(FL_ERR_INVALID_ARG, "B=%d T=%d outside 1..max_B=%d, 1..max_T=%d", B, T, c.max_B, c.max_T);
+  if ((long)B * T > (1l << 24)) return set_error(FL_ERR_UNSUPPORTED, "B*T too large");
+  load_params(L, params);
+  FL_TRY(check_ptrs(L->params, P_COUNT, "params"));
+  const void *io[2] = {X, Y};
+  FL_TRY(check_ptrs(io, 2, "X/Y"));
+  release_tape(L);
+  L->B = B; L->T = T; L->M = B * T; L->stream = st; L->lengths = lengths;
+  Tape &tp = L->tape;
+  const int D = c.d_model, F = c.d_ffn;
+  const int act = c.act == FL_ACT_RELU ? XF_RELU : XF_GELU;
+  const int sx = tp.new_slot();
+  tp.slots[sx].value = X;
+  L->slot_x = sx;
+  int s_qkv, s_o, s_r1, s_y1, s_g, s_out, s_n1;
+  if (c.norm == FL_NORM_POST) {
+    FL_TRY(op_linear(L, 0, sx, -1, XF_NONE, D, 3 * D, nullptr, &s_qkv));
+    FL_TRY(op_attention(L, s_qkv, &s_o));
+    FL_TRY(op_linear(L, 1, s_o, sx, XF_NONE, D, D, nullptr, &s_r1));      // R1 = X + O Wo^T + bo
+    FL_TRY(op_layernorm(L, 0, s_r1, nullptr, &s_y1));                      // Y1 = LN1(R1)
+    FL_TRY(op_linear(L, 2, s_y1, -1, act, D, F, nullptr, &s_g));           // G = act(Y1 W1^T + b1)
+    int s_r2;
+    FL_TRY(op_linear(L, 3, s_g, s_y1, XF_NONE, F, D, nullptr, &s_r2));     // R2 = Y1 + G W2^T + b2
+    FL_TRY(op_layernorm(L, 1, s_r2, Y, &s_out));                           // Y = LN2(R2)
+  } else {
+    FL_TRY(op_layernorm(L, 0, sx, nullptr, &s_n1));                        // N1 = LN1(X)
+    FL_TRY(op_linear(L, 0, s_n1, -1, XF_NONE, D, 3 * D, nullptr, &s_qkv));
+    FL_TRY(op_attention(L, s_qkv, &s_o));
+    FL_TRY(op_linear(L, 1, s_o, sx, XF_NONE, D, D, nullptr, &s_r1));      // R1 = X + O Wo^T + bo
+    FL_TRY(op_layernorm(L, 1, s_r1, nullptr, &s_y1));                      // N2 = LN2(R1)
+    FL_TRY(op_linear(L, 2, s_y1, -1, act, D, F, nullptr, &s_g));
+    FL_TRY(op_linear(L, 3, s_g, s_r1, XF_NONE, F, D, Y, &s_out));          // Y = R1 + G W2^T + b2
+  }
+  L->slot_y = s_out;
+  tp.recorded = true;
+  return 0;
+}
+
+int backward_impl(fl_layer *L, const fl_layer_params_t *params, const void *dY, void *dX, fl_layer_grads_t *grads,
+                  hipStream_t st) {
+  if (!L->tape.recorded) return set_error(FL_ERR_STATE, "backward without a recorded forward");
+  if (st != L->stream) return set_error(FL_ERR_STATE, "backward on a different stream than forward");
+  load_params(L, params);
+  FL_TRY(check_ptrs(L->params, P_COUNT, "params"));
+  void *g[P_COUNT] = {grads->Wqkv, grads->bqkv, grads->Wo, grads->bo, grads->W1, grads->b1, grads->W2, grads->b2,
+                      grads->ln1_g, grads->ln1_b, grads->ln2_g, grads->ln2_b};
+  memcpy(L->grads, g, sizeof(g));
+  FL_TRY(check_ptrs(L->grads, P_COUNT, "grads"));
+  const void *io[2] = {dY, dX};
+  FL_TRY(check_ptrs(io, 2, "dY/dX"));
+  Tape &tp = L->tape;
+  tp.slots[L->slot_y].grad = const_cast<void *>(dY);
+  tp.slots[L->slot_x].grad_dst = dX;
+  int rc = tp.replay_reverse(L);
+  const bool landed = rc == 0 && tp.slots[L->slot_x].grad == dX;
+  release_tape(L);
+  if (rc) return rc;
+  if (!landed) return set_error(FL_ERR_STATE, "input gradient did not reach its destination");
+  return 0;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ C ABI
+#define FL_GUARD_BEGIN try {
+#define FL_GUARD_END                                                         \
+  }                                                                          \
+  catch (const std::bad_alloc &) {                                           \
+    return (fl_status_t)set_error(FL_ERR_OOM, "host allocation failed");     \
+  }                                                                          \
+  catch (...) {                                                              \
+    return (fl_status_t)set_error(FL_ERR_DEVICE, "unexpected internal error"); \
+  }
+
+extern "C" {
+
+fl_status_t fl_layer_create(const fl_layer_config_t *cfg, fl_layer_t **out) {
+  FL_GUARD_BEGIN
+  if (!cfg || !out) return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "null argument");
+  *out = nullptr;
+  if (cfg->max_B < 1 || cfg->max_T < 1 || cfg->d_model < 1 || cfg->n_heads < 1 || cfg->d_ffn < 1)
+    return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "sizes must be positive");
+  if (cfg->d_model % cfg->n_heads)
+    return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "d_model=%d is not a multiple of n_heads=%d", cfg->d_model,
+                                  cfg->n_heads);
+  if ((unsigned)cfg->act > FL_ACT_GELU || (unsigned)cfg->norm > FL_NORM_PRE || (unsigned)cfg->dtype > FL_BF16)
+    return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "unknown activation, norm placement or dtype");
+  const int dh = cfg->d_model / cfg->n_heads;
+  if (cfg->d_model % 8 || cfg->d_ffn % 8 || dh % 16 || dh > 256 || cfg->d_model > 4096)
+    return (fl_status_t)set_error(FL_ERR_UNSUPPORTED,
+                                  "need d_model %% 8 == 0, d_ffn %% 8 == 0, head size %% 16 == 0 and <= 256, "
+                                  "d_model <= 4096 (got d_model=%d d_ffn=%d head size=%d)",
+                                  cfg->d_model, cfg->d_ffn, dh);
+  fl_layer *L = new fl_layer();
+  L->cfg = *cfg;
+  L->eps = cfg->ln_eps > 0.f ? cfg->ln_eps : 1e-5f;
+  L->dt = cfg->dtype == FL_F32 ? DT_F32 : DT_BF16;
+  *out = L;
+  return FL_OK;
+  FL_GUARD_END
+}
+
+fl_status_t fl_layer_forward(fl_layer_t *layer, const fl_layer_params_t *params, const void *X,
+                             const int32_t *lengths, int32_t B, int32_t T, void *Y, void *hip_stream) {
+  FL_GUARD_BEGIN
+  if (!layer || !params || !X || !Y) return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "null argument");
+  int rc = forward_impl(layer, params, X, lengths, B, T, Y, static_cast<hipStream_t>(hip_stream));
+  if (rc) release_tape(layer);
+  return (fl_status_t)rc;
+  FL_GUARD_END
+}
+
+fl_status_t fl_layer_backward(fl_layer_t *layer, const fl_layer_params_t *params, const void *dY, void *dX,
+                              fl_layer_grads_t *grads, void *hip_stream) {
+  FL_GUARD_BEGIN
+  if (!layer || !params || !dY || !dX || !grads) return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "null argument");
+  return (fl_status_t)backward_impl(layer, params, dY, dX, grads, static_cast<hipStream_t>(hip_stream));
+  FL_GUARD_END
+}
+
+fl_status_t fl_layer_destroy(fl_layer_t *layer) {
+  FL_GUARD_BEGIN
+  if (!layer) return FL_OK;
+  release_tape(layer);
+  delete layer;
+  return FL_OK;
+  FL_GUARD_END
+}
+
+const char *fl_last_error(void) { return g_err; }
+
+fl_status_t fl_alloc_get_stats(fl_alloc_stats_t *out) {
+  FL_GUARD_BEGIN
+  if (!out) return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "null argument");
+  AllocStats s = device_allocator().stats();
+  out->backing_mallocs = s.backing_mallocs; out->backing_bytes = s.backing_bytes;
+  out->cache_hits = s.cache_hits; out->cache_misses = s.cache_misses;
+  out->live_bytes = s.live_bytes; out->peak_bytes = s.peak_bytes;
+  out->cached_bytes = s.cached_bytes; out->split_count = s.split_count;
+  return FL_OK;
+  FL_GUARD_END
+}
+
+fl_status_t fl_alloc_trim(void) {
+  FL_GUARD_BEGIN
+  hipError_t e = hipDeviceSynchronize();
+  if (e != hipSuccess) return (fl_status_t)set_error(FL_ERR_DEVICE, "hipDeviceSynchronize: %s", hipGetErrorString(e));
+  device_allocator().trim();
+  return FL_OK;
+  FL_GUARD_END
+}
+
+fl_status_t fl_alloc_set_split_limit(uint64_t bytes) {
+  FL_GUARD_BEGIN
+  device_allocator().set_split_limit((size_t)bytes);
+  return FL_OK;
+  FL_GUARD_END
+}
+
+fl_status_t fl_prof_enable(uint32_t class_mask) {
+  FL_GUARD_BEGIN
+  Prof &P = prof();
+  std::lock_guard<std::mutex> g(P.mu);
+  P.mask = class_mask & ((1u << FL_K_CLASS_COUNT) - 1);
+  if (!P.mask) {
+    for (ProfEvent &ev : P.pending) {
+      P.pool.push_back(ev.a);
+      P.pool.push_back(ev.b);
+    }
+    P.pending.clear();
+  }
+  return FL_OK;
+  FL_GUARD_END
+}
+
+fl_status_t fl_prof_collect(fl_prof_entry_t *out, int32_t cap, int32_t *n) {
+  FL_GUARD_BEGIN
+  if (!out || !n || cap < 1) return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "null argument");
+  Prof &P = prof();
+  std::lock_guard<std::mutex> g(P.mu);
+  fl_prof_entry_t acc[FL_K_CLASS_COUNT];
+  for (int i = 0; i < FL_K_CLASS_COUNT; ++i) acc[i] = fl_prof_entry_t{i, 0, 0.0, 0.0, 0.0};
+  for (ProfEvent &ev : P.pending) {
+    hipError_t e = hipEventSynchronize(ev.b);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev.a, ev.b);
+    if (e != hipSuccess) return (fl_status_t)set_error(FL_ERR_DEVICE, "event timing: %s", hipGetErrorString(e));
+    acc[ev.cls].launches++;
+    acc[ev.cls].total_ms += ms;
+    acc[ev.cls].flops += ev.flops;
+    acc[ev.cls].bytes += ev.bytes;
+    P.pool.push_back(ev.a);
+    P.pool.push_back(ev.b);
+  }
+  P.pending.clear();
+  int k = 0;
+  for (int i = 0; i < FL_K_CLASS_COUNT && k < cap; ++i)
+    if (acc[i].launches) out[k++] = acc[i];
+  *n = k;
+  return FL_OK;
+  FL_GUARD_END
+}
+
+}  // extern "C"

@@ -1,0 +1,94 @@
+// Column reductions: second stage of every two-stage reduction (split-k GEMM
+// partials, LayerNorm-backward partials) and the stand-alone bias gradient
+// db[n] = sum_m dy[m,n] of a linear layer (the gradient function of the paper's
+// add primitive with a broadcast operand; Section 4.1.1 / Section 4.2).
+// Both stages are deterministic: fixed summation order, no atomics.
+#include "devutil.h"
+#include "kernels.h"
+
+namespace fl {
+namespace {
+
+// out_s[n..n+3] = sum_p partial[p*stride + s*seglen + n..n+3]
+template <typename T>
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ partial, int P, size_t stride,
+                                                              size_t seglen, T *out0, T *out1, T *out2) {
+  const size_t n = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (n >= seglen) return;
+  const int s = blockIdx.y;
+  const float *src = partial + (size_t)s * seglen + n;
+  float a[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int p = 0; p < P; ++p) {
+    float4 t = *reinterpret_cast<const float4 *>(src + (size_t)p * stride);
+    a[0] += t.x; a[1] += t.y; a[2] += t.z; a[3] += t.w;
+  }
+  T *out = s == 0 ? out0 : (s == 1 ? out1 : out2);
+  if (out) VecIO<T, 4>::store(out + n, a);
+}
+
+constexpr int CS_ROWS = 128;  // rows per first-stage block
+
+// ws[rb][n] = sum over the rows of block rb of in[m][n]; 64 lanes x VEC columns, 4 waves interleave rows
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_stage1_kernel(const T *__restrict__ in, int M, int N, float *ws) {
+  constexpr int VEC = Elem<T>::VEC;
+  __shared__ float red[4][64 * VEC];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = (blockIdx.x * 64 + lane) * VEC;
+  const int m0 = blockIdx.y * CS_ROWS, m1 = min(M, m0 + CS_ROWS);
+  float a[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) a[e] = 0.f;
+  if (n < N) {
+    for (int m = m0 + wave; m < m1; m += 4) {
+      float v[VEC];
+      VecIO<T, VEC>::load(in + (size_t)m * N + n, v);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) a[e] += v[e];
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) red[wave][lane * VEC + e] = a[e];
+  __syncthreads();
+  if (wave == 0 && n < N) {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e)
+      ws[(size_t)blockIdx.y * N + n + e] = red[0][lane * VEC + e] + red[1][lane * VEC + e] +
+                                           red[2][lane * VEC + e] + red[3][lane * VEC + e];
+  }
+}
+
+}  // namespace
+
+hipError_t launch_reduce_partials(int dt, const float *partial, int P, size_t stride, size_t seglen, int nseg,
+                                  void *out0, void *out1, void *out2, hipStream_t stream) {
+  if (!partial || P < 1 || nseg < 1 || nseg > 3 || seglen == 0 || seglen % 4 || stride % 4)
+    return hipErrorInvalidValue;
+  if ((size_t)nseg * seglen > stride && P > 1) return hipErrorInvalidValue;
+  dim3 grid((unsigned)((seglen / 4 + 255) / 256), nseg);
+  if (dt == DT_F32)
+    hipLaunchKernelGGL(reduce_partials_kernel<float>, grid, dim3(256), 0, stream, partial, P, stride, seglen,
+                       static_cast<float *>(out0), static_cast<float *>(out1), static_cast<float *>(out2));
+  else
+    hipLaunchKernelGGL(reduce_partials_kernel<bf16_t>, grid, dim3(256), 0, stream, partial, P, stride, seglen,
+                       static_cast<bf16_t *>(out0), static_cast<bf16_t *>(out1), static_cast<bf16_t *>(out2));
+  return hipGetLastError();
+}
+
+size_t colsum_ws_floats(int M, int N) { return (size_t)((M + CS_ROWS - 1) / CS_ROWS) * N; }
+
+hipError_t launch_colsum(int dt, const void *in, int M, int N, float *ws, void *out, hipStream_t stream) {
+  if (!in || !ws || !out || M < 1 || N < 1 || N % 8) return hipErrorInvalidValue;
+  const int rb = (M + CS_ROWS - 1) / CS_ROWS;
+  const int vec = dt == DT_F32 ? 4 : 8;
+  dim3 grid((N + 64 * vec - 1) / (64 * vec), rb);
+  if (dt == DT_F32)
+    hipLaunchKernelGGL(colsum_stage1_kernel<float>, grid, dim3(256), 0, stream, static_cast<const float *>(in), M, N, ws);
+  else
+    hipLaunchKernelGGL(colsum_stage1_kernel<bf16_t>, grid, dim3(256), 0, stream, static_cast<const bf16_t *>(in), M, N, ws);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_reduce_partials(dt, ws, rb, (size_t)N, (size_t)N, 1, out, nullptr, nullptr, stream);
+}
+
+}  // namespace fl

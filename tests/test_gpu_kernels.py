@@ -1,0 +1,218 @@
+"""Kernel-level parity: each HIP kernel, called through the C ABI's test entry
+points, against the matching step of the CPU oracle on the same seeded inputs.
+Sizes span several tiles and a ragged tail."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from gpu_util import (BF16_KERNEL_TOL, F32_KERNEL_TOL, dt_code, empty_dev, quantise, rel_err, stream_ptr, to_dev,
+                      to_np, torch_mod)
+
+pytestmark = pytest.mark.gpu
+
+
+def _tol(dtype):
+    return F32_KERNEL_TOL if dtype == "f32" else BF16_KERNEL_TOL
+
+
+def _lib():
+    from paper_2201_12465_amd import binding
+    return binding
+
+
+GEMM_SHAPES = [(32, 192, 64), (200, 136, 72), (257, 264, 328), (1024, 768, 256), (130, 8, 8)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mode", ["nt", "nn", "tn"])
+@pytest.mark.parametrize("shape", GEMM_SHAPES)
+def test_gemm_plain(dtype, mode, shape):
+    b = _lib()
+    M, N, K = shape
+    if mode == "tn" and M % 8:
+        M += 8 - M % 8          # the k-major A operand is contiguous along M
+    rng = np.random.default_rng(hash((mode, shape)) % 2**32)
+    A = quantise(rng.standard_normal((M, K)), dtype)     # logical A(m,k)
+    Bm = quantise(rng.standard_normal((N, K)), dtype)    # logical B(n,k)
+    ref = A.astype(np.float64) @ Bm.astype(np.float64).T
+    a_kc, b_kc = {"nt": (1, 1), "nn": (1, 0), "tn": (0, 0)}[mode]
+    dA = to_dev(A if a_kc else A.T.copy(), dtype)
+    dB = to_dev(Bm if b_kc else Bm.T.copy(), dtype)
+    for splits in ([1] if mode != "tn" else [1, 0, 3]):
+        dC = empty_dev((M, N), dtype)
+        s = splits if splits else b.lib().fl_test_gemm_splits(dt_code(dtype), M, N, K)
+        part = empty_dev((max(s, 1) * M * N,), "f32")
+        if splits == 3:      # k-ranges are whole k-tiles (32 fp32 / 64 bf16 values); none may be empty
+            kt = 32 if dtype == "f32" else 64
+            kps = -(-(-(-K // 3)) // kt) * kt
+            if 2 * kps >= K:
+                continue
+        b.check(b.lib().fl_test_gemm(dt_code(dtype), a_kc, b_kc, dA.data_ptr(), dB.data_ptr(), dC.data_ptr(), M, N, K,
+                                     None, None, 0, None, 0, None, splits, part.data_ptr(), stream_ptr()))
+        torch_mod().cuda.synchronize()
+        assert rel_err(to_np(dC), ref) <= _tol(dtype), (mode, shape, splits)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("act", [0, 1, 2])
+def test_gemm_forward_epilogue(dtype, act):
+    """v = x W^T + b; preact; act; + residual  (the forward linear layers)."""
+    b = _lib()
+    M, N, K = 200, 264, 136
+    rng = np.random.default_rng(5 + act)
+    x = quantise(rng.standard_normal((M, K)), dtype)
+    W = quantise(rng.standard_normal((N, K)) * 0.2, dtype)
+    bias = quantise(rng.standard_normal(N), dtype)
+    res = quantise(rng.standard_normal((M, N)), dtype)
+    u = orc.linear_fwd(x, W, bias)
+    g = u if act == 0 else orc.act_fwd(u, "relu" if act == 1 else "gelu")
+    ref = g + res
+    dC, dU = empty_dev((M, N), dtype), empty_dev((M, N), dtype)
+    tx, tW, tb, tr = (to_dev(a, dtype) for a in (x, W, bias, res))   # keep the device copies alive
+    b.check(b.lib().fl_test_gemm(dt_code(dtype), 1, 1, tx.data_ptr(), tW.data_ptr(), dC.data_ptr(), M, N, K,
+                                 tb.data_ptr(), tr.data_ptr(), act, dU.data_ptr(), 0, None, 1, None, stream_ptr()))
+    torch_mod().cuda.synchronize()
+    assert rel_err(to_np(dC), ref) <= _tol(dtype)
+    assert rel_err(to_np(dU), u) <= _tol(dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dact", [1, 2])
+def test_gemm_backward_epilogue(dtype, dact):
+    """dx = (dy W + skip) * act'(aux)  (the input-gradient GEMMs)."""
+    b = _lib()
+    M, N, K = 136, 200, 264      # dy [M,K] (k = out features), W [K,N] k-major, dx [M,N]
+    rng = np.random.default_rng(9 + dact)
+    dy = quantise(rng.standard_normal((M, K)), dtype)
+    W = quantise(rng.standard_normal((K, N)) * 0.2, dtype)
+    skip = quantise(rng.standard_normal((M, N)), dtype)
+    u = quantise(rng.standard_normal((M, N)), dtype)
+    aux = u if dact == 2 else quantise(np.maximum(u, 0), dtype)
+    lin = dy.astype(np.float64) @ W.astype(np.float64) + skip
+    ref = orc.act_bwd(lin, u, "relu" if dact == 1 else "gelu")
+    dC = empty_dev((M, N), dtype)
+    tdy, tW, ts, ta = (to_dev(a, dtype) for a in (dy, W, skip, aux))
+    b.check(b.lib().fl_test_gemm(dt_code(dtype), 1, 0, tdy.data_ptr(), tW.data_ptr(), dC.data_ptr(), M, N, K, None,
+                                 ts.data_ptr(), 0, None, dact, ta.data_ptr(), 1, None, stream_ptr()))
+    torch_mod().cuda.synchronize()
+    assert rel_err(to_np(dC), ref) <= _tol(dtype)
+
+
+def test_gemm_rejects_bad_shapes():
+    b = _lib()
+    d = empty_dev((64 * 64,), "f32")
+    p = d.data_ptr()
+    # N not a multiple of 8; misaligned pointer
+    assert b.lib().fl_test_gemm(0, 1, 1, p, p, p, 16, 12, 16, None, None, 0, None, 0, None, 1, None, 0) == b.FL_ERR_UNSUPPORTED
+    assert b.lib().fl_test_gemm(0, 1, 1, p + 4, p, p, 16, 16, 16, None, None, 0, None, 0, None, 1, None, 0) == b.FL_ERR_UNSUPPORTED
+    assert b"launch_gemm" in b.lib().fl_last_error()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(32, 64), (203, 768), (1024, 256), (7, 1032), (5, 4096)])
+def test_layernorm_forward_backward(dtype, shape):
+    b = _lib()
+    M, D = shape
+    rng = np.random.default_rng(M * 31 + D)
+    x = quantise(rng.standard_normal((M, D)) * 2 + 0.5, dtype)
+    gam = quantise(1 + 0.1 * rng.standard_normal(D), dtype)
+    bet = quantise(0.1 * rng.standard_normal(D), dtype)
+    dy = quantise(rng.standard_normal((M, D)), dtype)
+    add = quantise(rng.standard_normal((M, D)), dtype)
+    eps = 1e-5
+    y, xhat, rstd = orc.layernorm_fwd(x, gam, bet, eps)
+    dx, dg, db = orc.layernorm_bwd(dy, xhat, rstd, gam)
+    dX, dG, dB = to_dev(x, dtype), to_dev(gam, dtype), to_dev(bet, dtype)
+    dYo, mean, rs = empty_dev((M, D), dtype), empty_dev((M,), "f32"), empty_dev((M,), "f32")
+    b.check(b.lib().fl_test_layernorm_fwd(dt_code(dtype), dX.data_ptr(), dG.data_ptr(), dB.data_ptr(), eps, M, D,
+                                          dYo.data_ptr(), mean.data_ptr(), rs.data_ptr(), stream_ptr()))
+    torch_mod().cuda.synchronize()
+    assert rel_err(to_np(dYo), y) <= _tol(dtype)
+    assert rel_err(to_np(mean), x.astype(np.float64).mean(-1)) <= 1e-5
+    assert rel_err(to_np(rs), rstd[:, 0]) <= 1e-5
+    ws = empty_dev((b.lib().fl_test_layernorm_bwd_ws_floats(M, D),), "f32")
+    tdy, tadd = to_dev(dy, dtype), to_dev(add, dtype)
+    for with_add in (False, True):
+        odx, odg, odb, ods = (empty_dev((M, D), dtype), empty_dev((D,), dtype), empty_dev((D,), dtype),
+                              empty_dev((D,), dtype))
+        b.check(b.lib().fl_test_layernorm_bwd(dt_code(dtype), tdy.data_ptr(), dX.data_ptr(),
+                                              mean.data_ptr(), rs.data_ptr(), dG.data_ptr(),
+                                              tadd.data_ptr() if with_add else None, M, D,
+                                              odx.data_ptr(), odg.data_ptr(), odb.data_ptr(), ods.data_ptr(),
+                                              ws.data_ptr(), stream_ptr()))
+        torch_mod().cuda.synchronize()
+        want = dx + (add if with_add else 0)
+        assert rel_err(to_np(odx), want) <= _tol(dtype)
+        assert rel_err(to_np(odg), dg) <= _tol(dtype)
+        assert rel_err(to_np(odb), db) <= _tol(dtype)
+        assert rel_err(to_np(ods), want.sum(0)) <= _tol(dtype) * 4   # column sums of values near zero mean
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(32, 192), (1000, 264), (4096, 3072), (1, 8)])
+def test_colsum(dtype, shape):
+    b = _lib()
+    M, N = shape
+    rng = np.random.default_rng(M + N)
+    a = quantise(rng.standard_normal((M, N)), dtype)
+    ws = empty_dev((b.lib().fl_test_colsum_ws_floats(M, N),), "f32")
+    out = empty_dev((N,), dtype)
+    ta = to_dev(a, dtype)
+    b.check(b.lib().fl_test_colsum(dt_code(dtype), ta.data_ptr(), M, N, ws.data_ptr(), out.data_ptr(),
+                                   stream_ptr()))
+    torch_mod().cuda.synchronize()
+    assert rel_err(to_np(out), a.astype(np.float64).sum(0)) <= _tol(dtype)
+
+
+ATTN_CASES = [  # B, T, H, dh, lengths
+    (2, 16, 4, 16, None),
+    (3, 37, 2, 64, [1, 20, 37]),
+    (2, 128, 3, 64, [64, 128]),
+    (2, 197, 2, 64, None),
+    (1, 300, 2, 192, [171]),
+    (2, 70, 1, 256, [70, 33]),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", ATTN_CASES)
+def test_attention_forward_backward(dtype, case):
+    b = _lib()
+    B, T, H, dh, lengths = case
+    D = H * dh
+    rng = np.random.default_rng(B * 1000 + T)
+    qkv = quantise(rng.standard_normal((B, T, 3 * D)), dtype)
+    dO = quantise(rng.standard_normal((B, T, D)), dtype)
+    Q, K, V = (orc.split_heads(qkv[..., i * D:(i + 1) * D].astype(np.float64), H) for i in range(3))
+    Oh, P = orc.attention_fwd(Q, K, V, lengths)
+    O = orc.merge_heads(Oh)
+    S = (Q @ K.transpose(0, 1, 3, 2)) / math.sqrt(dh)
+    if lengths is not None:
+        S = np.where(orc.key_mask(lengths, B, T)[:, None, None, :], -np.inf, S)
+    lse_ref = np.log(np.exp(S - S.max(-1, keepdims=True)).sum(-1)) + S.max(-1)
+    dQ, dK, dV = orc.attention_bwd(orc.split_heads(dO.astype(np.float64), H), Q, K, V, P)
+    dqkv_ref = np.concatenate([orc.merge_heads(dQ), orc.merge_heads(dK), orc.merge_heads(dV)], -1)
+    torch = torch_mod()
+    dl = torch.tensor(lengths, dtype=torch.int32, device="cuda") if lengths is not None else None
+    dqkv_in = to_dev(qkv, dtype)
+    o, lse = empty_dev((B, T, D), dtype), empty_dev((B, H, T), "f32")
+    b.check(b.lib().fl_test_attention_fwd(dt_code(dtype), dqkv_in.data_ptr(), dl.data_ptr() if dl is not None else None,
+                                          B, T, H, dh, o.data_ptr(), lse.data_ptr(), stream_ptr()))
+    torch.cuda.synchronize()
+    assert rel_err(to_np(o), O) <= _tol(dtype)
+    assert rel_err(to_np(lse), lse_ref) <= 1e-5
+    # backward consumes the GPU's own o and lse, as in the layer
+    dqkv, delta = empty_dev((B, T, 3 * D), dtype), empty_dev((B, H, T), "f32")
+    tdo = to_dev(dO, dtype)
+    b.check(b.lib().fl_test_attention_bwd(dt_code(dtype), dqkv_in.data_ptr(), o.data_ptr(), tdo.data_ptr(),
+                                          lse.data_ptr(), dl.data_ptr() if dl is not None else None, B, T, H, dh,
+                                          dqkv.data_ptr(), delta.data_ptr(), stream_ptr()))
+    torch.cuda.synchronize()
+    got = to_np(dqkv)
+    for i, name in enumerate("qkv"):
+        assert rel_err(got[..., i * D:(i + 1) * D], dqkv_ref[..., i * D:(i + 1) * D]) <= _tol(dtype) * 2, name
+    if lengths is not None:      # masked keys: exactly zero gradient rows
+        for bi, n in enumerate(lengths):
+            assert np.all(got[bi, n:, D:] == 0.0)
