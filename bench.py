@@ -1,0 +1,163 @@
+#!/usr/bin/env python3
+"""Benchmark of the encoder-layer hot path on one MI355X.
+
+A step is one forward + one backward pass of the whole layer (every kernel of the
+path) over one batch of the seeded synthetic workload, inputs resident in HBM.
+Prints ONE JSON line: tokens/s (B*T per step), the roofline figures of the kernel
+class that takes the most time (measured with HIP events on the launch stream in a
+second pass of the same steps), and the fp64 CPU oracle timed on the host cores.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense MFMA peaks
+PEAK_HBM_GBS = 8000.0
+MFMA_CLASSES = ("gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd")
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg3_bert_base_bf16")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="skip the second, event-instrumented pass (used under rocprofv3)")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2201_12465_amd import binding as b
+    from workloads import CONFIGS, layer_flops, make_inputs, make_stack_inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    b.lib()   # fails loudly if the HIP library has not been built
+    cfg = CONFIGS[a.workload]
+    tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    dev = lambda x: torch.from_numpy(np.ascontiguousarray(x, np.float32)).cuda().to(tdt).contiguous()
+    if cfg.layers > 1:
+        inp = make_stack_inputs(cfg, seed=0)
+        plist = inp["params"]
+    else:
+        inp = make_inputs(cfg, seed=0)
+        plist = [inp["params"]]
+    nl = len(plist)
+    P = [{k: dev(v) for k, v in p.items()} for p in plist]
+    G = [{k: torch.empty_like(v) for k, v in p.items()} for p in P]
+    acts = [dev(inp["X"])] + [torch.empty(inp["X"].shape, dtype=tdt, device="cuda") for _ in range(nl)]
+    grads = [torch.empty(inp["X"].shape, dtype=tdt, device="cuda") for _ in range(nl)] + [dev(inp["dY"])]
+    L = torch.from_numpy(inp["lengths"]).cuda() if inp["lengths"] is not None else None
+    layers = [b.Layer(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F, cfg.act, cfg.norm, cfg.dtype, cfg.eps) for _ in range(nl)]
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step():
+        for l in range(nl):
+            layers[l].forward(P[l], acts[l], L, cfg.B, cfg.T, acts[l + 1], stream)
+        for l in reversed(range(nl)):
+            layers[l].backward(P[l], grads[l + 1], grads[l], G[l], stream)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    warm_stats = b.alloc_stats()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step()
+    torch.cuda.synchronize()
+    secs = time.perf_counter() - t0
+    end_stats = b.alloc_stats()
+    ms_per_step = secs / a.steps * 1e3
+    tokens = cfg.B * cfg.T
+    fl = layer_flops(cfg, inp["lengths"])
+    flops_step = fl["fwd_bwd"] * nl
+
+    out = {
+        "metric": "layer fwd+bwd tokens/s", "value": tokens * a.steps / secs, "unit": "tokens/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "B": cfg.B, "T": cfg.T, "d_model": cfg.D, "heads": cfg.H, "d_ffn": cfg.F,
+                   "act": cfg.act, "norm": cfg.norm, "layers": nl,
+                   "mask": "key-padding lengths" if L is not None else "none"},
+        "tflops_algorithmic": flops_step / (secs / a.steps) / 1e12,
+        "valid_tokens_per_s": (float(np.sum(inp["lengths"])) if L is not None else tokens) * a.steps / secs,
+        "device_mallocs_in_timed_region": end_stats["backing_mallocs"] - warm_stats["backing_mallocs"],
+    }
+
+    # ---- per-kernel-class timing: same steps again, every launch bracketed by HIP events on `stream`
+    if not a.no_kernel_timing:
+        ksteps = min(a.steps, 20)
+        b.prof_enable("all")
+        for _ in range(ksteps):
+            step()
+        torch.cuda.synchronize()
+        prof = b.prof_collect()
+        b.prof_enable(None)
+        mask_scale = (fl["fwd_attn"] / (4.0 * cfg.D * cfg.T * tokens)) if L is not None else 1.0
+        kernels = {}
+        for name, e in prof.items():
+            flops = e["flops"] * (mask_scale if name.startswith("attn") else 1.0)   # library counts dense attention
+            us = e["total_ms"] * 1e3 / e["launches"]
+            kernels[name] = {"launches_per_step": e["launches"] / ksteps, "avg_us": us,
+                             "ms_per_step": e["total_ms"] / ksteps,
+                             "tflops": flops / e["total_ms"] / 1e9 if flops else None,
+                             "gbs": e["bytes"] / e["total_ms"] / 1e6}
+        dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+        k = kernels[dom]
+        if dom in MFMA_CLASSES:
+            peak = PEAK_TFLOPS[cfg.dtype]
+            roof = {"kernel": dom, "bound": "mfma", "achieved": k["tflops"], "peak": peak, "unit": "TFLOP/s",
+                    "frac": k["tflops"] / peak, "traffic": None, "avg_us": k["avg_us"]}
+        else:
+            roof = {"kernel": dom, "bound": "hbm", "achieved": k["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": k["gbs"] / PEAK_HBM_GBS, "traffic": None, "avg_us": k["avg_us"]}
+        out["roofline"] = roof
+        out["kernels"] = kernels
+
+    # ---- the fp64 CPU oracle on the host cores (a reported baseline, not a target)
+    if not a.no_cpu_baseline:
+        from oracle import oracle as orc
+        threads = len(os.sched_getaffinity(0))
+        try:
+            from threadpoolctl import threadpool_info
+            blas = [i["num_threads"] for i in threadpool_info() if i.get("user_api") == "blas"]
+            if blas:
+                threads = max(blas)
+        except Exception:
+            pass
+        kw = dict(heads=cfg.H, act=cfg.act, norm=cfg.norm, eps=cfg.eps)
+        # bounded sample: the first sequences of the batch, sized for roughly 10-30 s of CPU work
+        nb = cfg.B if nl == 1 and cfg.M <= 4096 else max(1, min(cfg.B, 4096 // cfg.T))
+        sl = slice(0, nb)
+        lens = inp["lengths"][sl] if L is not None else None
+        t0 = time.perf_counter()
+        reps = 0
+        while reps < 1 or (time.perf_counter() - t0 < 8.0 and reps < 3):
+            orc.layer_forward_backward(plist[0], inp["X"][sl], inp["dY"][sl], lens, **kw)
+            reps += 1
+        cs = (time.perf_counter() - t0) / reps
+        out["cpu_baseline"] = {"value": nb * cfg.T / cs, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+                               "sample": f"{nb} of {cfg.B} sequences, one layer fwd+bwd, fp64 numpy, "
+                                         f"mean of {reps} run(s), {cs:.2f} s each"}
+    print(json.dumps(out))
+    for ly in layers:
+        ly.destroy()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

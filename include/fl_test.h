@@ -50,6 +50,9 @@ int32_t fl_test_attention_bwd(int32_t dtype, const void *qkv, const void *o, con
                               const int32_t *lengths, int32_t B, int32_t T, int32_t H, int32_t dh, void *dqkv,
                               float *delta, void *hip_stream);
 
+/* on != 0: bf16 attention uses the general (vector-ALU) kernels instead of the MFMA ones. */
+void fl_test_attention_force_general(int32_t on);
+
 /* The caching allocator (Section 4.1.2, Section 5.2.2) over a HOST-side backing store:
  * the two callbacks stand in for the device allocator; pointers are never dereferenced. */
 typedef int (*fl_test_backing_malloc_fn)(void **ptr, size_t bytes); /* 0 = ok */

@@ -90,6 +90,7 @@ def lib() -> C.CDLL:
             "fl_test_colsum": (i32, [i32, vp, i32, i32, vp, vp, vp]),
             "fl_test_attention_fwd": (i32, [i32, vp, vp, i32, i32, i32, i32, vp, vp, vp]),
             "fl_test_attention_bwd": (i32, [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]),
+            "fl_test_attention_force_general": (None, [i32]),
             "fl_test_alloc_create": (vp, [BACKING_MALLOC, BACKING_FREE]),
             "fl_test_alloc_destroy": (None, [vp]),
             "fl_test_alloc_alloc": (vp, [vp, u64, vp]),

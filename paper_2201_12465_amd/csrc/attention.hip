@@ -229,11 +229,17 @@ bool attn_shape_ok(int B, int T, int H, int dh) {
   return B >= 1 && T >= 1 && H >= 1 && dh >= 16 && dh % 16 == 0 && dh <= MAX_DH && H <= 65535 && B <= 65535;
 }
 
+bool g_force_general = false;
+
 }  // namespace
+
+void attention_force_general(bool on) { g_force_general = on; }
 
 hipError_t launch_attention_fwd(int dt, const void *qkv, const int32_t *lengths, int B, int T, int H, int dh, void *o,
                                 float *lse, hipStream_t stream) {
   if (!qkv || !o || !lse || !attn_shape_ok(B, T, H, dh)) return hipErrorInvalidValue;
+  if (dt == DT_BF16 && !g_force_general && attention_mfma_supported(dh))
+    return launch_attention_fwd_mfma(qkv, lengths, B, T, H, dh, o, lse, stream);
   const float scale = 1.0f / sqrtf((float)dh);
   dim3 grid((T + ROWS_PER_WG - 1) / ROWS_PER_WG, H, B), block(256);
   if (dt == DT_F32)
@@ -249,6 +255,8 @@ hipError_t launch_attention_bwd(int dt, const void *qkv, const void *o, const vo
                                 const int32_t *lengths, int B, int T, int H, int dh, void *dqkv, float *delta,
                                 hipStream_t stream) {
   if (!qkv || !o || !do_ || !lse || !dqkv || !delta || !attn_shape_ok(B, T, H, dh)) return hipErrorInvalidValue;
+  if (dt == DT_BF16 && !g_force_general && attention_mfma_supported(dh))
+    return launch_attention_bwd_mfma(qkv, o, do_, lse, lengths, B, T, H, dh, dqkv, delta, stream);
   const float scale = 1.0f / sqrtf((float)dh);
   dim3 grid((T + ROWS_PER_WG - 1) / ROWS_PER_WG, H, B), block(256);
   if (dt == DT_F32) {

@@ -1,0 +1,452 @@
+// Fused masked attention on the matrix cores (bf16 in, fp32 accumulate), forward
+// and backward, for head sizes that are multiples of 32.
+//
+// Same operator as attention.hip (the paper's matmul / exp / max / sum primitives,
+// Section 4.1.1, fused into one operator with a pre-fused gradient function,
+// Section 5.2.1), with the two contractions of each step on v_mfma_f32_32x32x16_bf16
+// and the softmax statistics in fp32 registers.  Scores and probabilities never
+// leave the wavefront.
+//
+// A wavefront owns 32 query rows (forward, dQ) or 32 key rows (dK/dV) and walks
+// the other sequence dimension in LDS tiles of 64 rows.  The MFMA that produces a
+// score block is oriented so that the index contracted NEXT ends up in a lane's
+// registers and the surviving index on the lanes:
+//   forward / dQ:  S^T[key, q] = K Q^T      -> lane = q, registers = 16 keys;
+//                  row max / sum = in-lane reduction + one exchange with lane^32;
+//                  O^T[d, q] += V^T[d, key] P^T[key, q] takes P straight from registers
+//   dK / dV:       S[q, key] = Q K^T        -> lane = key, registers = 16 queries;
+//                  dV^T[d, key] += dO^T[d, q] P[q, key],  dK^T[d, key] += Q^T[d, q] dS[q, key]
+// The "transposed" A operands (V^T, K^T, Q^T, dO^T) are read from row-major LDS
+// tiles with the transposing LDS load (ds_read_b64_tr_b16); tiles that are read in
+// both orientations are kept twice, each with the row padding that keeps its access
+// pattern free of bank conflicts.
+//
+// exp is evaluated as exp2 with log2(e) folded into the scale.  Masked keys
+// (j >= length) get probability exactly 0, so their dK / dV rows are exact zeros.
+#include "devutil.h"
+#include "kernels.h"
+
+namespace fl {
+namespace {
+
+constexpr int NT = 256;        // threads per workgroup (4 wavefronts)
+constexpr int ROWS_WG = 128;   // rows owned by a workgroup (32 per wavefront)
+constexpr int TILE = 64;       // rows of the walked dimension per LDS tile
+constexpr float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;
+
+// Row stride (elements) of a tile read with 16-byte row-fragment loads: 16 bytes of padding.
+constexpr int kc_stride(int dh) { return dh + 8; }
+// Row stride of a tile read with transposing loads: bytes = 64 (mod 128).
+constexpr int tr_stride(int dh) { return (((dh * 2 - 64 + 127) / 128) * 128 + 64) / 2; }
+
+typedef __attribute__((address_space(3))) s16x4_t *lds_s16x4_ptr;
+
+// A-operand fragment of the transposed tile: rows r0..r0+31 are COLUMNS of the LDS tile,
+// the 8 k-values of lane half h are tile rows klo + h*4 + {0..3} and klo + 8 + h*4 + {0..3}.
+__device__ __forceinline__ bf16x8_t tr_frag(const bf16_t *lds, int stride, int r0, int klo, int lane) {
+  const int g = lane >> 4, s = lane & 15;
+  const int col = r0 + (g & 1) * 16 + 4 * (s & 3);
+  const int k0 = klo + (g >> 1) * 4 + (s >> 2);
+  s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds + k0 * stride + col));
+  s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds + (k0 + 8) * stride + col));
+  typedef short s16x8_t __attribute__((ext_vector_type(8)));
+  s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8_t, v);
+}
+
+// Row fragment: tile row r0 + lane%32, elements kk*16 + (lane/32)*8 .. +7.
+__device__ __forceinline__ bf16x8_t kc_frag(const bf16_t *lds, int stride, int r0, int kk, int lane) {
+  return *reinterpret_cast<const bf16x8_t *>(lds + (r0 + (lane & 31)) * stride + kk * 16 + (lane >> 5) * 8);
+}
+
+__device__ __forceinline__ bf16x8_t zero_frag() {
+  bf16x8_t z;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) z[i] = static_cast<bf16_t>(0.f);
+  return z;
+}
+
+// Same layout straight from global memory (row pointer of this lane's row, or nullptr -> zeros).
+__device__ __forceinline__ bf16x8_t g_frag(const bf16_t *row, int kk, int lane) {
+  if (!row) return zero_frag();
+  return *reinterpret_cast<const bf16x8_t *>(row + kk * 16 + (lane >> 5) * 8);
+}
+
+// registers 8s..8s+7 of a score block, rounded to bf16: the B operand of the next MFMA
+__device__ __forceinline__ bf16x8_t pack8(const f32x16_t &v, int s) {
+  bf16x8_t o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = static_cast<bf16_t>(v[8 * s + e]);
+  return o;
+}
+
+// Copies up to TILE rows of DH elements (row stride ld) into one or two LDS tiles; rows >= nvalid are zero.
+template <int DH>
+__device__ __forceinline__ void stage_rows(const bf16_t *src, size_t ld, int nvalid, bf16_t *dst0, int stride0,
+                                           bf16_t *dst1, int stride1) {
+  constexpr int CPR = DH / 8;
+  for (int c = threadIdx.x; c < TILE * CPR; c += NT) {
+    const int r = c / CPR, ch = c % CPR;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (r < nvalid) v = *reinterpret_cast<const uint4 *>(src + (size_t)r * ld + ch * 8);
+    *reinterpret_cast<uint4 *>(dst0 + r * stride0 + ch * 8) = v;
+    if (dst1) *reinterpret_cast<uint4 *>(dst1 + r * stride1 + ch * 8) = v;
+  }
+}
+
+// index (within a 32-block) of accumulator register r for lane half h
+__device__ __forceinline__ int acc_row(int r, int h) { return (r >> 2) * 8 + h * 4 + (r & 3); }
+
+// ------------------------------------------------------------------------------------------ forward
+template <int DH>
+__global__ __launch_bounds__(NT) void attn_fwd_mfma(const bf16_t *__restrict__ qkv, const int32_t *__restrict__ lengths,
+                                                    int Tn, int H, float scale, bf16_t *__restrict__ o,
+                                                    float *__restrict__ lse) {
+  constexpr int KS = kc_stride(DH), VS = tr_stride(DH), NK = DH / 16, NB = DH / 32;
+  __shared__ __attribute__((aligned(16))) bf16_t sK[TILE * KS];
+  __shared__ __attribute__((aligned(16))) bf16_t sV[TILE * VS];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5;
+  const int b = blockIdx.z, hd = blockIdx.y;
+  const int D = H * DH;
+  const size_t ld = (size_t)3 * D;
+  const int len = lengths ? lengths[b] : Tn;
+  const bf16_t *base = qkv + (size_t)b * Tn * ld + hd * DH;
+  const int q = blockIdx.x * ROWS_WG + wave * 32 + (lane & 31);
+  const bf16_t *qrow = q < Tn ? base + (size_t)q * ld : nullptr;
+  bf16x8_t qf[NK];
+#pragma unroll
+  for (int kk = 0; kk < NK; ++kk) qf[kk] = g_frag(qrow, kk, lane);
+  const float c = scale * LOG2E;
+  float m = -INFINITY, l = 0.f;
+  f32x16_t oacc[NB];
+#pragma unroll
+  for (int i = 0; i < NB; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
+
+  for (int k0 = 0; k0 < len; k0 += TILE) {
+    __syncthreads();
+    const int nvalid = min(TILE, Tn - k0);
+    stage_rows<DH>(base + (size_t)k0 * ld + D, ld, nvalid, sK, KS, nullptr, 0);
+    stage_rows<DH>(base + (size_t)k0 * ld + 2 * D, ld, nvalid, sV, VS, nullptr, 0);
+    __syncthreads();
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      if (k0 + kb * 32 >= len) break;
+      f32x16_t s;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < NK; ++kk)
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc_frag(sK, KS, kb * 32, kk, lane), qf[kk], s, 0, 0, 0);
+      float mloc = -INFINITY;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = k0 + kb * 32 + acc_row(r, h2);
+        s[r] = key < len ? s[r] * c : -INFINITY;
+        mloc = fmaxf(mloc, s[r]);
+      }
+      mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+      const float mnew = fmaxf(m, mloc);
+      float rs = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        s[r] = exp2f(s[r] - mnew);
+        rs += s[r];
+      }
+      rs += __shfl_xor(rs, 32, 64);
+      const float corr = exp2f(m - mnew);
+      l = l * corr + rs;
+      m = mnew;
+      bf16x8_t pf[2] = {pack8(s, 0), pack8(s, 1)};
+#pragma unroll
+      for (int db = 0; db < NB; ++db) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[db][r] *= corr;
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(sV, VS, db * 32, kb * 32 + 16 * st, lane),
+                                                             pf[st], oacc[db], 0, 0, 0);
+      }
+    }
+  }
+  if (q < Tn) {
+    const float inv = 1.0f / l;
+    bf16_t *orow = o + ((size_t)b * Tn + q) * D + hd * DH;
+#pragma unroll
+    for (int db = 0; db < NB; ++db)
+#pragma unroll
+      for (int qd = 0; qd < 4; ++qd) {
+        float v[4] = {oacc[db][qd * 4] * inv, oacc[db][qd * 4 + 1] * inv, oacc[db][qd * 4 + 2] * inv,
+                      oacc[db][qd * 4 + 3] * inv};
+        VecIO<bf16_t, 4>::store(orow + db * 32 + qd * 8 + h2 * 4, v);
+      }
+    if (h2 == 0) lse[((size_t)b * H + hd) * Tn + q] = (m + log2f(l)) * LN2;
+  }
+}
+
+// ------------------------------------------------------------------------------------------ dQ (+ delta)
+template <int DH>
+__global__ __launch_bounds__(NT) void attn_bwd_dq_mfma(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ o,
+                                                       const bf16_t *__restrict__ dout,
+                                                       const float *__restrict__ lse,
+                                                       const int32_t *__restrict__ lengths, int Tn, int H,
+                                                       float scale, bf16_t *__restrict__ dqkv,
+                                                       float *__restrict__ delta) {
+  constexpr int KS = kc_stride(DH), TS = tr_stride(DH), NK = DH / 16, NB = DH / 32;
+  __shared__ __attribute__((aligned(16))) bf16_t sK[TILE * KS];   // K rows for S^T = K Q^T
+  __shared__ __attribute__((aligned(16))) bf16_t sKt[TILE * TS];  // K again, for K^T in dQ^T = K^T dS^T
+  __shared__ __attribute__((aligned(16))) bf16_t sV[TILE * KS];   // V rows for dP^T = V dO^T
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5;
+  const int b = blockIdx.z, hd = blockIdx.y;
+  const int D = H * DH;
+  const size_t ld = (size_t)3 * D;
+  const int len = lengths ? lengths[b] : Tn;
+  const bf16_t *base = qkv + (size_t)b * Tn * ld + hd * DH;
+  const int q = blockIdx.x * ROWS_WG + wave * 32 + (lane & 31);
+  const bool qok = q < Tn;
+  const bf16_t *qrow = qok ? base + (size_t)q * ld : nullptr;
+  const bf16_t *dorow = qok ? dout + ((size_t)b * Tn + q) * D + hd * DH : nullptr;
+  const bf16_t *orow = qok ? o + ((size_t)b * Tn + q) * D + hd * DH : nullptr;
+  bf16x8_t qf[NK], dof[NK];
+  float dl = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < NK; ++kk) {
+    qf[kk] = g_frag(qrow, kk, lane);
+    dof[kk] = g_frag(dorow, kk, lane);
+    bf16x8_t of = g_frag(orow, kk, lane);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dl += static_cast<float>(dof[kk][e]) * static_cast<float>(of[e]);
+  }
+  dl += __shfl_xor(dl, 32, 64);
+  const size_t st_idx = ((size_t)b * H + hd) * Tn + (qok ? q : 0);
+  const float L2 = qok ? lse[st_idx] * LOG2E : 0.f;
+  if (qok && h2 == 0) delta[st_idx] = dl;
+  const float c = scale * LOG2E;
+  f32x16_t acc[NB];
+#pragma unroll
+  for (int i = 0; i < NB; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+
+  for (int k0 = 0; k0 < len; k0 += TILE) {
+    __syncthreads();
+    const int nvalid = min(TILE, Tn - k0);
+    stage_rows<DH>(base + (size_t)k0 * ld + D, ld, nvalid, sK, KS, sKt, TS);
+    stage_rows<DH>(base + (size_t)k0 * ld + 2 * D, ld, nvalid, sV, KS, nullptr, 0);
+    __syncthreads();
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      if (k0 + kb * 32 >= len) break;
+      f32x16_t s, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] = 0.f, dp[r] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < NK; ++kk) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc_frag(sK, KS, kb * 32, kk, lane), qf[kk], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc_frag(sV, KS, kb * 32, kk, lane), dof[kk], dp, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = k0 + kb * 32 + acc_row(r, h2);
+        const float p = key < len ? exp2f(s[r] * c - L2) : 0.f;
+        s[r] = p * (dp[r] - dl);   // dS^T
+      }
+      bf16x8_t dsf[2] = {pack8(s, 0), pack8(s, 1)};
+#pragma unroll
+      for (int db = 0; db < NB; ++db)
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+          acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(sKt, TS, db * 32, kb * 32 + 16 * st, lane),
+                                                            dsf[st], acc[db], 0, 0, 0);
+    }
+  }
+  if (qok) {
+    bf16_t *drow = dqkv + ((size_t)b * Tn + q) * ld + hd * DH;
+#pragma unroll
+    for (int db = 0; db < NB; ++db)
+#pragma unroll
+      for (int qd = 0; qd < 4; ++qd) {
+        float v[4] = {acc[db][qd * 4] * scale, acc[db][qd * 4 + 1] * scale, acc[db][qd * 4 + 2] * scale,
+                      acc[db][qd * 4 + 3] * scale};
+        VecIO<bf16_t, 4>::store(drow + db * 32 + qd * 8 + h2 * 4, v);
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------ dK, dV
+template <int DH>
+__global__ __launch_bounds__(NT) void attn_bwd_dkv_mfma(const bf16_t *__restrict__ qkv,
+                                                        const bf16_t *__restrict__ dout,
+                                                        const float *__restrict__ lse,
+                                                        const float *__restrict__ delta,
+                                                        const int32_t *__restrict__ lengths, int Tn, int H,
+                                                        float scale, bf16_t *__restrict__ dqkv) {
+  constexpr int KS = kc_stride(DH), TS = tr_stride(DH), NK = DH / 16, NB = DH / 32;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t *sQ = reinterpret_cast<bf16_t *>(smem_raw);   // Q rows for S = Q K^T
+  bf16_t *sQt = sQ + TILE * KS;                        // Q again, for Q^T in dK^T = Q^T dS
+  bf16_t *sDO = sQt + TILE * TS;                       // dO rows for dP = dO V^T
+  bf16_t *sDOt = sDO + TILE * KS;                      // dO again, for dO^T in dV^T = dO^T P
+  float *sL = reinterpret_cast<float *>(sDOt + TILE * TS);  // lse*log2(e) of the tile's queries
+  float *sDl = sL + TILE;                                   // delta of the tile's queries
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5;
+  const int b = blockIdx.z, hd = blockIdx.y;
+  const int D = H * DH;
+  const size_t ld = (size_t)3 * D;
+  const int len = lengths ? lengths[b] : Tn;
+  const bf16_t *base = qkv + (size_t)b * Tn * ld + hd * DH;
+  const int key = blockIdx.x * ROWS_WG + wave * 32 + (lane & 31);
+  const bool kok = key < Tn;
+  const bf16_t *krow = kok ? base + (size_t)key * ld + D : nullptr;
+  const bf16_t *vrow = kok ? base + (size_t)key * ld + 2 * D : nullptr;
+  bf16x8_t kf[NK], vf[NK];
+#pragma unroll
+  for (int kk = 0; kk < NK; ++kk) {
+    kf[kk] = g_frag(krow, kk, lane);
+    vf[kk] = g_frag(vrow, kk, lane);
+  }
+  const float c = scale * LOG2E;
+  const bool live = key < len;   // a masked key has probability 0 against every query
+  f32x16_t dk[NB], dv[NB];
+#pragma unroll
+  for (int i = 0; i < NB; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dk[i][r] = 0.f, dv[i][r] = 0.f;
+  // a workgroup whose keys are all masked only writes zeros
+  const bool wg_live = blockIdx.x * ROWS_WG < len;
+  const size_t stat0 = ((size_t)b * H + hd) * Tn;
+  const bf16_t *dobase = dout + (size_t)b * Tn * D + hd * DH;
+
+  for (int q0 = 0; wg_live && q0 < Tn; q0 += TILE) {
+    __syncthreads();
+    const int nvalid = min(TILE, Tn - q0);
+    stage_rows<DH>(base + (size_t)q0 * ld, ld, nvalid, sQ, KS, sQt, TS);
+    stage_rows<DH>(dobase + (size_t)q0 * D, (size_t)D, nvalid, sDO, KS, sDOt, TS);
+    if (threadIdx.x < TILE) {
+      const bool ok = (int)threadIdx.x < nvalid;
+      sL[threadIdx.x] = ok ? lse[stat0 + q0 + threadIdx.x] * LOG2E : INFINITY;   // exp2(-inf) = 0 beyond T
+      sDl[threadIdx.x] = ok ? delta[stat0 + q0 + threadIdx.x] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      if (q0 + qb * 32 >= Tn) break;
+      f32x16_t s, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] = 0.f, dp[r] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < NK; ++kk) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc_frag(sQ, KS, qb * 32, kk, lane), kf[kk], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc_frag(sDO, KS, qb * 32, kk, lane), vf[kk], dp, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int qi = qb * 32 + acc_row(r, h2);
+        const float p = live ? exp2f(s[r] * c - sL[qi]) : 0.f;
+        dp[r] = p * (dp[r] - sDl[qi]);   // dS
+        s[r] = p;
+      }
+      bf16x8_t pf[2] = {pack8(s, 0), pack8(s, 1)}, dsf[2] = {pack8(dp, 0), pack8(dp, 1)};
+#pragma unroll
+      for (int db = 0; db < NB; ++db)
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+          dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(sDOt, TS, db * 32, qb * 32 + 16 * st, lane), pf[st],
+                                                           dv[db], 0, 0, 0);
+          dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(sQt, TS, db * 32, qb * 32 + 16 * st, lane), dsf[st],
+                                                           dk[db], 0, 0, 0);
+        }
+    }
+  }
+  if (kok) {
+    bf16_t *dkrow = dqkv + ((size_t)b * Tn + key) * ld + D + hd * DH;
+    bf16_t *dvrow = dkrow + D;
+#pragma unroll
+    for (int db = 0; db < NB; ++db)
+#pragma unroll
+      for (int qd = 0; qd < 4; ++qd) {
+        float a[4], v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          a[e] = dk[db][qd * 4 + e] * scale;
+          v[e] = dv[db][qd * 4 + e];
+        }
+        VecIO<bf16_t, 4>::store(dkrow + db * 32 + qd * 8 + h2 * 4, a);
+        VecIO<bf16_t, 4>::store(dvrow + db * 32 + qd * 8 + h2 * 4, v);
+      }
+  }
+}
+
+template <int DH> size_t dkv_lds_bytes() {
+  return (size_t)2 * TILE * (kc_stride(DH) + tr_stride(DH)) * sizeof(bf16_t) + 2 * TILE * sizeof(float);
+}
+
+template <int DH>
+hipError_t fwd_t(const void *qkv, const int32_t *lengths, int B, int T, int H, float scale, void *o, float *lse,
+                 hipStream_t s) {
+  dim3 grid((T + ROWS_WG - 1) / ROWS_WG, H, B);
+  hipLaunchKernelGGL(attn_fwd_mfma<DH>, grid, dim3(NT), 0, s, static_cast<const bf16_t *>(qkv), lengths, T, H, scale,
+                     static_cast<bf16_t *>(o), lse);
+  return hipGetLastError();
+}
+
+template <int DH>
+hipError_t bwd_t(const void *qkv, const void *o, const void *dout, const float *lse, const int32_t *lengths, int B,
+                 int T, int H, float scale, void *dqkv, float *delta, hipStream_t s) {
+  dim3 grid((T + ROWS_WG - 1) / ROWS_WG, H, B);
+  hipLaunchKernelGGL(attn_bwd_dq_mfma<DH>, grid, dim3(NT), 0, s, static_cast<const bf16_t *>(qkv),
+                     static_cast<const bf16_t *>(o), static_cast<const bf16_t *>(dout), lse, lengths, T, H, scale,
+                     static_cast<bf16_t *>(dqkv), delta);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const size_t lds = dkv_lds_bytes<DH>();
+  if (lds > 64 * 1024) {
+    static bool raised = false;   // allow more than the default 64 KiB of dynamic LDS, once
+    if (!raised) {
+      e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bwd_dkv_mfma<DH>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+      raised = true;
+    }
+  }
+  hipLaunchKernelGGL(attn_bwd_dkv_mfma<DH>, grid, dim3(NT), lds, s, static_cast<const bf16_t *>(qkv),
+                     static_cast<const bf16_t *>(dout), lse, delta, lengths, T, H, scale,
+                     static_cast<bf16_t *>(dqkv));
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool attention_mfma_supported(int dh) { return dh == 32 || dh == 64 || dh == 96 || dh == 128 || dh == 192 || dh == 256; }
+
+hipError_t launch_attention_fwd_mfma(const void *qkv, const int32_t *lengths, int B, int T, int H, int dh, void *o,
+                                     float *lse, hipStream_t s) {
+  const float scale = 1.0f / sqrtf((float)dh);
+  switch (dh) {
+    case 32: return fwd_t<32>(qkv, lengths, B, T, H, scale, o, lse, s);
+    case 64: return fwd_t<64>(qkv, lengths, B, T, H, scale, o, lse, s);
+    case 96: return fwd_t<96>(qkv, lengths, B, T, H, scale, o, lse, s);
+    case 128: return fwd_t<128>(qkv, lengths, B, T, H, scale, o, lse, s);
+    case 192: return fwd_t<192>(qkv, lengths, B, T, H, scale, o, lse, s);
+    case 256: return fwd_t<256>(qkv, lengths, B, T, H, scale, o, lse, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_attention_bwd_mfma(const void *qkv, const void *o, const void *dout, const float *lse,
+                                     const int32_t *lengths, int B, int T, int H, int dh, void *dqkv, float *delta,
+                                     hipStream_t s) {
+  const float scale = 1.0f / sqrtf((float)dh);
+  switch (dh) {
+    case 32: return bwd_t<32>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
+    case 64: return bwd_t<64>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
+    case 96: return bwd_t<96>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
+    case 128: return bwd_t<128>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
+    case 192: return bwd_t<192>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
+    case 256: return bwd_t<256>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace fl

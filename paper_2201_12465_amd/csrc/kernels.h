@@ -77,4 +77,15 @@ hipError_t launch_attention_bwd(int dt, const void *qkv, const void *o, const vo
                                 const int32_t *lengths, int B, int T, int H, int dh, void *dqkv, float *delta,
                                 hipStream_t stream);
 
+
+// bf16 attention on the matrix cores (attention_mfma.hip); the launchers above pick it when
+// dt is bf16 and the head size is one it is built for, unless the general kernels are forced.
+bool attention_mfma_supported(int dh);
+void attention_force_general(bool on);
+hipError_t launch_attention_fwd_mfma(const void *qkv, const int32_t *lengths, int B, int T, int H, int dh, void *o,
+                                     float *lse, hipStream_t s);
+hipError_t launch_attention_bwd_mfma(const void *qkv, const void *o, const void *dout, const float *lse,
+                                     const int32_t *lengths, int B, int T, int H, int dh, void *dqkv, float *delta,
+                                     hipStream_t s);
+
 }  // namespace fl

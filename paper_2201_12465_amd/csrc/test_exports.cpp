@@ -109,6 +109,8 @@ int32_t fl_test_attention_bwd(int32_t dtype, const void *qkv, const void *o, con
                     "launch_attention_bwd");
 }
 
+void fl_test_attention_force_general(int32_t on) { attention_force_general(on != 0); }
+
 // ---- allocator over a caller-supplied backing store -------------------------------------
 void *fl_test_alloc_create(fl_test_backing_malloc_fn m, fl_test_backing_free_fn f) {
   return new CachingAllocator(m, f);

@@ -168,6 +168,9 @@ def test_colsum(dtype, shape):
 
 ATTN_CASES = [  # B, T, H, dh, lengths
     (2, 16, 4, 16, None),
+    (2, 200, 2, 32, [200, 65]),
+    (1, 129, 1, 96, [100]),
+    (1, 64, 2, 128, None),
     (3, 37, 2, 64, [1, 20, 37]),
     (2, 128, 3, 64, [64, 128]),
     (2, 197, 2, 64, None),
@@ -176,10 +179,21 @@ ATTN_CASES = [  # B, T, H, dh, lengths
 ]
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "bf16-general"])
 @pytest.mark.parametrize("case", ATTN_CASES)
 def test_attention_forward_backward(dtype, case):
+    """bf16 runs the MFMA kernels where the head size allows; "bf16-general" forces the general ones."""
     b = _lib()
+    general = dtype == "bf16-general"
+    dtype = dtype.split("-")[0]
+    b.lib().fl_test_attention_force_general(1 if general else 0)
+    try:
+        _attention_case(b, dtype, case)
+    finally:
+        b.lib().fl_test_attention_force_general(0)
+
+
+def _attention_case(b, dtype, case):
     B, T, H, dh, lengths = case
     D = H * dh
     rng = np.random.default_rng(B * 1000 + T)

@@ -1,0 +1,228 @@
+"""CPU tests of the host-side logic behind the C ABI: the library loads without a
+GPU and exports every declared symbol; argument validation; the caching allocator
+over a fake backing store; the tape's reverse replay."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2201_12465_amd import binding as b
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = b.lib()
+    names = set()
+    for hdr in ("fl_layer.h", "fl_test.h"):
+        text = open(os.path.join(ROOT, "include", hdr)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(fl_[a-z0-9_]+)\s*\(", text))
+    names -= {n for n in names if n.endswith("_fn")}
+    assert len(names) >= 25
+    for n in sorted(names):
+        assert hasattr(lib, n), f"{n} is declared in include/ but not exported"
+
+
+def test_create_validates_arguments():
+    def status(*a, **kw):
+        try:
+            b.Layer(*a, **kw).destroy()
+            return b.FL_OK
+        except b.FlError as e:
+            assert str(e)
+            return e.status
+    assert status(2, 16, 64, 4, 256) == b.FL_OK
+    assert status(0, 16, 64, 4, 256) == b.FL_ERR_INVALID_ARG
+    assert status(2, 16, 64, 3, 256) == b.FL_ERR_INVALID_ARG       # D % heads
+    assert status(2, 16, 60, 4, 256) == b.FL_ERR_UNSUPPORTED       # D % 8
+    assert status(2, 16, 64, 8, 256) == b.FL_ERR_UNSUPPORTED       # head size 8
+    assert status(2, 16, 64, 4, 250) == b.FL_ERR_UNSUPPORTED       # F % 8
+    assert status(2, 16, 8192, 32, 256) == b.FL_ERR_UNSUPPORTED    # D too large
+    lib = b.lib()
+    assert lib.fl_layer_create(None, None) == b.FL_ERR_INVALID_ARG
+    assert b"null" in lib.fl_last_error()
+    assert lib.fl_layer_destroy(None) == b.FL_OK
+    assert lib.fl_layer_forward(None, None, None, None, 1, 1, None, None) == b.FL_ERR_INVALID_ARG
+    assert lib.fl_layer_backward(None, None, None, None, None, None) == b.FL_ERR_INVALID_ARG
+    assert lib.fl_alloc_get_stats(None) == b.FL_ERR_INVALID_ARG
+
+
+def test_forward_rejects_bad_arguments_before_touching_the_device():
+    layer = b.Layer(2, 16, 64, 4, 256)
+    fake = {n: 0x1000 for n in b.PARAM_FIELDS}
+    with pytest.raises(b.FlError) as e:
+        layer.forward(fake, 0x1000, None, 3, 16, 0x2000)            # B > max_B
+    assert e.value.status == b.FL_ERR_INVALID_ARG
+    with pytest.raises(b.FlError) as e:
+        layer.forward(fake, 0x1004, None, 2, 16, 0x2000)            # misaligned X
+    assert e.value.status == b.FL_ERR_UNSUPPORTED
+    with pytest.raises(b.FlError) as e:
+        layer.backward(fake, 0x1000, 0x2000, fake)                  # nothing recorded
+    assert e.value.status == b.FL_ERR_STATE
+    layer.destroy()
+
+
+class FakeStore:
+    """Stands in for the device allocator: hands out distinct fake addresses, can run dry."""
+
+    def __init__(self, capacity=1 << 40):
+        self.next, self.live, self.mallocs, self.frees, self.capacity = 1 << 32, {}, 0, 0, capacity
+
+        def m(pp, n):
+            if sum(self.live.values()) + n > self.capacity:
+                return 1
+            self.mallocs += 1
+            pp[0] = self.next
+            self.live[self.next] = n
+            self.next += (n + 4095) // 4096 * 4096 + 4096
+            return 0
+
+        def f(p):
+            self.frees += 1
+            del self.live[p]
+            return 0
+        self.m, self.f = b.BACKING_MALLOC(m), b.BACKING_FREE(f)
+
+
+@pytest.fixture
+def alloc():
+    lib = b.lib()
+    store = FakeStore()
+    a = lib.fl_test_alloc_create(store.m, store.f)
+
+    def stats():
+        s = b.fl_alloc_stats_t()
+        lib.fl_test_alloc_stats(a, C.byref(s))
+        return s.as_dict()
+    yield lib, a, store, stats
+    lib.fl_test_alloc_destroy(a)
+
+
+MB = 1 << 20
+
+
+def test_allocator_reuses_cached_blocks(alloc):
+    lib, a, store, stats = alloc
+    p1 = lib.fl_test_alloc_alloc(a, 5 * MB, None)
+    p2 = lib.fl_test_alloc_alloc(a, 5 * MB, None)
+    assert p1 and p2 and p1 != p2 and store.mallocs == 2
+    assert stats()["live_bytes"] == 2 * 5 * MB
+    assert lib.fl_test_alloc_release(a, p1) == 0
+    assert lib.fl_test_alloc_release(a, p1) == 1               # double release is reported
+    assert lib.fl_test_alloc_release(a, 12345) == 1            # unknown pointer
+    p3 = lib.fl_test_alloc_alloc(a, 5 * MB, None)
+    assert p3 == p1 and store.mallocs == 2                     # served from the cache
+    s = stats()
+    assert s["cache_hits"] == 1 and s["cache_misses"] == 2 and s["backing_mallocs"] == 2
+    assert s["peak_bytes"] == 2 * 5 * MB
+    for p in (p2, p3):
+        lib.fl_test_alloc_release(a, p)
+    # steady state: the same request sequence again needs no backing allocation
+    for _ in range(3):
+        ps = [lib.fl_test_alloc_alloc(a, n, None) for n in (5 * MB, 3 * MB, 5 * MB - 7)]
+        for p in ps:
+            lib.fl_test_alloc_release(a, p)
+    assert store.mallocs == 3 and stats()["live_bytes"] == 0
+
+
+def test_allocator_splits_and_merges(alloc):
+    lib, a, store, stats = alloc
+    big = lib.fl_test_alloc_alloc(a, 64 * MB, None)
+    lib.fl_test_alloc_release(a, big)
+    p1 = lib.fl_test_alloc_alloc(a, 10 * MB, None)              # split off the front of the cached 64 MiB
+    p2 = lib.fl_test_alloc_alloc(a, 20 * MB, None)
+    assert store.mallocs == 1 and p1 == big and p2 == big + 10 * MB
+    assert stats()["split_count"] >= 2 and stats()["cached_bytes"] == 34 * MB
+    lib.fl_test_alloc_release(a, p1)
+    lib.fl_test_alloc_release(a, p2)                            # neighbours merge back into one block
+    p3 = lib.fl_test_alloc_alloc(a, 64 * MB, None)
+    assert p3 == big and store.mallocs == 1
+    lib.fl_test_alloc_release(a, p3)
+    # small requests share a 2 MiB slab; sizes are rounded to 512 bytes
+    s1 = lib.fl_test_alloc_alloc(a, 100, None)
+    s2 = lib.fl_test_alloc_alloc(a, 100, None)
+    assert s2 - s1 == 512
+    lib.fl_test_alloc_release(a, s1)
+    lib.fl_test_alloc_release(a, s2)
+
+
+def test_allocator_split_limit(alloc):
+    lib, a, store, stats = alloc
+    big = lib.fl_test_alloc_alloc(a, 64 * MB, None)
+    lib.fl_test_alloc_release(a, big)
+    lib.fl_test_alloc_set_split_limit(a, 32 * MB)               # cached 64 MiB block may no longer be split
+    p = lib.fl_test_alloc_alloc(a, 10 * MB, None)
+    assert p != big and store.mallocs == 2                      # a fresh slab instead of carving the big block
+    q = lib.fl_test_alloc_alloc(a, 40 * MB, None)               # wastes < half: takes the big block whole
+    assert q == big and stats()["live_bytes"] == 10 * MB + 64 * MB
+    lib.fl_test_alloc_release(a, p)
+    lib.fl_test_alloc_release(a, q)
+    lib.fl_test_alloc_set_split_limit(a, 0)
+    r = lib.fl_test_alloc_alloc(a, 1 * MB + 512, None)
+    assert store.mallocs == 2                                   # splitting allowed again
+    lib.fl_test_alloc_release(a, r)
+
+
+def test_allocator_streams_do_not_share_cached_blocks(alloc):
+    lib, a, store, stats = alloc
+    p = lib.fl_test_alloc_alloc(a, 8 * MB, 0x10)
+    lib.fl_test_alloc_release(a, p)
+    q = lib.fl_test_alloc_alloc(a, 8 * MB, 0x20)                # other stream: kernels on 0x10 may still use p
+    assert q != p and store.mallocs == 2
+    r = lib.fl_test_alloc_alloc(a, 8 * MB, 0x10)
+    assert r == p and store.mallocs == 2
+    lib.fl_test_alloc_release(a, q)
+    lib.fl_test_alloc_release(a, r)
+
+
+def test_allocator_trim_and_out_of_memory():
+    lib = b.lib()
+    store = FakeStore(capacity=100 * MB)
+    a = lib.fl_test_alloc_create(store.m, store.f)
+    p = lib.fl_test_alloc_alloc(a, 60 * MB, None)
+    assert p
+    assert not lib.fl_test_alloc_alloc(a, 60 * MB, None)        # store exhausted -> NULL, allocator stays usable
+    lib.fl_test_alloc_release(a, p)
+    q = lib.fl_test_alloc_alloc(a, 70 * MB, None)               # cached 60 MiB slab is given back, then retried
+    assert q and store.frees == 1
+    lib.fl_test_alloc_release(a, q)
+    lib.fl_test_alloc_trim(a)
+    assert store.live == {} and store.frees == 2
+    s = b.fl_alloc_stats_t()
+    lib.fl_test_alloc_stats(a, C.byref(s))
+    assert s.backing_bytes == 0 and s.cached_bytes == 0 and s.live_bytes == 0
+    lib.fl_test_alloc_destroy(a)
+
+
+def _replay(in0, in1, n_inputs, fail_at=-1):
+    lib = b.lib()
+    n = len(in0)
+    arr = lambda v: (C.c_int32 * len(v))(*v)
+    order, ran = (C.c_int32 * n)(), C.c_int32(0)
+    nslots = n_inputs + n
+    fc = (C.c_int32 * nslots)()
+    rc = lib.fl_test_tape_replay(n, arr(in0), arr(in1), n_inputs, fail_at, order, C.byref(ran), fc, nslots)
+    return rc, list(order)[:ran.value], list(fc)
+
+
+def test_tape_replays_in_reverse_and_tracks_first_consumers():
+    # the post-LN layer's graph: slot 0 = X; nodes: qkv(0) attn(1) out-proj(2; residual X) ln1(3)
+    # ffn1(4) ffn2(5; residual = ln1's output) ln2(6); node i writes slot 1+i
+    in0 = [0, 1, 2, 3, 4, 5, 6]
+    in1 = [-1, -1, 0, -1, -1, 4, -1]
+    rc, order, fc = _replay(in0, in1, 1)
+    assert rc == 0 and order == [6, 5, 4, 3, 2, 1, 0]
+    assert fc[0] == 0          # X: first consumed by the QKV projection, which therefore finishes dX
+    assert fc[4] == 4          # ln1's output: first consumed by ffn1, not by ffn2's residual
+    assert fc[7] == -1         # the layer output has no consumer
+
+
+def test_tape_stops_at_a_failing_gradient_function():
+    rc, order, _ = _replay([0, 1, 2, 3], [-1, -1, -1, -1], 1, fail_at=1)
+    assert rc == 77 and order == [3, 2]
+    rc, order, _ = _replay([], [], 1)
+    assert rc == 0 and order == []
+    rc, _, _ = _replay([5], [-1], 1)       # reads a slot that does not exist
+    assert rc == -1
