@@ -72,15 +72,18 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T *__restrict__ x, co
   }
 }
 
-// Workgroup b walks rows b*rows_per_wg .. ; wave w takes every nw-th row of that range.
+// Workgroup b walks rows b*rows_per_wg .. ; wave w takes rows w, w+nw, ... of that range, two at a
+// time so that twice as many loads are in flight.  The three column partials live in registers and
+// are folded across the waves through LDS, one quantity at a time, by all threads.
 template <typename T, int NCH>
-__global__ __launch_bounds__(1024) void ln_bwd_kernel(const T *__restrict__ dy, const T *__restrict__ x,
-                                                      const float *__restrict__ mean, const float *__restrict__ rstd,
-                                                      const T *__restrict__ gamma, const T *__restrict__ add, int M,
-                                                      int D, int rows_per_wg, T *__restrict__ dx,
-                                                      float *__restrict__ ws) {
+__global__ __launch_bounds__(512) void ln_bwd_kernel(const T *__restrict__ dy, const T *__restrict__ x,
+                                                     const float *__restrict__ mean, const float *__restrict__ rstd,
+                                                     const T *__restrict__ gamma, const T *__restrict__ add, int M,
+                                                     int D, int rows_per_wg, T *__restrict__ dx,
+                                                     float *__restrict__ ws) {
   constexpr int VEC = Elem<T>::VEC;
-  extern __shared__ float red[];  // [(nw-1)][D]
+  constexpr int R = 2;
+  extern __shared__ float red[];  // [nw][D]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   const int nchunks = D / VEC;
   const float invD = 1.0f / D;
@@ -93,83 +96,96 @@ __global__ __launch_bounds__(1024) void ln_bwd_kernel(const T *__restrict__ dy, 
     if (c < nchunks) VecIO<T, VEC>::load(gamma + c * VEC, gam[i]);
   }
   const int m0 = blockIdx.x * rows_per_wg, m1 = min(M, m0 + rows_per_wg);
-  for (int m = m0 + wave; m < m1; m += nw) {
-    const float mu = mean[m], rs = rstd[m];
-    float g[NCH][VEC], xh[NCH][VEC];
-    float s1 = 0.f, s2 = 0.f;
+  for (int mb = m0 + wave; mb < m1; mb += R * nw) {
+    float d[R][NCH][VEC], xv[R][NCH][VEC], av[R][NCH][VEC], mu[R], rs[R];
+    bool ok[R];
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      const int c = lane + 64 * i;
-      if (c < nchunks) {
-        float d[VEC], xv[VEC];
-        VecIO<T, VEC>::load(dy + (size_t)m * D + c * VEC, d);
-        VecIO<T, VEC>::load(x + (size_t)m * D + c * VEC, xv);
+    for (int rr = 0; rr < R; ++rr) {
+      const int m = mb + rr * nw;
+      ok[rr] = m < m1;
+      mu[rr] = ok[rr] ? mean[m] : 0.f;
+      rs[rr] = ok[rr] ? rstd[m] : 0.f;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-          xh[i][e] = (xv[e] - mu) * rs;
-          g[i][e] = d[e] * gam[i][e];
-          s1 += g[i][e];
-          s2 += g[i][e] * xh[i][e];
-          pg[i][e] += d[e] * xh[i][e];
-          pb[i][e] += d[e];
+      for (int i = 0; i < NCH; ++i) {
+        const int c = lane + 64 * i;
+        if (ok[rr] && c < nchunks) {
+          VecIO<T, VEC>::load(dy + (size_t)m * D + c * VEC, d[rr][i]);
+          VecIO<T, VEC>::load(x + (size_t)m * D + c * VEC, xv[rr][i]);
+          if (add) VecIO<T, VEC>::load(add + (size_t)m * D + c * VEC, av[rr][i]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) d[rr][i][e] = 0.f, xv[rr][i][e] = mu[rr];
+        }
+        if (!add || !(ok[rr] && c < nchunks)) {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) av[rr][i][e] = 0.f;
         }
       }
     }
-    s1 = wave_sum(s1) * invD;
-    s2 = wave_sum(s2) * invD;
+    float s1[R], s2[R];
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      const int c = lane + 64 * i;
-      if (c < nchunks) {
+    for (int rr = 0; rr < R; ++rr) {
+      s1[rr] = 0.f, s2[rr] = 0.f;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          const float xh = (xv[rr][i][e] - mu[rr]) * rs[rr];
+          const float g = d[rr][i][e] * gam[i][e];
+          xv[rr][i][e] = xh;   // keep xhat
+          s1[rr] += g;
+          s2[rr] += g * xh;
+          pg[i][e] += d[rr][i][e] * xh;
+          pb[i][e] += d[rr][i][e];
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1)
+#pragma unroll
+      for (int rr = 0; rr < R; ++rr) {
+        s1[rr] += __shfl_xor(s1[rr], o, 64);
+        s2[rr] += __shfl_xor(s2[rr], o, 64);
+      }
+#pragma unroll
+    for (int rr = 0; rr < R; ++rr) {
+      const int m = mb + rr * nw;
+      const float a1 = s1[rr] * invD, a2 = s2[rr] * invD;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
+        const int c = lane + 64 * i;
         float o[VEC];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) o[e] = rs * (g[i][e] - s1 - xh[i][e] * s2);
-        if (add) {
-          float a[VEC];
-          VecIO<T, VEC>::load(add + (size_t)m * D + c * VEC, a);
-#pragma unroll
-          for (int e = 0; e < VEC; ++e) o[e] += a[e];
+        for (int e = 0; e < VEC; ++e) {
+          o[e] = rs[rr] * (d[rr][i][e] * gam[i][e] - a1 - xv[rr][i][e] * a2) + av[rr][i][e];
+          px[i][e] += o[e];
         }
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) px[i][e] += o[e];
-        VecIO<T, VEC>::store(dx + (size_t)m * D + c * VEC, o);
+        if (ok[rr] && c < nchunks) VecIO<T, VEC>::store(dx + (size_t)m * D + c * VEC, o);
       }
     }
   }
-  // fold the waves' partial rows, one quantity at a time, in a fixed order
+  // fold the waves' partial rows through LDS: wave w writes row w, then every thread sums columns
   float *out = ws + (size_t)blockIdx.x * 3 * D;
 #pragma unroll
   for (int qn = 0; qn < 3; ++qn) {
     float(*p)[VEC] = qn == 0 ? pg : (qn == 1 ? pb : px);
-    if (wave > 0) {
 #pragma unroll
-      for (int i = 0; i < NCH; ++i) {
-        const int c = lane + 64 * i;
-        if (c < nchunks)
+    for (int i = 0; i < NCH; ++i) {
+      const int c = lane + 64 * i;
+      if (c < nchunks)
 #pragma unroll
-          for (int e = 0; e < VEC; ++e) red[(size_t)(wave - 1) * D + c * VEC + e] = p[i][e];
-      }
+        for (int e = 0; e < VEC; ++e) red[(size_t)wave * D + c * VEC + e] = p[i][e];
     }
     __syncthreads();
-    if (wave == 0) {
-#pragma unroll
-      for (int i = 0; i < NCH; ++i) {
-        const int c = lane + 64 * i;
-        if (c < nchunks) {
-#pragma unroll
-          for (int e = 0; e < VEC; ++e) {
-            float a = p[i][e];
-            for (int w = 1; w < nw; ++w) a += red[(size_t)(w - 1) * D + c * VEC + e];
-            out[(size_t)qn * D + c * VEC + e] = a;
-          }
-        }
-      }
+    for (int col = threadIdx.x; col < D; col += blockDim.x) {
+      float a = 0.f;
+      for (int w = 0; w < nw; ++w) a += red[(size_t)w * D + col];
+      out[(size_t)qn * D + col] = a;
     }
     __syncthreads();
   }
 }
 
-int ln_waves(int D) { return D <= 1024 ? 16 : (D <= 2048 ? 8 : 4); }
+int ln_waves(int D) { return D <= 2048 ? 8 : 4; }
 
 template <typename T>
 hipError_t ln_fwd_t(const void *x, const void *g, const void *b, float eps, int M, int D, void *y, float *mean,
@@ -200,7 +216,7 @@ hipError_t ln_bwd_t(const void *dy, const void *x, const float *mean, const floa
   const int parts = ln_bwd_parts(M, D);
   const int rows_per_wg = (M + parts - 1) / parts;
   dim3 grid(parts), block(64 * nw);
-  const size_t lds = (size_t)(nw - 1) * D * sizeof(float);
+  const size_t lds = (size_t)nw * D * sizeof(float);
 #define FL_LN_BWD(N)                                                                                          \
   hipLaunchKernelGGL((ln_bwd_kernel<T, N>), grid, block, lds, s, static_cast<const T *>(dy),                  \
                      static_cast<const T *>(x), mean, rstd, static_cast<const T *>(g),                        \
@@ -219,7 +235,7 @@ hipError_t ln_bwd_t(const void *dy, const void *x, const float *mean, const floa
 
 int ln_bwd_parts(int M, int D) {
   const int nw = ln_waves(D);
-  int parts = (M + nw - 1) / nw;  // at least one row per wave
+  int parts = (M + 2 * nw - 1) / (2 * nw);  // at least two rows per wave
   if (parts > 256) parts = 256;
   const int rows = (M + parts - 1) / parts;
   return (M + rows - 1) / rows;  // no empty workgroup

@@ -26,7 +26,39 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
   if (out) VecIO<T, 4>::store(out + n, a);
 }
 
-constexpr int CS_ROWS = 128;  // rows per first-stage block
+// Same sums when there are many partial rows and few columns: a workgroup of 16 waves owns 64
+// float4 columns, wave w adds rows w, w+16, ..., and the 16 running sums meet in LDS.
+template <typename T>
+__global__ __launch_bounds__(1024) void reduce_partials_tall_kernel(const float *__restrict__ partial, int P,
+                                                                    size_t stride, size_t seglen, T *out0, T *out1,
+                                                                    T *out2) {
+  __shared__ float4 red[16][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const size_t n = ((size_t)blockIdx.x * 64 + lane) * 4;
+  const int s = blockIdx.y;
+  float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (n < seglen) {
+    const float *src = partial + (size_t)s * seglen + n;
+    for (int p = wave; p < P; p += 16) {
+      float4 t = *reinterpret_cast<const float4 *>(src + (size_t)p * stride);
+      a.x += t.x; a.y += t.y; a.z += t.z; a.w += t.w;
+    }
+  }
+  red[wave][lane] = a;
+  __syncthreads();
+  if (wave == 0 && n < seglen) {
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+      float4 t = red[w][lane];
+      v[0] += t.x; v[1] += t.y; v[2] += t.z; v[3] += t.w;
+    }
+    T *out = s == 0 ? out0 : (s == 1 ? out1 : out2);
+    if (out) VecIO<T, 4>::store(out + n, v);
+  }
+}
+
+constexpr int CS_ROWS = 32;   // rows per first-stage block
 
 // ws[rb][n] = sum over the rows of block rb of in[m][n]; 64 lanes x VEC columns, 4 waves interleave rows
 template <typename T>
@@ -65,6 +97,17 @@ hipError_t launch_reduce_partials(int dt, const float *partial, int P, size_t st
   if (!partial || P < 1 || nseg < 1 || nseg > 3 || seglen == 0 || seglen % 4 || stride % 4)
     return hipErrorInvalidValue;
   if ((size_t)nseg * seglen > stride && P > 1) return hipErrorInvalidValue;
+  if (P >= 32) {
+    dim3 tgrid((unsigned)((seglen / 4 + 63) / 64), nseg);
+    if (dt == DT_F32)
+      hipLaunchKernelGGL(reduce_partials_tall_kernel<float>, tgrid, dim3(1024), 0, stream, partial, P, stride, seglen,
+                         static_cast<float *>(out0), static_cast<float *>(out1), static_cast<float *>(out2));
+    else
+      hipLaunchKernelGGL(reduce_partials_tall_kernel<bf16_t>, tgrid, dim3(1024), 0, stream, partial, P, stride,
+                         seglen, static_cast<bf16_t *>(out0), static_cast<bf16_t *>(out1),
+                         static_cast<bf16_t *>(out2));
+    return hipGetLastError();
+  }
   dim3 grid((unsigned)((seglen / 4 + 255) / 256), nseg);
   if (dt == DT_F32)
     hipLaunchKernelGGL(reduce_partials_kernel<float>, grid, dim3(256), 0, stream, partial, P, stride, seglen,
