@@ -28,7 +28,13 @@ extern "C" {
 int32_t fl_test_gemm(int32_t dtype, int32_t a_kc, int32_t b_kc, const void *A, const void *B, void *C, int32_t M,
                      int32_t N, int32_t K, const void *bias, const void *residual, int32_t act, void *preact,
                      int32_t dact, const void *aux, int32_t splits, float *partial, void *hip_stream);
+/* Mean milliseconds (host pointer ms) of `iters` back-to-back launches of the plain GEMM. */
+int32_t fl_test_gemm_time(int32_t dtype, int32_t a_kc, int32_t b_kc, const void *A, const void *B, void *C, int32_t M,
+                          int32_t N, int32_t K, int32_t splits, float *partial, int32_t iters, float *ms,
+                          void *hip_stream);
 int32_t fl_test_gemm_splits(int32_t dtype, int32_t M, int32_t N, int32_t K);
+/* Tile/stage variant of the pipelined bf16 GEMM: -1 automatic, 0..3 forced, -2 use the plain kernel. */
+void fl_test_gemm_force_variant(int32_t v);
 
 /* LayerNorm (a normalisation primitive, Section 4.2) over the last dimension of x[M,D]. */
 int32_t fl_test_layernorm_fwd(int32_t dtype, const void *x, const void *gamma, const void *beta, float eps, int32_t M,

@@ -82,6 +82,8 @@ def lib() -> C.CDLL:
             "fl_prof_enable": (C.c_int, [C.c_uint32]),
             "fl_prof_collect": (C.c_int, [C.POINTER(fl_prof_entry_t), i32, C.POINTER(i32)]),
             "fl_test_gemm": (i32, [i32, i32, i32, vp, vp, vp, i32, i32, i32, vp, vp, i32, vp, i32, vp, i32, vp, vp]),
+            "fl_test_gemm_time": (i32, [i32, i32, i32, vp, vp, vp, i32, i32, i32, i32, vp, i32, C.POINTER(f32), vp]),
+            "fl_test_gemm_force_variant": (None, [i32]),
             "fl_test_gemm_splits": (i32, [i32, i32, i32, i32]),
             "fl_test_layernorm_fwd": (i32, [i32, vp, vp, vp, f32, i32, i32, vp, vp, vp, vp]),
             "fl_test_layernorm_bwd_ws_floats": (i32, [i32, i32]),

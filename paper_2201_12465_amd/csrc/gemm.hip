@@ -25,6 +25,7 @@
 // Workgroup ids are remapped so that each of the 8 XCDs (which receive ids
 // round-robin) works on a contiguous range of tiles and its L2 sees few panels.
 #include "devutil.h"
+#include "gemm_dev.h"
 #include "kernels.h"
 
 namespace fl {
@@ -37,17 +38,6 @@ constexpr int OPERAND_LDS_BYTES = 20480;
 template <typename T> struct Tile;
 template <> struct Tile<float> { static constexpr int KT = 32; static constexpr int LDK = 36; };
 template <> struct Tile<bf16_t> { static constexpr int KT = 64; static constexpr int LDK = 72; };
-
-struct GemmDev {
-  const void *A, *B;
-  void *C;
-  int M, N, K, lda, ldb, ldc;
-  const void *bias, *residual, *aux;
-  void *preact;
-  int act, dact;
-  float *partial;
-  int k_per_split, tiles_m, tiles_n;
-};
 
 __device__ __forceinline__ uint4 ld16(const void *p, bool ok) {
   return ok ? *reinterpret_cast<const uint4 *>(p) : make_uint4(0, 0, 0, 0);
@@ -198,7 +188,6 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(GemmDev p) {
 
   // Epilogue.  acc[i][j][q*4 + e] is C[m, n0 + e] with
   //   m = row0 + wm*64 + i*32 + lane%32,  n0 = col0 + wn*64 + j*32 + q*8 + (lane/32)*4.
-  T *C = static_cast<T *>(p.C);
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int m = row0 + wm * 64 + i * 32 + (lane & 31);
@@ -210,42 +199,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(GemmDev p) {
         const int n0 = col0 + wn * 64 + j * 32 + q * 8 + (lane >> 5) * 4;
         if (n0 >= p.N) continue;
         float v[4] = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
-        if (p.partial) {
-          float *dst = p.partial + ((size_t)blockIdx.z * p.M + m) * p.N + n0;
-          *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-          continue;
-        }
-        const size_t off = (size_t)m * p.ldc + n0;
-        float t[4];
-        if (p.bias) {
-          VecIO<T, 4>::load(static_cast<const T *>(p.bias) + n0, t);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] += t[e];
-        }
-        if (p.preact) VecIO<T, 4>::store(static_cast<T *>(p.preact) + off, v);
-        if (p.act == 1) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
-        } else if (p.act == 2) {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = gelu_f(v[e]);
-        }
-        if (p.residual) {
-          VecIO<T, 4>::load(static_cast<const T *>(p.residual) + off, t);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] += t[e];
-        }
-        if (p.dact) {
-          VecIO<T, 4>::load(static_cast<const T *>(p.aux) + off, t);
-          if (p.dact == 1) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = t[e] > 0.f ? v[e] : 0.f;
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_f(t[e]);
-          }
-        }
-        VecIO<T, 4>::store(C + off, v);
+        gemm_epilogue_quad<T>(p, m, n0, v);
       }
     }
   }
@@ -310,6 +264,10 @@ hipError_t launch_gemm(int dt, const GemmArgs &a, hipStream_t stream) {
   d.tiles_n = (a.N + BN - 1) / BN;
   // every k-range must be non-empty, or its partial slab would stay unwritten
   if ((long)(splits - 1) * kps >= a.K) return hipErrorInvalidValue;
+  if (dt == DT_BF16 && gemm_pipe_eligible(a, kps)) {
+    const int variant = gemm_pipe_pick_variant(a.a_kc, a.b_kc, a.M, a.N, a.K);
+    if (variant >= 0) return launch_gemm_bf16_pipe(a, &d, splits, variant, stream);
+  }
   dim3 grid(d.tiles_m * d.tiles_n, 1, splits);
   return dt == DT_F32 ? launch_t<float>(a, d, grid, stream) : launch_t<bf16_t>(a, d, grid, stream);
 }

@@ -1,0 +1,267 @@
+// Pipelined bf16 MFMA GEMM for gfx950 (same contraction and epilogue as gemm.hip;
+// this is the kernel the layer's large GEMMs run on).
+//
+//   C[M,N] = sum_k A(m,k) B(n,k),  k-range a multiple of 64.
+//
+// * Operand tiles travel HBM/L2 -> LDS with the direct-to-LDS load
+//   (global_load_lds_dwordx4): no VGPRs and no LDS-write instructions are spent on
+//   staging, so NS stages (k-tiles) can be in flight; one workgroup barrier per k-tile.
+//   A wave-level load writes 64 consecutive 16-byte chunks of LDS; WHICH global chunk a
+//   lane fetches is free, and that is where the bank-conflict swizzle is applied:
+//     k-contiguous tile  [rows][64 k]   : chunk c of row r sits at position c ^ ((r>>1)&7)
+//     k-major tile       [64 k][rows]   : chunk c of k-row k sits at position c ^ ((k&3)<<2)
+//   Both make the MFMA fragment reads (16-byte row reads, and the transposing
+//   ds_read_b64_tr_b16 for k-major tiles) touch every bank once per 32 lanes.
+// * Rows past the end of an operand are clamped to the last valid row (their products land in
+//   output rows/columns that are never stored), so no lane ever reads out of bounds.
+// * 256 threads = 4 wavefronts in a 2x2 grid over a BM x BN tile; each wavefront owns
+//   (BM/2) x (BN/2) = TM x TN MFMA tiles of 32x32 (v_mfma_f32_32x32x16_bf16), issued as
+//   D = B_frag x A_frag so that a lane ends with four consecutive n of one m.
+#include "devutil.h"
+#include "gemm_dev.h"
+#include "kernels.h"
+
+namespace fl {
+namespace {
+
+constexpr int NTHR = 256, KT = 64;
+
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+typedef const __attribute__((address_space(1))) void *glb_void_ptr;
+typedef __attribute__((address_space(3))) s16x4_t *lds_s16x4_ptr;
+
+// vmcnt(n) only (gfx9 encoding: vmcnt = imm[3:0] | imm[15:14]<<4; expcnt, lgkmcnt left at "no wait")
+#define FL_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
+
+template <int N> __device__ __forceinline__ void wait_vmcnt_le() { FL_WAIT_VMCNT(N); }
+
+// One operand's staging plan for this wave: element offsets (from the operand base) of the chunks
+// its lanes fetch, for each of its NOPS wave-level loads per k-tile.
+template <bool KC, int R> struct Stager {
+  static constexpr int NOPS = R / 32;  // R*128 bytes per stage / 1 KiB per load / 4 waves
+  int off[NOPS];
+  int kstep;  // element offset from one k-tile to the next
+  __device__ __forceinline__ void init(int ld, int row0, int nrows, int kbeg, int lane, int wave) {
+#pragma unroll
+    for (int j = 0; j < NOPS; ++j) {
+      const int P = (wave + 4 * j) * 64 + lane;  // chunk position inside the stage
+      if (KC) {
+        const int r = P >> 3, c = (P & 7) ^ ((r >> 1) & 7);
+        off[j] = min(row0 + r, nrows - 1) * ld + kbeg + c * 8;
+      } else {
+        constexpr int CPR = R / 8;
+        const int k = P / CPR, c = (P % CPR) ^ ((k & 3) << 2);
+        off[j] = (kbeg + k) * ld + min(row0 + c * 8, nrows - 8);
+      }
+    }
+    kstep = KC ? KT : KT * ld;
+  }
+  __device__ __forceinline__ void issue(const bf16_t *base, int kt, unsigned char *stage, int wave) const {
+#pragma unroll
+    for (int j = 0; j < NOPS; ++j) {
+      const bf16_t *src = base + (size_t)off[j] + (size_t)kt * kstep;
+      __builtin_amdgcn_global_load_lds((glb_void_ptr)src, (lds_void_ptr)(stage + (wave + 4 * j) * 1024), 16, 0, 0);
+    }
+  }
+};
+
+// Fragment (32 rows starting at tile row r0, k-step kk) out of a swizzled stage.
+template <bool KC, int R>
+__device__ __forceinline__ bf16x8_t frag(const unsigned char *stage, int r0, int kk, int lane) {
+  if (KC) {
+    const int r = r0 + (lane & 31);
+    const int c = (kk * 2 + (lane >> 5)) ^ ((r >> 1) & 7);
+    return *reinterpret_cast<const bf16x8_t *>(stage + r * 128 + c * 16);
+  } else {
+    const int g = lane >> 4, s = lane & 15;
+    const int kb = kk * 16 + (g >> 1) * 8 + (s >> 2);
+    const int rowpos = r0 + (g & 1) * 16 + 4 * (s & 3);
+    const int c = (rowpos >> 3) ^ ((kb & 3) << 2);
+    const unsigned char *a = stage + kb * (R * 2) + c * 16 + (rowpos & 7) * 2;
+    s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)a);
+    s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(a + 4 * R * 2));
+    typedef short s16x8_t __attribute__((ext_vector_type(8)));
+    s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8_t, v);
+  }
+}
+
+template <bool AKC, bool BKC, int BM, int BN, int NS>
+__global__ __launch_bounds__(NTHR) void gemm_bf16_pipe(GemmDev p) {
+  constexpr int TM = BM / 64, TN = BN / 64;
+  constexpr int A_BYTES = BM * 128, STAGE = (BM + BN) * 128;
+  constexpr int OPS = Stager<AKC, BM>::NOPS + Stager<BKC, BN>::NOPS;  // loads per wave per k-tile
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+
+  const int logical = xcd_tile_order(blockIdx.x, p.tiles_m * p.tiles_n);
+  const int row0 = (logical / p.tiles_n) * BM, col0 = (logical % p.tiles_n) * BN;
+  const int kbeg = blockIdx.z * p.k_per_split;
+  const int kend = min(p.K, kbeg + p.k_per_split);
+  const int nk = (kend - kbeg) / KT;
+  const bf16_t *A = static_cast<const bf16_t *>(p.A);
+  const bf16_t *B = static_cast<const bf16_t *>(p.B);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  Stager<AKC, BM> sa;
+  Stager<BKC, BN> sb;
+  sa.init(p.lda, row0, p.M, kbeg, lane, wave);
+  sb.init(p.ldb, col0, p.N, kbeg, lane, wave);
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // prologue: NS-1 k-tiles in flight
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s) {
+    if (s < nk) {
+      sa.issue(A, s, smem + s * STAGE, wave);
+      sb.issue(B, s, smem + s * STAGE + A_BYTES, wave);
+    }
+  }
+  for (int kt = 0; kt < nk; ++kt) {
+    // k-tile kt must have landed: allow the loads of the (up to NS-2) younger k-tiles to stay in flight
+    const int younger = min(NS - 2, nk - 1 - kt);
+    if (NS >= 4 && younger >= 2) wait_vmcnt_le<2 * OPS>();
+    else if (NS >= 3 && younger == 1) wait_vmcnt_le<OPS>();
+    else wait_vmcnt_le<0>();
+    // every wave's part of k-tile kt is in LDS; everyone is done reading k-tile kt-1.  A bare
+    // s_barrier: __syncthreads() would add a fence that waits for ALL loads, younger k-tiles included.
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (kt + NS - 1 < nk) {
+      unsigned char *st = smem + ((kt + NS - 1) % NS) * STAGE;
+      sa.issue(A, kt + NS - 1, st, wave);
+      sb.issue(B, kt + NS - 1, st + A_BYTES, wave);
+    }
+    const unsigned char *sA = smem + (kt % NS) * STAGE, *sB = sA + A_BYTES;
+    // fragments of k-step kk+1 are requested before the MFMAs of k-step kk are issued
+    bf16x8_t fa[2][TM], fb[2][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[0][i] = frag<AKC, BM>(sA, wm * (BM / 2) + i * 32, 0, lane);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[0][j] = frag<BKC, BN>(sB, wn * (BN / 2) + j * 32, 0, lane);
+#pragma unroll
+    for (int kk = 0; kk < KT / 16; ++kk) {
+      if (kk + 1 < KT / 16) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[(kk + 1) & 1][i] = frag<AKC, BM>(sA, wm * (BM / 2) + i * 32, kk + 1, lane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[(kk + 1) & 1][j] = frag<BKC, BN>(sB, wn * (BN / 2) + j * 32, kk + 1, lane);
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][j], fa[kk & 1][i], acc[i][j], 0, 0, 0);
+    }
+  }
+
+  // Epilogue through LDS: each wave parks its (BM/2) x (BN/2) fp32 block in its own LDS region
+  // (rows padded by 4 floats: conflict-free for the 16-byte writes below and the reads after),
+  // then walks it row-wise so that every global access is 16 bytes per lane and a row's
+  // BN/2 outputs form one contiguous segment.
+  constexpr int WR = TM * 32, WC = TN * 32, CS = WC + 4;
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();  // every wave is done reading the operand stages
+  asm volatile("" ::: "memory");
+  float *cw = reinterpret_cast<float *>(smem) + (size_t)wave * WR * CS;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        *reinterpret_cast<float4 *>(cw + (i * 32 + (lane & 31)) * CS + j * 32 + q * 8 + (lane >> 5) * 4) =
+            make_float4(acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
+  constexpr int LPR = WC / 8, RPP = 64 / LPR;  // lanes per row, rows per pass
+  const int rl = lane / LPR, c8 = lane % LPR;
+  const int n0 = col0 + wn * (BN / 2) + c8 * 8;
+#pragma unroll 4
+  for (int r = rl; r < WR; r += RPP) {
+    const int m = row0 + wm * (BM / 2) + r;
+    if (m >= p.M || n0 >= p.N) continue;
+    const float4 lo = *reinterpret_cast<const float4 *>(cw + r * CS + c8 * 8);
+    const float4 hi = *reinterpret_cast<const float4 *>(cw + r * CS + c8 * 8 + 4);
+    float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    gemm_epilogue_oct(p, m, n0, v);
+  }
+}
+
+template <bool AKC, bool BKC, int BM, int BN, int NS>
+hipError_t launch_cfg(GemmDev d, int splits, hipStream_t s) {
+  constexpr size_t stage_lds = (size_t)NS * (BM + BN) * 128;
+  constexpr size_t epi_lds = (size_t)4 * (BM / 2) * (BN / 2 + 4) * sizeof(float);
+  constexpr size_t lds = stage_lds > epi_lds ? stage_lds : epi_lds;
+  static_assert(lds <= 160 * 1024, "stages do not fit in LDS");
+  auto kern = gemm_bf16_pipe<AKC, BKC, BM, BN, NS>;
+  if (lds > 64 * 1024) {
+    static bool raised = false;
+    if (!raised) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+      raised = true;
+    }
+  }
+  d.tiles_m = (d.M + BM - 1) / BM;
+  d.tiles_n = (d.N + BN - 1) / BN;
+  dim3 grid(d.tiles_m * d.tiles_n, 1, splits);
+  hipLaunchKernelGGL(kern, grid, dim3(NTHR), lds, s, d);
+  return hipGetLastError();
+}
+
+template <bool AKC, bool BKC>
+hipError_t launch_layout(const GemmDev &d, int splits, int variant, hipStream_t s) {
+  switch (variant) {
+    case 0: return launch_cfg<AKC, BKC, 128, 128, 2>(d, splits, s);
+    case 1: return launch_cfg<AKC, BKC, 128, 128, 4>(d, splits, s);
+    case 2: return launch_cfg<AKC, BKC, 256, 128, 3>(d, splits, s);
+    case 3: return launch_cfg<AKC, BKC, 256, 128, 2>(d, splits, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+int g_variant = -1;  // -1: choose per problem; >= 0: forced (tuning / tests)
+
+}  // namespace
+
+void gemm_pipe_force_variant(int v) { g_variant = v; }
+
+bool gemm_pipe_eligible(const GemmArgs &a, int kps) {
+  // whole k-tiles only; operands must hold at least one full 8-element chunk per clamped row
+  return kps % KT == 0 && a.K % KT == 0 && a.M >= 8 && a.N >= 8 && (long)a.M * a.lda < (1l << 31) &&
+         (long)a.N * a.ldb < (1l << 31) && (long)a.K * (a.a_kc ? 1 : a.lda) < (1l << 31) &&
+         (long)a.K * (a.b_kc ? 1 : a.ldb) < (1l << 31);
+}
+
+void gemm_pipe_tile(int variant, int *bm, int *bn) {
+  static const int t[4][2] = {{128, 128}, {128, 128}, {256, 128}, {256, 128}};
+  *bm = t[variant][0];
+  *bn = t[variant][1];
+}
+
+int gemm_pipe_pick_variant(bool a_kc, bool b_kc, int M, int N, int K) {
+  if (g_variant != -1) return g_variant;
+  (void)M; (void)N; (void)K;
+  // Measured on the layer's shapes (M = 4096, N and K in {768, 2304, 3072}): with both operands
+  // k-contiguous the 128x128 / 2-stage variant (two workgroups per CU) is the fastest; with a
+  // k-major operand the register-staged kernel in gemm.hip is at least as fast.
+  return a_kc && b_kc ? 0 : -2;
+}
+
+hipError_t launch_gemm_bf16_pipe(const GemmArgs &a, const void *dev, int splits, int variant, hipStream_t s) {
+  const GemmDev &d = *static_cast<const GemmDev *>(dev);
+  if (a.a_kc && a.b_kc) return launch_layout<true, true>(d, splits, variant, s);
+  if (a.a_kc && !a.b_kc) return launch_layout<true, false>(d, splits, variant, s);
+  if (!a.a_kc && !a.b_kc) return launch_layout<false, false>(d, splits, variant, s);
+  return launch_layout<false, true>(d, splits, variant, s);
+}
+
+}  // namespace fl

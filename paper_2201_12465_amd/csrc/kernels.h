@@ -40,6 +40,12 @@ hipError_t launch_gemm(int dt, const GemmArgs &a, hipStream_t stream);
 // Number of k-ranges launch_gemm should use so that a small output still fills the chip.
 int gemm_pick_splits(int dt, int M, int N, int K);
 
+// The pipelined bf16 kernel (gemm_pipe.hip); launch_gemm uses it whenever the problem is eligible.
+bool gemm_pipe_eligible(const GemmArgs &a, int k_per_split);
+int gemm_pipe_pick_variant(bool a_kc, bool b_kc, int M, int N, int K);  // < 0: use the kernel in gemm.hip
+void gemm_pipe_force_variant(int v);  // -1 = automatic; >= 0 forces a tile/stage variant; -2 = never use it
+hipError_t launch_gemm_bf16_pipe(const GemmArgs &a, const void *gemm_dev, int splits, int variant, hipStream_t s);
+
 // out_s[n] = sum_p partial[p*stride + s*seglen + n]  for s < nseg (<= 3), n < seglen;
 // out_s has element type dt.  seglen % 4 == 0.
 hipError_t launch_reduce_partials(int dt, const float *partial, int P, size_t stride, size_t seglen,

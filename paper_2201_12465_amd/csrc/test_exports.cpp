@@ -60,6 +60,35 @@ int32_t fl_test_gemm(int32_t dtype, int32_t a_kc, int32_t b_kc, const void *A, c
   return hip_status(launch_gemm(dt, a, st), "launch_gemm");
 }
 
+// Times `iters` back-to-back launches of one GEMM (no epilogue) with HIP events on the stream;
+// *ms receives the mean milliseconds per launch.  Synchronises the stream.
+int32_t fl_test_gemm_time(int32_t dtype, int32_t a_kc, int32_t b_kc, const void *A, const void *B, void *C, int32_t M,
+                          int32_t N, int32_t K, int32_t splits, float *partial, int32_t iters, float *ms,
+                          void *hip_stream) {
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
+    return set_error(FL_ERR_DEVICE, "hipEventCreate failed");
+  int rc = 0;
+  for (int it = -2; it < iters && !rc; ++it) {
+    if (it == 0) (void)hipEventRecord(e0, st);
+    rc = fl_test_gemm(dtype, a_kc, b_kc, A, B, C, M, N, K, nullptr, nullptr, 0, nullptr, 0, nullptr, splits, partial,
+                      hip_stream);
+  }
+  (void)hipEventRecord(e1, st);
+  hipError_t e = hipEventSynchronize(e1);
+  float t = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&t, e0, e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (rc) return rc;
+  if (e != hipSuccess) return hip_status(e, "event timing");
+  *ms = t / (iters > 0 ? iters : 1);
+  return FL_OK;
+}
+
+void fl_test_gemm_force_variant(int32_t v) { gemm_pipe_force_variant(v); }
+
 int32_t fl_test_gemm_splits(int32_t dtype, int32_t M, int32_t N, int32_t K) {
   return gemm_pick_splits(dtype == FL_F32 ? DT_F32 : DT_BF16, M, N, K);
 }

@@ -55,6 +55,35 @@ def test_gemm_plain(dtype, mode, shape):
         assert rel_err(to_np(dC), ref) <= _tol(dtype), (mode, shape, splits)
 
 
+@pytest.mark.parametrize("variant", [-2, 0, 1, 2, 3])
+@pytest.mark.parametrize("mode", ["nt", "nn", "tn"])
+@pytest.mark.parametrize("shape", [(304, 264, 192), (520, 392, 128), (8, 8, 64), (1000, 776, 640)])
+def test_gemm_bf16_pipelined_variants(variant, mode, shape):
+    """Every tile/stage variant of the pipelined bf16 kernel (-2 = the plain kernel), ragged M and N."""
+    b = _lib()
+    M, N, K = shape
+    rng = np.random.default_rng(hash((mode, shape)) % 2**32)
+    A = quantise(rng.standard_normal((M, K)), "bf16")
+    Bm = quantise(rng.standard_normal((N, K)), "bf16")
+    ref = A.astype(np.float64) @ Bm.astype(np.float64).T
+    a_kc, b_kc = {"nt": (1, 1), "nn": (1, 0), "tn": (0, 0)}[mode]
+    dA = to_dev(A if a_kc else A.T.copy(), "bf16")
+    dB = to_dev(Bm if b_kc else Bm.T.copy(), "bf16")
+    b.lib().fl_test_gemm_force_variant(variant)
+    try:
+        for splits in (1, 2):
+            if splits == 2 and K < 128:
+                continue
+            dC = empty_dev((M, N), "bf16")
+            part = empty_dev((splits * M * N,), "f32")
+            b.check(b.lib().fl_test_gemm(1, a_kc, b_kc, dA.data_ptr(), dB.data_ptr(), dC.data_ptr(), M, N, K, None,
+                                         None, 0, None, 0, None, splits, part.data_ptr(), stream_ptr()))
+            torch_mod().cuda.synchronize()
+            assert rel_err(to_np(dC), ref) <= BF16_KERNEL_TOL, (variant, mode, shape, splits)
+    finally:
+        b.lib().fl_test_gemm_force_variant(-1)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("act", [0, 1, 2])
 def test_gemm_forward_epilogue(dtype, act):
