@@ -186,23 +186,11 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(GemmDev p) {
     __syncthreads();
   }
 
-  // Epilogue.  acc[i][j][q*4 + e] is C[m, n0 + e] with
-  //   m = row0 + wm*64 + i*32 + lane%32,  n0 = col0 + wn*64 + j*32 + q*8 + (lane/32)*4.
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int m = row0 + wm * 64 + i * 32 + (lane & 31);
-    if (m >= p.M) continue;
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n0 = col0 + wn * 64 + j * 32 + q * 8 + (lane >> 5) * 4;
-        if (n0 >= p.N) continue;
-        float v[4] = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
-        gemm_epilogue_quad<T>(p, m, n0, v);
-      }
-    }
-  }
+  // Epilogue through LDS (see gemm_staged_epilogue); the last __syncthreads() of the loop has
+  // made the operand tiles free, and 4 waves x 32 x 68 floats fit in them.
+  static_assert(4 * 32 * 68 * sizeof(float) <= 2 * OPERAND_LDS_BYTES, "epilogue staging does not fit");
+  float *cw = reinterpret_cast<float *>(smem) + (size_t)wave * 32 * 68;
+  gemm_staged_epilogue<T, 2, 2>(p, acc, cw, row0 + wm * 64, col0 + wn * 64, lane);
 }
 
 template <typename T>

@@ -57,22 +57,37 @@ __device__ __forceinline__ void gemm_epilogue_quad(const GemmDev &p, int m, int 
   VecIO<T, 4>::store(static_cast<T *>(p.C) + off, v);
 }
 
-// The same steps on eight consecutive outputs C[m, n0..n0+7] (bf16 storage): 16-byte accesses.
+// The same steps on eight consecutive outputs C[m, n0..n0+7]: 16-byte (bf16) / 32-byte (fp32) accesses.
+template <typename T> struct Oct;
+template <> struct Oct<bf16_t> {
+  static __device__ __forceinline__ void load(const bf16_t *p, float *v) { VecIO<bf16_t, 8>::load(p, v); }
+  static __device__ __forceinline__ void store(bf16_t *p, const float *v) { VecIO<bf16_t, 8>::store(p, v); }
+};
+template <> struct Oct<float> {
+  static __device__ __forceinline__ void load(const float *p, float *v) {
+    VecIO<float, 4>::load(p, v);
+    VecIO<float, 4>::load(p + 4, v + 4);
+  }
+  static __device__ __forceinline__ void store(float *p, const float *v) {
+    VecIO<float, 4>::store(p, v);
+    VecIO<float, 4>::store(p + 4, v + 4);
+  }
+};
+
+template <typename T>
 __device__ __forceinline__ void gemm_epilogue_oct(const GemmDev &p, int m, int n0, float (&v)[8]) {
   if (p.partial) {
-    float *dst = p.partial + ((size_t)blockIdx.z * p.M + m) * p.N + n0;
-    *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-    *reinterpret_cast<float4 *>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    Oct<float>::store(p.partial + ((size_t)blockIdx.z * p.M + m) * p.N + n0, v);
     return;
   }
   const size_t off = (size_t)m * p.ldc + n0;
   float t[8];
   if (p.bias) {
-    VecIO<bf16_t, 8>::load(static_cast<const bf16_t *>(p.bias) + n0, t);
+    Oct<T>::load(static_cast<const T *>(p.bias) + n0, t);
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] += t[e];
   }
-  if (p.preact) VecIO<bf16_t, 8>::store(static_cast<bf16_t *>(p.preact) + off, v);
+  if (p.preact) Oct<T>::store(static_cast<T *>(p.preact) + off, v);
   if (p.act == 1) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
@@ -81,12 +96,12 @@ __device__ __forceinline__ void gemm_epilogue_oct(const GemmDev &p, int m, int n
     for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
   }
   if (p.residual) {
-    VecIO<bf16_t, 8>::load(static_cast<const bf16_t *>(p.residual) + off, t);
+    Oct<T>::load(static_cast<const T *>(p.residual) + off, t);
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] += t[e];
   }
   if (p.dact) {
-    VecIO<bf16_t, 8>::load(static_cast<const bf16_t *>(p.aux) + off, t);
+    Oct<T>::load(static_cast<const T *>(p.aux) + off, t);
     if (p.dact == 1) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[e] = t[e] > 0.f ? v[e] : 0.f;
@@ -95,7 +110,43 @@ __device__ __forceinline__ void gemm_epilogue_oct(const GemmDev &p, int m, int n
       for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(t[e]);
     }
   }
-  VecIO<bf16_t, 8>::store(static_cast<bf16_t *>(p.C) + off, v);
+  Oct<T>::store(static_cast<T *>(p.C) + off, v);
+}
+
+// Epilogue of a wavefront's (TM*32) x (TN*32) accumulator block through LDS.  acc[i][j] is the
+// 32x32 MFMA tile (i, j) in the "D = B_frag x A_frag" orientation: register q*4+e of a lane holds
+// C[i*32 + lane%32, j*32 + q*8 + (lane/32)*4 + e].  Thirty-two rows at a time are parked in the
+// wave's own LDS region (rows padded by 4 floats: the 16-byte writes and the reads below touch
+// every bank once) and walked row-wise, so that every global access is 16 or 32 bytes per lane and
+// a row's TN*32 outputs form one contiguous segment.  `cw` must hold 32*(TN*32+4) floats per wave.
+// The caller has made sure (barrier) that nobody still reads the LDS this overwrites.
+template <typename T, int TM, int TN>
+__device__ __forceinline__ void gemm_staged_epilogue(const GemmDev &p, const f32x16_t (&acc)[TM][TN], float *cw,
+                                                     int mbase, int nbase, int lane) {
+  constexpr int WC = TN * 32, CS = WC + 4;
+  constexpr int LPR = WC / 8, RPP = 64 / LPR;  // lanes per row, rows per pass
+  const int rl = lane / LPR, c8 = lane % LPR;
+  const int n0 = nbase + c8 * 8;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        *reinterpret_cast<float4 *>(cw + (lane & 31) * CS + j * 32 + q * 8 + (lane >> 5) * 4) =
+            make_float4(acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
+    // the wave reads what its own lanes wrote: LDS operations of one wave complete in order
+#pragma unroll
+    for (int r = rl; r < 32; r += RPP) {
+      const int m = mbase + i * 32 + r;
+      const float4 lo = *reinterpret_cast<const float4 *>(cw + r * CS + c8 * 8);
+      const float4 hi = *reinterpret_cast<const float4 *>(cw + r * CS + c8 * 8 + 4);
+      if (m < p.M && n0 < p.N) {
+        float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        gemm_epilogue_oct<T>(p, m, n0, v);
+      }
+    }
+  }
 }
 
 // The 8 XCDs receive workgroup ids round-robin; give each a contiguous range of tiles.

@@ -163,41 +163,18 @@ __global__ __launch_bounds__(NTHR) void gemm_bf16_pipe(GemmDev p) {
     }
   }
 
-  // Epilogue through LDS: each wave parks its (BM/2) x (BN/2) fp32 block in its own LDS region
-  // (rows padded by 4 floats: conflict-free for the 16-byte writes below and the reads after),
-  // then walks it row-wise so that every global access is 16 bytes per lane and a row's
-  // BN/2 outputs form one contiguous segment.
-  constexpr int WR = TM * 32, WC = TN * 32, CS = WC + 4;
+  // Epilogue through LDS (see gemm_staged_epilogue): the operand stages are reused.
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();  // every wave is done reading the operand stages
   asm volatile("" ::: "memory");
-  float *cw = reinterpret_cast<float *>(smem) + (size_t)wave * WR * CS;
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-        *reinterpret_cast<float4 *>(cw + (i * 32 + (lane & 31)) * CS + j * 32 + q * 8 + (lane >> 5) * 4) =
-            make_float4(acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
-  constexpr int LPR = WC / 8, RPP = 64 / LPR;  // lanes per row, rows per pass
-  const int rl = lane / LPR, c8 = lane % LPR;
-  const int n0 = col0 + wn * (BN / 2) + c8 * 8;
-#pragma unroll 4
-  for (int r = rl; r < WR; r += RPP) {
-    const int m = row0 + wm * (BM / 2) + r;
-    if (m >= p.M || n0 >= p.N) continue;
-    const float4 lo = *reinterpret_cast<const float4 *>(cw + r * CS + c8 * 8);
-    const float4 hi = *reinterpret_cast<const float4 *>(cw + r * CS + c8 * 8 + 4);
-    float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-    gemm_epilogue_oct(p, m, n0, v);
-  }
+  float *cw = reinterpret_cast<float *>(smem) + (size_t)wave * 32 * (TN * 32 + 4);
+  gemm_staged_epilogue<bf16_t, TM, TN>(p, acc, cw, row0 + wm * (BM / 2), col0 + wn * (BN / 2), lane);
 }
 
 template <bool AKC, bool BKC, int BM, int BN, int NS>
 hipError_t launch_cfg(GemmDev d, int splits, hipStream_t s) {
   constexpr size_t stage_lds = (size_t)NS * (BM + BN) * 128;
-  constexpr size_t epi_lds = (size_t)4 * (BM / 2) * (BN / 2 + 4) * sizeof(float);
+  constexpr size_t epi_lds = (size_t)4 * 32 * (BN / 2 + 4) * sizeof(float);
   constexpr size_t lds = stage_lds > epi_lds ? stage_lds : epi_lds;
   static_assert(lds <= 160 * 1024, "stages do not fit in LDS");
   auto kern = gemm_bf16_pipe<AKC, BKC, BM, BN, NS>;
