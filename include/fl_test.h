@@ -35,6 +35,8 @@ int32_t fl_test_gemm_time(int32_t dtype, int32_t a_kc, int32_t b_kc, const void 
 int32_t fl_test_gemm_splits(int32_t dtype, int32_t M, int32_t N, int32_t K);
 /* Tile/stage variant of the pipelined bf16 GEMM: -1 automatic, 0..3 forced, -2 use the plain kernel. */
 void fl_test_gemm_force_variant(int32_t v);
+/* Tile height of the plain GEMM kernel: 0 automatic, 1 = 64x128 tiles, 2 = 128x128 tiles. */
+void fl_test_gemm_force_tile_height(int32_t tmw);
 
 /* LayerNorm (a normalisation primitive, Section 4.2) over the last dimension of x[M,D]. */
 int32_t fl_test_layernorm_fwd(int32_t dtype, const void *x, const void *gamma, const void *beta, float eps, int32_t M,

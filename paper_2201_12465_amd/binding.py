@@ -84,6 +84,7 @@ def lib() -> C.CDLL:
             "fl_test_gemm": (i32, [i32, i32, i32, vp, vp, vp, i32, i32, i32, vp, vp, i32, vp, i32, vp, i32, vp, vp]),
             "fl_test_gemm_time": (i32, [i32, i32, i32, vp, vp, vp, i32, i32, i32, i32, vp, i32, C.POINTER(f32), vp]),
             "fl_test_gemm_force_variant": (None, [i32]),
+            "fl_test_gemm_force_tile_height": (None, [i32]),
             "fl_test_gemm_splits": (i32, [i32, i32, i32, i32]),
             "fl_test_layernorm_fwd": (i32, [i32, vp, vp, vp, f32, i32, i32, vp, vp, vp, vp]),
             "fl_test_layernorm_bwd_ws_floats": (i32, [i32, i32]),

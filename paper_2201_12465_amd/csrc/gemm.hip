@@ -10,6 +10,8 @@
 //
 // Work decomposition: a workgroup of 256 threads (4 wavefronts, 2x2) owns a
 // 128x128 output tile; each wavefront owns 64x64 = 2x2 MFMA tiles of 32x32.
+// (A 64x128 variant -- wavefront tile 32x64 -- doubles the workgroup count for
+// outputs too small to give every CU more than one 128x128 tile.)
 // Per k-tile (64 bf16 / 32 fp32 values) both operand tiles are staged in LDS:
 //   k-contiguous operand: LDS [128 rows][k], rows padded by 16 bytes; a bf16 MFMA
 //     fragment is one 16-byte LDS read per lane;
@@ -32,7 +34,9 @@ namespace fl {
 namespace {
 
 constexpr int BM = 128, BN = 128, NTHREADS = 256;
-constexpr int LDR = 160;  // k-major LDS row stride in elements (128 + padding), both types
+// k-major LDS row stride in elements for a tile of ROWS rows (both types): ROWS + 32 keeps the
+// transposing reads and the fp32 word reads free of bank conflicts
+constexpr int ldr(int rows) { return rows + 32; }
 constexpr int OPERAND_LDS_BYTES = 20480;
 
 template <typename T> struct Tile;
@@ -43,47 +47,48 @@ __device__ __forceinline__ uint4 ld16(const void *p, bool ok) {
   return ok ? *reinterpret_cast<const uint4 *>(p) : make_uint4(0, 0, 0, 0);
 }
 
-// Global -> registers for one operand tile: 4 chunks of 16 bytes per thread.
-template <typename T, bool KC>
-__device__ __forceinline__ void load_tile(const T *base, int ld, int row0, int nrows, int k0, int kend, uint4 (&r)[4]) {
+// Global -> registers for one operand tile of ROWS rows: ROWS/32 chunks of 16 bytes per thread.
+template <typename T, bool KC, int ROWS>
+__device__ __forceinline__ void load_tile(const T *base, int ld, int row0, int nrows, int k0, int kend,
+                                          uint4 (&r)[ROWS / 32]) {
   constexpr int VEC = Elem<T>::VEC;
   constexpr int KT = Tile<T>::KT;
   const int tid = threadIdx.x;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < ROWS / 32; ++i) {
     int c = tid + NTHREADS * i;
     if (KC) {
       constexpr int CPR = KT / VEC;  // chunks per row (8)
       int row = row0 + c / CPR, k = k0 + (c % CPR) * VEC;
       r[i] = ld16(base + (size_t)row * ld + k, row < nrows && k < kend);
     } else {
-      constexpr int CPR = 128 / VEC;  // chunks per k-row
+      constexpr int CPR = ROWS / VEC;  // chunks per k-row
       int k = k0 + c / CPR, row = row0 + (c % CPR) * VEC;
       r[i] = ld16(base + (size_t)k * ld + row, k < kend && row < nrows);
     }
   }
 }
 
-template <typename T, bool KC>
-__device__ __forceinline__ void store_tile(T *lds, const uint4 (&r)[4]) {
+template <typename T, bool KC, int ROWS>
+__device__ __forceinline__ void store_tile(T *lds, const uint4 (&r)[ROWS / 32]) {
   constexpr int VEC = Elem<T>::VEC;
   constexpr int KT = Tile<T>::KT;
   const int tid = threadIdx.x;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < ROWS / 32; ++i) {
     int c = tid + NTHREADS * i;
     if (KC) {
       constexpr int CPR = KT / VEC;
       *reinterpret_cast<uint4 *>(lds + (c / CPR) * Tile<T>::LDK + (c % CPR) * VEC) = r[i];
     } else {
-      constexpr int CPR = 128 / VEC;
-      *reinterpret_cast<uint4 *>(lds + (c / CPR) * LDR + (c % CPR) * VEC) = r[i];
+      constexpr int CPR = ROWS / VEC;
+      *reinterpret_cast<uint4 *>(lds + (c / CPR) * ldr(ROWS) + (c % CPR) * VEC) = r[i];
     }
   }
 }
 
 // bf16 fragment of the 32 rows starting at r0 for k-step kk (16 values of k).
-template <bool KC>
+template <bool KC, int LDR>
 __device__ __forceinline__ bf16x8_t frag_bf16(const bf16_t *lds, int r0, int kk, int lane) {
   if (KC) {
     return *reinterpret_cast<const bf16x8_t *>(lds + (r0 + (lane & 31)) * Tile<bf16_t>::LDK + kk * 16 + (lane >> 5) * 8);
@@ -103,15 +108,16 @@ __device__ __forceinline__ bf16x8_t frag_bf16(const bf16_t *lds, int r0, int kk,
   }
 }
 
-template <bool KC>
+template <bool KC, int LDR>
 __device__ __forceinline__ float frag_f32(const float *lds, int r0, int kk, int lane) {
   if (KC) return lds[(r0 + (lane & 31)) * Tile<float>::LDK + kk * 2 + (lane >> 5)];
   return lds[(kk * 2 + (lane >> 5)) * LDR + r0 + (lane & 31)];
 }
 
-template <typename T, bool AKC, bool BKC>
+template <typename T, bool AKC, bool BKC, int TMW>
 __global__ __launch_bounds__(NTHREADS) void gemm_kernel(GemmDev p) {
   constexpr int KT = Tile<T>::KT;
+  constexpr int BMT = 64 * TMW;  // tile height: TMW MFMA tiles per wavefront in m
   __shared__ __attribute__((aligned(16))) unsigned char smem[2 * OPERAND_LDS_BYTES];
   T *ldsA = reinterpret_cast<T *>(smem);
   T *ldsB = reinterpret_cast<T *>(smem + OPERAND_LDS_BYTES);
@@ -121,7 +127,7 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(GemmDev p) {
   const int bid = blockIdx.x;
   const int xcd = bid & 7, idx = bid >> 3, per = nb >> 3, rem = nb & 7;
   const int logical = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
-  const int row0 = (logical / p.tiles_n) * BM, col0 = (logical % p.tiles_n) * BN;
+  const int row0 = (logical / p.tiles_n) * BMT, col0 = (logical % p.tiles_n) * BN;
 
   const int kbeg = blockIdx.z * p.k_per_split;
   const int kend = min(p.K, kbeg + p.k_per_split);
@@ -131,38 +137,39 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(GemmDev p) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
 
-  f32x16_t acc[2][2];
+  f32x16_t acc[TMW][2];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TMW; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  uint4 ra[4], rb[4];
+  uint4 ra[BMT / 32], rb[4];
   if (kbeg < kend) {
-    load_tile<T, AKC>(A, p.lda, row0, p.M, kbeg, kend, ra);
-    load_tile<T, BKC>(B, p.ldb, col0, p.N, kbeg, kend, rb);
+    load_tile<T, AKC, BMT>(A, p.lda, row0, p.M, kbeg, kend, ra);
+    load_tile<T, BKC, BN>(B, p.ldb, col0, p.N, kbeg, kend, rb);
   }
   for (int k0 = kbeg; k0 < kend; k0 += KT) {
-    store_tile<T, AKC>(ldsA, ra);
-    store_tile<T, BKC>(ldsB, rb);
+    store_tile<T, AKC, BMT>(ldsA, ra);
+    store_tile<T, BKC, BN>(ldsB, rb);
     __syncthreads();
     if (k0 + KT < kend) {  // next tile's loads stay in flight during the MFMAs
-      load_tile<T, AKC>(A, p.lda, row0, p.M, k0 + KT, kend, ra);
-      load_tile<T, BKC>(B, p.ldb, col0, p.N, k0 + KT, kend, rb);
+      load_tile<T, AKC, BMT>(A, p.lda, row0, p.M, k0 + KT, kend, ra);
+      load_tile<T, BKC, BN>(B, p.ldb, col0, p.N, k0 + KT, kend, rb);
     }
     if constexpr (sizeof(T) == 2) {
 #pragma unroll
       for (int kk = 0; kk < KT / 16; ++kk) {
-        bf16x8_t fa[2], fb[2];
+        bf16x8_t fa[TMW], fb[2];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          fa[i] = frag_bf16<AKC>(reinterpret_cast<const bf16_t *>(ldsA), wm * 64 + i * 32, kk, lane);
-          fb[i] = frag_bf16<BKC>(reinterpret_cast<const bf16_t *>(ldsB), wn * 64 + i * 32, kk, lane);
-        }
+        for (int i = 0; i < TMW; ++i)
+          fa[i] = frag_bf16<AKC, ldr(BMT)>(reinterpret_cast<const bf16_t *>(ldsA), wm * 32 * TMW + i * 32, kk, lane);
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j)
+          fb[j] = frag_bf16<BKC, ldr(BN)>(reinterpret_cast<const bf16_t *>(ldsB), wn * 64 + j * 32, kk, lane);
+#pragma unroll
+        for (int i = 0; i < TMW; ++i)
 #pragma unroll
           for (int j = 0; j < 2; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
@@ -170,14 +177,15 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(GemmDev p) {
     } else {
 #pragma unroll
       for (int kk = 0; kk < KT / 2; ++kk) {
-        float fa[2], fb[2];
+        float fa[TMW], fb[2];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          fa[i] = frag_f32<AKC>(reinterpret_cast<const float *>(ldsA), wm * 64 + i * 32, kk, lane);
-          fb[i] = frag_f32<BKC>(reinterpret_cast<const float *>(ldsB), wn * 64 + i * 32, kk, lane);
-        }
+        for (int i = 0; i < TMW; ++i)
+          fa[i] = frag_f32<AKC, ldr(BMT)>(reinterpret_cast<const float *>(ldsA), wm * 32 * TMW + i * 32, kk, lane);
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j)
+          fb[j] = frag_f32<BKC, ldr(BN)>(reinterpret_cast<const float *>(ldsB), wn * 64 + j * 32, kk, lane);
+#pragma unroll
+        for (int i = 0; i < TMW; ++i)
 #pragma unroll
           for (int j = 0; j < 2; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fb[j], fa[i], acc[i][j], 0, 0, 0);
@@ -190,25 +198,37 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(GemmDev p) {
   // made the operand tiles free, and 4 waves x 32 x 68 floats fit in them.
   static_assert(4 * 32 * 68 * sizeof(float) <= 2 * OPERAND_LDS_BYTES, "epilogue staging does not fit");
   float *cw = reinterpret_cast<float *>(smem) + (size_t)wave * 32 * 68;
-  gemm_staged_epilogue<T, 2, 2>(p, acc, cw, row0 + wm * 64, col0 + wn * 64, lane);
+  gemm_staged_epilogue<T, TMW, 2>(p, acc, cw, row0 + wm * 32 * TMW, col0 + wn * 64, lane);
 }
 
-template <typename T>
-hipError_t launch_t(const GemmArgs &a, const GemmDev &d, dim3 grid, hipStream_t s) {
+template <typename T, int TMW>
+hipError_t launch_tt(const GemmArgs &a, const GemmDev &d, dim3 grid, hipStream_t s) {
   if (a.a_kc && a.b_kc)
-    hipLaunchKernelGGL((gemm_kernel<T, true, true>), grid, dim3(NTHREADS), 0, s, d);
+    hipLaunchKernelGGL((gemm_kernel<T, true, true, TMW>), grid, dim3(NTHREADS), 0, s, d);
   else if (a.a_kc && !a.b_kc)
-    hipLaunchKernelGGL((gemm_kernel<T, true, false>), grid, dim3(NTHREADS), 0, s, d);
+    hipLaunchKernelGGL((gemm_kernel<T, true, false, TMW>), grid, dim3(NTHREADS), 0, s, d);
   else if (!a.a_kc && !a.b_kc)
-    hipLaunchKernelGGL((gemm_kernel<T, false, false>), grid, dim3(NTHREADS), 0, s, d);
+    hipLaunchKernelGGL((gemm_kernel<T, false, false, TMW>), grid, dim3(NTHREADS), 0, s, d);
   else
-    hipLaunchKernelGGL((gemm_kernel<T, false, true>), grid, dim3(NTHREADS), 0, s, d);
+    hipLaunchKernelGGL((gemm_kernel<T, false, true, TMW>), grid, dim3(NTHREADS), 0, s, d);
   return hipGetLastError();
 }
+
+// tmw = 2: 128x128 tiles; tmw = 1: 64x128 tiles
+template <typename T>
+hipError_t launch_t(const GemmArgs &a, GemmDev d, int tmw, int splits, hipStream_t s) {
+  d.tiles_m = (a.M + 64 * tmw - 1) / (64 * tmw);
+  dim3 grid(d.tiles_m * d.tiles_n, 1, splits);
+  return tmw == 1 ? launch_tt<T, 1>(a, d, grid, s) : launch_tt<T, 2>(a, d, grid, s);
+}
+
+int g_force_tmw = 0;  // 0: automatic; 1 / 2: forced (tests)
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 }  // namespace
+
+void gemm_force_tile_height(int tmw) { g_force_tmw = tmw; }
 
 int gemm_pick_splits(int dt, int M, int N, int K) {
   const int KT = dt == DT_F32 ? Tile<float>::KT : Tile<bf16_t>::KT;
@@ -256,8 +276,10 @@ hipError_t launch_gemm(int dt, const GemmArgs &a, hipStream_t stream) {
     const int variant = gemm_pipe_pick_variant(a.a_kc, a.b_kc, a.M, a.N, a.K);
     if (variant >= 0) return launch_gemm_bf16_pipe(a, &d, splits, variant, stream);
   }
-  dim3 grid(d.tiles_m * d.tiles_n, 1, splits);
-  return dt == DT_F32 ? launch_t<float>(a, d, grid, stream) : launch_t<bf16_t>(a, d, grid, stream);
+  // fewer than 1.5 full tiles per CU: halve the tile height so that twice as many workgroups run
+  int tmw = (long)d.tiles_m * d.tiles_n * splits < 384 && a.M > 64 ? 1 : 2;
+  if (g_force_tmw) tmw = g_force_tmw;
+  return dt == DT_F32 ? launch_t<float>(a, d, tmw, splits, stream) : launch_t<bf16_t>(a, d, tmw, splits, stream);
 }
 
 }  // namespace fl

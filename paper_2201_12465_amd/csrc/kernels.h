@@ -39,6 +39,7 @@ struct GemmArgs {
 hipError_t launch_gemm(int dt, const GemmArgs &a, hipStream_t stream);
 // Number of k-ranges launch_gemm should use so that a small output still fills the chip.
 int gemm_pick_splits(int dt, int M, int N, int K);
+void gemm_force_tile_height(int tmw);  // gemm.hip kernel: 0 automatic, 1 = 64x128 tiles, 2 = 128x128 tiles
 
 // The pipelined bf16 kernel (gemm_pipe.hip); launch_gemm uses it whenever the problem is eligible.
 bool gemm_pipe_eligible(const GemmArgs &a, int k_per_split);

@@ -88,6 +88,7 @@ int32_t fl_test_gemm_time(int32_t dtype, int32_t a_kc, int32_t b_kc, const void 
 }
 
 void fl_test_gemm_force_variant(int32_t v) { gemm_pipe_force_variant(v); }
+void fl_test_gemm_force_tile_height(int32_t tmw) { gemm_force_tile_height(tmw); }
 
 int32_t fl_test_gemm_splits(int32_t dtype, int32_t M, int32_t N, int32_t K) {
   return gemm_pick_splits(dtype == FL_F32 ? DT_F32 : DT_BF16, M, N, K);

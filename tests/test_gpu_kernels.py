@@ -55,6 +55,34 @@ def test_gemm_plain(dtype, mode, shape):
         assert rel_err(to_np(dC), ref) <= _tol(dtype), (mode, shape, splits)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mode", ["nt", "nn", "tn"])
+@pytest.mark.parametrize("tmw", [1, 2])
+@pytest.mark.parametrize("shape", [(200, 136, 72), (328, 264, 192)])
+def test_gemm_tile_heights(dtype, mode, tmw, shape):
+    """The register-staged kernel with 64x128 (tmw=1) and 128x128 (tmw=2) tiles, ragged M, N and K."""
+    b = _lib()
+    M, N, K = shape
+    rng = np.random.default_rng(hash((mode, shape, tmw)) % 2**32)
+    A = quantise(rng.standard_normal((M, K)), dtype)
+    Bm = quantise(rng.standard_normal((N, K)), dtype)
+    ref = A.astype(np.float64) @ Bm.astype(np.float64).T
+    a_kc, b_kc = {"nt": (1, 1), "nn": (1, 0), "tn": (0, 0)}[mode]
+    dA = to_dev(A if a_kc else A.T.copy(), dtype)
+    dB = to_dev(Bm if b_kc else Bm.T.copy(), dtype)
+    dC = empty_dev((M, N), dtype)
+    b.lib().fl_test_gemm_force_variant(-2)
+    b.lib().fl_test_gemm_force_tile_height(tmw)
+    try:
+        b.check(b.lib().fl_test_gemm(dt_code(dtype), a_kc, b_kc, dA.data_ptr(), dB.data_ptr(), dC.data_ptr(), M, N, K,
+                                     None, None, 0, None, 0, None, 1, None, stream_ptr()))
+        torch_mod().cuda.synchronize()
+    finally:
+        b.lib().fl_test_gemm_force_variant(-1)
+        b.lib().fl_test_gemm_force_tile_height(0)
+    assert rel_err(to_np(dC), ref) <= _tol(dtype), (dtype, mode, tmw, shape)
+
+
 @pytest.mark.parametrize("variant", [-2, 0, 1, 2, 3])
 @pytest.mark.parametrize("mode", ["nt", "nn", "tn"])
 @pytest.mark.parametrize("shape", [(304, 264, 192), (520, 392, 128), (8, 8, 64), (1000, 776, 640)])
