@@ -80,19 +80,29 @@ __device__ __forceinline__ bf16x8_t pack8(const f32x16_t &v, int s) {
   return o;
 }
 
-// Copies up to TILE rows of DH elements (row stride ld) into one or two LDS tiles; rows >= nvalid are zero.
-template <int DH>
-__device__ __forceinline__ void stage_rows(const bf16_t *src, size_t ld, int nvalid, bf16_t *dst0, int stride0,
-                                           bf16_t *dst1, int stride1) {
-  constexpr int CPR = DH / 8;
-  for (int c = threadIdx.x; c < TILE * CPR; c += NT) {
-    const int r = c / CPR, ch = c % CPR;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (r < nvalid) v = *reinterpret_cast<const uint4 *>(src + (size_t)r * ld + ch * 8);
-    *reinterpret_cast<uint4 *>(dst0 + r * stride0 + ch * 8) = v;
-    if (dst1) *reinterpret_cast<uint4 *>(dst1 + r * stride1 + ch * 8) = v;
+// A tile of up to TILE rows of DH elements on its way from global memory to LDS.  load() only
+// issues the global reads (into registers); store() writes them to one or two LDS tiles.  The
+// kernels load tile t+1 right after storing tile t, so the reads are in flight during the MFMAs.
+// Rows >= nvalid are zero.
+template <int DH> struct TileRegs {
+  static constexpr int CPR = DH / 8, N = TILE * CPR / NT;  // 16-byte chunks per row, per thread
+  uint4 r[N];
+  __device__ __forceinline__ void load(const bf16_t *src, size_t ld, int nvalid) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int c = threadIdx.x + NT * i, row = c / CPR, ch = c % CPR;
+      r[i] = row < nvalid ? *reinterpret_cast<const uint4 *>(src + (size_t)row * ld + ch * 8) : make_uint4(0, 0, 0, 0);
+    }
   }
-}
+  __device__ __forceinline__ void store(bf16_t *dst0, int stride0, bf16_t *dst1, int stride1) const {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int c = threadIdx.x + NT * i, row = c / CPR, ch = c % CPR;
+      *reinterpret_cast<uint4 *>(dst0 + row * stride0 + ch * 8) = r[i];
+      if (dst1) *reinterpret_cast<uint4 *>(dst1 + row * stride1 + ch * 8) = r[i];
+    }
+  }
+};
 
 // index (within a 32-block) of accumulator register r for lane half h
 __device__ __forceinline__ int acc_row(int r, int h) { return (r >> 2) * 8 + h * 4 + (r & 3); }
@@ -124,12 +134,18 @@ __global__ __launch_bounds__(NT) void attn_fwd_mfma(const bf16_t *__restrict__ q
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
 
+  TileRegs<DH> tk, tv;
+  tk.load(base + D, ld, min(TILE, Tn));
+  tv.load(base + 2 * D, ld, min(TILE, Tn));
   for (int k0 = 0; k0 < len; k0 += TILE) {
     __syncthreads();
-    const int nvalid = min(TILE, Tn - k0);
-    stage_rows<DH>(base + (size_t)k0 * ld + D, ld, nvalid, sK, KS, nullptr, 0);
-    stage_rows<DH>(base + (size_t)k0 * ld + 2 * D, ld, nvalid, sV, VS, nullptr, 0);
+    tk.store(sK, KS, nullptr, 0);
+    tv.store(sV, VS, nullptr, 0);
     __syncthreads();
+    if (k0 + TILE < len) {
+      tk.load(base + (size_t)(k0 + TILE) * ld + D, ld, min(TILE, Tn - k0 - TILE));
+      tv.load(base + (size_t)(k0 + TILE) * ld + 2 * D, ld, min(TILE, Tn - k0 - TILE));
+    }
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       if (k0 + kb * 32 >= len) break;
@@ -229,12 +245,18 @@ __global__ __launch_bounds__(NT) void attn_bwd_dq_mfma(const bf16_t *__restrict_
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
 
+  TileRegs<DH> tk, tv;
+  tk.load(base + D, ld, min(TILE, Tn));
+  tv.load(base + 2 * D, ld, min(TILE, Tn));
   for (int k0 = 0; k0 < len; k0 += TILE) {
     __syncthreads();
-    const int nvalid = min(TILE, Tn - k0);
-    stage_rows<DH>(base + (size_t)k0 * ld + D, ld, nvalid, sK, KS, sKt, TS);
-    stage_rows<DH>(base + (size_t)k0 * ld + 2 * D, ld, nvalid, sV, KS, nullptr, 0);
+    tk.store(sK, KS, sKt, TS);
+    tv.store(sV, KS, nullptr, 0);
     __syncthreads();
+    if (k0 + TILE < len) {
+      tk.load(base + (size_t)(k0 + TILE) * ld + D, ld, min(TILE, Tn - k0 - TILE));
+      tv.load(base + (size_t)(k0 + TILE) * ld + 2 * D, ld, min(TILE, Tn - k0 - TILE));
+    }
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       if (k0 + kb * 32 >= len) break;
@@ -275,13 +297,16 @@ __global__ __launch_bounds__(NT) void attn_bwd_dq_mfma(const bf16_t *__restrict_
 }
 
 // ------------------------------------------------------------------------------------------ dK, dV
-template <int DH>
+// MODE 0 computes both; MODE 1 only dV, MODE 2 only dK.  Large heads run it twice (1 then 2): two
+// accumulator sets of DH/32 x 16 registers plus the K and V fragments do not fit the register file.
+template <int DH, int MODE>
 __global__ __launch_bounds__(NT) void attn_bwd_dkv_mfma(const bf16_t *__restrict__ qkv,
                                                         const bf16_t *__restrict__ dout,
                                                         const float *__restrict__ lse,
                                                         const float *__restrict__ delta,
                                                         const int32_t *__restrict__ lengths, int Tn, int H,
                                                         float scale, bf16_t *__restrict__ dqkv) {
+  constexpr bool DO_DV = MODE != 2, DO_DK = MODE != 1;
   constexpr int KS = kc_stride(DH), TS = tr_stride(DH), NK = DH / 16, NB = DH / 32;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16_t *sQ = reinterpret_cast<bf16_t *>(smem_raw);   // Q rows for S = Q K^T
@@ -300,35 +325,51 @@ __global__ __launch_bounds__(NT) void attn_bwd_dkv_mfma(const bf16_t *__restrict
   const bool kok = key < Tn;
   const bf16_t *krow = kok ? base + (size_t)key * ld + D : nullptr;
   const bf16_t *vrow = kok ? base + (size_t)key * ld + 2 * D : nullptr;
-  bf16x8_t kf[NK], vf[NK];
+  bf16x8_t kf[NK], vf[DO_DK ? NK : 1];
 #pragma unroll
   for (int kk = 0; kk < NK; ++kk) {
     kf[kk] = g_frag(krow, kk, lane);
-    vf[kk] = g_frag(vrow, kk, lane);
+    if constexpr (DO_DK) vf[kk] = g_frag(vrow, kk, lane);
   }
   const float c = scale * LOG2E;
   const bool live = key < len;   // a masked key has probability 0 against every query
-  f32x16_t dk[NB], dv[NB];
+  f32x16_t dk[DO_DK ? NB : 1], dv[DO_DV ? NB : 1];
 #pragma unroll
   for (int i = 0; i < NB; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) dk[i][r] = 0.f, dv[i][r] = 0.f;
+    for (int r = 0; r < 16; ++r) {
+      if constexpr (DO_DK) dk[i][r] = 0.f;
+      if constexpr (DO_DV) dv[i][r] = 0.f;
+    }
   // a workgroup whose keys are all masked only writes zeros
   const bool wg_live = blockIdx.x * ROWS_WG < len;
   const size_t stat0 = ((size_t)b * H + hd) * Tn;
   const bf16_t *dobase = dout + (size_t)b * Tn * D + hd * DH;
 
-  for (int q0 = 0; wg_live && q0 < Tn; q0 += TILE) {
-    __syncthreads();
+  TileRegs<DH> tq, tdo;
+  float rl = INFINITY, rd = 0.f;   // this thread's lse / delta entry of the tile (threads < TILE)
+  auto load_tile = [&](int q0) {
     const int nvalid = min(TILE, Tn - q0);
-    stage_rows<DH>(base + (size_t)q0 * ld, ld, nvalid, sQ, KS, sQt, TS);
-    stage_rows<DH>(dobase + (size_t)q0 * D, (size_t)D, nvalid, sDO, KS, sDOt, TS);
+    tq.load(base + (size_t)q0 * ld, ld, nvalid);
+    tdo.load(dobase + (size_t)q0 * D, (size_t)D, nvalid);
     if (threadIdx.x < TILE) {
       const bool ok = (int)threadIdx.x < nvalid;
-      sL[threadIdx.x] = ok ? lse[stat0 + q0 + threadIdx.x] * LOG2E : INFINITY;   // exp2(-inf) = 0 beyond T
-      sDl[threadIdx.x] = ok ? delta[stat0 + q0 + threadIdx.x] : 0.f;
+      rl = ok ? lse[stat0 + q0 + threadIdx.x] * LOG2E : INFINITY;   // exp2(-inf) = 0 beyond T
+      rd = ok ? delta[stat0 + q0 + threadIdx.x] : 0.f;
+    }
+  };
+  if (wg_live) load_tile(0);
+  for (int q0 = 0; wg_live && q0 < Tn; q0 += TILE) {
+    __syncthreads();
+    tq.store(sQ, KS, DO_DK ? sQt : nullptr, TS);
+    if constexpr (DO_DK) tdo.store(sDO, KS, DO_DV ? sDOt : nullptr, TS);
+    else tdo.store(sDOt, TS, nullptr, 0);
+    if (threadIdx.x < TILE) {
+      sL[threadIdx.x] = rl;
+      sDl[threadIdx.x] = rd;
     }
     __syncthreads();
+    if (q0 + TILE < Tn) load_tile(q0 + TILE);
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       if (q0 + qb * 32 >= Tn) break;
@@ -338,25 +379,34 @@ __global__ __launch_bounds__(NT) void attn_bwd_dkv_mfma(const bf16_t *__restrict
 #pragma unroll
       for (int kk = 0; kk < NK; ++kk) {
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc_frag(sQ, KS, qb * 32, kk, lane), kf[kk], s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc_frag(sDO, KS, qb * 32, kk, lane), vf[kk], dp, 0, 0, 0);
+        if (DO_DK)
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc_frag(sDO, KS, qb * 32, kk, lane), vf[kk], dp, 0, 0, 0);
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int qi = qb * 32 + acc_row(r, h2);
         const float p = live ? exp2f(s[r] * c - sL[qi]) : 0.f;
-        dp[r] = p * (dp[r] - sDl[qi]);   // dS
+        if constexpr (DO_DK) dp[r] = p * (dp[r] - sDl[qi]);   // dS
         s[r] = p;
       }
-      bf16x8_t pf[2] = {pack8(s, 0), pack8(s, 1)}, dsf[2] = {pack8(dp, 0), pack8(dp, 1)};
+      if constexpr (DO_DV) {
+        bf16x8_t pf[2] = {pack8(s, 0), pack8(s, 1)};
 #pragma unroll
-      for (int db = 0; db < NB; ++db)
+        for (int db = 0; db < NB; ++db)
 #pragma unroll
-        for (int st = 0; st < 2; ++st) {
-          dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(sDOt, TS, db * 32, qb * 32 + 16 * st, lane), pf[st],
-                                                           dv[db], 0, 0, 0);
-          dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(sQt, TS, db * 32, qb * 32 + 16 * st, lane), dsf[st],
-                                                           dk[db], 0, 0, 0);
-        }
+          for (int st = 0; st < 2; ++st)
+            dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(sDOt, TS, db * 32, qb * 32 + 16 * st, lane),
+                                                             pf[st], dv[db], 0, 0, 0);
+      }
+      if constexpr (DO_DK) {
+        bf16x8_t dsf[2] = {pack8(dp, 0), pack8(dp, 1)};
+#pragma unroll
+        for (int db = 0; db < NB; ++db)
+#pragma unroll
+          for (int st = 0; st < 2; ++st)
+            dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(sQt, TS, db * 32, qb * 32 + 16 * st, lane),
+                                                             dsf[st], dk[db], 0, 0, 0);
+      }
     }
   }
   if (kok) {
@@ -366,14 +416,15 @@ __global__ __launch_bounds__(NT) void attn_bwd_dkv_mfma(const bf16_t *__restrict
     for (int db = 0; db < NB; ++db)
 #pragma unroll
       for (int qd = 0; qd < 4; ++qd) {
-        float a[4], v[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          a[e] = dk[db][qd * 4 + e] * scale;
-          v[e] = dv[db][qd * 4 + e];
+        if constexpr (DO_DK) {
+          float a[4] = {dk[db][qd * 4] * scale, dk[db][qd * 4 + 1] * scale, dk[db][qd * 4 + 2] * scale,
+                        dk[db][qd * 4 + 3] * scale};
+          VecIO<bf16_t, 4>::store(dkrow + db * 32 + qd * 8 + h2 * 4, a);
         }
-        VecIO<bf16_t, 4>::store(dkrow + db * 32 + qd * 8 + h2 * 4, a);
-        VecIO<bf16_t, 4>::store(dvrow + db * 32 + qd * 8 + h2 * 4, v);
+        if constexpr (DO_DV) {
+          float v[4] = {dv[db][qd * 4], dv[db][qd * 4 + 1], dv[db][qd * 4 + 2], dv[db][qd * 4 + 3]};
+          VecIO<bf16_t, 4>::store(dvrow + db * 32 + qd * 8 + h2 * 4, v);
+        }
       }
   }
 }
@@ -391,6 +442,24 @@ hipError_t fwd_t(const void *qkv, const int32_t *lengths, int B, int T, int H, f
   return hipGetLastError();
 }
 
+template <int DH, int MODE>
+hipError_t launch_dkv(dim3 grid, size_t lds, const void *qkv, const void *dout, const float *lse, const float *delta,
+                      const int32_t *lengths, int T, int H, float scale, void *dqkv, hipStream_t s) {
+  if (lds > 64 * 1024) {
+    static bool raised = false;   // allow more than the default 64 KiB of dynamic LDS, once
+    if (!raised) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bwd_dkv_mfma<DH, MODE>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+      raised = true;
+    }
+  }
+  hipLaunchKernelGGL((attn_bwd_dkv_mfma<DH, MODE>), grid, dim3(NT), lds, s, static_cast<const bf16_t *>(qkv),
+                     static_cast<const bf16_t *>(dout), lse, delta, lengths, T, H, scale,
+                     static_cast<bf16_t *>(dqkv));
+  return hipGetLastError();
+}
+
 template <int DH>
 hipError_t bwd_t(const void *qkv, const void *o, const void *dout, const float *lse, const int32_t *lengths, int B,
                  int T, int H, float scale, void *dqkv, float *delta, hipStream_t s) {
@@ -401,19 +470,9 @@ hipError_t bwd_t(const void *qkv, const void *o, const void *dout, const float *
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const size_t lds = dkv_lds_bytes<DH>();
-  if (lds > 64 * 1024) {
-    static bool raised = false;   // allow more than the default 64 KiB of dynamic LDS, once
-    if (!raised) {
-      e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bwd_dkv_mfma<DH>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      if (e != hipSuccess) return e;
-      raised = true;
-    }
-  }
-  hipLaunchKernelGGL(attn_bwd_dkv_mfma<DH>, grid, dim3(NT), lds, s, static_cast<const bf16_t *>(qkv),
-                     static_cast<const bf16_t *>(dout), lse, delta, lengths, T, H, scale,
-                     static_cast<bf16_t *>(dqkv));
-  return hipGetLastError();
+  e = launch_dkv<DH, DH >= 128 ? 1 : 0>(grid, lds, qkv, dout, lse, delta, lengths, T, H, scale, dqkv, s);
+  if (e != hipSuccess || DH < 128) return e;
+  return launch_dkv<DH, 2>(grid, lds, qkv, dout, lse, delta, lengths, T, H, scale, dqkv, s);
 }
 
 }  // namespace
