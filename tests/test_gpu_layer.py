@@ -128,6 +128,12 @@ def test_variants_ragged(dtype, norm, act, masked):
     check_against_oracle(cfg, inp, _tol(cfg))
 
 
+def test_config4_full_size():
+    """Config 4 as the benchmark spec states it (B=8, T=1000, 4 heads of 192, ReLU, masked)."""
+    cfg = CONFIGS["cfg4_speech_bf16"]
+    check_against_oracle(cfg, make_inputs(cfg, seed=0), _tol(cfg))
+
+
 def test_speech_shape_reduced():
     """Config 4's head size (192) and a long, masked, non-tile-multiple sequence, at reduced batch."""
     cfg = CONFIGS["cfg4_speech_bf16"].with_(B=2, T=333, len_lo=150, len_hi=333)
@@ -136,10 +142,19 @@ def test_speech_shape_reduced():
 
 def test_vit_stack_reduced():
     """Config 5's chain (pre-LN, GELU, T=197) through the same layer calls: 3 layers, batch 4."""
+    _run_stack(CONFIGS["cfg5_vit_b16_bf16"].with_(B=4, layers=3), nontrivial=True)
+
+
+def test_config5_full_stack():
+    """Config 5 as the benchmark spec states it: 12 pre-LN layers, B=64, T=197, final Y, dX at the stack
+    input and all 12 layers' parameter gradients against the oracle."""
+    _run_stack(CONFIGS["cfg5_vit_b16_bf16"], nontrivial=False)
+
+
+def _run_stack(cfg, nontrivial):
     from paper_2201_12465_amd import binding as b
     torch = torch_mod()
-    cfg = CONFIGS["cfg5_vit_b16_bf16"].with_(B=4, layers=3)
-    inp = make_stack_inputs(cfg, seed=0, nontrivial=True)
+    inp = make_stack_inputs(cfg, seed=0, nontrivial=nontrivial)
     dt = cfg.dtype
     layers = [b.Layer(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F, cfg.act, cfg.norm, dt, cfg.eps) for _ in range(cfg.layers)]
     P = [{k: to_dev(v, dt) for k, v in p.items()} for p in inp["params"]]
