@@ -128,6 +128,28 @@ def main() -> int:
         out["roofline"] = roof
         out["kernels"] = kernels
 
+    # ---- the fused optimizer step (NOT part of `value`: the metric is the layer's forward + backward)
+    if not a.no_kernel_timing:
+        names = list(P[0].keys())
+        ne = [P[0][k].numel() for k in names]
+        ms_ = [torch.zeros(n, dtype=torch.float32, device="cuda") for n in ne]
+        vs_ = [torch.zeros(n, dtype=torch.float32, device="cuda") for n in ne]
+        pcopy = [P[0][k].clone() for k in names]          # the benchmark's own parameters stay untouched
+        gl = [G[0][k] for k in names]
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for it in range(3):
+            b.opt_step("adam", cfg.dtype, pcopy, gl, ms_, vs_, ne, stream, lr=1e-4, step=it + 1)
+        e0.record()
+        for it in range(20):
+            b.opt_step("adam", cfg.dtype, pcopy, gl, ms_, vs_, ne, stream, lr=1e-4, step=it + 4)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / 20 * 1e3
+        esz = 4 if cfg.dtype == "f32" else 2
+        by = sum(ne) * (3 * esz + 16)                      # read p, g, m, v; write p, m, v
+        out["optimizer_step"] = {"kind": "adam", "tensors": len(ne), "elements": sum(ne), "avg_us": us,
+                                 "gbs": by / us / 1e3, "frac_of_hbm_peak": by / us / 1e3 / PEAK_HBM_GBS}
+
     # ---- the fp64 CPU oracle on the host cores (a reported baseline, not a target)
     if not a.no_cpu_baseline:
         from oracle import oracle as orc

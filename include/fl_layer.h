@@ -100,6 +100,13 @@ fl_status_t fl_layer_forward(fl_layer_t *layer, const fl_layer_params_t *params,
 fl_status_t fl_layer_backward(fl_layer_t *layer, const fl_layer_params_t *params, const void *dY,
                               void *dX, fl_layer_grads_t *grads, void *hip_stream);
 
+/* As fl_layer_backward, but with accumulate != 0 the 12 parameter gradients are ADDED to what
+ * `grads` already holds -- the paper's addGrad semantics (Section 4.2, cosine-operator listing),
+ * used to sum the gradients of several micro-batches before one optimizer step.  dX is always
+ * overwritten. */
+fl_status_t fl_layer_backward_accumulate(fl_layer_t *layer, const fl_layer_params_t *params, const void *dY,
+                                         void *dX, fl_layer_grads_t *grads, int32_t accumulate, void *hip_stream);
+
 /* Releases the handle and returns its buffers to the cache.  NULL is a no-op. */
 fl_status_t fl_layer_destroy(fl_layer_t *layer);
 
@@ -125,6 +132,28 @@ fl_status_t fl_alloc_trim(void);
  * (Section 5.2.2: restricting the splitting of large cache blocks reduced
  * fragmentation).  0 restores the default (no limit). */
 fl_status_t fl_alloc_set_split_limit(uint64_t bytes);
+
+/* ---- optimizer step (Section 4.2 "Optimizers"; the training-loop listing's opt.step() and
+ * opt.zeroGrad()).  One fused kernel updates up to 16 tensors:
+ *   SGD   g' = g + wd*p;  buf = momentum*buf + g';  p -= lr*buf      (momentum == 0: p -= lr*g')
+ *   Adam  g' = g + wd*p;  m = b1*m + (1-b1)*g';  v = b2*v + (1-b2)*g'^2;
+ *         p -= lr * (m/(1-b1^step)) / (sqrt(v/(1-b2^step)) + eps),   step = 1 for the first update
+ * params[i] / grads[i]: device tensors of `dtype` with numel[i] elements (numel % 8 == 0, pointers
+ * 16-byte aligned).  state_m[i] (SGD momentum buffer / Adam m) and state_v[i] (Adam v) are device
+ * fp32 buffers of numel[i] elements owned by the caller, zero before the first step; state_m may
+ * be NULL for SGD without momentum, state_v for SGD.  The pointer arrays themselves are HOST
+ * arrays.  Arithmetic is fp32; a bf16 parameter is rounded once when it is written back. */
+typedef enum { FL_OPT_SGD = 0, FL_OPT_ADAM = 1 } fl_opt_kind_t;
+typedef struct {
+  fl_opt_kind_t kind;
+  float lr, momentum, weight_decay, beta1, beta2, eps;
+  int32_t step;
+} fl_opt_config_t;
+fl_status_t fl_opt_step(const fl_opt_config_t *cfg, fl_dtype_t dtype, int32_t n, void *const *params,
+                        const void *const *grads, float *const *state_m, float *const *state_v, const int64_t *numel,
+                        void *hip_stream);
+/* Sets n gradient tensors to zero with one kernel (safe inside a captured graph). */
+fl_status_t fl_zero_grad(fl_dtype_t dtype, int32_t n, void *const *grads, const int64_t *numel, void *hip_stream);
 
 /* ---- per-kernel timing telemetry (host-side; used by the benchmark) -------------
  * While enabled, launches of the selected kernel classes are bracketed by HIP

@@ -51,6 +51,11 @@ class fl_alloc_stats_t(C.Structure):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
 
 
+class fl_opt_config_t(C.Structure):
+    _fields_ = [("kind", C.c_int), ("lr", C.c_float), ("momentum", C.c_float), ("weight_decay", C.c_float),
+                ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float), ("step", C.c_int32)]
+
+
 class fl_prof_entry_t(C.Structure):
     _fields_ = [("kernel_class", C.c_int32), ("launches", C.c_int32), ("total_ms", C.c_double),
                 ("flops", C.c_double), ("bytes", C.c_double)]
@@ -74,6 +79,11 @@ def lib() -> C.CDLL:
             "fl_layer_create": (C.c_int, [C.POINTER(fl_layer_config_t), C.POINTER(vp)]),
             "fl_layer_forward": (C.c_int, [vp, C.POINTER(fl_layer_params_t), vp, vp, i32, i32, vp, vp]),
             "fl_layer_backward": (C.c_int, [vp, C.POINTER(fl_layer_params_t), vp, vp, C.POINTER(fl_layer_grads_t), vp]),
+            "fl_layer_backward_accumulate": (C.c_int, [vp, C.POINTER(fl_layer_params_t), vp, vp,
+                                                       C.POINTER(fl_layer_grads_t), i32, vp]),
+            "fl_opt_step": (C.c_int, [C.POINTER(fl_opt_config_t), C.c_int, i32, C.POINTER(vp), C.POINTER(vp),
+                                      C.POINTER(vp), C.POINTER(vp), C.POINTER(i64), vp]),
+            "fl_zero_grad": (C.c_int, [C.c_int, i32, C.POINTER(vp), C.POINTER(i64), vp]),
             "fl_layer_destroy": (C.c_int, [vp]),
             "fl_last_error": (C.c_char_p, []),
             "fl_alloc_get_stats": (C.c_int, [C.POINTER(fl_alloc_stats_t)]),
@@ -146,10 +156,13 @@ class Layer:
         p = _pack(fl_layer_params_t, params)
         check(lib().fl_layer_forward(self._h, C.byref(p), ptr(X), ptr(lengths), B, T, ptr(Y), stream))
 
-    def backward(self, params: dict, dY, dX, grads: dict, stream: int = 0) -> None:
+    def backward(self, params: dict, dY, dX, grads: dict, stream: int = 0, accumulate: bool = False) -> None:
         p = _pack(fl_layer_params_t, params)
         g = _pack(fl_layer_grads_t, grads)
-        check(lib().fl_layer_backward(self._h, C.byref(p), ptr(dY), ptr(dX), C.byref(g), stream))
+        if accumulate:
+            check(lib().fl_layer_backward_accumulate(self._h, C.byref(p), ptr(dY), ptr(dX), C.byref(g), 1, stream))
+        else:
+            check(lib().fl_layer_backward(self._h, C.byref(p), ptr(dY), ptr(dX), C.byref(g), stream))
 
     def destroy(self) -> None:
         if self._h:
@@ -161,6 +174,32 @@ class Layer:
             self.destroy()
         except Exception:
             pass
+
+
+FL_OPT_SGD, FL_OPT_ADAM = 0, 1
+
+
+def _ptr_array(items):
+    if items is None:
+        return None
+    return (C.c_void_p * len(items))(*[ptr(x) for x in items])
+
+
+def opt_step(kind: str, dtype: str, params, grads, state_m, state_v, numel, stream: int = 0, *, lr, momentum=0.0,
+             weight_decay=0.0, beta1=0.9, beta2=0.999, eps=1e-8, step=1) -> None:
+    """One fused optimizer step over lists of tensors (see fl_opt_step)."""
+    cfg = fl_opt_config_t({"sgd": FL_OPT_SGD, "adam": FL_OPT_ADAM}[kind], lr, momentum, weight_decay, beta1, beta2,
+                          eps, step)
+    n = len(params)
+    ne = (C.c_int64 * n)(*[int(x) for x in numel])
+    check(lib().fl_opt_step(C.byref(cfg), {"f32": FL_F32, "bf16": FL_BF16}[dtype], n, _ptr_array(params),
+                            _ptr_array(grads), _ptr_array(state_m), _ptr_array(state_v), ne, stream))
+
+
+def zero_grad(dtype: str, grads, numel, stream: int = 0) -> None:
+    n = len(grads)
+    ne = (C.c_int64 * n)(*[int(x) for x in numel])
+    check(lib().fl_zero_grad({"f32": FL_F32, "bf16": FL_BF16}[dtype], n, _ptr_array(grads), ne, stream))
 
 
 def alloc_stats() -> dict:

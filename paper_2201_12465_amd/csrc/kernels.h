@@ -50,11 +50,13 @@ hipError_t launch_gemm_bf16_pipe(const GemmArgs &a, const void *gemm_dev, int sp
 // out_s[n] = sum_p partial[p*stride + s*seglen + n]  for s < nseg (<= 3), n < seglen;
 // out_s has element type dt.  seglen % 4 == 0.
 hipError_t launch_reduce_partials(int dt, const float *partial, int P, size_t stride, size_t seglen,
-                                  int nseg, void *out0, void *out1, void *out2, hipStream_t stream);
+                                  int nseg, void *out0, void *out1, void *out2, hipStream_t stream,
+                                  bool accumulate = false);  // accumulate: out_s += the sums
 
 // Column sums of in[M,N] (type dt) -> out[N] (type dt); ws must hold colsum_ws_floats(M,N) floats.
 size_t colsum_ws_floats(int M, int N);
-hipError_t launch_colsum(int dt, const void *in, int M, int N, float *ws, void *out, hipStream_t stream);
+hipError_t launch_colsum(int dt, const void *in, int M, int N, float *ws, void *out, hipStream_t stream,
+                         bool accumulate = false);
 
 // ---------------------------------------------------------------------------
 // LayerNorm over the last dimension D of x[M,D] (biased variance, eps inside the
@@ -94,5 +96,19 @@ hipError_t launch_attention_fwd_mfma(const void *qkv, const int32_t *lengths, in
 hipError_t launch_attention_bwd_mfma(const void *qkv, const void *o, const void *dout, const float *lse,
                                      const int32_t *lengths, int B, int T, int H, int dh, void *dqkv, float *delta,
                                      hipStream_t s);
+
+// ---------------------------------------------------------------------------
+// Fused optimizer step over up to OPT_MAX_TENSORS tensors in one launch (optimizer.hip).
+// kind 0 = SGD (momentum buffer m used iff momentum != 0), 1 = Adam (m, v).  params/grads have
+// type dt, state is fp32; numel % 8 == 0; every pointer 16-byte aligned.  inv_bias1/2 are
+// 1/(1-beta^t) computed on the host.
+constexpr int OPT_MAX_TENSORS = 16;
+struct OptHyper {
+  float lr, momentum, weight_decay, beta1, beta2, eps, inv_bias1, inv_bias2;
+};
+hipError_t launch_opt_step(int dt, int kind, const OptHyper &h, int n, void *const *params, const void *const *grads,
+                           float *const *m, float *const *v, const long long *numel, hipStream_t stream);
+// Zero-fills n buffers (byte counts multiples of 16) with one kernel.
+hipError_t launch_zero_tensors(int n, void *const *ptrs, const long long *bytes, hipStream_t stream);
 
 }  // namespace fl

@@ -126,6 +126,7 @@ struct fl_layer {
   const int32_t *lengths = nullptr;
   int slot_x = -1, slot_y = -1;
   // valid during backward
+  bool accumulate = false;  // parameter gradients are added to what the caller's buffers hold
   const void *params[P_COUNT];
   void *grads[P_COUNT];
 };
@@ -221,7 +222,7 @@ int linear_backward(void *ctx, Tape *tape, const Node *n) {
     Scratch ws;
     FL_TRY(ws.get(colsum_ws_floats(M, N) * sizeof(float), st));
     FL_HIP(timed(FL_K_COLSUM, 0, (double)M * N * e, st,
-                 [&] { return launch_colsum(dt, gy, M, N, ws.f32(), L->grads[kLinear[n->param].b], st); }));
+                 [&] { return launch_colsum(dt, gy, M, N, ws.f32(), L->grads[kLinear[n->param].b], st, L->accumulate); }));
   }
   // weight gradient: dW[N,K] = sum_m gy[m,n] x[m,k]
   {
@@ -238,9 +239,11 @@ int linear_backward(void *ctx, Tape *tape, const Node *n) {
       a.partial = ws.f32();
       FL_HIP(timed(FL_K_GEMM_TN, fl, by, st, [&] { return launch_gemm(dt, a, st); }));
       FL_HIP(timed(FL_K_SPLITK_REDUCE, 0, (double)(a.splits * 4 + e) * N * K, st, [&] {
-        return launch_reduce_partials(dt, ws.f32(), a.splits, (size_t)N * K, (size_t)N * K, 1, a.C, nullptr, nullptr, st);
+        return launch_reduce_partials(dt, ws.f32(), a.splits, (size_t)N * K, (size_t)N * K, 1, a.C, nullptr, nullptr, st,
+                                      L->accumulate);
       }));
     } else {
+      if (L->accumulate) a.residual = a.C;  // in place: each lane reads the elements it then writes
       FL_HIP(timed(FL_K_GEMM_TN, fl, by, st, [&] { return launch_gemm(dt, a, st); }));
     }
   }
@@ -366,7 +369,7 @@ int layernorm_backward(void *ctx, Tape *tape, const Node *n) {
   const bool want_bias = fin && xs.colsum_param >= 0;
   FL_HIP(timed(FL_K_COLSUM, 0, (double)parts * 3 * D * 4, st, [&] {
     return launch_reduce_partials(dt, ws.f32(), parts, (size_t)3 * D, (size_t)D, want_bias ? 3 : 2, L->grads[gi],
-                                  L->grads[bi], want_bias ? L->grads[xs.colsum_param] : nullptr, st);
+                                  L->grads[bi], want_bias ? L->grads[xs.colsum_param] : nullptr, st, L->accumulate);
   }));
   if (want_bias) xs.colsum_done = true;
   set_grad(ys, nullptr, nullptr);
@@ -573,7 +576,8 @@ int forward_impl(fl_layer *L, const fl_layer_params_t *params, const void *X, co
 }
 
 int backward_impl(fl_layer *L, const fl_layer_params_t *params, const void *dY, void *dX, fl_layer_grads_t *grads,
-                  hipStream_t st) {
+                  bool accumulate, hipStream_t st) {
+  L->accumulate = accumulate;
   if (!L->tape.recorded) return set_error(FL_ERR_STATE, "backward without a recorded forward");
   if (st != L->stream) return set_error(FL_ERR_STATE, "backward on a different stream than forward");
   load_params(L, params);
@@ -648,9 +652,58 @@ fl_status_t fl_layer_forward(fl_layer_t *layer, const fl_layer_params_t *params,
 
 fl_status_t fl_layer_backward(fl_layer_t *layer, const fl_layer_params_t *params, const void *dY, void *dX,
                               fl_layer_grads_t *grads, void *hip_stream) {
+  return fl_layer_backward_accumulate(layer, params, dY, dX, grads, 0, hip_stream);
+}
+
+fl_status_t fl_layer_backward_accumulate(fl_layer_t *layer, const fl_layer_params_t *params, const void *dY, void *dX,
+                                         fl_layer_grads_t *grads, int32_t accumulate, void *hip_stream) {
   FL_GUARD_BEGIN
   if (!layer || !params || !dY || !dX || !grads) return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "null argument");
-  return (fl_status_t)backward_impl(layer, params, dY, dX, grads, static_cast<hipStream_t>(hip_stream));
+  return (fl_status_t)backward_impl(layer, params, dY, dX, grads, accumulate != 0, static_cast<hipStream_t>(hip_stream));
+  FL_GUARD_END
+}
+
+fl_status_t fl_opt_step(const fl_opt_config_t *cfg, fl_dtype_t dtype, int32_t n, void *const *params,
+                        const void *const *grads, float *const *state_m, float *const *state_v, const int64_t *numel,
+                        void *hip_stream) {
+  FL_GUARD_BEGIN
+  if (!cfg || !params || !grads || !numel) return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "null argument");
+  if (n < 1 || n > OPT_MAX_TENSORS)
+    return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "n=%d outside 1..%d", n, OPT_MAX_TENSORS);
+  if ((unsigned)cfg->kind > FL_OPT_ADAM || (unsigned)dtype > FL_BF16)
+    return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "unknown optimizer kind or dtype");
+  if (cfg->kind == FL_OPT_ADAM && (cfg->step < 1 || !(cfg->beta1 >= 0.f && cfg->beta1 < 1.f) ||
+                                   !(cfg->beta2 >= 0.f && cfg->beta2 < 1.f)))
+    return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "Adam needs step >= 1 and betas in [0, 1)");
+  OptHyper h{cfg->lr, cfg->momentum, cfg->weight_decay, cfg->beta1, cfg->beta2, cfg->eps, 1.f, 1.f};
+  if (cfg->kind == FL_OPT_ADAM) {
+    h.inv_bias1 = (float)(1.0 / (1.0 - std::pow((double)cfg->beta1, (double)cfg->step)));
+    h.inv_bias2 = (float)(1.0 / (1.0 - std::pow((double)cfg->beta2, (double)cfg->step)));
+  }
+  long long ne[OPT_MAX_TENSORS];
+  for (int i = 0; i < n; ++i) ne[i] = (long long)numel[i];
+  hipError_t e = launch_opt_step(dtype == FL_F32 ? DT_F32 : DT_BF16, cfg->kind == FL_OPT_SGD ? 0 : 1, h, n, params,
+                                 grads, state_m, state_v, ne, static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess)
+    return (fl_status_t)set_error(e == hipErrorInvalidValue ? FL_ERR_UNSUPPORTED : FL_ERR_DEVICE,
+                                  "optimizer step: %s (needs numel %% 8 == 0, 16-byte aligned pointers, state "
+                                  "buffers for momentum / Adam)", hipGetErrorString(e));
+  return FL_OK;
+  FL_GUARD_END
+}
+
+fl_status_t fl_zero_grad(fl_dtype_t dtype, int32_t n, void *const *grads, const int64_t *numel, void *hip_stream) {
+  FL_GUARD_BEGIN
+  if (!grads || !numel) return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "null argument");
+  if (n < 1 || n > OPT_MAX_TENSORS || (unsigned)dtype > FL_BF16)
+    return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "n=%d outside 1..%d, or unknown dtype", n, OPT_MAX_TENSORS);
+  long long bytes[OPT_MAX_TENSORS];
+  for (int i = 0; i < n; ++i) bytes[i] = (long long)numel[i] * (dtype == FL_F32 ? 4 : 2);
+  hipError_t e = launch_zero_tensors(n, grads, bytes, static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess)
+    return (fl_status_t)set_error(e == hipErrorInvalidValue ? FL_ERR_UNSUPPORTED : FL_ERR_DEVICE, "zero_grad: %s",
+                                  hipGetErrorString(e));
+  return FL_OK;
   FL_GUARD_END
 }
 

@@ -12,7 +12,7 @@ namespace {
 // out_s[n..n+3] = sum_p partial[p*stride + s*seglen + n..n+3]
 template <typename T>
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ partial, int P, size_t stride,
-                                                              size_t seglen, T *out0, T *out1, T *out2) {
+                                                              size_t seglen, T *out0, T *out1, T *out2, int accumulate) {
   const size_t n = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
   if (n >= seglen) return;
   const int s = blockIdx.y;
@@ -23,7 +23,14 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
     a[0] += t.x; a[1] += t.y; a[2] += t.z; a[3] += t.w;
   }
   T *out = s == 0 ? out0 : (s == 1 ? out1 : out2);
-  if (out) VecIO<T, 4>::store(out + n, a);
+  if (out) {
+    if (accumulate) {
+      float o[4];
+      VecIO<T, 4>::load(out + n, o);
+      a[0] += o[0]; a[1] += o[1]; a[2] += o[2]; a[3] += o[3];
+    }
+    VecIO<T, 4>::store(out + n, a);
+  }
 }
 
 // Same sums when there are many partial rows and few columns: a workgroup of 16 waves owns 64
@@ -31,7 +38,7 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
 template <typename T>
 __global__ __launch_bounds__(1024) void reduce_partials_tall_kernel(const float *__restrict__ partial, int P,
                                                                     size_t stride, size_t seglen, T *out0, T *out1,
-                                                                    T *out2) {
+                                                                    T *out2, int accumulate) {
   __shared__ float4 red[16][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const size_t n = ((size_t)blockIdx.x * 64 + lane) * 4;
@@ -54,7 +61,14 @@ __global__ __launch_bounds__(1024) void reduce_partials_tall_kernel(const float 
       v[0] += t.x; v[1] += t.y; v[2] += t.z; v[3] += t.w;
     }
     T *out = s == 0 ? out0 : (s == 1 ? out1 : out2);
-    if (out) VecIO<T, 4>::store(out + n, v);
+    if (out) {
+      if (accumulate) {
+        float o[4];
+        VecIO<T, 4>::load(out + n, o);
+        v[0] += o[0]; v[1] += o[1]; v[2] += o[2]; v[3] += o[3];
+      }
+      VecIO<T, 4>::store(out + n, v);
+    }
   }
 }
 
@@ -93,7 +107,8 @@ __global__ __launch_bounds__(256) void colsum_stage1_kernel(const T *__restrict_
 }  // namespace
 
 hipError_t launch_reduce_partials(int dt, const float *partial, int P, size_t stride, size_t seglen, int nseg,
-                                  void *out0, void *out1, void *out2, hipStream_t stream) {
+                                  void *out0, void *out1, void *out2, hipStream_t stream, bool accumulate) {
+  const int acc = accumulate ? 1 : 0;
   if (!partial || P < 1 || nseg < 1 || nseg > 3 || seglen == 0 || seglen % 4 || stride % 4)
     return hipErrorInvalidValue;
   if ((size_t)nseg * seglen > stride && P > 1) return hipErrorInvalidValue;
@@ -101,26 +116,27 @@ hipError_t launch_reduce_partials(int dt, const float *partial, int P, size_t st
     dim3 tgrid((unsigned)((seglen / 4 + 63) / 64), nseg);
     if (dt == DT_F32)
       hipLaunchKernelGGL(reduce_partials_tall_kernel<float>, tgrid, dim3(1024), 0, stream, partial, P, stride, seglen,
-                         static_cast<float *>(out0), static_cast<float *>(out1), static_cast<float *>(out2));
+                         static_cast<float *>(out0), static_cast<float *>(out1), static_cast<float *>(out2), acc);
     else
       hipLaunchKernelGGL(reduce_partials_tall_kernel<bf16_t>, tgrid, dim3(1024), 0, stream, partial, P, stride,
                          seglen, static_cast<bf16_t *>(out0), static_cast<bf16_t *>(out1),
-                         static_cast<bf16_t *>(out2));
+                         static_cast<bf16_t *>(out2), acc);
     return hipGetLastError();
   }
   dim3 grid((unsigned)((seglen / 4 + 255) / 256), nseg);
   if (dt == DT_F32)
     hipLaunchKernelGGL(reduce_partials_kernel<float>, grid, dim3(256), 0, stream, partial, P, stride, seglen,
-                       static_cast<float *>(out0), static_cast<float *>(out1), static_cast<float *>(out2));
+                       static_cast<float *>(out0), static_cast<float *>(out1), static_cast<float *>(out2), acc);
   else
     hipLaunchKernelGGL(reduce_partials_kernel<bf16_t>, grid, dim3(256), 0, stream, partial, P, stride, seglen,
-                       static_cast<bf16_t *>(out0), static_cast<bf16_t *>(out1), static_cast<bf16_t *>(out2));
+                       static_cast<bf16_t *>(out0), static_cast<bf16_t *>(out1), static_cast<bf16_t *>(out2), acc);
   return hipGetLastError();
 }
 
 size_t colsum_ws_floats(int M, int N) { return (size_t)((M + CS_ROWS - 1) / CS_ROWS) * N; }
 
-hipError_t launch_colsum(int dt, const void *in, int M, int N, float *ws, void *out, hipStream_t stream) {
+hipError_t launch_colsum(int dt, const void *in, int M, int N, float *ws, void *out, hipStream_t stream,
+                         bool accumulate) {
   if (!in || !ws || !out || M < 1 || N < 1 || N % 8) return hipErrorInvalidValue;
   const int rb = (M + CS_ROWS - 1) / CS_ROWS;
   const int vec = dt == DT_F32 ? 4 : 8;
@@ -131,7 +147,7 @@ hipError_t launch_colsum(int dt, const void *in, int M, int N, float *ws, void *
     hipLaunchKernelGGL(colsum_stage1_kernel<bf16_t>, grid, dim3(256), 0, stream, static_cast<const bf16_t *>(in), M, N, ws);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  return launch_reduce_partials(dt, ws, rb, (size_t)N, (size_t)N, 1, out, nullptr, nullptr, stream);
+  return launch_reduce_partials(dt, ws, rb, (size_t)N, (size_t)N, 1, out, nullptr, nullptr, stream, accumulate);
 }
 
 }  // namespace fl
