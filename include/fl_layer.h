@@ -118,12 +118,47 @@ const char *fl_last_error(void);
  * backing_mallocs / backing_bytes: calls to and bytes obtained from the device
  * allocator so far; cache_hits / cache_misses: requests served from / not from
  * cached blocks; live_bytes: bytes handed out now; peak_bytes: its maximum;
- * cached_bytes: bytes held in free blocks; split_count: blocks split so far. */
+ * cached_bytes: bytes held in free blocks; split_count: blocks split so far;
+ * requested_bytes: what the live blocks were asked for before rounding, so
+ * 1 - requested_bytes/live_bytes is the internal fragmentation;
+ * largest_free_block / free_blocks: size of the largest and number of cached
+ * blocks, so 1 - largest_free_block/cached_bytes is the share of the cache that
+ * no single request can use (external fragmentation). */
 typedef struct {
   uint64_t backing_mallocs, backing_bytes, cache_hits, cache_misses;
   uint64_t live_bytes, peak_bytes, cached_bytes, split_count;
+  uint64_t requested_bytes, largest_free_block, free_blocks;
 } fl_alloc_stats_t;
 fl_status_t fl_alloc_get_stats(fl_alloc_stats_t *out);
+
+/* Allocation trace (Section 5.2.2: telemetry that ties individual tensor
+ * operations to specific allocations).  While enabled, every request to and
+ * release into the allocator is recorded in a ring of `capacity` events
+ * (the oldest are overwritten; capacity 0 switches the trace off; at most 2^20).
+ * tag = (position of the operator on the layer's tape << 8) | fl_op_kind_t; the
+ * release of a block carries the tag it was allocated with.
+ * fl_alloc_trace_read moves up to cap of the oldest events into the host array
+ * `out` and stores their number in *n. */
+typedef enum {
+  FL_OP_NONE = 0,
+  FL_OP_LINEAR_FWD = 1,
+  FL_OP_ATTENTION_FWD = 2,
+  FL_OP_LAYERNORM_FWD = 3,
+  FL_OP_LINEAR_BWD = 4,
+  FL_OP_ATTENTION_BWD = 5,
+  FL_OP_LAYERNORM_BWD = 6
+} fl_op_kind_t;
+typedef enum { FL_ALLOC_FROM_CACHE = 0, FL_ALLOC_FROM_DEVICE = 1, FL_ALLOC_RELEASE = 2 } fl_alloc_event_kind_t;
+typedef struct {
+  uint64_t seq;       /* running number of the event                          */
+  uint64_t ptr;       /* device address handed out / given back               */
+  uint64_t requested; /* bytes asked for (0 for a release)                    */
+  uint64_t granted;   /* size of the block                                    */
+  int32_t tag;        /* see above                                            */
+  int32_t kind;       /* fl_alloc_event_kind_t                                */
+} fl_alloc_event_t;
+fl_status_t fl_alloc_trace_enable(int32_t capacity);
+fl_status_t fl_alloc_trace_read(fl_alloc_event_t *out, int32_t cap, int32_t *n);
 
 /* Returns every cached (free) slab to the device.  Synchronises the device. */
 fl_status_t fl_alloc_trim(void);

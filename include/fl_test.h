@@ -72,6 +72,9 @@ int32_t fl_test_alloc_release(void *a, void *ptr);
 void fl_test_alloc_trim(void *a);
 void fl_test_alloc_set_split_limit(void *a, uint64_t bytes);
 void fl_test_alloc_stats(void *a, fl_alloc_stats_t *out);
+void *fl_test_alloc_alloc_tagged(void *a, uint64_t bytes, const void *stream, int32_t tag);
+void fl_test_alloc_trace_enable(void *a, int32_t capacity);
+int32_t fl_test_alloc_trace_read(void *a, fl_alloc_event_t *out, int32_t cap);
 
 /* The tape (Section 4.2) with stub gradient functions: see the definition for the arguments. */
 int32_t fl_test_tape_replay(int32_t n, const int32_t *in0, const int32_t *in1, int32_t n_input_slots, int32_t fail_at,

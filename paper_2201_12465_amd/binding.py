@@ -45,10 +45,20 @@ class fl_layer_grads_t(C.Structure):
 
 class fl_alloc_stats_t(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("backing_mallocs", "backing_bytes", "cache_hits", "cache_misses",
-                                           "live_bytes", "peak_bytes", "cached_bytes", "split_count")]
+                                           "live_bytes", "peak_bytes", "cached_bytes", "split_count",
+                                           "requested_bytes", "largest_free_block", "free_blocks")]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
+
+
+class fl_alloc_event_t(C.Structure):
+    _fields_ = [("seq", C.c_uint64), ("ptr", C.c_uint64), ("requested", C.c_uint64), ("granted", C.c_uint64),
+                ("tag", C.c_int32), ("kind", C.c_int32)]
+
+
+OP_KINDS = ("none", "linear_fwd", "attention_fwd", "layernorm_fwd", "linear_bwd", "attention_bwd", "layernorm_bwd")
+ALLOC_EVENT_KINDS = ("from_cache", "from_device", "release")
 
 
 class fl_opt_config_t(C.Structure):
@@ -87,6 +97,8 @@ def lib() -> C.CDLL:
             "fl_layer_destroy": (C.c_int, [vp]),
             "fl_last_error": (C.c_char_p, []),
             "fl_alloc_get_stats": (C.c_int, [C.POINTER(fl_alloc_stats_t)]),
+            "fl_alloc_trace_enable": (C.c_int, [i32]),
+            "fl_alloc_trace_read": (C.c_int, [C.POINTER(fl_alloc_event_t), i32, C.POINTER(i32)]),
             "fl_alloc_trim": (C.c_int, []),
             "fl_alloc_set_split_limit": (C.c_int, [u64]),
             "fl_prof_enable": (C.c_int, [C.c_uint32]),
@@ -111,6 +123,9 @@ def lib() -> C.CDLL:
             "fl_test_alloc_trim": (None, [vp]),
             "fl_test_alloc_set_split_limit": (None, [vp, u64]),
             "fl_test_alloc_stats": (None, [vp, C.POINTER(fl_alloc_stats_t)]),
+            "fl_test_alloc_alloc_tagged": (vp, [vp, u64, vp, i32]),
+            "fl_test_alloc_trace_enable": (None, [vp, i32]),
+            "fl_test_alloc_trace_read": (i32, [vp, C.POINTER(fl_alloc_event_t), i32]),
             "fl_test_tape_replay": (i32, [i32, C.POINTER(i32), C.POINTER(i32), i32, i32, C.POINTER(i32),
                                           C.POINTER(i32), C.POINTER(i32), i32]),
         }
@@ -206,6 +221,22 @@ def alloc_stats() -> dict:
     s = fl_alloc_stats_t()
     check(lib().fl_alloc_get_stats(C.byref(s)))
     return s.as_dict()
+
+
+def events_as_dicts(ev, n) -> list:
+    return [{"seq": int(e.seq), "ptr": int(e.ptr), "requested": int(e.requested), "granted": int(e.granted),
+             "op": OP_KINDS[e.tag & 0xFF], "node": e.tag >> 8, "kind": ALLOC_EVENT_KINDS[e.kind]} for e in ev[:n]]
+
+
+def alloc_trace_enable(capacity: int) -> None:
+    check(lib().fl_alloc_trace_enable(capacity))
+
+
+def alloc_trace_read(cap: int = 4096) -> list:
+    ev = (fl_alloc_event_t * cap)()
+    n = C.c_int32(0)
+    check(lib().fl_alloc_trace_read(ev, cap, C.byref(n)))
+    return events_as_dicts(ev, n.value)
 
 
 def alloc_trim() -> None:

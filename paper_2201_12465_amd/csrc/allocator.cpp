@@ -27,10 +27,11 @@ void CachingAllocator::free_erase(Block *b) {
   b->free = false;
 }
 
-void *CachingAllocator::alloc(size_t bytes, const void *stream) {
+void *CachingAllocator::alloc(size_t bytes, const void *stream, int tag) {
   std::lock_guard<std::mutex> g(mu_);
   size_t need = round_up(bytes ? bytes : 1, kAlign);
   Block *b = nullptr;
+  bool from_backing = false;
   // best fit among this stream's cached blocks
   auto it = free_map_.lower_bound(Key(stream, need));
   if (it != free_map_.end() && it->first.first == stream) {
@@ -53,6 +54,7 @@ void *CachingAllocator::alloc(size_t bytes, const void *stream) {
       if (bmalloc_(&p, slab) != 0 || !p) return nullptr;
     }
     st_.backing_mallocs++;
+    from_backing = true;
     st_.backing_bytes += slab;
     slabs_[p] = slab;
     b = new Block{static_cast<char *>(p), slab, false, stream, nullptr, nullptr, p};
@@ -68,8 +70,13 @@ void *CachingAllocator::alloc(size_t bytes, const void *stream) {
     st_.split_count++;
   }
   b->stream = stream;
+  b->requested = bytes;
+  b->tag = tag;
   live_[b->ptr] = b;
   st_.live_bytes += b->size;
+  st_.requested_bytes += bytes;
+  if (trace_cap_)
+    trace_push(AllocEvent{0, reinterpret_cast<uint64_t>(b->ptr), bytes, b->size, tag, from_backing ? 1 : 0});
   if (st_.live_bytes > st_.peak_bytes) st_.peak_bytes = st_.live_bytes;
   return b->ptr;
 }
@@ -81,6 +88,8 @@ bool CachingAllocator::release(void *ptr) {
   Block *b = it->second;
   live_.erase(it);
   st_.live_bytes -= b->size;
+  st_.requested_bytes -= b->requested;
+  if (trace_cap_) trace_push(AllocEvent{0, reinterpret_cast<uint64_t>(b->ptr), 0, b->size, b->tag, 2});
   // merge with free neighbours that belong to the same stream
   if (b->next && b->next->free && b->next->stream == b->stream) {
     Block *n = b->next;
@@ -116,6 +125,43 @@ void CachingAllocator::trim_locked() {
     slabs_.erase(b->slab);
     delete b;
   }
+}
+
+AllocStats CachingAllocator::stats() const {
+  std::lock_guard<std::mutex> g(mu_);
+  AllocStats s = st_;
+  s.free_blocks = free_map_.size();
+  s.largest_free_block = 0;
+  for (const auto &kv : free_map_)
+    if (kv.first.second > s.largest_free_block) s.largest_free_block = kv.first.second;
+  return s;
+}
+
+void CachingAllocator::trace_push(const AllocEvent &e) {
+  AllocEvent ev = e;
+  ev.seq = seq_++;
+  const size_t pos = (trace_head_ + trace_count_) % trace_cap_;
+  trace_[pos] = ev;
+  if (trace_count_ < trace_cap_) trace_count_++;
+  else trace_head_ = (trace_head_ + 1) % trace_cap_;  // the oldest entry is overwritten
+}
+
+void CachingAllocator::trace_enable(size_t capacity) {
+  std::lock_guard<std::mutex> g(mu_);
+  trace_.assign(capacity, AllocEvent{});
+  trace_cap_ = capacity;
+  trace_head_ = trace_count_ = 0;
+}
+
+size_t CachingAllocator::trace_read(AllocEvent *out, size_t cap) {
+  std::lock_guard<std::mutex> g(mu_);
+  size_t n = 0;
+  while (n < cap && trace_count_ > 0) {
+    out[n++] = trace_[trace_head_];
+    trace_head_ = (trace_head_ + 1) % trace_cap_;
+    trace_count_--;
+  }
+  return n;
 }
 
 void CachingAllocator::trim() {

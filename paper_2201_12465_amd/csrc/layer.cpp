@@ -146,8 +146,16 @@ namespace {
     if (rc_) return rc_;    \
   } while (0)
 
+// Operator on whose behalf this thread allocates right now: (tape position << 8) | fl_op_kind_t.
+thread_local int g_op_tag = 0;
+struct OpTag {
+  int saved;
+  OpTag(int kind, int node) : saved(g_op_tag) { g_op_tag = (node << 8) | kind; }
+  ~OpTag() { g_op_tag = saved; }
+};
+
 Buf *buf_new(size_t bytes, hipStream_t s) {
-  void *p = device_allocator().alloc(bytes, s);
+  void *p = device_allocator().alloc(bytes, s, g_op_tag);
   if (!p) return nullptr;
   Buf *b = new (std::nothrow) Buf();
   if (!b) {
@@ -208,6 +216,7 @@ const LinearShape kLinear[4] = {{P_WQKV, P_BQKV}, {P_WO, P_BO}, {P_W1, P_B1}, {P
 int linear_backward(void *ctx, Tape *tape, const Node *n) {
   fl_layer *L = static_cast<fl_layer *>(ctx);
   const int self = tape->index_of(n);
+  OpTag tag(FL_OP_LINEAR_BWD, self);
   hipStream_t st = L->stream;
   Slot &ys = tape->slots[n->out];
   const int M = n->rows, K = n->n_in, N = n->n_out, dt = L->dt;
@@ -299,6 +308,7 @@ int linear_backward(void *ctx, Tape *tape, const Node *n) {
 int attention_backward(void *ctx, Tape *tape, const Node *n) {
   fl_layer *L = static_cast<fl_layer *>(ctx);
   const int self = tape->index_of(n);
+  OpTag tag(FL_OP_ATTENTION_BWD, self);
   hipStream_t st = L->stream;
   Slot &os = tape->slots[n->out], &qs = tape->slots[n->in0];
   const int D = L->cfg.d_model, H = L->cfg.n_heads, dh = D / H, M = L->M;
@@ -335,6 +345,7 @@ int attention_backward(void *ctx, Tape *tape, const Node *n) {
 int layernorm_backward(void *ctx, Tape *tape, const Node *n) {
   fl_layer *L = static_cast<fl_layer *>(ctx);
   const int self = tape->index_of(n);
+  OpTag tag(FL_OP_LAYERNORM_BWD, self);
   hipStream_t st = L->stream;
   Slot &ys = tape->slots[n->out], &xs = tape->slots[n->in0];
   const int D = L->cfg.d_model, M = L->M, dt = L->dt;
@@ -385,6 +396,7 @@ int layernorm_backward(void *ctx, Tape *tape, const Node *n) {
 // y = x W^T + b, optional activation (records the request for its derivative on y) and residual.
 int op_linear(fl_layer *L, int lin, int xslot, int rslot, int act, int K, int N, void *y_ext, int *yslot) {
   Tape &tp = L->tape;
+  OpTag tag(FL_OP_LINEAR_FWD, (int)tp.nodes.size());
   hipStream_t st = L->stream;
   const int M = L->M, dt = L->dt;
   const size_t e = esize(L);
@@ -440,6 +452,7 @@ int op_linear(fl_layer *L, int lin, int xslot, int rslot, int act, int K, int N,
 
 int op_attention(fl_layer *L, int qslot, int *oslot) {
   Tape &tp = L->tape;
+  OpTag tag(FL_OP_ATTENTION_FWD, (int)tp.nodes.size());
   hipStream_t st = L->stream;
   const int D = L->cfg.d_model, H = L->cfg.n_heads, dh = D / H, M = L->M;
   const size_t e = esize(L);
@@ -477,6 +490,7 @@ int op_attention(fl_layer *L, int qslot, int *oslot) {
 
 int op_layernorm(fl_layer *L, int which, int xslot, void *y_ext, int *yslot) {
   Tape &tp = L->tape;
+  OpTag tag(FL_OP_LAYERNORM_FWD, (int)tp.nodes.size());
   hipStream_t st = L->stream;
   const int D = L->cfg.d_model, M = L->M;
   const size_t e = esize(L);
@@ -726,6 +740,26 @@ fl_status_t fl_alloc_get_stats(fl_alloc_stats_t *out) {
   out->cache_hits = s.cache_hits; out->cache_misses = s.cache_misses;
   out->live_bytes = s.live_bytes; out->peak_bytes = s.peak_bytes;
   out->cached_bytes = s.cached_bytes; out->split_count = s.split_count;
+  out->requested_bytes = s.requested_bytes; out->largest_free_block = s.largest_free_block;
+  out->free_blocks = s.free_blocks;
+  return FL_OK;
+  FL_GUARD_END
+}
+
+fl_status_t fl_alloc_trace_enable(int32_t capacity) {
+  FL_GUARD_BEGIN
+  if (capacity < 0 || capacity > (1 << 20))
+    return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "trace capacity %d outside [0, 2^20]", capacity);
+  device_allocator().trace_enable((size_t)capacity);
+  return FL_OK;
+  FL_GUARD_END
+}
+
+fl_status_t fl_alloc_trace_read(fl_alloc_event_t *out, int32_t cap, int32_t *n) {
+  FL_GUARD_BEGIN
+  if (!out || !n || cap < 0) return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "null argument or negative capacity");
+  static_assert(sizeof(fl_alloc_event_t) == sizeof(AllocEvent), "the two event records must have one layout");
+  *n = (int32_t)device_allocator().trace_read(reinterpret_cast<AllocEvent *>(out), (size_t)cap);
   return FL_OK;
   FL_GUARD_END
 }

@@ -160,6 +160,18 @@ void fl_test_alloc_stats(void *a, fl_alloc_stats_t *out) {
   out->cache_hits = s.cache_hits; out->cache_misses = s.cache_misses;
   out->live_bytes = s.live_bytes; out->peak_bytes = s.peak_bytes;
   out->cached_bytes = s.cached_bytes; out->split_count = s.split_count;
+  out->requested_bytes = s.requested_bytes; out->largest_free_block = s.largest_free_block;
+  out->free_blocks = s.free_blocks;
+}
+void *fl_test_alloc_alloc_tagged(void *a, uint64_t bytes, const void *stream, int32_t tag) {
+  return static_cast<CachingAllocator *>(a)->alloc((size_t)bytes, stream, tag);
+}
+void fl_test_alloc_trace_enable(void *a, int32_t capacity) {
+  static_cast<CachingAllocator *>(a)->trace_enable(capacity > 0 ? (size_t)capacity : 0);
+}
+int32_t fl_test_alloc_trace_read(void *a, fl_alloc_event_t *out, int32_t cap) {
+  static_assert(sizeof(fl_alloc_event_t) == sizeof(AllocEvent), "the two event records must have one layout");
+  return (int32_t)static_cast<CachingAllocator *>(a)->trace_read(reinterpret_cast<AllocEvent *>(out), cap > 0 ? (size_t)cap : 0);
 }
 
 // ---- tape with stub operators -------------------------------------------------------------

@@ -217,6 +217,49 @@ def test_steady_state_has_no_device_mallocs_and_is_deterministic():
             assert np.array_equal(o[2][k], outs[0][2][k]), k
 
 
+def test_allocation_trace_names_the_operator_of_every_buffer():
+    """Section 5.2.2 telemetry: each intermediate buffer of one forward + backward is tied to the
+    operator that asked for it, and everything handed out comes back."""
+    from paper_2201_12465_amd import binding as b
+    cfg = CONFIGS["cfg2_small_f32"]
+    inp = make_inputs(cfg, seed=0)
+    layer = b.Layer(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F, cfg.act, cfg.norm, cfg.dtype, cfg.eps)
+    run_layer_gpu(cfg, inp, layer=layer)                  # warm the cache
+    b.alloc_trace_enable(1024)
+    try:
+        run_layer_gpu(cfg, inp, layer=layer)
+        ev = b.alloc_trace_read(1024)
+    finally:
+        b.alloc_trace_enable(0)
+        layer.destroy()
+    allocs = [e for e in ev if e["kind"] != "release"]
+    assert allocs and all(e["kind"] == "from_cache" for e in allocs)       # steady state: no device allocation
+    assert all(e["op"] != "none" for e in allocs)
+    fwd = [e for e in allocs if e["op"].endswith("_fwd")]
+    M, el = cfg.B * cfg.T, 4
+    # forward, post-LN with ReLU: qkv, attention output, out-projection, LN1, the two feed-forward linears
+    # (LN2 writes the caller's Y); the log-sum-exp and LayerNorm statistics are the smaller buffers
+    assert [(e["op"], e["node"]) for e in fwd if e["requested"] >= M * cfg.D * el] == [
+        ("linear_fwd", 0), ("attention_fwd", 1), ("linear_fwd", 2), ("layernorm_fwd", 3),
+        ("linear_fwd", 4), ("linear_fwd", 5)]
+    assert fwd[0]["requested"] == M * 3 * cfg.D * el
+    assert [e["requested"] for e in fwd if e["node"] == 4] == [M * cfg.F * el]
+    assert sorted(e["requested"] for e in fwd if e["requested"] < M * cfg.D * el) == sorted(
+        [cfg.B * cfg.H * cfg.T * 4, 2 * M * 4, 2 * M * 4])
+    assert {e["op"] for e in allocs} >= {"linear_bwd", "attention_bwd", "layernorm_bwd"}
+    # every block handed out during the traced pass is given back during it, under the tag it was handed out with
+    open_ = {}
+    for e in ev:
+        if e["kind"] == "release":
+            if e["ptr"] in open_:
+                a = open_.pop(e["ptr"])
+                assert (a["op"], a["node"]) == (e["op"], e["node"]) and a["granted"] == e["granted"]
+        else:
+            assert e["ptr"] not in open_ and e["granted"] >= e["requested"]
+            open_[e["ptr"]] = e
+    assert open_ == {}
+
+
 def test_error_paths():
     from paper_2201_12465_amd import binding as b
     cfg = CONFIGS["cfg1_tiny_f32"]

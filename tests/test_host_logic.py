@@ -196,6 +196,95 @@ def test_allocator_trim_and_out_of_memory():
     lib.fl_test_alloc_destroy(a)
 
 
+def test_allocator_fragmentation_figures(alloc):
+    lib, a, store, stats = alloc
+    p = lib.fl_test_alloc_alloc(a, 5 * MB + 1, None)            # rounded up to 512 bytes, slab to 2 MiB
+    s = stats()
+    assert s["requested_bytes"] == 5 * MB + 1 and s["live_bytes"] == 5 * MB + 512
+    assert s["free_blocks"] == 1 and s["largest_free_block"] == MB - 512 == s["cached_bytes"]
+    q = lib.fl_test_alloc_alloc(a, 3 * MB, None)                # does not fit the rest: a 4 MiB slab of its own
+    lib.fl_test_alloc_release(a, p)                             # merges with the rest of its slab
+    s = stats()
+    assert s["requested_bytes"] == 3 * MB and s["live_bytes"] == 3 * MB
+    assert s["free_blocks"] == 2 and s["largest_free_block"] == 6 * MB and s["cached_bytes"] == 7 * MB
+    lib.fl_test_alloc_release(a, q)
+    s = stats()
+    assert s["requested_bytes"] == 0 and s["free_blocks"] == 2 and s["largest_free_block"] == 6 * MB
+    assert s["cached_bytes"] == 10 * MB == s["backing_bytes"]
+
+
+def test_allocator_trace_ties_operators_to_allocations(alloc):
+    lib, a, store, stats = alloc
+
+    def read(cap=64):
+        ev = (b.fl_alloc_event_t * cap)()
+        return b.events_as_dicts(ev, lib.fl_test_alloc_trace_read(a, ev, cap))
+
+    x = lib.fl_test_alloc_alloc_tagged(a, 4 * MB, None, (3 << 8) | 1)
+    assert read() == []                                          # nothing is recorded while the trace is off
+    lib.fl_test_alloc_trace_enable(a, 8)
+    y = lib.fl_test_alloc_alloc_tagged(a, 6 * MB - 100, None, (5 << 8) | 4)
+    lib.fl_test_alloc_release(a, x)
+    z = lib.fl_test_alloc_alloc_tagged(a, 4 * MB, None, (7 << 8) | 6)
+    ev = read()
+    assert [e["kind"] for e in ev] == ["from_device", "release", "from_cache"]
+    assert [(e["op"], e["node"]) for e in ev] == [("linear_bwd", 5), ("linear_fwd", 3), ("layernorm_bwd", 7)]
+    assert ev[0]["ptr"] == y and ev[0]["requested"] == 6 * MB - 100 and ev[0]["granted"] == 6 * MB
+    assert ev[1]["ptr"] == x and ev[1]["requested"] == 0 and ev[1]["granted"] == 4 * MB
+    assert ev[2]["ptr"] == z == x                                # the released block serves the next operator
+    assert [e["seq"] for e in ev] == [0, 1, 2]
+    assert read() == []                                          # reading drains the ring
+    # the ring keeps the newest `capacity` events
+    ps = [lib.fl_test_alloc_alloc_tagged(a, 1 * MB, None, i << 8) for i in range(12)]
+    ev = read()
+    assert len(ev) == 8 and [e["node"] for e in ev] == list(range(4, 12))
+    assert [e["seq"] for e in ev] == list(range(7, 15))
+    lib.fl_test_alloc_trace_enable(a, 0)
+    for p in ps + [y, z]:
+        lib.fl_test_alloc_release(a, p)
+    assert read() == []
+
+
+def _replay_requests(lib, a, store, requests):
+    """requests: ('a', key, bytes) / ('r', key).  Returns bytes obtained from the backing store."""
+    live = {}
+    for r in requests:
+        if r[0] == "a":
+            live[r[1]] = lib.fl_test_alloc_alloc(a, r[2], None)
+            assert live[r[1]]
+        else:
+            assert lib.fl_test_alloc_release(a, live.pop(r[1])) == 0
+    for p in live.values():
+        lib.fl_test_alloc_release(a, p)
+    return sum(store.live.values())
+
+
+def test_split_limit_reduces_fragmentation_on_mixed_sizes():
+    """Section 5.2.2's finding on a request stream with its cause in it: a large activation buffer is
+    freed, long-lived small buffers are then carved out of it, and the next iteration's large request
+    no longer fits the carved block, so the device is asked for more memory.  With a split limit the
+    large block stays whole and the total taken from the device is smaller."""
+    lib = b.lib()
+    seq = []
+    for it in range(4):
+        seq.append(("a", ("big", it), 96 * MB))
+        seq.append(("r", ("big", it)))
+        for j in range(3):                                        # small buffers that outlive the iteration
+            seq.append(("a", ("small", it, j), 3 * MB))
+    taken = {}
+    for limit in (0, 32 * MB):
+        store = FakeStore()
+        a = lib.fl_test_alloc_create(store.m, store.f)
+        lib.fl_test_alloc_set_split_limit(a, limit)
+        taken[limit] = _replay_requests(lib, a, store, seq)
+        s = b.fl_alloc_stats_t()
+        lib.fl_test_alloc_stats(a, C.byref(s))
+        assert s.live_bytes == 0 and s.cached_bytes == taken[limit]
+        lib.fl_test_alloc_destroy(a)
+    assert taken[0] == 2 * 96 * MB                               # the carved slab forces a second large one
+    assert taken[32 * MB] == 96 * MB + 12 * 4 * MB               # one large slab, a 4 MiB slab per small buffer
+
+
 def _replay(in0, in1, n_inputs, fail_at=-1):
     lib = b.lib()
     n = len(in0)
