@@ -8,6 +8,13 @@ class that takes the most time (measured with HIP events on the launch stream in
 second pass of the same steps), and the fp64 CPU oracle timed on the host cores.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+roofline.traffic cannot be measured from inside the process (the HBM byte counters need
+rocprofv3 around it); it is read from the committed summary profiles/layer_<workload>_hbm_traffic.txt
+of two counter runs of this same command (written by `python -m paper_2201_12465_amd.profile_summary
+traffic ...`, which also gives the commands) and is null when no summary exists for the workload.
+`--copy-calibration` runs only the library's plain copy kernel over a known size: the kernel those
+counters are scaled by.
 """
 import argparse
 import json
@@ -21,6 +28,34 @@ sys.path.insert(0, ROOT)
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense MFMA peaks
 PEAK_HBM_GBS = 8000.0
 MFMA_CLASSES = ("gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd")
+COPY_BYTES = 256 << 20
+
+
+def stored_traffic(workload: str, kernel_class: str):
+    """HBM bytes per launch of one kernel class from the committed counter summary, or None."""
+    path = os.path.join(ROOT, "profiles", f"layer_{workload}_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None, None
+    for line in open(path):
+        f = line.split()
+        if len(f) >= 4 and f[0] == "traffic" and f[1] == kernel_class and f[2] == "bytes_per_launch":
+            return float(f[3]), os.path.relpath(path, ROOT)
+    return None, None
+
+
+def copy_run(b, torch, stream, launches: int):
+    """`launches` plain copies of COPY_BYTES; returns GB/s of read + written bytes."""
+    src = torch.ones(COPY_BYTES // 4, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    b.check(b.lib().fl_test_copy(src.data_ptr(), dst.data_ptr(), COPY_BYTES, stream))
+    e0.record()
+    for _ in range(launches):
+        b.check(b.lib().fl_test_copy(src.data_ptr(), dst.data_ptr(), COPY_BYTES, stream))
+    e1.record()
+    torch.cuda.synchronize()
+    assert bool((dst[:: 1 << 16] == 1).all())
+    return 2.0 * COPY_BYTES * launches / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
 def main() -> int:
@@ -32,6 +67,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the second, event-instrumented pass (used under rocprofv3)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only 5 launches of the plain copy kernel over 256 MiB (counter calibration)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
@@ -46,6 +83,11 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     b.lib()   # fails loudly if the HIP library has not been built
+    if a.copy_calibration:
+        gbs = copy_run(b, torch, torch.cuda.current_stream().cuda_stream, 4)
+        print(json.dumps({"copy_kernel": "copy_kernel", "bytes_read": COPY_BYTES, "bytes_written": COPY_BYTES,
+                          "launches": 5, "gbs": gbs}))
+        return 0
     cfg = CONFIGS[a.workload]
     tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
     dev = lambda x: torch.from_numpy(np.ascontiguousarray(x, np.float32)).cuda().to(tdt).contiguous()
@@ -111,11 +153,13 @@ def main() -> int:
         kernels = {}
         for name, e in prof.items():
             flops = e["flops"] * (mask_scale if name.startswith("attn") else 1.0)   # library counts dense attention
-            us = e["total_ms"] * 1e3 / e["launches"]
+            us = e["total_ms"] * 1e3 / e["launches"]    # event bracket: the kernel plus a few microseconds
             kernels[name] = {"launches_per_step": e["launches"] / ksteps, "avg_us": us,
                              "ms_per_step": e["total_ms"] / ksteps,
                              "tflops": flops / e["total_ms"] / 1e9 if flops else None,
                              "gbs": e["bytes"] / e["total_ms"] / 1e6}
+        # what a bracket with no kernel in it reads (an upper bound of the part of avg_us that is not the kernel)
+        out["event_bracket_empty_us"] = next(iter(prof.values()))["empty_bracket_ms"] * 1e3 if prof else None
         dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
         k = kernels[dom]
         if dom in MFMA_CLASSES:
@@ -125,8 +169,13 @@ def main() -> int:
         else:
             roof = {"kernel": dom, "bound": "hbm", "achieved": k["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": k["gbs"] / PEAK_HBM_GBS, "traffic": None, "avg_us": k["avg_us"]}
+        roof["traffic"], src = stored_traffic(cfg.name, dom)
+        if src:
+            roof["traffic_source"] = src
+            roof["algorithmic_bytes_per_launch"] = k["gbs"] * 1e9 * k["avg_us"] * 1e-6
         out["roofline"] = roof
         out["kernels"] = kernels
+        out["hbm_copy_gbs"] = copy_run(b, torch, stream, 10)   # what a plain copy reaches on this GPU
 
     # ---- the fused optimizer step (NOT part of `value`: the metric is the layer's forward + backward)
     if not a.no_kernel_timing:
@@ -168,7 +217,7 @@ def main() -> int:
         lens = inp["lengths"][sl] if L is not None else None
         t0 = time.perf_counter()
         reps = 0
-        while reps < 1 or (time.perf_counter() - t0 < 8.0 and reps < 3):
+        while reps < 1 or (time.perf_counter() - t0 < 10.0 and reps < 20):
             orc.layer_forward_backward(plist[0], inp["X"][sl], inp["dY"][sl], lens, **kw)
             reps += 1
         cs = (time.perf_counter() - t0) / reps

@@ -195,7 +195,10 @@ fl_status_t fl_zero_grad(fl_dtype_t dtype, int32_t n, void *const *grads, const 
  * events on the caller's stream.  fl_prof_collect() synchronises those events
  * and fills `out` (host array of `cap` entries) with one entry per kernel class
  * seen: launches, total milliseconds, algorithmic flops and bytes summed over
- * the launches.  Returns the number of entries through *n. */
+ * the launches, and empty_bracket_ms: what a pair of events reads on that stream
+ * with no kernel between them (the same figure in every entry; each bracket's
+ * reading exceeds its kernel's duration by about this much).  Returns the number
+ * of entries through *n. */
 typedef enum {
   FL_K_GEMM_NT = 0,   /* y = x W^T (+bias, +activation, +residual)           */
   FL_K_GEMM_NN = 1,   /* dx = dy W (+activation derivative, +skip gradient)  */
@@ -211,7 +214,7 @@ typedef enum {
 typedef struct {
   int32_t kernel_class;
   int32_t launches;
-  double total_ms, flops, bytes;
+  double total_ms, flops, bytes, empty_bracket_ms;
 } fl_prof_entry_t;
 fl_status_t fl_prof_enable(uint32_t class_mask); /* bit i = class i; 0 disables and drops pending events */
 fl_status_t fl_prof_collect(fl_prof_entry_t *out, int32_t cap, int32_t *n);

@@ -51,6 +51,10 @@ int32_t fl_test_layernorm_bwd(int32_t dtype, const void *dy, const void *x, cons
 int64_t fl_test_colsum_ws_floats(int32_t M, int32_t N);
 int32_t fl_test_colsum(int32_t dtype, const void *in, int32_t M, int32_t N, float *ws, void *out, void *hip_stream);
 
+/* dst = src for nbytes (a multiple of 16): a plain copy kernel of known traffic (nbytes read, nbytes
+ * written), against which the HBM byte counters are calibrated and copy bandwidth is measured. */
+int32_t fl_test_copy(const void *src, void *dst, uint64_t nbytes, void *hip_stream);
+
 /* Masked scaled-dot-product attention on qkv[B*T, 3*H*dh]; lse and delta are fp32 [B,H,T]. */
 int32_t fl_test_attention_fwd(int32_t dtype, const void *qkv, const int32_t *lengths, int32_t B, int32_t T, int32_t H,
                               int32_t dh, void *o, float *lse, void *hip_stream);

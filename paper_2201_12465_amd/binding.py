@@ -68,7 +68,7 @@ class fl_opt_config_t(C.Structure):
 
 class fl_prof_entry_t(C.Structure):
     _fields_ = [("kernel_class", C.c_int32), ("launches", C.c_int32), ("total_ms", C.c_double),
-                ("flops", C.c_double), ("bytes", C.c_double)]
+                ("flops", C.c_double), ("bytes", C.c_double), ("empty_bracket_ms", C.c_double)]
 
 
 BACKING_MALLOC = C.CFUNCTYPE(C.c_int, C.POINTER(C.c_void_p), C.c_size_t)
@@ -111,6 +111,7 @@ def lib() -> C.CDLL:
             "fl_test_layernorm_fwd": (i32, [i32, vp, vp, vp, f32, i32, i32, vp, vp, vp, vp]),
             "fl_test_layernorm_bwd_ws_floats": (i32, [i32, i32]),
             "fl_test_layernorm_bwd": (i32, [i32, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp]),
+            "fl_test_copy": (i32, [vp, vp, u64, vp]),
             "fl_test_colsum_ws_floats": (i64, [i32, i32]),
             "fl_test_colsum": (i32, [i32, vp, i32, i32, vp, vp, vp]),
             "fl_test_attention_fwd": (i32, [i32, vp, vp, i32, i32, i32, i32, vp, vp, vp]),
@@ -263,5 +264,6 @@ def prof_collect() -> dict:
     n = C.c_int32(0)
     check(lib().fl_prof_collect(arr, len(KERNEL_CLASSES), C.byref(n)))
     return {KERNEL_CLASSES[arr[i].kernel_class]: {"launches": arr[i].launches, "total_ms": arr[i].total_ms,
-                                                  "flops": arr[i].flops, "bytes": arr[i].bytes}
+                                                  "flops": arr[i].flops, "bytes": arr[i].bytes,
+                                                  "empty_bracket_ms": arr[i].empty_bracket_ms}
             for i in range(n.value)}

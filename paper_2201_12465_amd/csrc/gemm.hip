@@ -122,12 +122,9 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(GemmDev p) {
   T *ldsA = reinterpret_cast<T *>(smem);
   T *ldsB = reinterpret_cast<T *>(smem + OPERAND_LDS_BYTES);
 
-  // XCD-aware tile order: ids 0,8,16,.. land on XCD 0, which gets the first contiguous range
-  const int nb = p.tiles_m * p.tiles_n;
-  const int bid = blockIdx.x;
-  const int xcd = bid & 7, idx = bid >> 3, per = nb >> 3, rem = nb & 7;
-  const int logical = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
-  const int row0 = (logical / p.tiles_n) * BMT, col0 = (logical % p.tiles_n) * BN;
+  int tile_m, tile_n;
+  xcd_tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, 1024 / BMT, tile_m, tile_n);
+  const int row0 = tile_m * BMT, col0 = tile_n * BN;
 
   const int kbeg = blockIdx.z * p.k_per_split;
   const int kend = min(p.K, kbeg + p.k_per_split);

@@ -155,4 +155,17 @@ __device__ __forceinline__ int xcd_tile_order(int bid, int nb) {
   return (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
 }
 
+// Tile (tm, tn) of workgroup `bid`.  Each XCD has its own L2 and takes a contiguous range of a tile
+// order with two-dimensional locality: row-tiles are taken in groups of `gm`, and inside a group the
+// order runs down the group's rows before it moves to the next column, so the tiles an XCD works
+// on at one time share few operand panels and those stay in its L2.
+__device__ __forceinline__ void xcd_tile_coords(int bid, int tiles_m, int tiles_n, int gm, int &tm, int &tn) {
+  const int id = xcd_tile_order(bid, tiles_m * tiles_n);
+  const int per_group = gm * tiles_n;
+  const int g = id / per_group, r = id - g * per_group;
+  const int rows = min(gm, tiles_m - g * gm);  // the last group may be shorter
+  tn = r / rows;
+  tm = g * gm + (r - tn * rows);
+}
+
 }  // namespace fl

@@ -93,8 +93,9 @@ __global__ __launch_bounds__(NTHR) void gemm_bf16_pipe(GemmDev p) {
   constexpr int OPS = Stager<AKC, BM>::NOPS + Stager<BKC, BN>::NOPS;  // loads per wave per k-tile
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
-  const int logical = xcd_tile_order(blockIdx.x, p.tiles_m * p.tiles_n);
-  const int row0 = (logical / p.tiles_n) * BM, col0 = (logical % p.tiles_n) * BN;
+  int tile_m, tile_n;
+  xcd_tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, 1024 / BM, tile_m, tile_n);
+  const int row0 = tile_m * BM, col0 = tile_n * BN;
   const int kbeg = blockIdx.z * p.k_per_split;
   const int kend = min(p.K, kbeg + p.k_per_split);
   const int nk = (kend - kbeg) / KT;

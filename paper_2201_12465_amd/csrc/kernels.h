@@ -58,6 +58,9 @@ size_t colsum_ws_floats(int M, int N);
 hipError_t launch_colsum(int dt, const void *in, int M, int N, float *ws, void *out, hipStream_t stream,
                          bool accumulate = false);
 
+// dst[0..nbytes) = src[0..nbytes): nbytes % 16 == 0, both pointers 16-byte aligned.
+hipError_t launch_copy(const void *src, void *dst, size_t nbytes, hipStream_t stream);
+
 // ---------------------------------------------------------------------------
 // LayerNorm over the last dimension D of x[M,D] (biased variance, eps inside the
 // square root).  Forward writes y and the per-row mean / reciprocal std (fp32).

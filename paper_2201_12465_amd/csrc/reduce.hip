@@ -150,4 +150,23 @@ hipError_t launch_colsum(int dt, const void *in, int M, int N, float *ws, void *
   return launch_reduce_partials(dt, ws, rb, (size_t)N, (size_t)N, 1, out, nullptr, nullptr, stream, accumulate);
 }
 
+// Plain copy of nbytes (a multiple of 16; 16-byte aligned): the reference for what one read plus one
+// write of a buffer costs, and the known-size kernel the HBM byte counters are calibrated against.
+namespace {
+__global__ __launch_bounds__(256) void copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n16) {
+  const size_t step = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += step) dst[i] = src[i];
+}
+}  // namespace
+
+hipError_t launch_copy(const void *src, void *dst, size_t nbytes, hipStream_t stream) {
+  if (!src || !dst || nbytes % 16 || ((uintptr_t)src | (uintptr_t)dst) % 16) return hipErrorInvalidValue;
+  if (nbytes == 0) return hipSuccess;
+  const size_t n16 = nbytes / 16;
+  const size_t want = (n16 + 256 * 4 - 1) / (256 * 4);  // about four 16-byte pieces per lane
+  const int grid = (int)(want < 1 ? 1 : (want > 256 * 32 ? 256 * 32 : want));
+  copy_kernel<<<grid, 256, 0, stream>>>(static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), n16);
+  return hipGetLastError();
+}
+
 }  // namespace fl

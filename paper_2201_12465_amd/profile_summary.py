@@ -1,0 +1,155 @@
+"""Turns rocprofv3 output of bench.py into the short text summaries kept with the measurements.
+
+    python -m paper_2201_12465_amd.profile_summary kernel-trace <dir> [--workload NAME] > summary.txt
+    python -m paper_2201_12465_amd.profile_summary traffic <bench_fetch_dir> <bench_write_dir> \
+           <copy_fetch_dir> <copy_write_dir> [--workload NAME] > summary.txt
+
+kernel-trace: <dir> is the -d directory of
+    rocprofv3 --kernel-trace --stats --output-format csv -d <dir> -- python3 bench.py ...
+traffic: the four directories come from `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` (one
+counter per run) around `python3 bench.py --no-kernel-timing --no-cpu-baseline ...` and around
+`python3 bench.py --copy-calibration`.  The counters are in KiB per dispatch; each is scaled by
+(bytes the plain copy kernel is known to move) / (what the same counter reads for it), and the
+per-class lines `traffic <class> bytes_per_launch <bytes>` are what bench.py reports as
+roofline.traffic.  Only text parsing happens here: nothing touches the GPU.
+"""
+import argparse
+import collections
+import csv
+import glob
+import re
+import sys
+
+COPY_BYTES = 256 << 20
+
+
+def classify(name: str) -> str:
+    """Kernel class (as in fl_kernel_class_t) of a kernel name, mangled or demangled."""
+    n = name
+    if "copy_kernel" in n:
+        return "copy"
+    if "gemm_bf16_pipe" in n:
+        m = re.search(r"gemm_bf16_pipe(?:<|ILb)(true|false|1|0)(?:, |ELb)(true|false|1|0)", n)
+        if m:
+            a, bb = (x in ("true", "1") for x in m.groups())
+            return {(True, True): "gemm_nt", (True, False): "gemm_nn", (False, False): "gemm_tn"}.get((a, bb), "gemm")
+        return "gemm_nt"
+    if "gemm_kernel" in n:
+        m = re.search(r"gemm_kernelI\w+?Lb([01])ELb([01])E", n)
+        if m:
+            a, bb = m.group(1) == "1", m.group(2) == "1"
+        else:  # demangled; the element type may be printed oddly, the two booleans follow it
+            bools = re.findall(r"\b(true|false)\b", n)
+            # some demanglers swallow the first boolean of <T, true, false, h>: then one is left
+            a, bb = (bools[0] == "true", bools[1] == "true") if len(bools) >= 2 else (True, bools[0] == "true")
+        return {(True, True): "gemm_nt", (True, False): "gemm_nn", (False, False): "gemm_tn"}.get((a, bb), "gemm")
+    table = (("reduce_partials", "splitk_reduce"), ("colsum", "colsum"), ("attn_fwd", "attn_fwd"),
+             ("attn_bwd", "attn_bwd"), ("attn_delta", "attn_bwd"), ("ln_fwd", "ln_fwd"), ("ln_bwd", "ln_bwd"),
+             ("opt_step", "optimizer"), ("zero_tensors", "optimizer"))
+    for key, cls in table:
+        if key in n:
+            return cls
+    return "other"
+
+
+def ours(name: str) -> bool:
+    return "fl::" in name or "_ZN2fl" in name
+
+
+def short(name: str, width: int = 72) -> str:
+    n = name.replace("void ", "").replace("fl::(anonymous namespace)::", "").replace("_ZN2fl12_GLOBAL__N_1", "")
+    return n[:width]
+
+
+def kernel_trace(args) -> int:
+    files = glob.glob(args.dir + "/**/*kernel_stats.csv", recursive=True)
+    if not files:
+        print(f"no *kernel_stats.csv under {args.dir}", file=sys.stderr)
+        return 1
+    rows = [r for r in csv.DictReader(open(files[0])) if ours(r["Name"])]
+    total = sum(float(r["TotalDurationNs"]) for r in rows)
+    print("# made by (from /tmp, TMPDIR=/tmp, on one MI355X):")
+    print(f"#   rocprofv3 --kernel-trace --stats --output-format csv -d <dir> -- python3 bench.py "
+          f"--workload {args.workload} --steps 50 --warmup 10 --no-cpu-baseline --no-kernel-timing")
+    print(f"#   python3 -m paper_2201_12465_amd.profile_summary kernel-trace <dir> --workload {args.workload}")
+    print(f"workload {args.workload}; kernels of this library only; durations in microseconds")
+    print(f"{'class':14s} {'kernel':72s} {'calls':>6s} {'avg_us':>9s} {'min_us':>9s} {'max_us':>9s} {'share':>6s}")
+    per_class = collections.defaultdict(lambda: [0, 0.0])
+    for r in sorted(rows, key=lambda r: -float(r["TotalDurationNs"])):
+        c = classify(r["Name"])
+        per_class[c][0] += int(r["Calls"])
+        per_class[c][1] += float(r["TotalDurationNs"])
+        print(f"{c:14s} {short(r['Name']):72s} {r['Calls']:>6s} {float(r['AverageNs']) / 1e3:9.2f} "
+              f"{float(r['MinNs']) / 1e3:9.2f} {float(r['MaxNs']) / 1e3:9.2f} "
+              f"{100 * float(r['TotalDurationNs']) / total:5.1f}%")
+    print()
+    for c, (calls, ns) in sorted(per_class.items(), key=lambda kv: -kv[1][1]):
+        print(f"class {c:14s} calls {calls:6d} avg_us {ns / calls / 1e3:9.2f} share {100 * ns / total:5.1f}%")
+    return 0
+
+
+def load_counter(d: str) -> dict:
+    acc = collections.defaultdict(list)
+    for f in glob.glob(d + "/**/*counter_collection.csv", recursive=True):
+        for r in csv.DictReader(open(f)):
+            acc[r["Kernel_Name"]].append(float(r["Counter_Value"]))
+    return acc
+
+
+def traffic(args) -> int:
+    print("# made by (from /tmp, TMPDIR=/tmp, on one MI355X; C = FETCH_SIZE, then WRITE_SIZE, one counter per run):")
+    print("#   rocprofv3 --pmc C --output-format csv -d <copy_C> -- python3 bench.py --copy-calibration")
+    print(f"#   rocprofv3 --pmc C --output-format csv -d <bench_C> -- python3 bench.py --workload {args.workload} "
+          f"--steps 6 --warmup 2 --no-cpu-baseline --no-kernel-timing")
+    print(f"#   python3 -m paper_2201_12465_amd.profile_summary traffic <bench_FETCH_SIZE> <bench_WRITE_SIZE> "
+          f"<copy_FETCH_SIZE> <copy_WRITE_SIZE> --workload {args.workload}")
+    print("# FETCH_SIZE / WRITE_SIZE count what the L2 caches of the 8 XCDs exchange with the memory side (the")
+    print("# shared last-level cache or HBM), in KiB per dispatch; an operand panel used by several XCDs is")
+    print("# fetched once by each of them, so a GEMM's figure exceeds its algorithmic bytes by construction.")
+    factor = {}
+    for which, d, known in (("FETCH_SIZE", args.copy_fetch, COPY_BYTES), ("WRITE_SIZE", args.copy_write, COPY_BYTES)):
+        v = [x for k, xs in load_counter(d).items() if classify(k) == "copy" for x in xs]
+        if not v:
+            print(f"no copy_kernel dispatches under {d}", file=sys.stderr)
+            return 1
+        factor[which] = known / (sum(v) / len(v) * 1024.0)
+        print(f"calibration {which}: copy kernel of {known} bytes reads {sum(v) / len(v):.1f} KiB "
+              f"over {len(v)} launches -> factor {factor[which]:.4f}")
+    fetch, write = load_counter(args.bench_fetch), load_counter(args.bench_write)
+    print(f"workload {args.workload}; per launch, KiB as counted and bytes after scaling")
+    print(f"{'class':14s} {'kernel':72s} {'n':>5s} {'FETCH_KiB':>11s} {'WRITE_KiB':>11s} {'hbm_bytes':>13s}")
+    per_class = collections.defaultdict(lambda: [0, 0.0])
+    for k in sorted(set(fetch) | set(write)):
+        if not ours(k) or classify(k) == "copy":
+            continue
+        fv, wv = fetch.get(k, []), write.get(k, [])
+        f = sum(fv) / len(fv) if fv else 0.0
+        w = sum(wv) / len(wv) if wv else 0.0
+        n = max(len(fv), len(wv))
+        by = (f * factor["FETCH_SIZE"] + w * factor["WRITE_SIZE"]) * 1024.0
+        c = classify(k)
+        per_class[c][0] += n
+        per_class[c][1] += by * n
+        print(f"{c:14s} {short(k):72s} {n:5d} {f:11.1f} {w:11.1f} {by:13.0f}")
+    print()
+    for c, (n, tot) in sorted(per_class.items()):
+        print(f"traffic {c} bytes_per_launch {tot / n:.0f}")
+    return 0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    sub = ap.add_subparsers(dest="cmd", required=True)
+    k = sub.add_parser("kernel-trace")
+    k.add_argument("dir")
+    k.add_argument("--workload", default="cfg3_bert_base_bf16")
+    t = sub.add_parser("traffic")
+    for n in ("bench_fetch", "bench_write", "copy_fetch", "copy_write"):
+        t.add_argument(n)
+    t.add_argument("--workload", default="cfg3_bert_base_bf16")
+    a = ap.parse_args()
+    return kernel_trace(a) if a.cmd == "kernel-trace" else traffic(a)
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -315,3 +315,25 @@ def test_tape_stops_at_a_failing_gradient_function():
     assert rc == 0 and order == []
     rc, _, _ = _replay([5], [-1], 1)       # reads a slot that does not exist
     assert rc == -1
+
+
+def test_profile_summary_classifies_kernel_names():
+    from paper_2201_12465_amd.profile_summary import classify
+    cases = {
+        "_ZN2fl12_GLOBAL__N_111gemm_kernelIDF16bLb0ELb0ELi2EEEvNS_7GemmDevE": "gemm_tn",
+        "_ZN2fl12_GLOBAL__N_111gemm_kernelIDF16bLb1ELb0ELi1EEEvNS_7GemmDevE": "gemm_nn",
+        "_ZN2fl12_GLOBAL__N_111gemm_kernelIfLb1ELb1ELi2EEEvNS_7GemmDevE": "gemm_nt",
+        "void fl::(anonymous namespace)::gemm_kernel<bool _Accum, bool, E, false, 1>(fl::GemmDev)": "gemm_nn",
+        "void fl::(anonymous namespace)::gemm_kernel<float, false, false, 2>(fl::GemmDev)": "gemm_tn",
+        "void fl::(anonymous namespace)::gemm_bf16_pipe<true, true, 128, 128, 2>(fl::GemmDev)": "gemm_nt",
+        "_ZN2fl12_GLOBAL__N_122reduce_partials_kernelIDF16bEEvPKfimmPT_S5_S5_": "splitk_reduce",
+        "_ZN2fl12_GLOBAL__N_127reduce_partials_tall_kernelIDF16bEEvPKfimmPT_S5_S5_": "splitk_reduce",
+        "_ZN2fl12_GLOBAL__N_117attn_bwd_dkv_mfmaILi64EEEvPKDF16bS3_PKfS5_PKiiifPDF16b": "attn_bwd",
+        "void fl::(anonymous namespace)::attn_fwd_mfma<64>(bool _Accum const*, int const, int)": "attn_fwd",
+        "_ZN2fl12_GLOBAL__N_113ln_bwd_kernelIDF16bLi2EEEvPKT_S4_PKfS6_S4_S4_iiiPS2_Pf": "ln_bwd",
+        "_ZN2fl12_GLOBAL__N_113ln_fwd_kernelIDF16bLi2EEEvPKT_S4_S4_fiiPS2_PfS6_": "ln_fwd",
+        "_ZN2fl12_GLOBAL__N_120colsum_stage1_kernelIDF16bEEvPKT_iiPf": "colsum",
+        "fl::(anonymous namespace)::copy_kernel(HIP_vector_type<unsigned int, 4u> const*, ...)": "copy",
+    }
+    for name, cls in cases.items():
+        assert classify(name) == cls, name
