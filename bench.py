@@ -67,6 +67,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the second, event-instrumented pass (used under rocprofv3)")
+    ap.add_argument("--no-grad-overlap", action="store_true",
+                    help="run the parameter-gradient kernels in order on the main stream instead of beside "
+                         "the input-gradient chain (every kernel then runs alone: the mode for kernel traces)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only 5 launches of the plain copy kernel over 256 MiB (counter calibration)")
     a = ap.parse_args()
@@ -88,6 +91,7 @@ def main() -> int:
         print(json.dumps({"copy_kernel": "copy_kernel", "bytes_read": COPY_BYTES, "bytes_written": COPY_BYTES,
                           "launches": 5, "gbs": gbs}))
         return 0
+    b.set_grad_overlap(not a.no_grad_overlap)
     cfg = CONFIGS[a.workload]
     tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
     dev = lambda x: torch.from_numpy(np.ascontiguousarray(x, np.float32)).cuda().to(tdt).contiguous()
@@ -138,17 +142,29 @@ def main() -> int:
         "tflops_algorithmic": flops_step / (secs / a.steps) / 1e12,
         "valid_tokens_per_s": (float(np.sum(inp["lengths"])) if L is not None else tokens) * a.steps / secs,
         "device_mallocs_in_timed_region": end_stats["backing_mallocs"] - warm_stats["backing_mallocs"],
+        "grad_overlap": not a.no_grad_overlap,
     }
 
     # ---- per-kernel-class timing: same steps again, every launch bracketed by HIP events on `stream`
     if not a.no_kernel_timing:
+        # with the side stream off, so that each kernel runs alone and its duration is its own
         ksteps = min(a.steps, 20)
+        b.set_grad_overlap(False)
+        for _ in range(3):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(ksteps):
+            step()
+        torch.cuda.synchronize()
+        out["ms_per_step_without_grad_overlap"] = (time.perf_counter() - t0) / ksteps * 1e3
         b.prof_enable("all")
         for _ in range(ksteps):
             step()
         torch.cuda.synchronize()
         prof = b.prof_collect()
         b.prof_enable(None)
+        b.set_grad_overlap(not a.no_grad_overlap)
         mask_scale = (fl["fwd_attn"] / (4.0 * cfg.D * cfg.T * tokens)) if L is not None else 1.0
         kernels = {}
         for name, e in prof.items():

@@ -113,6 +113,17 @@ fl_status_t fl_layer_destroy(fl_layer_t *layer);
 /* Thread-local text of the last error returned on this thread ("" if none). */
 const char *fl_last_error(void);
 
+/* Backward passes started after this call do (non-zero, the default) or do not (0) run the
+ * parameter-gradient kernels -- bias sums, the dW contractions and the second stages of their
+ * reductions -- on a library-owned side stream beside the input-gradient chain (Section 4.1.3: the
+ * backward pass is a reverse replay of the recorded graph; kernels of independent branches of that
+ * graph may run at the same time).  The side stream waits, through events, for the gradients it
+ * reads, and the caller's stream waits for it before fl_layer_backward returns control of dX and
+ * the gradient buffers to work enqueued later on that stream: the caller sees the same ordering
+ * either way, and the results are bit-identical.  Process-wide; not thread-safe against
+ * concurrent backward calls. */
+fl_status_t fl_set_grad_overlap(int32_t enabled);
+
 /* Caching device allocator telemetry (Section 4.1.2; Section 5.2.2 describes
  * size-bucketed caches, block splitting and allocation telemetry).
  * backing_mallocs / backing_bytes: calls to and bytes obtained from the device

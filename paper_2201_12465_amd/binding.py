@@ -99,6 +99,7 @@ def lib() -> C.CDLL:
             "fl_alloc_get_stats": (C.c_int, [C.POINTER(fl_alloc_stats_t)]),
             "fl_alloc_trace_enable": (C.c_int, [i32]),
             "fl_alloc_trace_read": (C.c_int, [C.POINTER(fl_alloc_event_t), i32, C.POINTER(i32)]),
+            "fl_set_grad_overlap": (C.c_int, [i32]),
             "fl_alloc_trim": (C.c_int, []),
             "fl_alloc_set_split_limit": (C.c_int, [u64]),
             "fl_prof_enable": (C.c_int, [C.c_uint32]),
@@ -238,6 +239,10 @@ def alloc_trace_read(cap: int = 4096) -> list:
     n = C.c_int32(0)
     check(lib().fl_alloc_trace_read(ev, cap, C.byref(n)))
     return events_as_dicts(ev, n.value)
+
+
+def set_grad_overlap(enabled: bool) -> None:
+    check(lib().fl_set_grad_overlap(1 if enabled else 0))
 
 
 def alloc_trim() -> None:

@@ -72,11 +72,30 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
-__device__ __forceinline__ float gelu_f(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752f)); }
+// erf(x) and E = exp(-x^2) without branches: the rational approximation 7.1.26 of Abramowitz & Stegun,
+// erf(|x|) = 1 - (a1 t + ... + a5 t^5) exp(-x^2), t = 1 / (1 + p |x|), absolute error below 1.5e-7
+// (the spacing of fp32 numbers near 1).  The library's erff costs several times as much inside a
+// GEMM epilogue, where nothing overlaps it.
+__device__ __forceinline__ float erf_exp_f(float x, float &E) {
+  const float ax = fabsf(x);
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
+  E = __expf(-ax * ax);
+  float q = fmaf(t, 1.061405429f, -1.453152027f);
+  q = fmaf(t, q, 1.421413741f);
+  q = fmaf(t, q, -0.284496736f);
+  q = fmaf(t, q, 0.254829592f);
+  const float r = fmaf(-q * t, E, 1.0f);
+  return copysignf(r, x);
+}
+// Exact (erf-based) GELU and its derivative:  gelu(u) = u Phi(u),  gelu'(u) = Phi(u) + u phi(u).
+__device__ __forceinline__ float gelu_f(float u) {
+  float E;
+  return 0.5f * u * (1.0f + erf_exp_f(u * 0.70710678118654752f, E));
+}
 __device__ __forceinline__ float gelu_grad_f(float u) {
-  float cdf = 0.5f * (1.0f + erff(u * 0.70710678118654752f));
-  float pdf = 0.39894228040143268f * __expf(-0.5f * u * u);
-  return cdf + u * pdf;
+  float E;  // exp(-u^2 / 2), shared by the two terms
+  const float cdf = 0.5f * (1.0f + erf_exp_f(u * 0.70710678118654752f, E));
+  return fmaf(u * 0.39894228040143268f, E, cdf);
 }
 
 }  // namespace fl

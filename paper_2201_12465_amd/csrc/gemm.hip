@@ -122,11 +122,12 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(GemmDev p) {
   T *ldsA = reinterpret_cast<T *>(smem);
   T *ldsB = reinterpret_cast<T *>(smem + OPERAND_LDS_BYTES);
 
-  int tile_m, tile_n;
-  xcd_tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, 1024 / BMT, tile_m, tile_n);
+  int split, tile_m, tile_n;
+  xcd_work_coords(blockIdx.x, p.tiles_m, p.tiles_n, p.splits, 1024 / BMT, split, tile_m, tile_n);
   const int row0 = tile_m * BMT, col0 = tile_n * BN;
 
-  const int kbeg = blockIdx.z * p.k_per_split;
+  const int kbeg = split * p.k_per_split;
+  if (p.partial) p.partial += (size_t)split * p.M * p.N;
   const int kend = min(p.K, kbeg + p.k_per_split);
   const T *A = static_cast<const T *>(p.A);
   const T *B = static_cast<const T *>(p.B);
@@ -215,7 +216,8 @@ hipError_t launch_tt(const GemmArgs &a, const GemmDev &d, dim3 grid, hipStream_t
 template <typename T>
 hipError_t launch_t(const GemmArgs &a, GemmDev d, int tmw, int splits, hipStream_t s) {
   d.tiles_m = (a.M + 64 * tmw - 1) / (64 * tmw);
-  dim3 grid(d.tiles_m * d.tiles_n, 1, splits);
+  d.splits = splits;
+  dim3 grid(d.tiles_m * d.tiles_n * splits);
   return tmw == 1 ? launch_tt<T, 1>(a, d, grid, s) : launch_tt<T, 2>(a, d, grid, s);
 }
 

@@ -12,7 +12,7 @@ struct GemmDev {
   void *preact;
   int act, dact;
   float *partial;
-  int k_per_split, tiles_m, tiles_n;
+  int k_per_split, tiles_m, tiles_n, splits;
 };
 
 
@@ -20,7 +20,7 @@ struct GemmDev {
 template <typename T>
 __device__ __forceinline__ void gemm_epilogue_quad(const GemmDev &p, int m, int n0, float (&v)[4]) {
   if (p.partial) {
-    float *dst = p.partial + ((size_t)blockIdx.z * p.M + m) * p.N + n0;
+    float *dst = p.partial + (size_t)m * p.N + n0;  // the kernel has moved `partial` to its k-range's slab
     *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
     return;
   }
@@ -77,7 +77,7 @@ template <> struct Oct<float> {
 template <typename T>
 __device__ __forceinline__ void gemm_epilogue_oct(const GemmDev &p, int m, int n0, float (&v)[8]) {
   if (p.partial) {
-    Oct<float>::store(p.partial + ((size_t)blockIdx.z * p.M + m) * p.N + n0, v);
+    Oct<float>::store(p.partial + (size_t)m * p.N + n0, v);
     return;
   }
   const size_t off = (size_t)m * p.ldc + n0;
@@ -155,12 +155,18 @@ __device__ __forceinline__ int xcd_tile_order(int bid, int nb) {
   return (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
 }
 
-// Tile (tm, tn) of workgroup `bid`.  Each XCD has its own L2 and takes a contiguous range of a tile
-// order with two-dimensional locality: row-tiles are taken in groups of `gm`, and inside a group the
-// order runs down the group's rows before it moves to the next column, so the tiles an XCD works
-// on at one time share few operand panels and those stay in its L2.
-__device__ __forceinline__ void xcd_tile_coords(int bid, int tiles_m, int tiles_n, int gm, int &tm, int &tn) {
-  const int id = xcd_tile_order(bid, tiles_m * tiles_n);
+// Work item (k-range `split`, tile (tm, tn)) of workgroup `bid` of a one-dimensional grid of
+// splits * tiles_m * tiles_n workgroups.  Each XCD has its own L2 and takes a contiguous range of an
+// order in which neighbours share operands: k-range first (so that an XCD reads one k-slice of both
+// operands rather than all of them), then row-tiles in groups of `gm`, and inside a group down the
+// group's rows before moving to the next column, so the tiles an XCD works on at one time share few
+// operand panels and those stay in its L2.
+__device__ __forceinline__ void xcd_work_coords(int bid, int tiles_m, int tiles_n, int splits, int gm, int &split,
+                                                int &tm, int &tn) {
+  const int tiles = tiles_m * tiles_n;
+  int id = xcd_tile_order(bid, tiles * splits);
+  split = id / tiles;
+  id -= split * tiles;
   const int per_group = gm * tiles_n;
   const int g = id / per_group, r = id - g * per_group;
   const int rows = min(gm, tiles_m - g * gm);  // the last group may be shorter

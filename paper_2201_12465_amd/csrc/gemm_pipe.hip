@@ -24,7 +24,7 @@
 namespace fl {
 namespace {
 
-constexpr int NTHR = 256, KT = 64;
+constexpr int KT = 64;
 
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
 typedef const __attribute__((address_space(1))) void *glb_void_ptr;
@@ -37,14 +37,14 @@ template <int N> __device__ __forceinline__ void wait_vmcnt_le() { FL_WAIT_VMCNT
 
 // One operand's staging plan for this wave: element offsets (from the operand base) of the chunks
 // its lanes fetch, for each of its NOPS wave-level loads per k-tile.
-template <bool KC, int R> struct Stager {
-  static constexpr int NOPS = R / 32;  // R*128 bytes per stage / 1 KiB per load / 4 waves
+template <bool KC, int R, int NW> struct Stager {
+  static constexpr int NOPS = R / (8 * NW);  // R*128 bytes per stage / 1 KiB per load / NW waves
   int off[NOPS];
   int kstep;  // element offset from one k-tile to the next
   __device__ __forceinline__ void init(int ld, int row0, int nrows, int kbeg, int lane, int wave) {
 #pragma unroll
     for (int j = 0; j < NOPS; ++j) {
-      const int P = (wave + 4 * j) * 64 + lane;  // chunk position inside the stage
+      const int P = (wave + NW * j) * 64 + lane;  // chunk position inside the stage
       if (KC) {
         const int r = P >> 3, c = (P & 7) ^ ((r >> 1) & 7);
         off[j] = min(row0 + r, nrows - 1) * ld + kbeg + c * 8;
@@ -60,7 +60,7 @@ template <bool KC, int R> struct Stager {
 #pragma unroll
     for (int j = 0; j < NOPS; ++j) {
       const bf16_t *src = base + (size_t)off[j] + (size_t)kt * kstep;
-      __builtin_amdgcn_global_load_lds((glb_void_ptr)src, (lds_void_ptr)(stage + (wave + 4 * j) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_void_ptr)src, (lds_void_ptr)(stage + (wave + NW * j) * 1024), 16, 0, 0);
     }
   }
 };
@@ -86,26 +86,29 @@ __device__ __forceinline__ bf16x8_t frag(const unsigned char *stage, int r0, int
   }
 }
 
-template <bool AKC, bool BKC, int BM, int BN, int NS>
-__global__ __launch_bounds__(NTHR) void gemm_bf16_pipe(GemmDev p) {
-  constexpr int TM = BM / 64, TN = BN / 64;
+// WM x WN wavefronts share a BM x BN tile; each owns TM x TN MFMA tiles of 32x32.
+template <bool AKC, bool BKC, int BM, int BN, int NS, int WM, int WN>
+__global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_pipe(GemmDev p) {
+  constexpr int NW = WM * WN;
+  constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);
   constexpr int A_BYTES = BM * 128, STAGE = (BM + BN) * 128;
-  constexpr int OPS = Stager<AKC, BM>::NOPS + Stager<BKC, BN>::NOPS;  // loads per wave per k-tile
+  constexpr int OPS = Stager<AKC, BM, NW>::NOPS + Stager<BKC, BN, NW>::NOPS;  // loads per wave per k-tile
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
-  int tile_m, tile_n;
-  xcd_tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, 1024 / BM, tile_m, tile_n);
+  int split, tile_m, tile_n;
+  xcd_work_coords(blockIdx.x, p.tiles_m, p.tiles_n, p.splits, 1024 / BM, split, tile_m, tile_n);
   const int row0 = tile_m * BM, col0 = tile_n * BN;
-  const int kbeg = blockIdx.z * p.k_per_split;
+  const int kbeg = split * p.k_per_split;
+  if (p.partial) p.partial += (size_t)split * p.M * p.N;
   const int kend = min(p.K, kbeg + p.k_per_split);
   const int nk = (kend - kbeg) / KT;
   const bf16_t *A = static_cast<const bf16_t *>(p.A);
   const bf16_t *B = static_cast<const bf16_t *>(p.B);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WN, wn = wave % WN;
 
-  Stager<AKC, BM> sa;
-  Stager<BKC, BN> sb;
+  Stager<AKC, BM, NW> sa;
+  Stager<BKC, BN, NW> sb;
   sa.init(p.lda, row0, p.M, kbeg, lane, wave);
   sb.init(p.ldb, col0, p.N, kbeg, lane, wave);
 
@@ -145,16 +148,16 @@ __global__ __launch_bounds__(NTHR) void gemm_bf16_pipe(GemmDev p) {
     // fragments of k-step kk+1 are requested before the MFMAs of k-step kk are issued
     bf16x8_t fa[2][TM], fb[2][TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) fa[0][i] = frag<AKC, BM>(sA, wm * (BM / 2) + i * 32, 0, lane);
+    for (int i = 0; i < TM; ++i) fa[0][i] = frag<AKC, BM>(sA, wm * (BM / WM) + i * 32, 0, lane);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) fb[0][j] = frag<BKC, BN>(sB, wn * (BN / 2) + j * 32, 0, lane);
+    for (int j = 0; j < TN; ++j) fb[0][j] = frag<BKC, BN>(sB, wn * (BN / WN) + j * 32, 0, lane);
 #pragma unroll
     for (int kk = 0; kk < KT / 16; ++kk) {
       if (kk + 1 < KT / 16) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) fa[(kk + 1) & 1][i] = frag<AKC, BM>(sA, wm * (BM / 2) + i * 32, kk + 1, lane);
+        for (int i = 0; i < TM; ++i) fa[(kk + 1) & 1][i] = frag<AKC, BM>(sA, wm * (BM / WM) + i * 32, kk + 1, lane);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) fb[(kk + 1) & 1][j] = frag<BKC, BN>(sB, wn * (BN / 2) + j * 32, kk + 1, lane);
+        for (int j = 0; j < TN; ++j) fb[(kk + 1) & 1][j] = frag<BKC, BN>(sB, wn * (BN / WN) + j * 32, kk + 1, lane);
       }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
@@ -169,16 +172,16 @@ __global__ __launch_bounds__(NTHR) void gemm_bf16_pipe(GemmDev p) {
   __builtin_amdgcn_s_barrier();  // every wave is done reading the operand stages
   asm volatile("" ::: "memory");
   float *cw = reinterpret_cast<float *>(smem) + (size_t)wave * 32 * (TN * 32 + 4);
-  gemm_staged_epilogue<bf16_t, TM, TN>(p, acc, cw, row0 + wm * (BM / 2), col0 + wn * (BN / 2), lane);
+  gemm_staged_epilogue<bf16_t, TM, TN>(p, acc, cw, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane);
 }
 
-template <bool AKC, bool BKC, int BM, int BN, int NS>
+template <bool AKC, bool BKC, int BM, int BN, int NS, int WM = 2, int WN = 2>
 hipError_t launch_cfg(GemmDev d, int splits, hipStream_t s) {
   constexpr size_t stage_lds = (size_t)NS * (BM + BN) * 128;
-  constexpr size_t epi_lds = (size_t)4 * 32 * (BN / 2 + 4) * sizeof(float);
+  constexpr size_t epi_lds = (size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float);
   constexpr size_t lds = stage_lds > epi_lds ? stage_lds : epi_lds;
   static_assert(lds <= 160 * 1024, "stages do not fit in LDS");
-  auto kern = gemm_bf16_pipe<AKC, BKC, BM, BN, NS>;
+  auto kern = gemm_bf16_pipe<AKC, BKC, BM, BN, NS, WM, WN>;
   if (lds > 64 * 1024) {
     static bool raised = false;
     if (!raised) {
@@ -190,8 +193,9 @@ hipError_t launch_cfg(GemmDev d, int splits, hipStream_t s) {
   }
   d.tiles_m = (d.M + BM - 1) / BM;
   d.tiles_n = (d.N + BN - 1) / BN;
-  dim3 grid(d.tiles_m * d.tiles_n, 1, splits);
-  hipLaunchKernelGGL(kern, grid, dim3(NTHR), lds, s, d);
+  d.splits = splits;
+  dim3 grid(d.tiles_m * d.tiles_n * splits);
+  hipLaunchKernelGGL(kern, grid, dim3(WM * WN * 64), lds, s, d);
   return hipGetLastError();
 }
 
@@ -202,6 +206,12 @@ hipError_t launch_layout(const GemmDev &d, int splits, int variant, hipStream_t 
     case 1: return launch_cfg<AKC, BKC, 128, 128, 4>(d, splits, s);
     case 2: return launch_cfg<AKC, BKC, 256, 128, 3>(d, splits, s);
     case 3: return launch_cfg<AKC, BKC, 256, 128, 2>(d, splits, s);
+    case 4: return launch_cfg<AKC, BKC, 256, 256, 2>(d, splits, s);
+    case 5: return launch_cfg<AKC, BKC, 256, 256, 2, 2, 4>(d, splits, s);
+    case 6: return launch_cfg<AKC, BKC, 256, 128, 3, 4, 2>(d, splits, s);
+    case 7:  // 192 columns: the k-major swizzle needs a power-of-two row length, so k-contiguous operands only
+      if constexpr (AKC && BKC) return launch_cfg<AKC, BKC, 256, 192, 2, 4, 2>(d, splits, s);
+      else return hipErrorInvalidValue;
   }
   return hipErrorInvalidValue;
 }
@@ -220,18 +230,25 @@ bool gemm_pipe_eligible(const GemmArgs &a, int kps) {
 }
 
 void gemm_pipe_tile(int variant, int *bm, int *bn) {
-  static const int t[4][2] = {{128, 128}, {128, 128}, {256, 128}, {256, 128}};
+  static const int t[8][2] = {{128, 128}, {128, 128}, {256, 128}, {256, 128}, {256, 256}, {256, 256}, {256, 128}, {256, 192}};
   *bm = t[variant][0];
   *bn = t[variant][1];
 }
 
 int gemm_pipe_pick_variant(bool a_kc, bool b_kc, int M, int N, int K) {
-  if (g_variant != -1) return g_variant;
-  (void)M; (void)N; (void)K;
-  // Measured on the layer's shapes (M = 4096, N and K in {768, 2304, 3072}): with both operands
-  // k-contiguous the 128x128 / 2-stage variant (two workgroups per CU) is the fastest; with a
-  // k-major operand the register-staged kernel in gemm.hip is at least as fast.
-  return a_kc && b_kc ? 0 : -2;
+  if (g_variant != -1) return g_variant == 7 && !(a_kc && b_kc) ? -2 : g_variant;
+  (void)K;
+  // Measured on the layer's shapes (M = 4096, N and K in {768, 2304, 3072}).  With a k-major operand
+  // the register-staged kernel in gemm.hip is at least as fast.  With both operands k-contiguous:
+  // 256x192 tiles on 8 wavefronts halve the L1 and LDS traffic per flop and win when they fill the
+  // chip in whole rounds (one workgroup per CU); otherwise 128x128 / 2 stages, two workgroups per CU.
+  if (!(a_kc && b_kc)) return -2;
+  if (N % 192 == 0) {
+    const long tiles = (long)((M + 255) / 256) * (N / 192);
+    const long rounds = (tiles + 255) / 256;
+    if (tiles >= 160 && 100 * tiles >= 74 * rounds * 256) return 7;
+  }
+  return 0;
 }
 
 hipError_t launch_gemm_bf16_pipe(const GemmArgs &a, const void *dev, int splits, int variant, hipStream_t s) {

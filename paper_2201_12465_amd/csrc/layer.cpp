@@ -129,6 +129,13 @@ struct fl_layer {
   int slot_x = -1, slot_y = -1;
   // valid during backward
   bool accumulate = false;  // parameter gradients are added to what the caller's buffers hold
+  // Parameter-gradient work (bias sums, dW GEMMs, second-stage reductions) is enqueued on a side
+  // stream so that it runs beside the input-gradient chain; see side_fork() / side_join().
+  hipStream_t side = nullptr;          // non-null while this backward uses the side stream
+  std::vector<hipEvent_t> fork_events; // one per fork, reused by the next backward
+  size_t forks = 0;
+  hipEvent_t join_event = nullptr;
+  std::vector<Buf *> held;             // buffers the side stream reads: released after the join
   const void *params[P_COUNT];
   void *grads[P_COUNT];
 };
@@ -188,6 +195,66 @@ struct Scratch {
   float *f32() { return static_cast<float *>(b->ptr); }
 };
 
+// ---- side stream ---------------------------------------------------------------------------
+// One stream per process, default priority, never destroyed.  It has no implicit ordering with
+// any other stream: every dependency is an event.
+bool g_overlap = true;
+hipStream_t side_stream() {
+  static hipStream_t s = [] {
+    hipStream_t t = nullptr;
+    if (hipStreamCreateWithFlags(&t, hipStreamNonBlocking) != hipSuccess) t = nullptr;
+    return t;
+  }();
+  return s;
+}
+// Makes the side stream wait for everything enqueued on the layer's stream so far and returns the
+// stream to launch the parameter-gradient kernels on (the layer's own stream when overlap is off).
+int side_fork(fl_layer *L, hipStream_t *out) {
+  *out = L->stream;
+  if (!L->side) return 0;
+  if (L->forks == L->fork_events.size()) {
+    hipEvent_t e = nullptr;
+    FL_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    L->fork_events.push_back(e);
+  }
+  hipEvent_t e = L->fork_events[L->forks++];
+  FL_HIP(hipEventRecord(e, L->stream));
+  FL_HIP(hipStreamWaitEvent(L->side, e, 0));
+  *out = L->side;
+  return 0;
+}
+// A buffer that kernels on the side stream read must not go back to the cache of the layer's stream
+// (where later kernels could overwrite it) before the join.
+void side_hold(fl_layer *L, Buf *b) {
+  if (!L->side || !b) return;
+  b->refs++;
+  L->held.push_back(b);
+}
+// The layer's stream waits for the side stream; afterwards the held buffers may be reused.
+// wait_host: on an error path, where the order of what was enqueued is no longer known.
+int side_join(fl_layer *L, bool wait_host) {
+  int rc = 0;
+  if (L->side && L->forks) {
+    if (wait_host) {
+      hipStreamSynchronize(L->side);
+    } else {
+      hipError_t e = hipSuccess;
+      if (!L->join_event) e = hipEventCreateWithFlags(&L->join_event, hipEventDisableTiming);
+      if (e == hipSuccess) e = hipEventRecord(L->join_event, L->side);
+      if (e == hipSuccess) e = hipStreamWaitEvent(L->stream, L->join_event, 0);
+      if (e != hipSuccess) {
+        hipStreamSynchronize(L->side);
+        rc = set_error(FL_ERR_DEVICE, "joining the side stream failed: %s", hipGetErrorString(e));
+      }
+    }
+  }
+  for (Buf *&b : L->held) buf_unref(b);
+  L->held.clear();
+  L->forks = 0;
+  L->side = nullptr;
+  return rc;
+}
+
 void release_tape(fl_layer *L) {
   for (Slot &s : L->tape.slots) {
     buf_unref(s.value_buf);
@@ -228,12 +295,18 @@ int linear_backward(void *ctx, Tape *tape, const Node *n) {
     return set_error(FL_ERR_STATE, "linear node %d: activation derivative was not applied upstream", self);
   const void *gy = ys.grad;
   const void *W = L->params[kLinear[n->param].w];
+  // The parameter gradients need gy and the saved input only and nobody waits for them before the
+  // backward pass ends: they go to the side stream, beside the input-gradient chain.
+  hipStream_t ps;
+  FL_TRY(side_fork(L, &ps));
+  side_hold(L, ys.grad_buf);
+  side_hold(L, tape->slots[n->in0].value_buf);
   // bias gradient, unless the kernel that finished gy already produced it
   if (!ys.colsum_done) {
     Scratch ws;
-    FL_TRY(ws.get(colsum_ws_floats(M, N) * sizeof(float), st));
-    FL_HIP(timed(FL_K_COLSUM, 0, (double)M * N * e, st,
-                 [&] { return launch_colsum(dt, gy, M, N, ws.f32(), L->grads[kLinear[n->param].b], st, L->accumulate); }));
+    FL_TRY(ws.get(colsum_ws_floats(M, N) * sizeof(float), ps));
+    FL_HIP(timed(FL_K_COLSUM, 0, (double)M * N * e, ps,
+                 [&] { return launch_colsum(dt, gy, M, N, ws.f32(), L->grads[kLinear[n->param].b], ps, L->accumulate); }));
   }
   // weight gradient: dW[N,K] = sum_m gy[m,n] x[m,k]
   {
@@ -246,16 +319,16 @@ int linear_backward(void *ctx, Tape *tape, const Node *n) {
     const double fl = 2.0 * M * N * K, by = ((double)M * N + (double)M * K + (double)N * K) * e;
     if (a.splits > 1) {
       Scratch ws;
-      FL_TRY(ws.get((size_t)a.splits * N * K * sizeof(float), st));
+      FL_TRY(ws.get((size_t)a.splits * N * K * sizeof(float), ps));
       a.partial = ws.f32();
-      FL_HIP(timed(FL_K_GEMM_TN, fl, by, st, [&] { return launch_gemm(dt, a, st); }));
-      FL_HIP(timed(FL_K_SPLITK_REDUCE, 0, (double)(a.splits * 4 + e) * N * K, st, [&] {
-        return launch_reduce_partials(dt, ws.f32(), a.splits, (size_t)N * K, (size_t)N * K, 1, a.C, nullptr, nullptr, st,
+      FL_HIP(timed(FL_K_GEMM_TN, fl, by, ps, [&] { return launch_gemm(dt, a, ps); }));
+      FL_HIP(timed(FL_K_SPLITK_REDUCE, 0, (double)(a.splits * 4 + e) * N * K, ps, [&] {
+        return launch_reduce_partials(dt, ws.f32(), a.splits, (size_t)N * K, (size_t)N * K, 1, a.C, nullptr, nullptr, ps,
                                       L->accumulate);
       }));
     } else {
       if (L->accumulate) a.residual = a.C;  // in place: each lane reads the elements it then writes
-      FL_HIP(timed(FL_K_GEMM_TN, fl, by, st, [&] { return launch_gemm(dt, a, st); }));
+      FL_HIP(timed(FL_K_GEMM_TN, fl, by, ps, [&] { return launch_gemm(dt, a, ps); }));
     }
   }
   // input gradient: dx[M,K] = gy W (+ what other consumers of x already contributed)
@@ -380,9 +453,13 @@ int layernorm_backward(void *ctx, Tape *tape, const Node *n) {
   }
   set_grad(xs, dst, nb);
   const bool want_bias = fin && xs.colsum_param >= 0;
-  FL_HIP(timed(FL_K_COLSUM, 0, (double)parts * 3 * D * 4, st, [&] {
+  // second stage of the parameter-gradient sums: beside the input-gradient chain
+  hipStream_t ps;
+  FL_TRY(side_fork(L, &ps));
+  side_hold(L, ws.b);
+  FL_HIP(timed(FL_K_COLSUM, 0, (double)parts * 3 * D * 4, ps, [&] {
     return launch_reduce_partials(dt, ws.f32(), parts, (size_t)3 * D, (size_t)D, want_bias ? 3 : 2, L->grads[gi],
-                                  L->grads[bi], want_bias ? L->grads[xs.colsum_param] : nullptr, st, L->accumulate);
+                                  L->grads[bi], want_bias ? L->grads[xs.colsum_param] : nullptr, ps, L->accumulate);
   }));
   if (want_bias) xs.colsum_done = true;
   set_grad(ys, nullptr, nullptr);
@@ -607,10 +684,14 @@ int backward_impl(fl_layer *L, const fl_layer_params_t *params, const void *dY, 
   Tape &tp = L->tape;
   tp.slots[L->slot_y].grad = const_cast<void *>(dY);
   tp.slots[L->slot_x].grad_dst = dX;
+  L->side = g_overlap ? side_stream() : nullptr;
+  L->forks = 0;
   int rc = tp.replay_reverse(L);
   const bool landed = rc == 0 && tp.slots[L->slot_x].grad == dX;
+  const int jrc = side_join(L, rc != 0);
   release_tape(L);
   if (rc) return rc;
+  if (jrc) return jrc;
   if (!landed) return set_error(FL_ERR_STATE, "input gradient did not reach its destination");
   return 0;
 }
@@ -727,12 +808,19 @@ fl_status_t fl_layer_destroy(fl_layer_t *layer) {
   FL_GUARD_BEGIN
   if (!layer) return FL_OK;
   release_tape(layer);
+  for (hipEvent_t e : layer->fork_events) hipEventDestroy(e);  // work already enqueued against them still completes
+  if (layer->join_event) hipEventDestroy(layer->join_event);
   delete layer;
   return FL_OK;
   FL_GUARD_END
 }
 
 const char *fl_last_error(void) { return g_err; }
+
+fl_status_t fl_set_grad_overlap(int32_t enabled) {
+  g_overlap = enabled != 0;
+  return FL_OK;
+}
 
 fl_status_t fl_alloc_get_stats(fl_alloc_stats_t *out) {
   FL_GUARD_BEGIN

@@ -70,7 +70,7 @@ def kernel_trace(args) -> int:
     total = sum(float(r["TotalDurationNs"]) for r in rows)
     print("# made by (from /tmp, TMPDIR=/tmp, on one MI355X):")
     print(f"#   rocprofv3 --kernel-trace --stats --output-format csv -d <dir> -- python3 bench.py "
-          f"--workload {args.workload} --steps 50 --warmup 10 --no-cpu-baseline --no-kernel-timing")
+          f"--workload {args.workload} --steps 50 --warmup 10 --no-cpu-baseline --no-kernel-timing --no-grad-overlap")
     print(f"#   python3 -m paper_2201_12465_amd.profile_summary kernel-trace <dir> --workload {args.workload}")
     print(f"workload {args.workload}; kernels of this library only; durations in microseconds")
     print(f"{'class':14s} {'kernel':72s} {'calls':>6s} {'avg_us':>9s} {'min_us':>9s} {'max_us':>9s} {'share':>6s}")
@@ -100,7 +100,7 @@ def traffic(args) -> int:
     print("# made by (from /tmp, TMPDIR=/tmp, on one MI355X; C = FETCH_SIZE, then WRITE_SIZE, one counter per run):")
     print("#   rocprofv3 --pmc C --output-format csv -d <copy_C> -- python3 bench.py --copy-calibration")
     print(f"#   rocprofv3 --pmc C --output-format csv -d <bench_C> -- python3 bench.py --workload {args.workload} "
-          f"--steps 6 --warmup 2 --no-cpu-baseline --no-kernel-timing")
+          f"--steps 6 --warmup 2 --no-cpu-baseline --no-kernel-timing --no-grad-overlap")
     print(f"#   python3 -m paper_2201_12465_amd.profile_summary traffic <bench_FETCH_SIZE> <bench_WRITE_SIZE> "
           f"<copy_FETCH_SIZE> <copy_WRITE_SIZE> --workload {args.workload}")
     print("# FETCH_SIZE / WRITE_SIZE count what the L2 caches of the 8 XCDs exchange with the memory side (the")

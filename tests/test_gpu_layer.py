@@ -173,8 +173,12 @@ def _run_stack(cfg, nontrivial):
     for l in range(cfg.layers):
         for k in PARAM_NAMES:
             errs[f"L{l}.d{k}"] = rel_err(to_np(G[l][k]), rg[l][k])
-    bad = {k: v for k, v in errs.items() if not v <= BF16_TOL}
-    assert not bad, bad
+    # Every layer rounds its activations and gradients to bf16 on its own, so the single-layer bound
+    # compounds over the chain like independent errors: in quadrature.
+    tol = BF16_TOL * np.sqrt(cfg.layers)
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, (tol, bad)
+    print(f"stack of {cfg.layers}: largest error {max(errs.values()):.4f} (bound {tol:.4f})")
     for L in layers:
         L.destroy()
 
@@ -215,6 +219,31 @@ def test_steady_state_has_no_device_mallocs_and_is_deterministic():
         assert np.array_equal(o[0], outs[0][0]) and np.array_equal(o[1], outs[0][1])
         for k in PARAM_NAMES:
             assert np.array_equal(o[2][k], outs[0][2][k]), k
+
+
+@pytest.mark.parametrize("name", ["cfg2_small_f32", "cfg3_bert_base_bf16"])
+def test_side_stream_for_parameter_gradients_changes_no_bit(name):
+    """The parameter-gradient kernels run beside the input-gradient chain on a side stream; with that
+    switched off everything runs in order on the caller's stream.  Same kernels, same summation order:
+    the two must agree bit for bit, also when gradients are accumulated over two backward passes."""
+    from paper_2201_12465_amd import binding as b
+    cfg = CONFIGS[name]
+    inp = make_inputs(cfg, seed=3)
+    ref = None
+    try:
+        for overlap in (True, False, True):
+            b.set_grad_overlap(overlap)
+            layer = b.Layer(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F, cfg.act, cfg.norm, cfg.dtype, cfg.eps)
+            for _ in range(2):                      # the second pass reuses cached blocks of both streams
+                res = run_layer_gpu(cfg, inp, layer=layer)
+            layer.destroy()
+            ref = ref or res
+            assert np.array_equal(res[0], ref[0]) and np.array_equal(res[1], ref[1]), overlap
+            for k in PARAM_NAMES:
+                assert np.array_equal(res[2][k], ref[2][k]), (overlap, k)
+    finally:
+        b.set_grad_overlap(True)
+    assert b.alloc_stats()["live_bytes"] == 0
 
 
 def test_allocation_trace_names_the_operator_of_every_buffer():
