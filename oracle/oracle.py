@@ -26,6 +26,9 @@ notes of the repository):
   * scores are (q . k) / sqrt(dh); key j of sequence b is masked out iff
     j >= lengths[b] (score -inf before the softmax, probability exactly 0);
     padded *query* rows are ordinary rows;
+  * the causal variant (the autoregressive language-model task named in Section 4.3
+    "Text") additionally masks out key j for query i iff j > i; with lengths >= 1 every
+    query keeps at least key 0;
   * LayerNorm uses the biased variance and eps inside the square root;
   * GELU is the exact erf form; relu'(0) = 0;
   * no dropout.
@@ -152,10 +155,11 @@ def key_mask(lengths, B, T):
     return np.arange(T)[None, :] >= lengths[:, None]
 
 
-def attention_fwd(Q, K, V, lengths=None):
+def attention_fwd(Q, K, V, lengths=None, causal=False):
     """Masked scaled-dot-product attention.  Q, K, V: [B, H, T, dh].
 
     S = Q K^T / sqrt(dh); masked keys get -inf; P = softmax over keys; O = P V.
+    Masked: padding keys (j >= lengths[b]) and, if causal, keys after the query (j > i).
     Returns O [B, H, T, dh] and P [B, H, T, T].
     """
     Q, K, V = _f64(Q), _f64(K), _f64(V)
@@ -163,6 +167,9 @@ def attention_fwd(Q, K, V, lengths=None):
     S = (Q @ K.transpose(0, 1, 3, 2)) / math.sqrt(dh)
     pad = key_mask(lengths, B, T)
     S = np.where(pad[:, None, None, :], -np.inf, S)
+    if causal:
+        future = np.arange(T)[None, :] > np.arange(T)[:, None]      # [query i, key j]: j > i
+        S = np.where(future[None, None, :, :], -np.inf, S)
     S = S - S.max(axis=-1, keepdims=True)
     E = np.exp(S)
     P = E / E.sum(axis=-1, keepdims=True)
@@ -191,13 +198,13 @@ def attention_bwd(dO, Q, K, V, P):
 # the layer
 # ----------------------------------------------------------------------------
 
-def _self_attention_fwd(x, p, H, lengths):
+def _self_attention_fwd(x, p, H, lengths, causal=False):
     D = x.shape[-1]
     qkv = linear_fwd(x, p["Wqkv"], p["bqkv"])
     Q = split_heads(qkv[..., :D], H)
     K = split_heads(qkv[..., D:2 * D], H)
     V = split_heads(qkv[..., 2 * D:], H)
-    Oh, P = attention_fwd(Q, K, V, lengths)
+    Oh, P = attention_fwd(Q, K, V, lengths, causal)
     O = merge_heads(Oh)
     A = linear_fwd(O, p["Wo"], p["bo"])
     return A, dict(x=x, Q=Q, K=K, V=V, P=P, O=O)
@@ -227,8 +234,8 @@ def _ffn_bwd(dFo, p, c, act, g):
     return dx
 
 
-def layer_forward(params, X, lengths=None, *, heads, act="relu", norm="post", eps=1e-5):
-    """Forward pass.  X: [B, T, D].  Returns (Y, cache).
+def layer_forward(params, X, lengths=None, *, heads, act="relu", norm="post", eps=1e-5, causal=False):
+    """Forward pass.  X: [B, T, D].  Returns (Y, cache).  causal: query i attends to keys j <= i only.
 
     post-LN:  Y1 = LN1(X + Attn(X));   Y = LN2(Y1 + FFN(Y1))
     pre-LN:   R1 = X + Attn(LN1(X));   Y = R1 + FFN(LN2(R1))
@@ -237,7 +244,7 @@ def layer_forward(params, X, lengths=None, *, heads, act="relu", norm="post", ep
     X = _f64(X)
     c = {"act": act, "norm": norm}
     if norm == "post":
-        A, c["attn"] = _self_attention_fwd(X, p, heads, lengths)
+        A, c["attn"] = _self_attention_fwd(X, p, heads, lengths, causal)
         R1 = X + A
         Y1, c["xhat1"], c["rstd1"] = layernorm_fwd(R1, p["ln1_g"], p["ln1_b"], eps)
         Fo, c["ffn"] = _ffn_fwd(Y1, p, act)
@@ -245,7 +252,7 @@ def layer_forward(params, X, lengths=None, *, heads, act="relu", norm="post", ep
         Y, c["xhat2"], c["rstd2"] = layernorm_fwd(R2, p["ln2_g"], p["ln2_b"], eps)
     elif norm == "pre":
         N1, c["xhat1"], c["rstd1"] = layernorm_fwd(X, p["ln1_g"], p["ln1_b"], eps)
-        A, c["attn"] = _self_attention_fwd(N1, p, heads, lengths)
+        A, c["attn"] = _self_attention_fwd(N1, p, heads, lengths, causal)
         R1 = X + A
         N2, c["xhat2"], c["rstd2"] = layernorm_fwd(R1, p["ln2_g"], p["ln2_b"], eps)
         Fo, c["ffn"] = _ffn_fwd(N2, p, act)

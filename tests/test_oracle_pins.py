@@ -281,7 +281,7 @@ def test_against_torch_encoder_layer(norm, act, masked):
 
 
 # ---------------------------------------------------------------- (6) brute force, loops only
-def _loops_forward(p, X, lengths, H, act, norm, eps):
+def _loops_forward(p, X, lengths, H, act, norm, eps, causal=False):
     B, T, D = X.shape
     dh = D // H
     F = p["W1"].shape[0]
@@ -306,13 +306,14 @@ def _loops_forward(p, X, lengths, H, act, norm, eps):
         O = [[0.0] * D for _ in range(T)]
         for h in range(H):
             for i in range(T):
+                nk = min(n, i + 1) if causal else n          # keys this query may look at
                 s = [sum(qkv[i][h * dh + d] * qkv[j][D + h * dh + d] for d in range(dh)) / math.sqrt(dh)
-                     for j in range(n)]
+                     for j in range(nk)]
                 m = max(s)
                 e = [math.exp(v - m) for v in s]
                 z = sum(e)
                 for d in range(dh):
-                    O[i][h * dh + d] = sum(e[j] / z * qkv[j][2 * D + h * dh + d] for j in range(n))
+                    O[i][h * dh + d] = sum(e[j] / z * qkv[j][2 * D + h * dh + d] for j in range(nk))
         for t in range(T):
             a = lin(O[t], p["Wo"], p["bo"])
             r1 = [xin[t][i] + a[i] for i in range(D)]
@@ -359,3 +360,111 @@ def test_stack_matches_chained_single_layers():
         for k in PARAM_NAMES:
             assert np.array_equal(g[k], grads[l][k])
     assert np.array_equal(d, dX)
+
+
+# ---------------------------------------------------------------- (8) the causal variant
+@pytest.mark.parametrize("norm", ["post", "pre"])
+def test_causal_against_scalar_loops(norm):
+    cfg = CFG1.with_(B=2, T=5, D=4, H=2, F=8)
+    inp = make_inputs(cfg, seed=10, nontrivial=True)
+    p = {k: v.astype(np.float64) for k, v in inp["params"].items()}
+    X = inp["X"].astype(np.float64)
+    for lengths in (None, np.array([3, 5], np.int32)):
+        want = _loops_forward(p, X, lengths, cfg.H, "gelu", norm, 1e-5, causal=True)
+        got, _ = orc.layer_forward(p, X, lengths, heads=cfg.H, act="gelu", norm=norm, eps=1e-5, causal=True)
+        assert np.allclose(got, want, atol=1e-13)
+        plain, _ = orc.layer_forward(p, X, lengths, heads=cfg.H, act="gelu", norm=norm, eps=1e-5)
+        assert not np.allclose(got, plain, atol=1e-3)          # the mask does something
+
+
+@pytest.mark.parametrize("norm", ["post", "pre"])
+@pytest.mark.parametrize("masked", [False, True])
+def test_causal_against_torch_encoder_layer(norm, masked):
+    """torch's encoder layer with a boolean upper-triangular src_mask (fp64), values and all gradients."""
+    torch = pytest.importorskip("torch")
+    cfg = CFG1
+    lengths = [13, 4] if masked else None
+    inp = _inputs(cfg, seed=8, lengths=lengths)
+    p, X, dY = inp["params"], inp["X"], inp["dY"]
+    layer = torch.nn.TransformerEncoderLayer(cfg.D, cfg.H, cfg.F, dropout=0.0, activation="gelu",
+                                             layer_norm_eps=cfg.eps, batch_first=True,
+                                             norm_first=(norm == "pre"), dtype=torch.float64)
+    layer.train()
+    t = lambda a: torch.tensor(np.asarray(a, np.float64))
+    names = {"Wqkv": layer.self_attn.in_proj_weight, "bqkv": layer.self_attn.in_proj_bias,
+             "Wo": layer.self_attn.out_proj.weight, "bo": layer.self_attn.out_proj.bias,
+             "W1": layer.linear1.weight, "b1": layer.linear1.bias, "W2": layer.linear2.weight,
+             "b2": layer.linear2.bias, "ln1_g": layer.norm1.weight, "ln1_b": layer.norm1.bias,
+             "ln2_g": layer.norm2.weight, "ln2_b": layer.norm2.bias}
+    with torch.no_grad():
+        for k, w in names.items():
+            w.copy_(t(p[k]))
+    x = t(X).requires_grad_(True)
+    future = torch.triu(torch.ones(cfg.T, cfg.T, dtype=torch.bool), diagonal=1)      # True = not allowed
+    pad = None
+    if masked:
+        pad = torch.arange(cfg.T)[None, :] >= torch.tensor(lengths)[:, None]
+    y = layer(x, src_mask=future, src_key_padding_mask=pad)
+    (y * t(dY)).sum().backward()
+    Y, dX, g = orc.layer_forward_backward(p, X, dY, inp["lengths"], heads=cfg.H, act="gelu", norm=norm,
+                                          eps=cfg.eps, causal=True)
+    assert np.allclose(Y, y.detach().numpy(), atol=1e-11)
+    assert np.allclose(dX, x.grad.numpy(), atol=1e-10)
+    for k, w in names.items():
+        assert np.allclose(g[k], w.grad.numpy(), atol=1e-10), k
+
+
+def test_causal_finite_differences():
+    cfg = CFG1
+    inp = _inputs(cfg, seed=5, lengths=[12, 7])
+    kw = dict(heads=cfg.H, act="gelu", norm="post", eps=cfg.eps, causal=True)
+    p = {k: v.astype(np.float64) for k, v in inp["params"].items()}
+    X, dY, L = inp["X"].astype(np.float64), inp["dY"].astype(np.float64), inp["lengths"]
+    _, dX, g = orc.layer_forward_backward(p, X, dY, L, **kw)
+    rng = np.random.default_rng(12)
+    h = 1e-6
+    for name, arr, grad, n in [("X", X, dX, 60), ("Wqkv", p["Wqkv"], g["Wqkv"], 40), ("bqkv", p["bqkv"], g["bqkv"], 20),
+                               ("Wo", p["Wo"], g["Wo"], 20)]:
+        flat = arr.reshape(-1)
+        scale = np.max(np.abs(grad)) + 1e-30
+        for i in rng.choice(flat.size, size=min(n, flat.size), replace=False):
+            old = flat[i]
+            flat[i] = old + h
+            lp = _loss(p, X, dY, L, kw)
+            flat[i] = old - h
+            lm = _loss(p, X, dY, L, kw)
+            flat[i] = old
+            assert abs((lp - lm) / (2 * h) - grad.reshape(-1)[i]) <= 2e-6 * scale, (name, int(i))
+
+
+def test_causal_structure():
+    """No information flows backwards in time; probabilities above the diagonal are exactly 0."""
+    cfg = CFG1
+    inp = _inputs(cfg, seed=6, lengths=[16, 9])
+    p, X, dY, L = inp["params"], inp["X"].astype(np.float64), inp["dY"].astype(np.float64), inp["lengths"]
+    kw = dict(heads=cfg.H, act="relu", norm="pre", eps=cfg.eps, causal=True)
+    Y, c = orc.layer_forward(p, X, L, **kw)
+    P = c["attn"]["P"]
+    iu = np.triu_indices(cfg.T, k=1)
+    assert np.all(P[:, :, iu[0], iu[1]] == 0.0)
+    assert np.allclose(P.sum(-1), 1.0, atol=1e-14)
+    assert np.all(P[1, :, :, 9:] == 0.0)                        # padding keys stay masked too
+    assert np.allclose(P[:, :, 0, 0], 1.0)                      # the first query sees only itself
+    t0 = 6
+    X2 = X.copy()
+    X2[:, t0:] += np.random.default_rng(0).standard_normal(X2[:, t0:].shape)
+    Y2, _ = orc.layer_forward(p, X2, L, **kw)
+    assert np.array_equal(Y2[:, :t0], Y[:, :t0])                # earlier positions do not see the change
+    assert not np.allclose(Y2[:, t0:], Y[:, t0:])
+    # and the gradient of early outputs w.r.t. later inputs is zero
+    dY0 = dY.copy()
+    dY0[:, t0:] = 0.0
+    _, dX, _ = orc.layer_forward_backward(p, X, dY0, L, **kw)
+    assert np.all(dX[:, t0:] == 0.0) and np.any(dX[:, :t0] != 0.0)
+    # a single-token sequence is unaffected by the causal mask
+    cfg1 = CFG1.with_(T=1)
+    inp1 = make_inputs(cfg1, seed=2, nontrivial=True)
+    a, _ = orc.layer_forward(inp1["params"], inp1["X"], None, heads=cfg1.H, act="relu", norm="post", eps=cfg1.eps)
+    b_, _ = orc.layer_forward(inp1["params"], inp1["X"], None, heads=cfg1.H, act="relu", norm="post", eps=cfg1.eps,
+                              causal=True)
+    assert np.array_equal(a, b_)
