@@ -64,6 +64,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg3_bert_base_bf16")
+    ap.add_argument("--causal", action="store_true", help="the workload with the causal attention mask added")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the second, event-instrumented pass (used under rocprofv3)")
@@ -93,6 +94,8 @@ def main() -> int:
         return 0
     b.set_grad_overlap(not a.no_grad_overlap)
     cfg = CONFIGS[a.workload]
+    if a.causal:
+        cfg = cfg.with_(name=cfg.name + "+causal", causal=True)
     tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
     dev = lambda x: torch.from_numpy(np.ascontiguousarray(x, np.float32)).cuda().to(tdt).contiguous()
     if cfg.layers > 1:
@@ -107,7 +110,8 @@ def main() -> int:
     acts = [dev(inp["X"])] + [torch.empty(inp["X"].shape, dtype=tdt, device="cuda") for _ in range(nl)]
     grads = [torch.empty(inp["X"].shape, dtype=tdt, device="cuda") for _ in range(nl)] + [dev(inp["dY"])]
     L = torch.from_numpy(inp["lengths"]).cuda() if inp["lengths"] is not None else None
-    layers = [b.Layer(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F, cfg.act, cfg.norm, cfg.dtype, cfg.eps) for _ in range(nl)]
+    layers = [b.Layer(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F, cfg.act, cfg.norm, cfg.dtype, cfg.eps, cfg.causal)
+              for _ in range(nl)]
     stream = torch.cuda.current_stream().cuda_stream
 
     def step():
@@ -138,7 +142,7 @@ def main() -> int:
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "B": cfg.B, "T": cfg.T, "d_model": cfg.D, "heads": cfg.H, "d_ffn": cfg.F,
                    "act": cfg.act, "norm": cfg.norm, "layers": nl,
-                   "mask": "key-padding lengths" if L is not None else "none"},
+                   "mask": ("key-padding lengths" if L is not None else "none") + (" + causal" if cfg.causal else "")},
         "tflops_algorithmic": flops_step / (secs / a.steps) / 1e12,
         "valid_tokens_per_s": (float(np.sum(inp["lengths"])) if L is not None else tokens) * a.steps / secs,
         "device_mallocs_in_timed_region": end_stats["backing_mallocs"] - warm_stats["backing_mallocs"],
@@ -165,7 +169,7 @@ def main() -> int:
         prof = b.prof_collect()
         b.prof_enable(None)
         b.set_grad_overlap(not a.no_grad_overlap)
-        mask_scale = (fl["fwd_attn"] / (4.0 * cfg.D * cfg.T * tokens)) if L is not None else 1.0
+        mask_scale = fl["fwd_attn"] / (4.0 * cfg.D * cfg.T * tokens)      # 1 without a mask
         kernels = {}
         for name, e in prof.items():
             flops = e["flops"] * (mask_scale if name.startswith("attn") else 1.0)   # library counts dense attention
@@ -226,7 +230,7 @@ def main() -> int:
                 threads = max(blas)
         except Exception:
             pass
-        kw = dict(heads=cfg.H, act=cfg.act, norm=cfg.norm, eps=cfg.eps)
+        kw = dict(heads=cfg.H, act=cfg.act, norm=cfg.norm, eps=cfg.eps, causal=cfg.causal)
         # bounded sample: the first sequences of the batch, sized for roughly 10-30 s of CPU work
         nb = cfg.B if nl == 1 and cfg.M <= 4096 else max(1, min(cfg.B, 4096 // cfg.T))
         sl = slice(0, nb)

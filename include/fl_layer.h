@@ -54,13 +54,16 @@ typedef enum { FL_NORM_POST = 0, FL_NORM_PRE = 1 } fl_norm_t;
 
 /* Host struct.  Supported shapes: d_model % 8 == 0, d_ffn % 8 == 0,
  * head size dh = d_model / n_heads with dh % 16 == 0 and dh <= 256,
- * d_model <= 4096.  ln_eps <= 0 selects the default 1e-5. */
+ * d_model <= 4096.  ln_eps <= 0 selects the default 1e-5.
+ * causal != 0: query i attends to keys j <= i only (the autoregressive
+ * language-model task of Section 4.3 "Text"), on top of the key-padding mask. */
 typedef struct {
   int32_t max_B, max_T, d_model, n_heads, d_ffn;
   fl_act_t act;
   fl_norm_t norm;
   fl_dtype_t dtype;
   float ln_eps;
+  int32_t causal;
 } fl_layer_config_t;
 
 /* Host structs of device pointers; all 12 must be non-null.  Parameters are

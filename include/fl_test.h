@@ -55,12 +55,13 @@ int32_t fl_test_colsum(int32_t dtype, const void *in, int32_t M, int32_t N, floa
  * written), against which the HBM byte counters are calibrated and copy bandwidth is measured. */
 int32_t fl_test_copy(const void *src, void *dst, uint64_t nbytes, void *hip_stream);
 
-/* Masked scaled-dot-product attention on qkv[B*T, 3*H*dh]; lse and delta are fp32 [B,H,T]. */
-int32_t fl_test_attention_fwd(int32_t dtype, const void *qkv, const int32_t *lengths, int32_t B, int32_t T, int32_t H,
-                              int32_t dh, void *o, float *lse, void *hip_stream);
+/* Masked scaled-dot-product attention on qkv[B*T, 3*H*dh]; lse and delta are fp32 [B,H,T];
+ * causal != 0 adds the mask j > i. */
+int32_t fl_test_attention_fwd(int32_t dtype, const void *qkv, const int32_t *lengths, int32_t causal, int32_t B,
+                              int32_t T, int32_t H, int32_t dh, void *o, float *lse, void *hip_stream);
 int32_t fl_test_attention_bwd(int32_t dtype, const void *qkv, const void *o, const void *dout, const float *lse,
-                              const int32_t *lengths, int32_t B, int32_t T, int32_t H, int32_t dh, void *dqkv,
-                              float *delta, void *hip_stream);
+                              const int32_t *lengths, int32_t causal, int32_t B, int32_t T, int32_t H, int32_t dh,
+                              void *dqkv, float *delta, void *hip_stream);
 
 /* on != 0: bf16 attention uses the general (vector-ALU) kernels instead of the MFMA ones. */
 void fl_test_attention_force_general(int32_t on);

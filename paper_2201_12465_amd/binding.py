@@ -32,7 +32,7 @@ class FlError(RuntimeError):
 class fl_layer_config_t(C.Structure):
     _fields_ = [("max_B", C.c_int32), ("max_T", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
                 ("d_ffn", C.c_int32), ("act", C.c_int), ("norm", C.c_int), ("dtype", C.c_int),
-                ("ln_eps", C.c_float)]
+                ("ln_eps", C.c_float), ("causal", C.c_int32)]
 
 
 class fl_layer_params_t(C.Structure):
@@ -115,8 +115,8 @@ def lib() -> C.CDLL:
             "fl_test_copy": (i32, [vp, vp, u64, vp]),
             "fl_test_colsum_ws_floats": (i64, [i32, i32]),
             "fl_test_colsum": (i32, [i32, vp, i32, i32, vp, vp, vp]),
-            "fl_test_attention_fwd": (i32, [i32, vp, vp, i32, i32, i32, i32, vp, vp, vp]),
-            "fl_test_attention_bwd": (i32, [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]),
+            "fl_test_attention_fwd": (i32, [i32, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp]),
+            "fl_test_attention_bwd": (i32, [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp]),
             "fl_test_attention_force_general": (None, [i32]),
             "fl_test_alloc_create": (vp, [BACKING_MALLOC, BACKING_FREE]),
             "fl_test_alloc_destroy": (None, [vp]),
@@ -161,11 +161,12 @@ def _pack(struct_type, tensors: dict):
 class Layer:
     """Thin handle wrapper: create / forward / backward / destroy."""
 
-    def __init__(self, max_B, max_T, d_model, n_heads, d_ffn, act="relu", norm="post", dtype="f32", ln_eps=1e-5):
+    def __init__(self, max_B, max_T, d_model, n_heads, d_ffn, act="relu", norm="post", dtype="f32", ln_eps=1e-5,
+                 causal=False):
         cfg = fl_layer_config_t(max_B, max_T, d_model, n_heads, d_ffn,
                                 {"relu": FL_ACT_RELU, "gelu": FL_ACT_GELU}[act],
                                 {"post": FL_NORM_POST, "pre": FL_NORM_PRE}[norm],
-                                {"f32": FL_F32, "bf16": FL_BF16}[dtype], ln_eps)
+                                {"f32": FL_F32, "bf16": FL_BF16}[dtype], ln_eps, 1 if causal else 0)
         self._h = C.c_void_p()
         check(lib().fl_layer_create(C.byref(cfg), C.byref(self._h)))
 

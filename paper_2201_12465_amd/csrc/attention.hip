@@ -6,8 +6,8 @@
 // hand-written gradient function (Section 4.2; Section 5.2.1 "pre-fused gradient
 // computation for common sequences").  The softmax is computed online over key
 // tiles of 64 (running row maximum and row sum), so any sequence length fits;
-// masked keys (j >= length) are simply never visited, which gives them
-// probability exactly 0.  The backward pass recomputes the probabilities from
+// masked keys (j >= length; with the causal mask also j > i) are never visited or
+// get probability exactly 0.  The backward pass recomputes the probabilities from
 // the saved log-sum-exp:  P = exp(S - LSE), dV = P^T dO, dP = dO V^T,
 // dS = P (dP - delta), delta_i = sum_d dO_i O_i, dQ = dS K / sqrt(dh),
 // dK = dS^T Q / sqrt(dh).
@@ -38,8 +38,8 @@ __device__ __forceinline__ float dot_row(const float *__restrict__ s, const T *_
 
 template <typename T>
 __global__ __launch_bounds__(256) void attn_fwd_rows(const T *__restrict__ qkv, const int32_t *__restrict__ lengths,
-                                                     int Tn, int H, int dh, float scale, T *__restrict__ o,
-                                                     float *__restrict__ lse) {
+                                                     int causal, int Tn, int H, int dh, float scale,
+                                                     T *__restrict__ o, float *__restrict__ lse) {
   __shared__ float sq[4][MAX_DH];
   __shared__ float sp[4][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -55,18 +55,22 @@ __global__ __launch_bounds__(256) void attn_fwd_rows(const T *__restrict__ qkv, 
     for (int d = lane; d < dh; d += 64) sq[wave][d] = to_f32(base[(size_t)i * ld + h * dh + d]) * scale;
     __syncthreads();
     float mrun = -INFINITY, lrun = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int j0 = 0; j0 < len; j0 += 64) {
+    // keys this row may see, and the (workgroup-uniform) end of the key loop for the four rows of this round
+    const int lim = causal ? min(len, i + 1) : len;
+    const int jend = causal ? min(len, min(Tn, blockIdx.x * ROWS_PER_WG + r * 4 + 4)) : len;
+    for (int j0 = 0; j0 < jend; j0 += 64) {
       const int j = j0 + lane;
       float s = -INFINITY;
-      if (j < len) s = dot_row<T>(sq[wave], base + (size_t)j * ld + D + h * dh, dh);
+      if (j < lim) s = dot_row<T>(sq[wave], base + (size_t)j * ld + D + h * dh, dh);
+      // the first tile holds key 0, which every row may see: mnew is finite from then on
       const float mnew = fmaxf(mrun, wave_max(s));
-      const float p = j < len ? __expf(s - mnew) : 0.f;
+      const float p = j < lim ? __expf(s - mnew) : 0.f;
       const float corr = __expf(mrun - mnew);
       lrun = lrun * corr + wave_sum(p);
       mrun = mnew;
       sp[wave][lane] = p;
       __syncthreads();
-      const int nj = min(64, len - j0);
+      const int nj = min(64, jend - j0);
 #pragma unroll
       for (int c = 0; c < 4; ++c) acc[c] *= corr;
       for (int jj = 0; jj < nj; ++jj) {
@@ -95,8 +99,8 @@ __global__ __launch_bounds__(256) void attn_fwd_rows(const T *__restrict__ qkv, 
 template <typename T>
 __global__ __launch_bounds__(256) void attn_bwd_dq_rows(const T *__restrict__ qkv, const T *__restrict__ o,
                                                         const T *__restrict__ dout, const float *__restrict__ lse,
-                                                        const int32_t *__restrict__ lengths, int Tn, int H, int dh,
-                                                        float scale, T *__restrict__ dqkv,
+                                                        const int32_t *__restrict__ lengths, int causal, int Tn,
+                                                        int H, int dh, float scale, T *__restrict__ dqkv,
                                                         float *__restrict__ delta) {
   __shared__ float sq[4][MAX_DH];
   __shared__ float sdo[4][MAX_DH];
@@ -124,17 +128,19 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_rows(const T *__restrict__ qk
     if (active && lane == 0) delta[((size_t)b * H + h) * Tn + i] = dl;
     __syncthreads();
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int j0 = 0; j0 < len; j0 += 64) {
+    const int lim = causal ? min(len, i + 1) : len;
+    const int jend = causal ? min(len, min(Tn, blockIdx.x * ROWS_PER_WG + r * 4 + 4)) : len;
+    for (int j0 = 0; j0 < jend; j0 += 64) {
       const int j = j0 + lane;
       float ds = 0.f;
-      if (j < len) {
+      if (j < lim) {
         const float s = dot_row<T>(sq[wave], base + (size_t)j * ld + D + h * dh, dh);
         const float dp = dot_row<T>(sdo[wave], base + (size_t)j * ld + 2 * D + h * dh, dh);
         ds = __expf(s - L) * (dp - dl);
       }
       sp[wave][lane] = ds;
       __syncthreads();
-      const int nj = min(64, len - j0);
+      const int nj = min(64, jend - j0);
       for (int jj = 0; jj < nj; ++jj) {
         const float dj = sp[wave][jj];
         const T *krow = base + (size_t)(j0 + jj) * ld + D + h * dh;
@@ -160,8 +166,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_rows(const T *__restrict__ qkv, const T *__restrict__ dout,
                                                          const float *__restrict__ lse,
                                                          const float *__restrict__ delta,
-                                                         const int32_t *__restrict__ lengths, int Tn, int H, int dh,
-                                                         float scale, T *__restrict__ dqkv) {
+                                                         const int32_t *__restrict__ lengths, int causal, int Tn,
+                                                         int H, int dh, float scale, T *__restrict__ dqkv) {
   __shared__ float sk[4][MAX_DH];
   __shared__ float sv[4][MAX_DH];
   __shared__ float sp[4][64];
@@ -183,10 +189,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_rows(const T *__restrict__ q
     }
     __syncthreads();
     float ak[4] = {0.f, 0.f, 0.f, 0.f}, av[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int i0 = 0; i0 < Tn; i0 += 64) {
+    // with the causal mask only queries i >= j see key j; start at the tile of the workgroup's first key
+    const int ibeg = causal ? (blockIdx.x * ROWS_PER_WG) / 64 * 64 : 0;
+    for (int i0 = ibeg; i0 < Tn; i0 += 64) {
       const int i = i0 + lane;
       float p = 0.f, ds = 0.f;
-      if (i < Tn && !masked) {
+      if (i < Tn && !masked && (!causal || i >= j)) {
         const float s = dot_row<T>(sk[wave], base + (size_t)i * ld + h * dh, dh);
         const float dp = dot_row<T>(sv[wave], dout + ((size_t)b * Tn + i) * D + h * dh, dh);
         const size_t st = ((size_t)b * H + h) * Tn + i;
@@ -235,43 +243,43 @@ bool g_force_general = false;
 
 void attention_force_general(bool on) { g_force_general = on; }
 
-hipError_t launch_attention_fwd(int dt, const void *qkv, const int32_t *lengths, int B, int T, int H, int dh, void *o,
-                                float *lse, hipStream_t stream) {
+hipError_t launch_attention_fwd(int dt, const void *qkv, const int32_t *lengths, int causal, int B, int T, int H,
+                                int dh, void *o, float *lse, hipStream_t stream) {
   if (!qkv || !o || !lse || !attn_shape_ok(B, T, H, dh)) return hipErrorInvalidValue;
   if (dt == DT_BF16 && !g_force_general && attention_mfma_supported(dh))
-    return launch_attention_fwd_mfma(qkv, lengths, B, T, H, dh, o, lse, stream);
+    return launch_attention_fwd_mfma(qkv, lengths, causal, B, T, H, dh, o, lse, stream);
   const float scale = 1.0f / sqrtf((float)dh);
   dim3 grid((T + ROWS_PER_WG - 1) / ROWS_PER_WG, H, B), block(256);
   if (dt == DT_F32)
-    hipLaunchKernelGGL(attn_fwd_rows<float>, grid, block, 0, stream, static_cast<const float *>(qkv), lengths, T, H,
-                       dh, scale, static_cast<float *>(o), lse);
+    hipLaunchKernelGGL(attn_fwd_rows<float>, grid, block, 0, stream, static_cast<const float *>(qkv), lengths,
+                       causal, T, H, dh, scale, static_cast<float *>(o), lse);
   else
-    hipLaunchKernelGGL(attn_fwd_rows<bf16_t>, grid, block, 0, stream, static_cast<const bf16_t *>(qkv), lengths, T, H,
-                       dh, scale, static_cast<bf16_t *>(o), lse);
+    hipLaunchKernelGGL(attn_fwd_rows<bf16_t>, grid, block, 0, stream, static_cast<const bf16_t *>(qkv), lengths,
+                       causal, T, H, dh, scale, static_cast<bf16_t *>(o), lse);
   return hipGetLastError();
 }
 
 hipError_t launch_attention_bwd(int dt, const void *qkv, const void *o, const void *do_, const float *lse,
-                                const int32_t *lengths, int B, int T, int H, int dh, void *dqkv, float *delta,
-                                hipStream_t stream) {
+                                const int32_t *lengths, int causal, int B, int T, int H, int dh, void *dqkv,
+                                float *delta, hipStream_t stream) {
   if (!qkv || !o || !do_ || !lse || !dqkv || !delta || !attn_shape_ok(B, T, H, dh)) return hipErrorInvalidValue;
   if (dt == DT_BF16 && !g_force_general && attention_mfma_supported(dh))
-    return launch_attention_bwd_mfma(qkv, o, do_, lse, lengths, B, T, H, dh, dqkv, delta, stream);
+    return launch_attention_bwd_mfma(qkv, o, do_, lse, lengths, causal, B, T, H, dh, dqkv, delta, stream);
   const float scale = 1.0f / sqrtf((float)dh);
   dim3 grid((T + ROWS_PER_WG - 1) / ROWS_PER_WG, H, B), block(256);
   if (dt == DT_F32) {
     hipLaunchKernelGGL(attn_bwd_dq_rows<float>, grid, block, 0, stream, static_cast<const float *>(qkv),
-                       static_cast<const float *>(o), static_cast<const float *>(do_), lse, lengths, T, H, dh, scale,
-                       static_cast<float *>(dqkv), delta);
+                       static_cast<const float *>(o), static_cast<const float *>(do_), lse, lengths, causal, T, H, dh,
+                       scale, static_cast<float *>(dqkv), delta);
     hipLaunchKernelGGL(attn_bwd_dkv_rows<float>, grid, block, 0, stream, static_cast<const float *>(qkv),
-                       static_cast<const float *>(do_), lse, delta, lengths, T, H, dh, scale,
+                       static_cast<const float *>(do_), lse, delta, lengths, causal, T, H, dh, scale,
                        static_cast<float *>(dqkv));
   } else {
     hipLaunchKernelGGL(attn_bwd_dq_rows<bf16_t>, grid, block, 0, stream, static_cast<const bf16_t *>(qkv),
-                       static_cast<const bf16_t *>(o), static_cast<const bf16_t *>(do_), lse, lengths, T, H, dh,
-                       scale, static_cast<bf16_t *>(dqkv), delta);
+                       static_cast<const bf16_t *>(o), static_cast<const bf16_t *>(do_), lse, lengths, causal, T, H,
+                       dh, scale, static_cast<bf16_t *>(dqkv), delta);
     hipLaunchKernelGGL(attn_bwd_dkv_rows<bf16_t>, grid, block, 0, stream, static_cast<const bf16_t *>(qkv),
-                       static_cast<const bf16_t *>(do_), lse, delta, lengths, T, H, dh, scale,
+                       static_cast<const bf16_t *>(do_), lse, delta, lengths, causal, T, H, dh, scale,
                        static_cast<bf16_t *>(dqkv));
   }
   return hipGetLastError();

@@ -108,10 +108,10 @@ template <int DH> struct TileRegs {
 __device__ __forceinline__ int acc_row(int r, int h) { return (r >> 2) * 8 + h * 4 + (r & 3); }
 
 // ------------------------------------------------------------------------------------------ forward
-template <int DH>
+template <int DH, bool CAUSAL>
 __global__ __launch_bounds__(NT) void attn_fwd_mfma(const bf16_t *__restrict__ qkv, const int32_t *__restrict__ lengths,
-                                                    int Tn, int H, float scale, bf16_t *__restrict__ o,
-                                                    float *__restrict__ lse) {
+                                                    int Tn, int H, float scale,
+                                                    bf16_t *__restrict__ o, float *__restrict__ lse) {
   constexpr int KS = kc_stride(DH), VS = tr_stride(DH), NK = DH / 16, NB = DH / 32;
   __shared__ __attribute__((aligned(16))) bf16_t sK[TILE * KS];
   __shared__ __attribute__((aligned(16))) bf16_t sV[TILE * VS];
@@ -134,21 +134,26 @@ __global__ __launch_bounds__(NT) void attn_fwd_mfma(const bf16_t *__restrict__ q
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
 
+  // With the causal mask the workgroup needs keys up to its last query only, and a wavefront keys up
+  // to the last of its 32 queries.  Wavefront rows and key blocks are both aligned to 32, so every key
+  // block a wavefront visits holds at least one allowed key for each of its queries.
+  const int kend = CAUSAL ? min(len, (int)(blockIdx.x * ROWS_WG + ROWS_WG)) : len;
+  const int wend = CAUSAL ? min(len, (int)(blockIdx.x * ROWS_WG + wave * 32 + 32)) : len;
   TileRegs<DH> tk, tv;
   tk.load(base + D, ld, min(TILE, Tn));
   tv.load(base + 2 * D, ld, min(TILE, Tn));
-  for (int k0 = 0; k0 < len; k0 += TILE) {
+  for (int k0 = 0; k0 < kend; k0 += TILE) {
     __syncthreads();
     tk.store(sK, KS, nullptr, 0);
     tv.store(sV, VS, nullptr, 0);
     __syncthreads();
-    if (k0 + TILE < len) {
+    if (k0 + TILE < kend) {
       tk.load(base + (size_t)(k0 + TILE) * ld + D, ld, min(TILE, Tn - k0 - TILE));
       tv.load(base + (size_t)(k0 + TILE) * ld + 2 * D, ld, min(TILE, Tn - k0 - TILE));
     }
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
-      if (k0 + kb * 32 >= len) break;
+      if (k0 + kb * 32 >= wend) break;
       f32x16_t s;
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = 0.f;
@@ -159,7 +164,7 @@ __global__ __launch_bounds__(NT) void attn_fwd_mfma(const bf16_t *__restrict__ q
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int key = k0 + kb * 32 + acc_row(r, h2);
-        s[r] = key < len ? s[r] * c : -INFINITY;
+        s[r] = (key < len && (!CAUSAL || key <= q)) ? s[r] * c : -INFINITY;
         mloc = fmaxf(mloc, s[r]);
       }
       mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
@@ -202,7 +207,7 @@ __global__ __launch_bounds__(NT) void attn_fwd_mfma(const bf16_t *__restrict__ q
 }
 
 // ------------------------------------------------------------------------------------------ dQ (+ delta)
-template <int DH>
+template <int DH, bool CAUSAL>
 __global__ __launch_bounds__(NT) void attn_bwd_dq_mfma(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ o,
                                                        const bf16_t *__restrict__ dout,
                                                        const float *__restrict__ lse,
@@ -245,21 +250,23 @@ __global__ __launch_bounds__(NT) void attn_bwd_dq_mfma(const bf16_t *__restrict_
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
 
+  const int kend = CAUSAL ? min(len, (int)(blockIdx.x * ROWS_WG + ROWS_WG)) : len;       // as in the forward kernel
+  const int wend = CAUSAL ? min(len, (int)(blockIdx.x * ROWS_WG + wave * 32 + 32)) : len;
   TileRegs<DH> tk, tv;
   tk.load(base + D, ld, min(TILE, Tn));
   tv.load(base + 2 * D, ld, min(TILE, Tn));
-  for (int k0 = 0; k0 < len; k0 += TILE) {
+  for (int k0 = 0; k0 < kend; k0 += TILE) {
     __syncthreads();
     tk.store(sK, KS, sKt, TS);
     tv.store(sV, KS, nullptr, 0);
     __syncthreads();
-    if (k0 + TILE < len) {
+    if (k0 + TILE < kend) {
       tk.load(base + (size_t)(k0 + TILE) * ld + D, ld, min(TILE, Tn - k0 - TILE));
       tv.load(base + (size_t)(k0 + TILE) * ld + 2 * D, ld, min(TILE, Tn - k0 - TILE));
     }
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
-      if (k0 + kb * 32 >= len) break;
+      if (k0 + kb * 32 >= wend) break;
       f32x16_t s, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = 0.f, dp[r] = 0.f;
@@ -271,7 +278,7 @@ __global__ __launch_bounds__(NT) void attn_bwd_dq_mfma(const bf16_t *__restrict_
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int key = k0 + kb * 32 + acc_row(r, h2);
-        const float p = key < len ? exp2f(s[r] * c - L2) : 0.f;
+        const float p = (key < len && (!CAUSAL || key <= q)) ? exp2f(s[r] * c - L2) : 0.f;
         s[r] = p * (dp[r] - dl);   // dS^T
       }
       bf16x8_t dsf[2] = {pack8(s, 0), pack8(s, 1)};
@@ -299,7 +306,7 @@ __global__ __launch_bounds__(NT) void attn_bwd_dq_mfma(const bf16_t *__restrict_
 // ------------------------------------------------------------------------------------------ dK, dV
 // MODE 0 computes both; MODE 1 only dV, MODE 2 only dK.  Large heads run it twice (1 then 2): two
 // accumulator sets of DH/32 x 16 registers plus the K and V fragments do not fit the register file.
-template <int DH, int MODE>
+template <int DH, int MODE, bool CAUSAL>
 __global__ __launch_bounds__(NT) void attn_bwd_dkv_mfma(const bf16_t *__restrict__ qkv,
                                                         const bf16_t *__restrict__ dout,
                                                         const float *__restrict__ lse,
@@ -358,8 +365,12 @@ __global__ __launch_bounds__(NT) void attn_bwd_dkv_mfma(const bf16_t *__restrict
       rd = ok ? delta[stat0 + q0 + threadIdx.x] : 0.f;
     }
   };
-  if (wg_live) load_tile(0);
-  for (int q0 = 0; wg_live && q0 < Tn; q0 += TILE) {
+  // with the causal mask only queries at or after a key see it: start at the tile of the workgroup's
+  // first key (ROWS_WG is a multiple of TILE) and let a wavefront skip query blocks before its keys
+  const int qbeg = CAUSAL ? (int)(blockIdx.x * ROWS_WG) : 0;
+  const int wkey0 = blockIdx.x * ROWS_WG + wave * 32;
+  if (wg_live) load_tile(qbeg);
+  for (int q0 = qbeg; wg_live && q0 < Tn; q0 += TILE) {
     __syncthreads();
     tq.store(sQ, KS, DO_DK ? sQt : nullptr, TS);
     if constexpr (DO_DK) tdo.store(sDO, KS, DO_DV ? sDOt : nullptr, TS);
@@ -373,6 +384,7 @@ __global__ __launch_bounds__(NT) void attn_bwd_dkv_mfma(const bf16_t *__restrict
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       if (q0 + qb * 32 >= Tn) break;
+      if (CAUSAL && q0 + qb * 32 + 31 < wkey0) continue;
       f32x16_t s, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = 0.f, dp[r] = 0.f;
@@ -385,7 +397,7 @@ __global__ __launch_bounds__(NT) void attn_bwd_dkv_mfma(const bf16_t *__restrict
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int qi = qb * 32 + acc_row(r, h2);
-        const float p = live ? exp2f(s[r] * c - sL[qi]) : 0.f;
+        const float p = (live && (!CAUSAL || q0 + qi >= key)) ? exp2f(s[r] * c - sL[qi]) : 0.f;
         if constexpr (DO_DK) dp[r] = p * (dp[r] - sDl[qi]);   // dS
         s[r] = p;
       }
@@ -433,77 +445,95 @@ template <int DH> size_t dkv_lds_bytes() {
   return (size_t)2 * TILE * (kc_stride(DH) + tr_stride(DH)) * sizeof(bf16_t) + 2 * TILE * sizeof(float);
 }
 
-template <int DH>
+template <int DH, bool CAUSAL>
 hipError_t fwd_t(const void *qkv, const int32_t *lengths, int B, int T, int H, float scale, void *o, float *lse,
                  hipStream_t s) {
   dim3 grid((T + ROWS_WG - 1) / ROWS_WG, H, B);
-  hipLaunchKernelGGL(attn_fwd_mfma<DH>, grid, dim3(NT), 0, s, static_cast<const bf16_t *>(qkv), lengths, T, H, scale,
-                     static_cast<bf16_t *>(o), lse);
+  hipLaunchKernelGGL((attn_fwd_mfma<DH, CAUSAL>), grid, dim3(NT), 0, s, static_cast<const bf16_t *>(qkv), lengths, T, H,
+                     scale, static_cast<bf16_t *>(o), lse);
   return hipGetLastError();
 }
 
-template <int DH, int MODE>
+template <int DH, int MODE, bool CAUSAL>
 hipError_t launch_dkv(dim3 grid, size_t lds, const void *qkv, const void *dout, const float *lse, const float *delta,
                       const int32_t *lengths, int T, int H, float scale, void *dqkv, hipStream_t s) {
   if (lds > 64 * 1024) {
     static bool raised = false;   // allow more than the default 64 KiB of dynamic LDS, once
     if (!raised) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bwd_dkv_mfma<DH, MODE>),
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bwd_dkv_mfma<DH, MODE, CAUSAL>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (e != hipSuccess) return e;
       raised = true;
     }
   }
-  hipLaunchKernelGGL((attn_bwd_dkv_mfma<DH, MODE>), grid, dim3(NT), lds, s, static_cast<const bf16_t *>(qkv),
+  hipLaunchKernelGGL((attn_bwd_dkv_mfma<DH, MODE, CAUSAL>), grid, dim3(NT), lds, s, static_cast<const bf16_t *>(qkv),
                      static_cast<const bf16_t *>(dout), lse, delta, lengths, T, H, scale,
                      static_cast<bf16_t *>(dqkv));
   return hipGetLastError();
 }
 
-template <int DH>
+template <int DH, bool CAUSAL>
 hipError_t bwd_t(const void *qkv, const void *o, const void *dout, const float *lse, const int32_t *lengths, int B,
                  int T, int H, float scale, void *dqkv, float *delta, hipStream_t s) {
   dim3 grid((T + ROWS_WG - 1) / ROWS_WG, H, B);
-  hipLaunchKernelGGL(attn_bwd_dq_mfma<DH>, grid, dim3(NT), 0, s, static_cast<const bf16_t *>(qkv),
+  hipLaunchKernelGGL((attn_bwd_dq_mfma<DH, CAUSAL>), grid, dim3(NT), 0, s, static_cast<const bf16_t *>(qkv),
                      static_cast<const bf16_t *>(o), static_cast<const bf16_t *>(dout), lse, lengths, T, H, scale,
                      static_cast<bf16_t *>(dqkv), delta);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const size_t lds = dkv_lds_bytes<DH>();
-  e = launch_dkv<DH, DH >= 128 ? 1 : 0>(grid, lds, qkv, dout, lse, delta, lengths, T, H, scale, dqkv, s);
+  e = launch_dkv<DH, DH >= 128 ? 1 : 0, CAUSAL>(grid, lds, qkv, dout, lse, delta, lengths, T, H, scale, dqkv, s);
   if (e != hipSuccess || DH < 128) return e;
-  return launch_dkv<DH, 2>(grid, lds, qkv, dout, lse, delta, lengths, T, H, scale, dqkv, s);
+  return launch_dkv<DH, 2, CAUSAL>(grid, lds, qkv, dout, lse, delta, lengths, T, H, scale, dqkv, s);
 }
 
 }  // namespace
 
 bool attention_mfma_supported(int dh) { return dh == 32 || dh == 64 || dh == 96 || dh == 128 || dh == 192 || dh == 256; }
 
-hipError_t launch_attention_fwd_mfma(const void *qkv, const int32_t *lengths, int B, int T, int H, int dh, void *o,
-                                     float *lse, hipStream_t s) {
+hipError_t launch_attention_fwd_mfma(const void *qkv, const int32_t *lengths, int causal, int B, int T, int H, int dh,
+                                     void *o, float *lse, hipStream_t s) {
   const float scale = 1.0f / sqrtf((float)dh);
   switch (dh) {
-    case 32: return fwd_t<32>(qkv, lengths, B, T, H, scale, o, lse, s);
-    case 64: return fwd_t<64>(qkv, lengths, B, T, H, scale, o, lse, s);
-    case 96: return fwd_t<96>(qkv, lengths, B, T, H, scale, o, lse, s);
-    case 128: return fwd_t<128>(qkv, lengths, B, T, H, scale, o, lse, s);
-    case 192: return fwd_t<192>(qkv, lengths, B, T, H, scale, o, lse, s);
-    case 256: return fwd_t<256>(qkv, lengths, B, T, H, scale, o, lse, s);
+    case 32:
+      return causal ? fwd_t<32, true>(qkv, lengths, B, T, H, scale, o, lse, s)
+                    : fwd_t<32, false>(qkv, lengths, B, T, H, scale, o, lse, s);
+    case 64:
+      return causal ? fwd_t<64, true>(qkv, lengths, B, T, H, scale, o, lse, s)
+                    : fwd_t<64, false>(qkv, lengths, B, T, H, scale, o, lse, s);
+    case 96:
+      return causal ? fwd_t<96, true>(qkv, lengths, B, T, H, scale, o, lse, s)
+                    : fwd_t<96, false>(qkv, lengths, B, T, H, scale, o, lse, s);
+    case 128:
+      return causal ? fwd_t<128, true>(qkv, lengths, B, T, H, scale, o, lse, s)
+                    : fwd_t<128, false>(qkv, lengths, B, T, H, scale, o, lse, s);
+    case 192:
+      return causal ? fwd_t<192, true>(qkv, lengths, B, T, H, scale, o, lse, s)
+                    : fwd_t<192, false>(qkv, lengths, B, T, H, scale, o, lse, s);
+    case 256:
+      return causal ? fwd_t<256, true>(qkv, lengths, B, T, H, scale, o, lse, s)
+                    : fwd_t<256, false>(qkv, lengths, B, T, H, scale, o, lse, s);
   }
   return hipErrorInvalidValue;
 }
 
 hipError_t launch_attention_bwd_mfma(const void *qkv, const void *o, const void *dout, const float *lse,
-                                     const int32_t *lengths, int B, int T, int H, int dh, void *dqkv, float *delta,
-                                     hipStream_t s) {
+                                     const int32_t *lengths, int causal, int B, int T, int H, int dh, void *dqkv,
+                                     float *delta, hipStream_t s) {
   const float scale = 1.0f / sqrtf((float)dh);
   switch (dh) {
-    case 32: return bwd_t<32>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
-    case 64: return bwd_t<64>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
-    case 96: return bwd_t<96>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
-    case 128: return bwd_t<128>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
-    case 192: return bwd_t<192>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
-    case 256: return bwd_t<256>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
+    case 32: return causal ? bwd_t<32, true>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s)
+                    : bwd_t<32, false>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
+    case 64: return causal ? bwd_t<64, true>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s)
+                    : bwd_t<64, false>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
+    case 96: return causal ? bwd_t<96, true>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s)
+                    : bwd_t<96, false>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
+    case 128: return causal ? bwd_t<128, true>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s)
+                    : bwd_t<128, false>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
+    case 192: return causal ? bwd_t<192, true>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s)
+                    : bwd_t<192, false>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
+    case 256: return causal ? bwd_t<256, true>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s)
+                    : bwd_t<256, false>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
   }
   return hipErrorInvalidValue;
 }

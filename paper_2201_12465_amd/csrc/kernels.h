@@ -79,26 +79,27 @@ hipError_t launch_layernorm_bwd(int dt, const void *dy, const void *x, const flo
 // ---------------------------------------------------------------------------
 // Masked scaled-dot-product attention on the fused projection buffer
 // qkv[B*T, 3D] (q | k | v slabs, head h = columns h*dh..).  lengths: device
-// int32[B] or nullptr.  Forward writes o[B*T, D] and lse[B,H,T] (log-sum-exp of
-// the scaled, masked scores; fp32).  dh % 16 == 0, dh <= 256.
-hipError_t launch_attention_fwd(int dt, const void *qkv, const int32_t *lengths, int B, int T, int H, int dh,
-                                void *o, float *lse, hipStream_t stream);
+// int32[B] or nullptr (key j of sequence b is masked iff j >= lengths[b]); causal != 0
+// additionally masks key j for query i iff j > i.  Forward writes o[B*T, D] and
+// lse[B,H,T] (log-sum-exp of the scaled, masked scores; fp32).  dh % 16 == 0, dh <= 256.
+hipError_t launch_attention_fwd(int dt, const void *qkv, const int32_t *lengths, int causal, int B, int T, int H,
+                                int dh, void *o, float *lse, hipStream_t stream);
 // Backward: dqkv[B*T, 3D] from do_[B*T, D]; delta is fp32 scratch [B,H,T]
 // (delta_i = sum_d dO_i O_i).  Rows of dk, dv at masked keys are written as 0.
 hipError_t launch_attention_bwd(int dt, const void *qkv, const void *o, const void *do_, const float *lse,
-                                const int32_t *lengths, int B, int T, int H, int dh, void *dqkv, float *delta,
-                                hipStream_t stream);
+                                const int32_t *lengths, int causal, int B, int T, int H, int dh, void *dqkv,
+                                float *delta, hipStream_t stream);
 
 
 // bf16 attention on the matrix cores (attention_mfma.hip); the launchers above pick it when
 // dt is bf16 and the head size is one it is built for, unless the general kernels are forced.
 bool attention_mfma_supported(int dh);
 void attention_force_general(bool on);
-hipError_t launch_attention_fwd_mfma(const void *qkv, const int32_t *lengths, int B, int T, int H, int dh, void *o,
-                                     float *lse, hipStream_t s);
+hipError_t launch_attention_fwd_mfma(const void *qkv, const int32_t *lengths, int causal, int B, int T, int H, int dh,
+                                     void *o, float *lse, hipStream_t s);
 hipError_t launch_attention_bwd_mfma(const void *qkv, const void *o, const void *dout, const float *lse,
-                                     const int32_t *lengths, int B, int T, int H, int dh, void *dqkv, float *delta,
-                                     hipStream_t s);
+                                     const int32_t *lengths, int causal, int B, int T, int H, int dh, void *dqkv,
+                                     float *delta, hipStream_t s);
 
 // ---------------------------------------------------------------------------
 // Fused optimizer step over up to OPT_MAX_TENSORS tensors in one launch (optimizer.hip).

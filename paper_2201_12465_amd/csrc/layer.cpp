@@ -402,7 +402,7 @@ int attention_backward(void *ctx, Tape *tape, const Node *n) {
   const double fl = 10.0 * D * L->T * (double)M, by = 8.0 * M * D * e + 8.0 * L->B * H * L->T;
   hipError_t he = timed(FL_K_ATTN_BWD, fl, by, st, [&] {
     return launch_attention_bwd(L->dt, qs.value, os.value, os.grad, static_cast<const float *>(n->s0), L->lengths,
-                                L->B, L->T, H, dh, nb->ptr, delta.f32(), st);
+                                L->cfg.causal, L->B, L->T, H, dh, nb->ptr, delta.f32(), st);
   });
   if (he != hipSuccess) {
     buf_unref(nb);
@@ -544,7 +544,7 @@ int op_attention(fl_layer *L, int qslot, int *oslot) {
   }
   const double fl = 4.0 * D * L->T * (double)M, by = 4.0 * M * D * e + 4.0 * L->B * H * L->T;
   hipError_t he = timed(FL_K_ATTN_FWD, fl, by, st, [&] {
-    return launch_attention_fwd(L->dt, tp.slots[qslot].value, L->lengths, L->B, L->T, H, dh, ob->ptr,
+    return launch_attention_fwd(L->dt, tp.slots[qslot].value, L->lengths, L->cfg.causal, L->B, L->T, H, dh, ob->ptr,
                                 static_cast<float *>(lb->ptr), st);
   });
   if (he != hipSuccess) {

@@ -128,18 +128,18 @@ int32_t fl_test_colsum(int32_t dtype, const void *in, int32_t M, int32_t N, floa
                     "launch_colsum");
 }
 
-int32_t fl_test_attention_fwd(int32_t dtype, const void *qkv, const int32_t *lengths, int32_t B, int32_t T, int32_t H,
-                              int32_t dh, void *o, float *lse, void *hip_stream) {
-  return hip_status(launch_attention_fwd(dtype == FL_F32 ? DT_F32 : DT_BF16, qkv, lengths, B, T, H, dh, o, lse,
+int32_t fl_test_attention_fwd(int32_t dtype, const void *qkv, const int32_t *lengths, int32_t causal, int32_t B,
+                              int32_t T, int32_t H, int32_t dh, void *o, float *lse, void *hip_stream) {
+  return hip_status(launch_attention_fwd(dtype == FL_F32 ? DT_F32 : DT_BF16, qkv, lengths, causal, B, T, H, dh, o, lse,
                                          static_cast<hipStream_t>(hip_stream)),
                     "launch_attention_fwd");
 }
 
 int32_t fl_test_attention_bwd(int32_t dtype, const void *qkv, const void *o, const void *dout, const float *lse,
-                              const int32_t *lengths, int32_t B, int32_t T, int32_t H, int32_t dh, void *dqkv,
-                              float *delta, void *hip_stream) {
-  return hip_status(launch_attention_bwd(dtype == FL_F32 ? DT_F32 : DT_BF16, qkv, o, dout, lse, lengths, B, T, H, dh,
-                                         dqkv, delta, static_cast<hipStream_t>(hip_stream)),
+                              const int32_t *lengths, int32_t causal, int32_t B, int32_t T, int32_t H, int32_t dh,
+                              void *dqkv, float *delta, void *hip_stream) {
+  return hip_status(launch_attention_bwd(dtype == FL_F32 ? DT_F32 : DT_BF16, qkv, o, dout, lse, lengths, causal, B, T,
+                                         H, dh, dqkv, delta, static_cast<hipStream_t>(hip_stream)),
                     "launch_attention_bwd");
 }
 

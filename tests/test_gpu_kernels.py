@@ -236,32 +236,35 @@ ATTN_CASES = [  # B, T, H, dh, lengths
 ]
 
 
+@pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "bf16-general"])
 @pytest.mark.parametrize("case", ATTN_CASES)
-def test_attention_forward_backward(dtype, case):
+def test_attention_forward_backward(dtype, case, causal):
     """bf16 runs the MFMA kernels where the head size allows; "bf16-general" forces the general ones."""
     b = _lib()
     general = dtype == "bf16-general"
     dtype = dtype.split("-")[0]
     b.lib().fl_test_attention_force_general(1 if general else 0)
     try:
-        _attention_case(b, dtype, case)
+        _attention_case(b, dtype, case, causal)
     finally:
         b.lib().fl_test_attention_force_general(0)
 
 
-def _attention_case(b, dtype, case):
+def _attention_case(b, dtype, case, causal=False):
     B, T, H, dh, lengths = case
     D = H * dh
     rng = np.random.default_rng(B * 1000 + T)
     qkv = quantise(rng.standard_normal((B, T, 3 * D)), dtype)
     dO = quantise(rng.standard_normal((B, T, D)), dtype)
     Q, K, V = (orc.split_heads(qkv[..., i * D:(i + 1) * D].astype(np.float64), H) for i in range(3))
-    Oh, P = orc.attention_fwd(Q, K, V, lengths)
+    Oh, P = orc.attention_fwd(Q, K, V, lengths, causal)
     O = orc.merge_heads(Oh)
     S = (Q @ K.transpose(0, 1, 3, 2)) / math.sqrt(dh)
     if lengths is not None:
         S = np.where(orc.key_mask(lengths, B, T)[:, None, None, :], -np.inf, S)
+    if causal:
+        S = np.where(np.triu(np.ones((T, T), bool), 1)[None, None], -np.inf, S)
     lse_ref = np.log(np.exp(S - S.max(-1, keepdims=True)).sum(-1)) + S.max(-1)
     dQ, dK, dV = orc.attention_bwd(orc.split_heads(dO.astype(np.float64), H), Q, K, V, P)
     dqkv_ref = np.concatenate([orc.merge_heads(dQ), orc.merge_heads(dK), orc.merge_heads(dV)], -1)
@@ -270,7 +273,7 @@ def _attention_case(b, dtype, case):
     dqkv_in = to_dev(qkv, dtype)
     o, lse = empty_dev((B, T, D), dtype), empty_dev((B, H, T), "f32")
     b.check(b.lib().fl_test_attention_fwd(dt_code(dtype), dqkv_in.data_ptr(), dl.data_ptr() if dl is not None else None,
-                                          B, T, H, dh, o.data_ptr(), lse.data_ptr(), stream_ptr()))
+                                          int(causal), B, T, H, dh, o.data_ptr(), lse.data_ptr(), stream_ptr()))
     torch.cuda.synchronize()
     assert rel_err(to_np(o), O) <= _tol(dtype)
     assert rel_err(to_np(lse), lse_ref) <= 1e-5
@@ -278,8 +281,8 @@ def _attention_case(b, dtype, case):
     dqkv, delta = empty_dev((B, T, 3 * D), dtype), empty_dev((B, H, T), "f32")
     tdo = to_dev(dO, dtype)
     b.check(b.lib().fl_test_attention_bwd(dt_code(dtype), dqkv_in.data_ptr(), o.data_ptr(), tdo.data_ptr(),
-                                          lse.data_ptr(), dl.data_ptr() if dl is not None else None, B, T, H, dh,
-                                          dqkv.data_ptr(), delta.data_ptr(), stream_ptr()))
+                                          lse.data_ptr(), dl.data_ptr() if dl is not None else None, int(causal),
+                                          B, T, H, dh, dqkv.data_ptr(), delta.data_ptr(), stream_ptr()))
     torch.cuda.synchronize()
     got = to_np(dqkv)
     for i, name in enumerate("qkv"):

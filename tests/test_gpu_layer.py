@@ -17,7 +17,7 @@ def run_layer_gpu(cfg, inp, layer=None, keep=False):
     dt = cfg.dtype
     own = layer is None
     if own:
-        layer = b.Layer(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F, cfg.act, cfg.norm, dt, cfg.eps)
+        layer = b.Layer(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F, cfg.act, cfg.norm, dt, cfg.eps, cfg.causal)
     p = {k: to_dev(v, dt) for k, v in inp["params"].items()}
     g = {k: empty_dev(v.shape, dt) for k, v in inp["params"].items()}
     X, dY = to_dev(inp["X"], dt), to_dev(inp["dY"], dt)
@@ -42,7 +42,7 @@ def avoid_relu_kink(cfg, inp, margin=2e-5):
     pre-activations carry bf16 rounding of their inputs; its tolerance absorbs the effect.)"""
     if cfg.act != "relu" or cfg.dtype != "f32":
         return inp
-    kw = dict(heads=cfg.H, act=cfg.act, norm=cfg.norm, eps=cfg.eps)
+    kw = dict(heads=cfg.H, act=cfg.act, norm=cfg.norm, eps=cfg.eps, causal=cfg.causal)
     for _ in range(50):
         _, c = orc.layer_forward(inp["params"], inp["X"], inp["lengths"], **kw)
         cols = np.unique(np.nonzero(np.abs(c["ffn"]["U"]) < margin)[-1])
@@ -82,7 +82,7 @@ def relu_kink_allowance(cfg, inp, cache, base, samples=3):
 def check_against_oracle(cfg, inp, tol):
     inp = avoid_relu_kink(cfg, inp)
     Y, dX, g = run_layer_gpu(cfg, inp)
-    kw = dict(heads=cfg.H, act=cfg.act, norm=cfg.norm, eps=cfg.eps)
+    kw = dict(heads=cfg.H, act=cfg.act, norm=cfg.norm, eps=cfg.eps, causal=cfg.causal)
     rY, cache = orc.layer_forward(inp["params"], inp["X"], inp["lengths"], **kw)
     rdX, rg = orc.layer_backward(inp["params"], cache, inp["dY"])
     base = {"dX": rdX, **{"d" + k: rg[k] for k in PARAM_NAMES}}
@@ -126,6 +126,38 @@ def test_variants_ragged(dtype, norm, act, masked):
     if masked:
         inp["lengths"] = np.array([1, 20, 37], np.int32)
     check_against_oracle(cfg, inp, _tol(cfg))
+
+
+@pytest.mark.parametrize("dtype,norm,act,masked", [("f32", "post", "relu", False), ("f32", "pre", "gelu", True),
+                                                   ("bf16", "post", "gelu", True), ("bf16", "pre", "relu", False)])
+def test_causal_variants_ragged(dtype, norm, act, masked):
+    """The autoregressive variant (key j masked for query i iff j > i) on ragged shapes that span
+    several query and key tiles, with and without the key-padding mask on top."""
+    cfg = CONFIGS["cfg2_small_f32"].with_(B=3, T=203, D=192, H=3, F=384, dtype=dtype, norm=norm, act=act,
+                                          causal=True, len_lo=70 if masked else 0, len_hi=203 if masked else 0,
+                                          init="normal0.02" if dtype == "bf16" else "xavier")
+    check_against_oracle(cfg, make_inputs(cfg, seed=4, nontrivial=True), _tol(cfg))
+
+
+def test_causal_config3_full_size():
+    """Config 3's shape with the causal mask added: the second workload of the attention kernel."""
+    cfg = CONFIGS["cfg3_bert_base_bf16"].with_(causal=True)
+    check_against_oracle(cfg, make_inputs(cfg, seed=0, nontrivial=True), _tol(cfg))
+
+
+def test_causal_rows_do_not_see_the_future():
+    """Changing the input from position t0 on must leave every earlier output row bit-identical."""
+    cfg = CONFIGS["cfg2_small_f32"].with_(B=2, T=160, dtype="bf16", act="gelu", causal=True, init="normal0.02")
+    inp = make_inputs(cfg, seed=5, nontrivial=True)
+    Y1 = run_layer_gpu(cfg, inp)[0]
+    t0 = 97
+    inp2 = dict(inp)
+    X2 = inp["X"].copy()
+    X2[:, t0:] = np.random.default_rng(1).standard_normal(X2[:, t0:].shape).astype(X2.dtype)
+    inp2["X"] = X2
+    Y2 = run_layer_gpu(cfg, inp2)[0]
+    assert np.array_equal(Y1[:, :t0], Y2[:, :t0])
+    assert not np.array_equal(Y1[:, t0:], Y2[:, t0:])
 
 
 def test_config4_full_size():

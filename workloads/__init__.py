@@ -39,6 +39,7 @@ class LayerConfig:
     len_hi: int = 0
     layers: int = 1
     eps: float = 1e-5
+    causal: bool = False   # query i attends to keys j <= i only (autoregressive variant)
 
     @property
     def M(self) -> int:
@@ -163,15 +164,16 @@ def make_stack_inputs(cfg: LayerConfig, seed: int = 0, nontrivial: bool = False)
 def layer_flops(cfg: LayerConfig, lengths=None) -> dict:
     """Algorithmic flop counts of one layer (multiply-add = 2 flops).
 
-    Linear part forward: M(8D^2 + 4DF).  Attention forward: 4*D*sum_b T*len_b
-    (every query row against the valid keys only).  Forward+backward is three
-    times the forward count.
+    Linear part forward: M(8D^2 + 4DF).  Attention forward: 4*D*(number of
+    (query, allowed key) pairs): sum_b T*len_b, or with the causal mask
+    sum_b sum_i min(len_b, i+1).  Forward+backward is three times the forward count.
     """
     M, D, F = cfg.M, cfg.D, cfg.F
     lin = M * (8 * D * D + 4 * D * F)
-    if lengths is None:
-        keys = cfg.B * cfg.T
+    lens = np.full(cfg.B, cfg.T, np.int64) if lengths is None else np.asarray(lengths, np.int64)
+    if cfg.causal:
+        pairs = int(sum(np.minimum(n, np.arange(1, cfg.T + 1)).sum() for n in lens))
     else:
-        keys = int(np.sum(lengths))
-    attn = 4 * D * cfg.T * keys
+        pairs = int(cfg.T * lens.sum())
+    attn = 4 * D * pairs
     return {"fwd_linear": lin, "fwd_attn": attn, "fwd": lin + attn, "fwd_bwd": 3 * (lin + attn)}
