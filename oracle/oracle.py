@@ -31,7 +31,11 @@ notes of the repository):
     query keeps at least key 0;
   * LayerNorm uses the biased variance and eps inside the square root;
   * GELU is the exact erf form; relu'(0) = 0;
-  * no dropout.
+  * dropout is off unless the caller passes `masks` (the four scaled keep masks of
+    oracle/dropout.py: attention probabilities after the softmax, the attention
+    projection's output and the second feed-forward linear's output before their
+    residual adds, the feed-forward activation's output); the softmax itself and its
+    backward rule are unchanged, the mask multiplies P on the way to P V.
 
 Every function works on float64 numpy arrays; inputs of other dtypes are
 promoted.  Parity pins live in tests/test_oracle_*.py.
@@ -155,8 +159,9 @@ def key_mask(lengths, B, T):
     return np.arange(T)[None, :] >= lengths[:, None]
 
 
-def attention_fwd(Q, K, V, lengths=None, causal=False):
+def attention_fwd(Q, K, V, lengths=None, causal=False, keep=None):
     """Masked scaled-dot-product attention.  Q, K, V: [B, H, T, dh].
+    keep (optional, [B, H, T, T]): scaled dropout keep mask; then O = (P * keep) V, P is returned undropped.
 
     S = Q K^T / sqrt(dh); masked keys get -inf; P = softmax over keys; O = P V.
     Masked: padding keys (j >= lengths[b]) and, if causal, keys after the query (j > i).
@@ -173,20 +178,24 @@ def attention_fwd(Q, K, V, lengths=None, causal=False):
     S = S - S.max(axis=-1, keepdims=True)
     E = np.exp(S)
     P = E / E.sum(axis=-1, keepdims=True)
-    return P @ V, P
+    return (P if keep is None else P * _f64(keep)) @ V, P
 
 
-def attention_bwd(dO, Q, K, V, P):
+def attention_bwd(dO, Q, K, V, P, keep=None):
     """Gradient function of attention_fwd.
 
     dV = P^T dO;  dP = dO V^T;  dS = P * (dP - rowsum(dP * P));
     dQ = dS K / sqrt(dh);  dK = dS^T Q / sqrt(dh).
     Masked keys have P = 0, hence dS = 0 there and zero rows in dK, dV.
+    With a dropout keep mask the forward used Pd = P * keep:  dV = Pd^T dO and dP = (dO V^T) * keep.
     """
     dO, Q, K, V, P = map(_f64, (dO, Q, K, V, P))
     dh = Q.shape[-1]
-    dV = P.transpose(0, 1, 3, 2) @ dO
+    Pd = P if keep is None else P * _f64(keep)
+    dV = Pd.transpose(0, 1, 3, 2) @ dO
     dP = dO @ V.transpose(0, 1, 3, 2)
+    if keep is not None:
+        dP = dP * _f64(keep)
     dS = P * (dP - (dP * P).sum(axis=-1, keepdims=True))
     scale = 1.0 / math.sqrt(dh)
     dQ = (dS @ K) * scale
@@ -198,65 +207,76 @@ def attention_bwd(dO, Q, K, V, P):
 # the layer
 # ----------------------------------------------------------------------------
 
-def _self_attention_fwd(x, p, H, lengths, causal=False):
+def _self_attention_fwd(x, p, H, lengths, causal=False, keep=None):
     D = x.shape[-1]
     qkv = linear_fwd(x, p["Wqkv"], p["bqkv"])
     Q = split_heads(qkv[..., :D], H)
     K = split_heads(qkv[..., D:2 * D], H)
     V = split_heads(qkv[..., 2 * D:], H)
-    Oh, P = attention_fwd(Q, K, V, lengths, causal)
+    Oh, P = attention_fwd(Q, K, V, lengths, causal, keep)
     O = merge_heads(Oh)
     A = linear_fwd(O, p["Wo"], p["bo"])
-    return A, dict(x=x, Q=Q, K=K, V=V, P=P, O=O)
+    return A, dict(x=x, Q=Q, K=K, V=V, P=P, O=O, keep=keep)
 
 
 def _self_attention_bwd(dA, p, c, g):
     """Adds dWo, dbo, dWqkv, dbqkv to g and returns the gradient w.r.t. the block's input."""
     dO, g["Wo"], g["bo"] = linear_bwd(dA, c["O"], p["Wo"])
     H = c["Q"].shape[1]
-    dQ, dK, dV = attention_bwd(split_heads(dO, H), c["Q"], c["K"], c["V"], c["P"])
+    dQ, dK, dV = attention_bwd(split_heads(dO, H), c["Q"], c["K"], c["V"], c["P"], c.get("keep"))
     dqkv = np.concatenate([merge_heads(dQ), merge_heads(dK), merge_heads(dV)], axis=-1)
     dx, g["Wqkv"], g["bqkv"] = linear_bwd(dqkv, c["x"], p["Wqkv"])
     return dx
 
 
-def _ffn_fwd(x, p, act):
+def _ffn_fwd(x, p, act, keep=None):
+    """keep (optional): scaled dropout keep mask on the activation's output; G is what the second linear reads."""
     U = linear_fwd(x, p["W1"], p["b1"])
     G = act_fwd(U, act)
+    if keep is not None:
+        G = G * _f64(keep)
     Fo = linear_fwd(G, p["W2"], p["b2"])
-    return Fo, dict(x=x, U=U, G=G)
+    return Fo, dict(x=x, U=U, G=G, keep=keep)
 
 
 def _ffn_bwd(dFo, p, c, act, g):
     dG, g["W2"], g["b2"] = linear_bwd(dFo, c["G"], p["W2"])
+    if c.get("keep") is not None:
+        dG = dG * _f64(c["keep"])
     dU = act_bwd(dG, c["U"], act)
     dx, g["W1"], g["b1"] = linear_bwd(dU, c["x"], p["W1"])
     return dx
 
 
-def layer_forward(params, X, lengths=None, *, heads, act="relu", norm="post", eps=1e-5, causal=False):
+def layer_forward(params, X, lengths=None, *, heads, act="relu", norm="post", eps=1e-5, causal=False, masks=None):
     """Forward pass.  X: [B, T, D].  Returns (Y, cache).  causal: query i attends to keys j <= i only.
+    masks: None (no dropout) or the dict of scaled keep masks "attn", "proj", "ffn", "out".
 
     post-LN:  Y1 = LN1(X + Attn(X));   Y = LN2(Y1 + FFN(Y1))
     pre-LN:   R1 = X + Attn(LN1(X));   Y = R1 + FFN(LN2(R1))
+    With dropout, Attn(.) and FFN(.) stand for the dropped-out branch outputs (keep masks "proj" and
+    "out" applied right before the residual adds).
     """
     p = {k: _f64(v) for k, v in params.items()}
     X = _f64(X)
-    c = {"act": act, "norm": norm}
+    mk = masks or {}
+    ka, kp, kf, ko = (None if mk.get(k) is None else _f64(mk[k]) for k in ("attn", "proj", "ffn", "out"))
+    drop = lambda a, k: a if k is None else a * k
+    c = {"act": act, "norm": norm, "keep_proj": kp, "keep_out": ko}
     if norm == "post":
-        A, c["attn"] = _self_attention_fwd(X, p, heads, lengths, causal)
-        R1 = X + A
+        A, c["attn"] = _self_attention_fwd(X, p, heads, lengths, causal, ka)
+        R1 = X + drop(A, kp)
         Y1, c["xhat1"], c["rstd1"] = layernorm_fwd(R1, p["ln1_g"], p["ln1_b"], eps)
-        Fo, c["ffn"] = _ffn_fwd(Y1, p, act)
-        R2 = Y1 + Fo
+        Fo, c["ffn"] = _ffn_fwd(Y1, p, act, kf)
+        R2 = Y1 + drop(Fo, ko)
         Y, c["xhat2"], c["rstd2"] = layernorm_fwd(R2, p["ln2_g"], p["ln2_b"], eps)
     elif norm == "pre":
         N1, c["xhat1"], c["rstd1"] = layernorm_fwd(X, p["ln1_g"], p["ln1_b"], eps)
-        A, c["attn"] = _self_attention_fwd(N1, p, heads, lengths, causal)
-        R1 = X + A
+        A, c["attn"] = _self_attention_fwd(N1, p, heads, lengths, causal, ka)
+        R1 = X + drop(A, kp)
         N2, c["xhat2"], c["rstd2"] = layernorm_fwd(R1, p["ln2_g"], p["ln2_b"], eps)
-        Fo, c["ffn"] = _ffn_fwd(N2, p, act)
-        Y = R1 + Fo
+        Fo, c["ffn"] = _ffn_fwd(N2, p, act, kf)
+        Y = R1 + drop(Fo, ko)
     else:
         raise ValueError(norm)
     return Y, c
@@ -267,16 +287,19 @@ def layer_backward(params, cache, dY):
     p = {k: _f64(v) for k, v in params.items()}
     c, dY, g = cache, _f64(dY), {}
     act = c["act"]
+    # the gradient that enters a dropped-out branch is the residual sum's gradient times the keep mask
+    drop = lambda a, k: a if k is None else a * k
+    kp, ko = c.get("keep_proj"), c.get("keep_out")
     if c["norm"] == "post":
         dR2, g["ln2_g"], g["ln2_b"] = layernorm_bwd(dY, c["xhat2"], c["rstd2"], p["ln2_g"])
-        dY1 = dR2 + _ffn_bwd(dR2, p, c["ffn"], act, g)          # Y1 feeds the residual and the FFN
+        dY1 = dR2 + _ffn_bwd(drop(dR2, ko), p, c["ffn"], act, g)          # Y1 feeds the residual and the FFN
         dR1, g["ln1_g"], g["ln1_b"] = layernorm_bwd(dY1, c["xhat1"], c["rstd1"], p["ln1_g"])
-        dX = dR1 + _self_attention_bwd(dR1, p, c["attn"], g)    # X feeds the residual and attention
+        dX = dR1 + _self_attention_bwd(drop(dR1, kp), p, c["attn"], g)    # X feeds the residual and attention
     else:
-        dN2 = _ffn_bwd(dY, p, c["ffn"], act, g)
+        dN2 = _ffn_bwd(drop(dY, ko), p, c["ffn"], act, g)
         dR1_ln, g["ln2_g"], g["ln2_b"] = layernorm_bwd(dN2, c["xhat2"], c["rstd2"], p["ln2_g"])
         dR1 = dY + dR1_ln
-        dN1 = _self_attention_bwd(dR1, p, c["attn"], g)
+        dN1 = _self_attention_bwd(drop(dR1, kp), p, c["attn"], g)
         dX_ln, g["ln1_g"], g["ln1_b"] = layernorm_bwd(dN1, c["xhat1"], c["rstd1"], p["ln1_g"])
         dX = dR1 + dX_ln
     return dX, g

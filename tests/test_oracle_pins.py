@@ -281,7 +281,7 @@ def test_against_torch_encoder_layer(norm, act, masked):
 
 
 # ---------------------------------------------------------------- (6) brute force, loops only
-def _loops_forward(p, X, lengths, H, act, norm, eps, causal=False):
+def _loops_forward(p, X, lengths, H, act, norm, eps, causal=False, masks=None):
     B, T, D = X.shape
     dh = D // H
     F = p["W1"].shape[0]
@@ -297,6 +297,8 @@ def _loops_forward(p, X, lengths, H, act, norm, eps, causal=False):
     def actf(u):
         return max(u, 0.0) if act == "relu" else 0.5 * u * (1 + math.erf(u / math.sqrt(2)))
 
+    mk = masks or {}
+    keep = lambda name, *idx: 1.0 if mk.get(name) is None else float(mk[name][idx])
     Y = np.zeros((B, T, D))
     for b in range(B):
         n = T if lengths is None else int(lengths[b])
@@ -313,18 +315,19 @@ def _loops_forward(p, X, lengths, H, act, norm, eps, causal=False):
                 e = [math.exp(v - m) for v in s]
                 z = sum(e)
                 for d in range(dh):
-                    O[i][h * dh + d] = sum(e[j] / z * qkv[j][2 * D + h * dh + d] for j in range(nk))
+                    O[i][h * dh + d] = sum(e[j] / z * keep("attn", b, h, i, j) * qkv[j][2 * D + h * dh + d]
+                                           for j in range(nk))
         for t in range(T):
             a = lin(O[t], p["Wo"], p["bo"])
-            r1 = [xin[t][i] + a[i] for i in range(D)]
+            r1 = [xin[t][i] + a[i] * keep("proj", b, t, i) for i in range(D)]
             if norm == "post":
                 y1 = ln(r1, p["ln1_g"], p["ln1_b"])
                 f_in, skip = y1, y1
             else:
                 f_in, skip = ln(r1, p["ln2_g"], p["ln2_b"]), r1
             u = lin(f_in, p["W1"], p["b1"])
-            fo = lin([actf(v) for v in u], p["W2"], p["b2"])
-            r2 = [skip[i] + fo[i] for i in range(D)]
+            fo = lin([actf(v) * keep("ffn", b, t, k) for k, v in enumerate(u)], p["W2"], p["b2"])
+            r2 = [skip[i] + fo[i] * keep("out", b, t, i) for i in range(D)]
             Y[b, t] = ln(r2, p["ln2_g"], p["ln2_b"]) if norm == "post" else r2
     return Y
 
