@@ -65,6 +65,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg3_bert_base_bf16")
     ap.add_argument("--causal", action="store_true", help="the workload with the causal attention mask added")
+    ap.add_argument("--dropout", type=float, default=0.0,
+                    help="training mode: this rate at all four dropout sites, a new seed every step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the second, event-instrumented pass (used under rocprofv3)")
@@ -96,6 +98,8 @@ def main() -> int:
     cfg = CONFIGS[a.workload]
     if a.causal:
         cfg = cfg.with_(name=cfg.name + "+causal", causal=True)
+    if a.dropout > 0:
+        cfg = cfg.with_(name=cfg.name + f"+dropout{a.dropout:g}")
     tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
     dev = lambda x: torch.from_numpy(np.ascontiguousarray(x, np.float32)).cuda().to(tdt).contiguous()
     if cfg.layers > 1:
@@ -114,8 +118,12 @@ def main() -> int:
               for _ in range(nl)]
     stream = torch.cuda.current_stream().cuda_stream
 
+    seeds = iter(range(1, 1 << 30))
+
     def step():
         for l in range(nl):
+            if a.dropout > 0:
+                layers[l].set_dropout(a.dropout, a.dropout, next(seeds))
             layers[l].forward(P[l], acts[l], L, cfg.B, cfg.T, acts[l + 1], stream)
         for l in reversed(range(nl)):
             layers[l].backward(P[l], grads[l + 1], grads[l], G[l], stream)
@@ -231,6 +239,8 @@ def main() -> int:
         except Exception:
             pass
         kw = dict(heads=cfg.H, act=cfg.act, norm=cfg.norm, eps=cfg.eps, causal=cfg.causal)
+        if a.dropout > 0:   # the oracle pays for drawing the masks, as the kernels do
+            from oracle import dropout as odr
         # bounded sample: the first sequences of the batch, sized for roughly 10-30 s of CPU work
         nb = cfg.B if nl == 1 and cfg.M <= 4096 else max(1, min(cfg.B, 4096 // cfg.T))
         sl = slice(0, nb)
@@ -238,6 +248,8 @@ def main() -> int:
         t0 = time.perf_counter()
         reps = 0
         while reps < 1 or (time.perf_counter() - t0 < 10.0 and reps < 20):
+            if a.dropout > 0:
+                kw["masks"] = odr.layer_masks(nb, cfg.T, cfg.D, cfg.H, cfg.F, a.dropout, a.dropout, reps + 1)
             orc.layer_forward_backward(plist[0], inp["X"][sl], inp["dY"][sl], lens, **kw)
             reps += 1
         cs = (time.perf_counter() - t0) / reps

@@ -110,6 +110,20 @@ fl_status_t fl_layer_backward(fl_layer_t *layer, const fl_layer_params_t *params
 fl_status_t fl_layer_backward_accumulate(fl_layer_t *layer, const fl_layer_params_t *params, const void *dY,
                                          void *dX, fl_layer_grads_t *grads, int32_t accumulate, void *hip_stream);
 
+/* Dropout for the forward passes that follow (training mode; the paper's Transformer workloads train
+ * with it, Section 4.2 shows the module).  Four sites, as in the usual encoder layer: the attention
+ * probabilities (rate p_attn) and, with rate p_hidden, the output of the attention projection and of
+ * the second feed-forward linear right before their residual adds, and the output of the
+ * feed-forward activation.  Kept elements are multiplied by 1/(1-p).  Every decision is a pure
+ * function of (seed, site, element position) through the counter-based generator Philox4x32-10
+ * (Salmon et al., SC'11): key = (seed mod 2^32, seed div 2^32); counter = (column div 4, row, site, c3),
+ * the element uses word (column mod 4); kept iff word >= min(2^32-1, floor(p * 2^32)).
+ * Site 1 (attention): row = query, column = key, c3 = b*H + h.  Sites 2 (projection), 3 (activation),
+ * 4 (second linear): row = b*T + t, column = feature, c3 = 0.  A backward pass uses the settings of
+ * the forward pass it belongs to.  Rates of 0 (the default) switch dropout off; pass a new seed per
+ * step.  Rates must be in [0, 1). */
+fl_status_t fl_layer_set_dropout(fl_layer_t *layer, float p_attn, float p_hidden, uint64_t seed);
+
 /* Releases the handle and returns its buffers to the cache.  NULL is a no-op. */
 fl_status_t fl_layer_destroy(fl_layer_t *layer);
 

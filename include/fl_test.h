@@ -56,12 +56,16 @@ int32_t fl_test_colsum(int32_t dtype, const void *in, int32_t M, int32_t N, floa
 int32_t fl_test_copy(const void *src, void *dst, uint64_t nbytes, void *hip_stream);
 
 /* Masked scaled-dot-product attention on qkv[B*T, 3*H*dh]; lse and delta are fp32 [B,H,T];
- * causal != 0 adds the mask j > i. */
-int32_t fl_test_attention_fwd(int32_t dtype, const void *qkv, const int32_t *lengths, int32_t causal, int32_t B,
-                              int32_t T, int32_t H, int32_t dh, void *o, float *lse, void *hip_stream);
+ * causal != 0 adds the mask j > i; p_drop > 0 drops probabilities out (site 1 of fl_layer_set_dropout). */
+int32_t fl_test_attention_fwd(int32_t dtype, const void *qkv, const int32_t *lengths, int32_t causal, float p_drop,
+                              uint64_t seed, int32_t B, int32_t T, int32_t H, int32_t dh, void *o, float *lse,
+                              void *hip_stream);
 int32_t fl_test_attention_bwd(int32_t dtype, const void *qkv, const void *o, const void *dout, const float *lse,
-                              const int32_t *lengths, int32_t causal, int32_t B, int32_t T, int32_t H, int32_t dh,
-                              void *dqkv, float *delta, void *hip_stream);
+                              const int32_t *lengths, int32_t causal, float p_drop, uint64_t seed, int32_t B,
+                              int32_t T, int32_t H, int32_t dh, void *dqkv, float *delta, void *hip_stream);
+/* out[m,n] = in[m,n] * keep(m,n) for a hidden-state site (2, 3 or 4) of fl_layer_set_dropout; p > 0. */
+int32_t fl_test_dropout_mul(int32_t dtype, const void *in, void *out, int32_t M, int32_t N, int32_t site, float p,
+                            uint64_t seed, void *hip_stream);
 
 /* on != 0: bf16 attention uses the general (vector-ALU) kernels instead of the MFMA ones. */
 void fl_test_attention_force_general(int32_t on);

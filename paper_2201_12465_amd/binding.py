@@ -94,6 +94,7 @@ def lib() -> C.CDLL:
             "fl_opt_step": (C.c_int, [C.POINTER(fl_opt_config_t), C.c_int, i32, C.POINTER(vp), C.POINTER(vp),
                                       C.POINTER(vp), C.POINTER(vp), C.POINTER(i64), vp]),
             "fl_zero_grad": (C.c_int, [C.c_int, i32, C.POINTER(vp), C.POINTER(i64), vp]),
+            "fl_layer_set_dropout": (C.c_int, [vp, f32, f32, u64]),
             "fl_layer_destroy": (C.c_int, [vp]),
             "fl_last_error": (C.c_char_p, []),
             "fl_alloc_get_stats": (C.c_int, [C.POINTER(fl_alloc_stats_t)]),
@@ -115,8 +116,9 @@ def lib() -> C.CDLL:
             "fl_test_copy": (i32, [vp, vp, u64, vp]),
             "fl_test_colsum_ws_floats": (i64, [i32, i32]),
             "fl_test_colsum": (i32, [i32, vp, i32, i32, vp, vp, vp]),
-            "fl_test_attention_fwd": (i32, [i32, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp]),
-            "fl_test_attention_bwd": (i32, [i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp, vp]),
+            "fl_test_attention_fwd": (i32, [i32, vp, vp, i32, f32, u64, i32, i32, i32, i32, vp, vp, vp]),
+            "fl_test_attention_bwd": (i32, [i32, vp, vp, vp, vp, vp, i32, f32, u64, i32, i32, i32, i32, vp, vp, vp]),
+            "fl_test_dropout_mul": (i32, [i32, vp, vp, i32, i32, i32, f32, u64, vp]),
             "fl_test_attention_force_general": (None, [i32]),
             "fl_test_alloc_create": (vp, [BACKING_MALLOC, BACKING_FREE]),
             "fl_test_alloc_destroy": (None, [vp]),
@@ -169,6 +171,9 @@ class Layer:
                                 {"f32": FL_F32, "bf16": FL_BF16}[dtype], ln_eps, 1 if causal else 0)
         self._h = C.c_void_p()
         check(lib().fl_layer_create(C.byref(cfg), C.byref(self._h)))
+
+    def set_dropout(self, p_attn: float, p_hidden: float, seed: int) -> None:
+        check(lib().fl_layer_set_dropout(self._h, p_attn, p_hidden, seed))
 
     def forward(self, params: dict, X, lengths, B: int, T: int, Y, stream: int = 0) -> None:
         p = _pack(fl_layer_params_t, params)

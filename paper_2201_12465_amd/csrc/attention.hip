@@ -16,6 +16,7 @@
 // vector ALUs): one wavefront per query row (forward, dQ) or per key row (dK, dV).
 #include "devutil.h"
 #include "kernels.h"
+#include "philox.h"
 
 namespace fl {
 namespace {
@@ -38,7 +39,7 @@ __device__ __forceinline__ float dot_row(const float *__restrict__ s, const T *_
 
 template <typename T>
 __global__ __launch_bounds__(256) void attn_fwd_rows(const T *__restrict__ qkv, const int32_t *__restrict__ lengths,
-                                                     int causal, int Tn, int H, int dh, float scale,
+                                                     int causal, DropSpec drop, int Tn, int H, int dh, float scale,
                                                      T *__restrict__ o, float *__restrict__ lse) {
   __shared__ float sq[4][MAX_DH];
   __shared__ float sp[4][64];
@@ -66,9 +67,9 @@ __global__ __launch_bounds__(256) void attn_fwd_rows(const T *__restrict__ qkv, 
       const float mnew = fmaxf(mrun, wave_max(s));
       const float p = j < lim ? __expf(s - mnew) : 0.f;
       const float corr = __expf(mrun - mnew);
-      lrun = lrun * corr + wave_sum(p);
+      lrun = lrun * corr + wave_sum(p);   // the softmax denominator ignores dropout
       mrun = mnew;
-      sp[wave][lane] = p;
+      sp[wave][lane] = (drop.thr && j < lim) ? p * drop_keep1(drop, j, i, b * H + h) : p;
       __syncthreads();
       const int nj = min(64, jend - j0);
 #pragma unroll
@@ -99,9 +100,9 @@ __global__ __launch_bounds__(256) void attn_fwd_rows(const T *__restrict__ qkv, 
 template <typename T>
 __global__ __launch_bounds__(256) void attn_bwd_dq_rows(const T *__restrict__ qkv, const T *__restrict__ o,
                                                         const T *__restrict__ dout, const float *__restrict__ lse,
-                                                        const int32_t *__restrict__ lengths, int causal, int Tn,
-                                                        int H, int dh, float scale, T *__restrict__ dqkv,
-                                                        float *__restrict__ delta) {
+                                                        const int32_t *__restrict__ lengths, int causal,
+                                                        DropSpec drop, int Tn, int H, int dh, float scale,
+                                                        T *__restrict__ dqkv, float *__restrict__ delta) {
   __shared__ float sq[4][MAX_DH];
   __shared__ float sdo[4][MAX_DH];
   __shared__ float sp[4][64];
@@ -135,7 +136,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_rows(const T *__restrict__ qk
       float ds = 0.f;
       if (j < lim) {
         const float s = dot_row<T>(sq[wave], base + (size_t)j * ld + D + h * dh, dh);
-        const float dp = dot_row<T>(sdo[wave], base + (size_t)j * ld + 2 * D + h * dh, dh);
+        float dp = dot_row<T>(sdo[wave], base + (size_t)j * ld + 2 * D + h * dh, dh);
+        if (drop.thr) dp *= drop_keep1(drop, j, i, b * H + h);
         ds = __expf(s - L) * (dp - dl);
       }
       sp[wave][lane] = ds;
@@ -166,8 +168,9 @@ template <typename T>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_rows(const T *__restrict__ qkv, const T *__restrict__ dout,
                                                          const float *__restrict__ lse,
                                                          const float *__restrict__ delta,
-                                                         const int32_t *__restrict__ lengths, int causal, int Tn,
-                                                         int H, int dh, float scale, T *__restrict__ dqkv) {
+                                                         const int32_t *__restrict__ lengths, int causal,
+                                                         DropSpec drop, int Tn, int H, int dh, float scale,
+                                                         T *__restrict__ dqkv) {
   __shared__ float sk[4][MAX_DH];
   __shared__ float sv[4][MAX_DH];
   __shared__ float sp[4][64];
@@ -196,10 +199,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_rows(const T *__restrict__ q
       float p = 0.f, ds = 0.f;
       if (i < Tn && !masked && (!causal || i >= j)) {
         const float s = dot_row<T>(sk[wave], base + (size_t)i * ld + h * dh, dh);
-        const float dp = dot_row<T>(sv[wave], dout + ((size_t)b * Tn + i) * D + h * dh, dh);
+        float dp = dot_row<T>(sv[wave], dout + ((size_t)b * Tn + i) * D + h * dh, dh);
         const size_t st = ((size_t)b * H + h) * Tn + i;
         p = __expf(s - lse[st]);
-        ds = p * (dp - delta[st]);
+        const float keep = drop.thr ? drop_keep1(drop, j, i, b * H + h) : 1.f;
+        ds = p * (dp * keep - delta[st]);
+        p *= keep;   // dV sees the dropped-out probabilities
       }
       sp[wave][lane] = p;
       sds[wave][lane] = ds;
@@ -243,43 +248,43 @@ bool g_force_general = false;
 
 void attention_force_general(bool on) { g_force_general = on; }
 
-hipError_t launch_attention_fwd(int dt, const void *qkv, const int32_t *lengths, int causal, int B, int T, int H,
-                                int dh, void *o, float *lse, hipStream_t stream) {
+hipError_t launch_attention_fwd(int dt, const void *qkv, const int32_t *lengths, int causal, const DropSpec &drop,
+                                int B, int T, int H, int dh, void *o, float *lse, hipStream_t stream) {
   if (!qkv || !o || !lse || !attn_shape_ok(B, T, H, dh)) return hipErrorInvalidValue;
   if (dt == DT_BF16 && !g_force_general && attention_mfma_supported(dh))
-    return launch_attention_fwd_mfma(qkv, lengths, causal, B, T, H, dh, o, lse, stream);
+    return launch_attention_fwd_mfma(qkv, lengths, causal, drop, B, T, H, dh, o, lse, stream);
   const float scale = 1.0f / sqrtf((float)dh);
   dim3 grid((T + ROWS_PER_WG - 1) / ROWS_PER_WG, H, B), block(256);
   if (dt == DT_F32)
     hipLaunchKernelGGL(attn_fwd_rows<float>, grid, block, 0, stream, static_cast<const float *>(qkv), lengths,
-                       causal, T, H, dh, scale, static_cast<float *>(o), lse);
+                       causal, drop, T, H, dh, scale, static_cast<float *>(o), lse);
   else
     hipLaunchKernelGGL(attn_fwd_rows<bf16_t>, grid, block, 0, stream, static_cast<const bf16_t *>(qkv), lengths,
-                       causal, T, H, dh, scale, static_cast<bf16_t *>(o), lse);
+                       causal, drop, T, H, dh, scale, static_cast<bf16_t *>(o), lse);
   return hipGetLastError();
 }
 
 hipError_t launch_attention_bwd(int dt, const void *qkv, const void *o, const void *do_, const float *lse,
-                                const int32_t *lengths, int causal, int B, int T, int H, int dh, void *dqkv,
-                                float *delta, hipStream_t stream) {
+                                const int32_t *lengths, int causal, const DropSpec &drop, int B, int T, int H, int dh,
+                                void *dqkv, float *delta, hipStream_t stream) {
   if (!qkv || !o || !do_ || !lse || !dqkv || !delta || !attn_shape_ok(B, T, H, dh)) return hipErrorInvalidValue;
   if (dt == DT_BF16 && !g_force_general && attention_mfma_supported(dh))
-    return launch_attention_bwd_mfma(qkv, o, do_, lse, lengths, causal, B, T, H, dh, dqkv, delta, stream);
+    return launch_attention_bwd_mfma(qkv, o, do_, lse, lengths, causal, drop, B, T, H, dh, dqkv, delta, stream);
   const float scale = 1.0f / sqrtf((float)dh);
   dim3 grid((T + ROWS_PER_WG - 1) / ROWS_PER_WG, H, B), block(256);
   if (dt == DT_F32) {
     hipLaunchKernelGGL(attn_bwd_dq_rows<float>, grid, block, 0, stream, static_cast<const float *>(qkv),
-                       static_cast<const float *>(o), static_cast<const float *>(do_), lse, lengths, causal, T, H, dh,
+                       static_cast<const float *>(o), static_cast<const float *>(do_), lse, lengths, causal, drop, T, H, dh,
                        scale, static_cast<float *>(dqkv), delta);
     hipLaunchKernelGGL(attn_bwd_dkv_rows<float>, grid, block, 0, stream, static_cast<const float *>(qkv),
-                       static_cast<const float *>(do_), lse, delta, lengths, causal, T, H, dh, scale,
+                       static_cast<const float *>(do_), lse, delta, lengths, causal, drop, T, H, dh, scale,
                        static_cast<float *>(dqkv));
   } else {
     hipLaunchKernelGGL(attn_bwd_dq_rows<bf16_t>, grid, block, 0, stream, static_cast<const bf16_t *>(qkv),
-                       static_cast<const bf16_t *>(o), static_cast<const bf16_t *>(do_), lse, lengths, causal, T, H,
+                       static_cast<const bf16_t *>(o), static_cast<const bf16_t *>(do_), lse, lengths, causal, drop, T, H,
                        dh, scale, static_cast<bf16_t *>(dqkv), delta);
     hipLaunchKernelGGL(attn_bwd_dkv_rows<bf16_t>, grid, block, 0, stream, static_cast<const bf16_t *>(qkv),
-                       static_cast<const bf16_t *>(do_), lse, delta, lengths, causal, T, H, dh, scale,
+                       static_cast<const bf16_t *>(do_), lse, delta, lengths, causal, drop, T, H, dh, scale,
                        static_cast<bf16_t *>(dqkv));
   }
   return hipGetLastError();

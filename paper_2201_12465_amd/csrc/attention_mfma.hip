@@ -25,6 +25,7 @@
 // (j >= length) get probability exactly 0, so their dK / dV rows are exact zeros.
 #include "devutil.h"
 #include "kernels.h"
+#include "philox.h"
 
 namespace fl {
 namespace {
@@ -108,9 +109,9 @@ template <int DH> struct TileRegs {
 __device__ __forceinline__ int acc_row(int r, int h) { return (r >> 2) * 8 + h * 4 + (r & 3); }
 
 // ------------------------------------------------------------------------------------------ forward
-template <int DH, bool CAUSAL>
+template <int DH, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(NT) void attn_fwd_mfma(const bf16_t *__restrict__ qkv, const int32_t *__restrict__ lengths,
-                                                    int Tn, int H, float scale,
+                                                    DropSpec drop, int Tn, int H, float scale,
                                                     bf16_t *__restrict__ o, float *__restrict__ lse) {
   constexpr int KS = kc_stride(DH), VS = tr_stride(DH), NK = DH / 16, NB = DH / 32;
   __shared__ __attribute__((aligned(16))) bf16_t sK[TILE * KS];
@@ -177,8 +178,17 @@ __global__ __launch_bounds__(NT) void attn_fwd_mfma(const bf16_t *__restrict__ q
       }
       rs += __shfl_xor(rs, 32, 64);
       const float corr = exp2f(m - mnew);
-      l = l * corr + rs;
+      l = l * corr + rs;   // the softmax denominator ignores dropout
       m = mnew;
+      if constexpr (DROP) {  // registers 4g..4g+3 hold four consecutive keys: one generator call
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float kp[4];
+          drop_keep4(drop, (uint32_t)(k0 + kb * 32 + g * 8 + h2 * 4) >> 2, (uint32_t)q, (uint32_t)(b * H + hd), kp);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) s[g * 4 + e] *= kp[e];
+        }
+      }
       bf16x8_t pf[2] = {pack8(s, 0), pack8(s, 1)};
 #pragma unroll
       for (int db = 0; db < NB; ++db) {
@@ -207,12 +217,12 @@ __global__ __launch_bounds__(NT) void attn_fwd_mfma(const bf16_t *__restrict__ q
 }
 
 // ------------------------------------------------------------------------------------------ dQ (+ delta)
-template <int DH, bool CAUSAL>
+template <int DH, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(NT) void attn_bwd_dq_mfma(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ o,
                                                        const bf16_t *__restrict__ dout,
                                                        const float *__restrict__ lse,
-                                                       const int32_t *__restrict__ lengths, int Tn, int H,
-                                                       float scale, bf16_t *__restrict__ dqkv,
+                                                       const int32_t *__restrict__ lengths, DropSpec drop, int Tn,
+                                                       int H, float scale, bf16_t *__restrict__ dqkv,
                                                        float *__restrict__ delta) {
   constexpr int KS = kc_stride(DH), TS = tr_stride(DH), NK = DH / 16, NB = DH / 32;
   __shared__ __attribute__((aligned(16))) bf16_t sK[TILE * KS];   // K rows for S^T = K Q^T
@@ -275,6 +285,15 @@ __global__ __launch_bounds__(NT) void attn_bwd_dq_mfma(const bf16_t *__restrict_
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc_frag(sK, KS, kb * 32, kk, lane), qf[kk], s, 0, 0, 0);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc_frag(sV, KS, kb * 32, kk, lane), dof[kk], dp, 0, 0, 0);
       }
+      if constexpr (DROP) {  // dP = (dO V^T) * keep
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float kp[4];
+          drop_keep4(drop, (uint32_t)(k0 + kb * 32 + g * 8 + h2 * 4) >> 2, (uint32_t)q, (uint32_t)(b * H + hd), kp);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) dp[g * 4 + e] *= kp[e];
+        }
+      }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int key = k0 + kb * 32 + acc_row(r, h2);
@@ -306,13 +325,13 @@ __global__ __launch_bounds__(NT) void attn_bwd_dq_mfma(const bf16_t *__restrict_
 // ------------------------------------------------------------------------------------------ dK, dV
 // MODE 0 computes both; MODE 1 only dV, MODE 2 only dK.  Large heads run it twice (1 then 2): two
 // accumulator sets of DH/32 x 16 registers plus the K and V fragments do not fit the register file.
-template <int DH, int MODE, bool CAUSAL>
+template <int DH, int MODE, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(NT) void attn_bwd_dkv_mfma(const bf16_t *__restrict__ qkv,
                                                         const bf16_t *__restrict__ dout,
                                                         const float *__restrict__ lse,
                                                         const float *__restrict__ delta,
-                                                        const int32_t *__restrict__ lengths, int Tn, int H,
-                                                        float scale, bf16_t *__restrict__ dqkv) {
+                                                        const int32_t *__restrict__ lengths, DropSpec drop, int Tn,
+                                                        int H, float scale, bf16_t *__restrict__ dqkv) {
   constexpr bool DO_DV = MODE != 2, DO_DK = MODE != 1;
   constexpr int KS = kc_stride(DH), TS = tr_stride(DH), NK = DH / 16, NB = DH / 32;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -398,8 +417,10 @@ __global__ __launch_bounds__(NT) void attn_bwd_dkv_mfma(const bf16_t *__restrict
       for (int r = 0; r < 16; ++r) {
         const int qi = qb * 32 + acc_row(r, h2);
         const float p = (live && (!CAUSAL || q0 + qi >= key)) ? exp2f(s[r] * c - sL[qi]) : 0.f;
-        if constexpr (DO_DK) dp[r] = p * (dp[r] - sDl[qi]);   // dS
-        s[r] = p;
+        float keep = 1.f;   // this lane's key against sixteen different queries: one generator call each
+        if constexpr (DROP) keep = drop_keep1(drop, (uint32_t)key, (uint32_t)(q0 + qi), (uint32_t)(b * H + hd));
+        if constexpr (DO_DK) dp[r] = p * (dp[r] * keep - sDl[qi]);   // dS
+        s[r] = p * keep;   // dV sees the dropped-out probabilities
       }
       if constexpr (DO_DV) {
         bf16x8_t pf[2] = {pack8(s, 0), pack8(s, 1)};
@@ -445,95 +466,99 @@ template <int DH> size_t dkv_lds_bytes() {
   return (size_t)2 * TILE * (kc_stride(DH) + tr_stride(DH)) * sizeof(bf16_t) + 2 * TILE * sizeof(float);
 }
 
-template <int DH, bool CAUSAL>
-hipError_t fwd_t(const void *qkv, const int32_t *lengths, int B, int T, int H, float scale, void *o, float *lse,
-                 hipStream_t s) {
+template <int DH, bool CAUSAL, bool DROP>
+hipError_t fwd_t(const void *qkv, const int32_t *lengths, const DropSpec &drop, int B, int T, int H, float scale,
+                 void *o, float *lse, hipStream_t s) {
   dim3 grid((T + ROWS_WG - 1) / ROWS_WG, H, B);
-  hipLaunchKernelGGL((attn_fwd_mfma<DH, CAUSAL>), grid, dim3(NT), 0, s, static_cast<const bf16_t *>(qkv), lengths, T, H,
-                     scale, static_cast<bf16_t *>(o), lse);
+  hipLaunchKernelGGL((attn_fwd_mfma<DH, CAUSAL, DROP>), grid, dim3(NT), 0, s, static_cast<const bf16_t *>(qkv), lengths,
+                     drop, T, H, scale, static_cast<bf16_t *>(o), lse);
   return hipGetLastError();
 }
 
-template <int DH, int MODE, bool CAUSAL>
+template <int DH, int MODE, bool CAUSAL, bool DROP>
 hipError_t launch_dkv(dim3 grid, size_t lds, const void *qkv, const void *dout, const float *lse, const float *delta,
-                      const int32_t *lengths, int T, int H, float scale, void *dqkv, hipStream_t s) {
+                      const int32_t *lengths, const DropSpec &drop, int T, int H, float scale, void *dqkv,
+                      hipStream_t s) {
   if (lds > 64 * 1024) {
     static bool raised = false;   // allow more than the default 64 KiB of dynamic LDS, once
     if (!raised) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bwd_dkv_mfma<DH, MODE, CAUSAL>),
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bwd_dkv_mfma<DH, MODE, CAUSAL, DROP>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (e != hipSuccess) return e;
       raised = true;
     }
   }
-  hipLaunchKernelGGL((attn_bwd_dkv_mfma<DH, MODE, CAUSAL>), grid, dim3(NT), lds, s, static_cast<const bf16_t *>(qkv),
-                     static_cast<const bf16_t *>(dout), lse, delta, lengths, T, H, scale,
-                     static_cast<bf16_t *>(dqkv));
+  hipLaunchKernelGGL((attn_bwd_dkv_mfma<DH, MODE, CAUSAL, DROP>), grid, dim3(NT), lds, s,
+                     static_cast<const bf16_t *>(qkv), static_cast<const bf16_t *>(dout), lse, delta, lengths, drop, T, H,
+                     scale, static_cast<bf16_t *>(dqkv));
   return hipGetLastError();
 }
 
-template <int DH, bool CAUSAL>
-hipError_t bwd_t(const void *qkv, const void *o, const void *dout, const float *lse, const int32_t *lengths, int B,
-                 int T, int H, float scale, void *dqkv, float *delta, hipStream_t s) {
+template <int DH, bool CAUSAL, bool DROP>
+hipError_t bwd_t(const void *qkv, const void *o, const void *dout, const float *lse, const int32_t *lengths,
+                 const DropSpec &drop, int B, int T, int H, float scale, void *dqkv, float *delta, hipStream_t s) {
   dim3 grid((T + ROWS_WG - 1) / ROWS_WG, H, B);
-  hipLaunchKernelGGL((attn_bwd_dq_mfma<DH, CAUSAL>), grid, dim3(NT), 0, s, static_cast<const bf16_t *>(qkv),
-                     static_cast<const bf16_t *>(o), static_cast<const bf16_t *>(dout), lse, lengths, T, H, scale,
+  hipLaunchKernelGGL((attn_bwd_dq_mfma<DH, CAUSAL, DROP>), grid, dim3(NT), 0, s, static_cast<const bf16_t *>(qkv),
+                     static_cast<const bf16_t *>(o), static_cast<const bf16_t *>(dout), lse, lengths, drop, T, H, scale,
                      static_cast<bf16_t *>(dqkv), delta);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const size_t lds = dkv_lds_bytes<DH>();
-  e = launch_dkv<DH, DH >= 128 ? 1 : 0, CAUSAL>(grid, lds, qkv, dout, lse, delta, lengths, T, H, scale, dqkv, s);
+  e = launch_dkv<DH, DH >= 128 ? 1 : 0, CAUSAL, DROP>(grid, lds, qkv, dout, lse, delta, lengths, drop, T, H, scale, dqkv,
+                                                      s);
   if (e != hipSuccess || DH < 128) return e;
-  return launch_dkv<DH, 2, CAUSAL>(grid, lds, qkv, dout, lse, delta, lengths, T, H, scale, dqkv, s);
+  return launch_dkv<DH, 2, CAUSAL, DROP>(grid, lds, qkv, dout, lse, delta, lengths, drop, T, H, scale, dqkv, s);
+}
+
+// the four (causal, dropout) instances of one head size
+template <int DH>
+hipError_t fwd_pick(int causal, const void *qkv, const int32_t *lengths, const DropSpec &drop, int B, int T, int H,
+                    float scale, void *o, float *lse, hipStream_t s) {
+  if (causal) return drop.thr ? fwd_t<DH, true, true>(qkv, lengths, drop, B, T, H, scale, o, lse, s)
+                              : fwd_t<DH, true, false>(qkv, lengths, drop, B, T, H, scale, o, lse, s);
+  return drop.thr ? fwd_t<DH, false, true>(qkv, lengths, drop, B, T, H, scale, o, lse, s)
+                  : fwd_t<DH, false, false>(qkv, lengths, drop, B, T, H, scale, o, lse, s);
+}
+template <int DH>
+hipError_t bwd_pick(int causal, const void *qkv, const void *o, const void *dout, const float *lse,
+                    const int32_t *lengths, const DropSpec &drop, int B, int T, int H, float scale, void *dqkv,
+                    float *delta, hipStream_t s) {
+  if (causal)
+    return drop.thr ? bwd_t<DH, true, true>(qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s)
+                    : bwd_t<DH, true, false>(qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s);
+  return drop.thr ? bwd_t<DH, false, true>(qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s)
+                  : bwd_t<DH, false, false>(qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s);
 }
 
 }  // namespace
 
 bool attention_mfma_supported(int dh) { return dh == 32 || dh == 64 || dh == 96 || dh == 128 || dh == 192 || dh == 256; }
 
-hipError_t launch_attention_fwd_mfma(const void *qkv, const int32_t *lengths, int causal, int B, int T, int H, int dh,
-                                     void *o, float *lse, hipStream_t s) {
+hipError_t launch_attention_fwd_mfma(const void *qkv, const int32_t *lengths, int causal, const DropSpec &drop, int B,
+                                     int T, int H, int dh, void *o, float *lse, hipStream_t s) {
   const float scale = 1.0f / sqrtf((float)dh);
   switch (dh) {
-    case 32:
-      return causal ? fwd_t<32, true>(qkv, lengths, B, T, H, scale, o, lse, s)
-                    : fwd_t<32, false>(qkv, lengths, B, T, H, scale, o, lse, s);
-    case 64:
-      return causal ? fwd_t<64, true>(qkv, lengths, B, T, H, scale, o, lse, s)
-                    : fwd_t<64, false>(qkv, lengths, B, T, H, scale, o, lse, s);
-    case 96:
-      return causal ? fwd_t<96, true>(qkv, lengths, B, T, H, scale, o, lse, s)
-                    : fwd_t<96, false>(qkv, lengths, B, T, H, scale, o, lse, s);
-    case 128:
-      return causal ? fwd_t<128, true>(qkv, lengths, B, T, H, scale, o, lse, s)
-                    : fwd_t<128, false>(qkv, lengths, B, T, H, scale, o, lse, s);
-    case 192:
-      return causal ? fwd_t<192, true>(qkv, lengths, B, T, H, scale, o, lse, s)
-                    : fwd_t<192, false>(qkv, lengths, B, T, H, scale, o, lse, s);
-    case 256:
-      return causal ? fwd_t<256, true>(qkv, lengths, B, T, H, scale, o, lse, s)
-                    : fwd_t<256, false>(qkv, lengths, B, T, H, scale, o, lse, s);
+    case 32: return fwd_pick<32>(causal, qkv, lengths, drop, B, T, H, scale, o, lse, s);
+    case 64: return fwd_pick<64>(causal, qkv, lengths, drop, B, T, H, scale, o, lse, s);
+    case 96: return fwd_pick<96>(causal, qkv, lengths, drop, B, T, H, scale, o, lse, s);
+    case 128: return fwd_pick<128>(causal, qkv, lengths, drop, B, T, H, scale, o, lse, s);
+    case 192: return fwd_pick<192>(causal, qkv, lengths, drop, B, T, H, scale, o, lse, s);
+    case 256: return fwd_pick<256>(causal, qkv, lengths, drop, B, T, H, scale, o, lse, s);
   }
   return hipErrorInvalidValue;
 }
 
 hipError_t launch_attention_bwd_mfma(const void *qkv, const void *o, const void *dout, const float *lse,
-                                     const int32_t *lengths, int causal, int B, int T, int H, int dh, void *dqkv,
-                                     float *delta, hipStream_t s) {
+                                     const int32_t *lengths, int causal, const DropSpec &drop, int B, int T, int H,
+                                     int dh, void *dqkv, float *delta, hipStream_t s) {
   const float scale = 1.0f / sqrtf((float)dh);
   switch (dh) {
-    case 32: return causal ? bwd_t<32, true>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s)
-                    : bwd_t<32, false>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
-    case 64: return causal ? bwd_t<64, true>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s)
-                    : bwd_t<64, false>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
-    case 96: return causal ? bwd_t<96, true>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s)
-                    : bwd_t<96, false>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
-    case 128: return causal ? bwd_t<128, true>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s)
-                    : bwd_t<128, false>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
-    case 192: return causal ? bwd_t<192, true>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s)
-                    : bwd_t<192, false>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
-    case 256: return causal ? bwd_t<256, true>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s)
-                    : bwd_t<256, false>(qkv, o, dout, lse, lengths, B, T, H, scale, dqkv, delta, s);
+    case 32: return bwd_pick<32>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s);
+    case 64: return bwd_pick<64>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s);
+    case 96: return bwd_pick<96>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s);
+    case 128: return bwd_pick<128>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s);
+    case 192: return bwd_pick<192>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s);
+    case 256: return bwd_pick<256>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s);
   }
   return hipErrorInvalidValue;
 }

@@ -114,7 +114,7 @@ __device__ __forceinline__ float frag_f32(const float *lds, int r0, int kk, int 
   return lds[(kk * 2 + (lane >> 5)) * LDR + r0 + (lane & 31)];
 }
 
-template <typename T, bool AKC, bool BKC, int TMW>
+template <typename T, bool AKC, bool BKC, int TMW, bool DROP>
 __global__ __launch_bounds__(NTHREADS) void gemm_kernel(GemmDev p) {
   constexpr int KT = Tile<T>::KT;
   constexpr int BMT = 64 * TMW;  // tile height: TMW MFMA tiles per wavefront in m
@@ -196,20 +196,25 @@ __global__ __launch_bounds__(NTHREADS) void gemm_kernel(GemmDev p) {
   // made the operand tiles free, and 4 waves x 32 x 68 floats fit in them.
   static_assert(4 * 32 * 68 * sizeof(float) <= 2 * OPERAND_LDS_BYTES, "epilogue staging does not fit");
   float *cw = reinterpret_cast<float *>(smem) + (size_t)wave * 32 * 68;
-  gemm_staged_epilogue<T, TMW, 2>(p, acc, cw, row0 + wm * 32 * TMW, col0 + wn * 64, lane);
+  gemm_staged_epilogue<T, TMW, 2, DROP>(p, acc, cw, row0 + wm * 32 * TMW, col0 + wn * 64, lane);
 }
 
+template <typename T, int TMW, bool DROP>
+hipError_t launch_ttd(const GemmArgs &a, const GemmDev &d, dim3 grid, hipStream_t s) {
+  if (a.a_kc && a.b_kc)
+    hipLaunchKernelGGL((gemm_kernel<T, true, true, TMW, DROP>), grid, dim3(NTHREADS), 0, s, d);
+  else if (a.a_kc && !a.b_kc)
+    hipLaunchKernelGGL((gemm_kernel<T, true, false, TMW, DROP>), grid, dim3(NTHREADS), 0, s, d);
+  else if (!a.a_kc && !a.b_kc)
+    hipLaunchKernelGGL((gemm_kernel<T, false, false, TMW, DROP>), grid, dim3(NTHREADS), 0, s, d);
+  else
+    hipLaunchKernelGGL((gemm_kernel<T, false, true, TMW, DROP>), grid, dim3(NTHREADS), 0, s, d);
+  return hipGetLastError();
+}
+// the instances with the dropout steps in their epilogue are separate kernels
 template <typename T, int TMW>
 hipError_t launch_tt(const GemmArgs &a, const GemmDev &d, dim3 grid, hipStream_t s) {
-  if (a.a_kc && a.b_kc)
-    hipLaunchKernelGGL((gemm_kernel<T, true, true, TMW>), grid, dim3(NTHREADS), 0, s, d);
-  else if (a.a_kc && !a.b_kc)
-    hipLaunchKernelGGL((gemm_kernel<T, true, false, TMW>), grid, dim3(NTHREADS), 0, s, d);
-  else if (!a.a_kc && !a.b_kc)
-    hipLaunchKernelGGL((gemm_kernel<T, false, false, TMW>), grid, dim3(NTHREADS), 0, s, d);
-  else
-    hipLaunchKernelGGL((gemm_kernel<T, false, true, TMW>), grid, dim3(NTHREADS), 0, s, d);
-  return hipGetLastError();
+  return d.drop_where ? launch_ttd<T, TMW, true>(a, d, grid, s) : launch_ttd<T, TMW, false>(a, d, grid, s);
 }
 
 // tmw = 2: 128x128 tiles; tmw = 1: 64x128 tiles
@@ -251,7 +256,7 @@ hipError_t launch_gemm(int dt, const GemmArgs &a, hipStream_t stream) {
   if ((a.a_kc ? a.K : a.M) % 8 || (a.b_kc ? a.K : a.N) % 8) return hipErrorInvalidValue;
   if (!aligned16(a.A) || !aligned16(a.B)) return hipErrorInvalidValue;
   if (splits > 1) {
-    if (!a.partial || a.bias || a.residual || a.preact || a.act || a.dact || !aligned16(a.partial))
+    if (!a.partial || a.bias || a.residual || a.preact || a.act || a.dact || a.drop_where || !aligned16(a.partial))
       return hipErrorInvalidValue;
   } else {
     if (!a.C || a.ldc % 8 || !aligned16(a.C) || !aligned16(a.bias) || !aligned16(a.residual) ||
@@ -263,6 +268,8 @@ hipError_t launch_gemm(int dt, const GemmArgs &a, hipStream_t stream) {
   d.M = a.M; d.N = a.N; d.K = a.K; d.lda = a.lda; d.ldb = a.ldb; d.ldc = a.ldc;
   d.bias = a.bias; d.residual = a.residual; d.aux = a.aux; d.preact = a.preact;
   d.act = a.act; d.dact = a.dact;
+  d.drop_where = a.drop.thr ? a.drop_where : 0;
+  d.drop = a.drop;
   d.partial = splits > 1 ? a.partial : nullptr;
   int kps = (a.K + splits - 1) / splits;
   kps = (kps + KT - 1) / KT * KT;
@@ -272,7 +279,8 @@ hipError_t launch_gemm(int dt, const GemmArgs &a, hipStream_t stream) {
   // every k-range must be non-empty, or its partial slab would stay unwritten
   if ((long)(splits - 1) * kps >= a.K) return hipErrorInvalidValue;
   if (dt == DT_BF16 && gemm_pipe_eligible(a, kps)) {
-    const int variant = gemm_pipe_pick_variant(a.a_kc, a.b_kc, a.M, a.N, a.K);
+    int variant = gemm_pipe_pick_variant(a.a_kc, a.b_kc, a.M, a.N, a.K);
+    if (variant == 7 && d.drop_where) variant = 0;  // with the dropout steps the 256x192 instance spills
     if (variant >= 0) return launch_gemm_bf16_pipe(a, &d, splits, variant, stream);
   }
   // fewer than 1.5 full tiles per CU: halve the tile height so that twice as many workgroups run

@@ -1,6 +1,7 @@
 // Device-side argument block and epilogue shared by the GEMM kernels.
 #pragma once
 #include "devutil.h"
+#include "philox.h"
 
 namespace fl {
 
@@ -13,11 +14,14 @@ struct GemmDev {
   int act, dact;
   float *partial;
   int k_per_split, tiles_m, tiles_n, splits;
+  int drop_where;  // 0 none, 1 = after the activation (forward), 2 = with the activation derivative (backward)
+  DropSpec drop;
 };
 
 
 // Epilogue on four consecutive outputs C[m, n0..n0+3] (see GemmArgs for the order of the steps).
-template <typename T>
+// DROP: the kernel instance was built with the dropout steps (they cost registers even when unused).
+template <typename T, bool DROP>
 __device__ __forceinline__ void gemm_epilogue_quad(const GemmDev &p, int m, int n0, float (&v)[4]) {
   if (p.partial) {
     float *dst = p.partial + (size_t)m * p.N + n0;  // the kernel has moved `partial` to its k-range's slab
@@ -39,6 +43,11 @@ __device__ __forceinline__ void gemm_epilogue_quad(const GemmDev &p, int m, int 
 #pragma unroll
     for (int e = 0; e < 4; ++e) v[e] = gelu_f(v[e]);
   }
+  if (DROP && p.drop_where == 1) {
+    drop_keep4(p.drop, (uint32_t)n0 >> 2, (uint32_t)m, 0u, t);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] *= t[e];
+  }
   if (p.residual) {
     VecIO<T, 4>::load(static_cast<const T *>(p.residual) + off, t);
 #pragma unroll
@@ -53,6 +62,11 @@ __device__ __forceinline__ void gemm_epilogue_quad(const GemmDev &p, int m, int 
 #pragma unroll
       for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_f(t[e]);
     }
+  }
+  if (DROP && p.drop_where == 2) {
+    drop_keep4(p.drop, (uint32_t)n0 >> 2, (uint32_t)m, 0u, t);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] *= t[e];
   }
   VecIO<T, 4>::store(static_cast<T *>(p.C) + off, v);
 }
@@ -74,7 +88,7 @@ template <> struct Oct<float> {
   }
 };
 
-template <typename T>
+template <typename T, bool DROP>
 __device__ __forceinline__ void gemm_epilogue_oct(const GemmDev &p, int m, int n0, float (&v)[8]) {
   if (p.partial) {
     Oct<float>::store(p.partial + (size_t)m * p.N + n0, v);
@@ -95,6 +109,13 @@ __device__ __forceinline__ void gemm_epilogue_oct(const GemmDev &p, int m, int n
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
   }
+  if (DROP && p.drop_where == 1) {
+    float k0[4], k1[4];
+    drop_keep4(p.drop, (uint32_t)n0 >> 2, (uint32_t)m, 0u, k0);
+    drop_keep4(p.drop, ((uint32_t)n0 >> 2) + 1, (uint32_t)m, 0u, k1);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] *= k0[e], v[e + 4] *= k1[e];
+  }
   if (p.residual) {
     Oct<T>::load(static_cast<const T *>(p.residual) + off, t);
 #pragma unroll
@@ -110,6 +131,13 @@ __device__ __forceinline__ void gemm_epilogue_oct(const GemmDev &p, int m, int n
       for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(t[e]);
     }
   }
+  if (DROP && p.drop_where == 2) {
+    float k0[4], k1[4];
+    drop_keep4(p.drop, (uint32_t)n0 >> 2, (uint32_t)m, 0u, k0);
+    drop_keep4(p.drop, ((uint32_t)n0 >> 2) + 1, (uint32_t)m, 0u, k1);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] *= k0[e], v[e + 4] *= k1[e];
+  }
   Oct<T>::store(static_cast<T *>(p.C) + off, v);
 }
 
@@ -120,7 +148,7 @@ __device__ __forceinline__ void gemm_epilogue_oct(const GemmDev &p, int m, int n
 // every bank once) and walked row-wise, so that every global access is 16 or 32 bytes per lane and
 // a row's TN*32 outputs form one contiguous segment.  `cw` must hold 32*(TN*32+4) floats per wave.
 // The caller has made sure (barrier) that nobody still reads the LDS this overwrites.
-template <typename T, int TM, int TN>
+template <typename T, int TM, int TN, bool DROP>
 __device__ __forceinline__ void gemm_staged_epilogue(const GemmDev &p, const f32x16_t (&acc)[TM][TN], float *cw,
                                                      int mbase, int nbase, int lane) {
   constexpr int WC = TN * 32, CS = WC + 4;
@@ -143,7 +171,7 @@ __device__ __forceinline__ void gemm_staged_epilogue(const GemmDev &p, const f32
       const float4 hi = *reinterpret_cast<const float4 *>(cw + r * CS + c8 * 8 + 4);
       if (m < p.M && n0 < p.N) {
         float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-        gemm_epilogue_oct<T>(p, m, n0, v);
+        gemm_epilogue_oct<T, DROP>(p, m, n0, v);
       }
     }
   }

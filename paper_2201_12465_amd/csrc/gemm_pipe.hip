@@ -87,7 +87,7 @@ __device__ __forceinline__ bf16x8_t frag(const unsigned char *stage, int r0, int
 }
 
 // WM x WN wavefronts share a BM x BN tile; each owns TM x TN MFMA tiles of 32x32.
-template <bool AKC, bool BKC, int BM, int BN, int NS, int WM, int WN>
+template <bool AKC, bool BKC, int BM, int BN, int NS, int WM, int WN, bool DROP>
 __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_pipe(GemmDev p) {
   constexpr int NW = WM * WN;
   constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);
@@ -172,16 +172,16 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_pipe(GemmDev p) {
   __builtin_amdgcn_s_barrier();  // every wave is done reading the operand stages
   asm volatile("" ::: "memory");
   float *cw = reinterpret_cast<float *>(smem) + (size_t)wave * 32 * (TN * 32 + 4);
-  gemm_staged_epilogue<bf16_t, TM, TN>(p, acc, cw, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane);
+  gemm_staged_epilogue<bf16_t, TM, TN, DROP>(p, acc, cw, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane);
 }
 
-template <bool AKC, bool BKC, int BM, int BN, int NS, int WM = 2, int WN = 2>
-hipError_t launch_cfg(GemmDev d, int splits, hipStream_t s) {
+template <bool AKC, bool BKC, int BM, int BN, int NS, int WM, int WN, bool DROP>
+hipError_t launch_cfg_d(GemmDev d, int splits, hipStream_t s) {
   constexpr size_t stage_lds = (size_t)NS * (BM + BN) * 128;
   constexpr size_t epi_lds = (size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float);
   constexpr size_t lds = stage_lds > epi_lds ? stage_lds : epi_lds;
   static_assert(lds <= 160 * 1024, "stages do not fit in LDS");
-  auto kern = gemm_bf16_pipe<AKC, BKC, BM, BN, NS, WM, WN>;
+  auto kern = gemm_bf16_pipe<AKC, BKC, BM, BN, NS, WM, WN, DROP>;
   if (lds > 64 * 1024) {
     static bool raised = false;
     if (!raised) {
@@ -197,6 +197,18 @@ hipError_t launch_cfg(GemmDev d, int splits, hipStream_t s) {
   dim3 grid(d.tiles_m * d.tiles_n * splits);
   hipLaunchKernelGGL(kern, grid, dim3(WM * WN * 64), lds, s, d);
   return hipGetLastError();
+}
+
+// Dropout in the epilogue exists for the 128x128 / 2-stage variant (the forward GEMMs in training mode).
+template <bool AKC, bool BKC, int BM, int BN, int NS, int WM = 2, int WN = 2>
+hipError_t launch_cfg(const GemmDev &d, int splits, hipStream_t s) {
+  if (d.drop_where) {
+    if constexpr (AKC && BKC && NS == 2 && BM == 128 && BN == 128)
+      return launch_cfg_d<AKC, BKC, BM, BN, NS, WM, WN, true>(d, splits, s);
+    else
+      return hipErrorInvalidValue;
+  }
+  return launch_cfg_d<AKC, BKC, BM, BN, NS, WM, WN, false>(d, splits, s);
 }
 
 template <bool AKC, bool BKC>

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime_api.h>
 #include <cstddef>
 #include <cstdint>
+#include "philox.h"
 
 namespace fl {
 
@@ -20,6 +21,9 @@ static inline size_t dt_size(int dt) { return dt == DT_F32 ? 4 : 2; }
 // Epilogue, in this order, on v = accumulator:
 //   v += bias[n];  preact[m,n] = v (if preact);  v = act(v);  v += residual[m,n];
 //   v *= act'(aux[m,n]) (dact: 1 = aux > 0, 2 = exact-GELU derivative at aux);  C[m,n] = v
+// Dropout (drop_where, drop): 1 multiplies v by the keep mask of element (m, n) right after the
+// activation (before the residual is added); 2 multiplies it at the very end (the backward of a
+// dropped-out activation output: mask and activation derivative commute).
 // With splits > 1 (k is cut into `splits` ranges) the raw partial sums go to
 // `partial` (fp32 [splits][M][N]) and the epilogue must be empty; the caller then
 // runs reduce_partials.
@@ -35,6 +39,8 @@ struct GemmArgs {
   int act = 0, dact = 0;
   float *partial = nullptr;
   int splits = 1;
+  int drop_where = 0;
+  DropSpec drop;
 };
 hipError_t launch_gemm(int dt, const GemmArgs &a, hipStream_t stream);
 // Number of k-ranges launch_gemm should use so that a small output still fills the chip.
@@ -57,6 +63,9 @@ hipError_t launch_reduce_partials(int dt, const float *partial, int P, size_t st
 size_t colsum_ws_floats(int M, int N);
 hipError_t launch_colsum(int dt, const void *in, int M, int N, float *ws, void *out, hipStream_t stream,
                          bool accumulate = false);
+
+// out[m,n] = in[m,n] * keep(m,n) for the hidden-state site in d (in == out allowed); N % 4 == 0.
+hipError_t launch_dropout_mul(int dt, const void *in, void *out, int M, int N, const DropSpec &d, hipStream_t stream);
 
 // dst[0..nbytes) = src[0..nbytes): nbytes % 16 == 0, both pointers 16-byte aligned.
 hipError_t launch_copy(const void *src, void *dst, size_t nbytes, hipStream_t stream);
@@ -82,24 +91,25 @@ hipError_t launch_layernorm_bwd(int dt, const void *dy, const void *x, const flo
 // int32[B] or nullptr (key j of sequence b is masked iff j >= lengths[b]); causal != 0
 // additionally masks key j for query i iff j > i.  Forward writes o[B*T, D] and
 // lse[B,H,T] (log-sum-exp of the scaled, masked scores; fp32).  dh % 16 == 0, dh <= 256.
-hipError_t launch_attention_fwd(int dt, const void *qkv, const int32_t *lengths, int causal, int B, int T, int H,
-                                int dh, void *o, float *lse, hipStream_t stream);
+// drop (site 1; thr == 0 = off): the probabilities are multiplied by the keep mask on their way to P V.
+hipError_t launch_attention_fwd(int dt, const void *qkv, const int32_t *lengths, int causal, const DropSpec &drop,
+                                int B, int T, int H, int dh, void *o, float *lse, hipStream_t stream);
 // Backward: dqkv[B*T, 3D] from do_[B*T, D]; delta is fp32 scratch [B,H,T]
 // (delta_i = sum_d dO_i O_i).  Rows of dk, dv at masked keys are written as 0.
 hipError_t launch_attention_bwd(int dt, const void *qkv, const void *o, const void *do_, const float *lse,
-                                const int32_t *lengths, int causal, int B, int T, int H, int dh, void *dqkv,
-                                float *delta, hipStream_t stream);
+                                const int32_t *lengths, int causal, const DropSpec &drop, int B, int T, int H, int dh,
+                                void *dqkv, float *delta, hipStream_t stream);
 
 
 // bf16 attention on the matrix cores (attention_mfma.hip); the launchers above pick it when
 // dt is bf16 and the head size is one it is built for, unless the general kernels are forced.
 bool attention_mfma_supported(int dh);
 void attention_force_general(bool on);
-hipError_t launch_attention_fwd_mfma(const void *qkv, const int32_t *lengths, int causal, int B, int T, int H, int dh,
-                                     void *o, float *lse, hipStream_t s);
+hipError_t launch_attention_fwd_mfma(const void *qkv, const int32_t *lengths, int causal, const DropSpec &drop, int B,
+                                     int T, int H, int dh, void *o, float *lse, hipStream_t s);
 hipError_t launch_attention_bwd_mfma(const void *qkv, const void *o, const void *dout, const float *lse,
-                                     const int32_t *lengths, int causal, int B, int T, int H, int dh, void *dqkv,
-                                     float *delta, hipStream_t s);
+                                     const int32_t *lengths, int causal, const DropSpec &drop, int B, int T, int H,
+                                     int dh, void *dqkv, float *delta, hipStream_t s);
 
 // ---------------------------------------------------------------------------
 // Fused optimizer step over up to OPT_MAX_TENSORS tensors in one launch (optimizer.hip).

@@ -127,6 +127,11 @@ struct fl_layer {
   hipStream_t stream = nullptr;
   const int32_t *lengths = nullptr;
   int slot_x = -1, slot_y = -1;
+  // dropout: what the next forward will use, and what the recorded forward used (its backward needs the same)
+  float p_attn = 0.f, p_hidden = 0.f;
+  uint64_t seed = 0;
+  float rec_p_attn = 0.f, rec_p_hidden = 0.f;
+  uint64_t rec_seed = 0;
   // valid during backward
   bool accumulate = false;  // parameter gradients are added to what the caller's buffers hold
   // Parameter-gradient work (bias sums, dW GEMMs, second-stage reductions) is enqueued on a side
@@ -295,11 +300,28 @@ int linear_backward(void *ctx, Tape *tape, const Node *n) {
     return set_error(FL_ERR_STATE, "linear node %d: activation derivative was not applied upstream", self);
   const void *gy = ys.grad;
   const void *W = L->params[kLinear[n->param].w];
+  // The linear output was dropped out before it was added to the residual stream: the identity branch
+  // (below) passes the sum's gradient on as it is, the linear layer sees it times the keep mask.
+  Buf *gm = nullptr;
+  if (n->flags && L->rec_p_hidden > 0.f) {
+    gm = buf_new((size_t)M * N * e, st);
+    if (!gm) return set_error(FL_ERR_OOM, "device allocation of %zu bytes failed", (size_t)M * N * e);
+    hipError_t he = launch_dropout_mul(dt, gy, gm->ptr, M, N, make_drop_spec(L->rec_p_hidden, L->rec_seed, n->flags), st);
+    if (he != hipSuccess) {
+      buf_unref(gm);
+      FL_HIP(he);
+    }
+    gy = gm->ptr;
+  }
+  struct Unref {  // gm lives until this function returns (the side stream holds its own reference)
+    Buf *&b;
+    ~Unref() { buf_unref(b); }
+  } unref_gm{gm};
   // The parameter gradients need gy and the saved input only and nobody waits for them before the
   // backward pass ends: they go to the side stream, beside the input-gradient chain.
   hipStream_t ps;
   FL_TRY(side_fork(L, &ps));
-  side_hold(L, ys.grad_buf);
+  side_hold(L, gm ? gm : ys.grad_buf);
   side_hold(L, tape->slots[n->in0].value_buf);
   // bias gradient, unless the kernel that finished gy already produced it
   if (!ys.colsum_done) {
@@ -343,6 +365,10 @@ int linear_backward(void *ctx, Tape *tape, const Node *n) {
     if (fin && xs.xform != XF_NONE) {
       a.dact = xs.xform;
       a.aux = xs.xform_aux;
+      if (xs.xform_drop_site && L->rec_p_hidden > 0.f) {
+        a.drop_where = 2;
+        a.drop = make_drop_spec(L->rec_p_hidden, L->rec_seed, xs.xform_drop_site);
+      }
     }
     Buf *nb = nullptr;
     if (fin && xs.grad_dst) {
@@ -402,7 +428,8 @@ int attention_backward(void *ctx, Tape *tape, const Node *n) {
   const double fl = 10.0 * D * L->T * (double)M, by = 8.0 * M * D * e + 8.0 * L->B * H * L->T;
   hipError_t he = timed(FL_K_ATTN_BWD, fl, by, st, [&] {
     return launch_attention_bwd(L->dt, qs.value, os.value, os.grad, static_cast<const float *>(n->s0), L->lengths,
-                                L->cfg.causal, L->B, L->T, H, dh, nb->ptr, delta.f32(), st);
+                                L->cfg.causal, make_drop_spec(L->rec_p_attn, L->rec_seed, 1), L->B, L->T, H, dh, nb->ptr,
+                                delta.f32(), st);
   });
   if (he != hipSuccess) {
     buf_unref(nb);
@@ -472,8 +499,10 @@ int layernorm_backward(void *ctx, Tape *tape, const Node *n) {
 
 // ---- forward operators (each enqueues its kernel and records its node) ------------------
 
-// y = x W^T + b, optional activation (records the request for its derivative on y) and residual.
-int op_linear(fl_layer *L, int lin, int xslot, int rslot, int act, int K, int N, void *y_ext, int *yslot) {
+// y = x W^T + b, optional activation (records the request for its derivative on y), optional dropout
+// (site: 0 none, else the hidden-state site whose keep mask multiplies the result before the residual
+// is added) and residual.
+int op_linear(fl_layer *L, int lin, int xslot, int rslot, int act, int K, int N, void *y_ext, int *yslot, int site) {
   Tape &tp = L->tape;
   OpTag tag(FL_OP_LINEAR_FWD, (int)tp.nodes.size());
   hipStream_t st = L->stream;
@@ -493,6 +522,11 @@ int op_linear(fl_layer *L, int lin, int xslot, int rslot, int act, int K, int N,
   a.bias = L->params[kLinear[lin].b];
   a.act = act;
   if (rslot >= 0) a.residual = tp.slots[rslot].value;
+  const bool dropped = site != 0 && L->rec_p_hidden > 0.f;
+  if (dropped) {
+    a.drop_where = 1;
+    a.drop = make_drop_spec(L->rec_p_hidden, L->rec_seed, (uint32_t)site);
+  }
   if (act == XF_GELU) {  // the derivative needs the pre-activation
     ub = buf_new((size_t)M * N * e, st);
     if (!ub) {
@@ -512,15 +546,19 @@ int op_linear(fl_layer *L, int lin, int xslot, int rslot, int act, int K, int N,
   Slot &s = tp.slots[ys];
   s.value = y;
   s.value_buf = yb;
-  s.colsum_param = kLinear[lin].b;
+  // the bias gradient is the column sum of the gradient that enters the linear layer: with a dropped-out
+  // output in front of a residual add that is NOT the gradient of this slot (linear_backward masks it first)
+  s.colsum_param = dropped && act == XF_NONE ? -1 : kLinear[lin].b;
   if (act != XF_NONE) {
     s.xform = act;
     s.xform_aux = act == XF_GELU ? ub->ptr : y;  // ReLU: the output's sign is the pre-activation's
+    if (dropped) s.xform_drop_site = site;       // and the kept outputs were scaled: same mask on the way back
   }
   Node n;
   n.backward = linear_backward;
   n.op = OP_LINEAR;
   n.in0 = xslot; n.in1 = rslot; n.out = ys; n.param = lin;
+  n.flags = dropped && act == XF_NONE ? site : 0;
   n.s0 = tp.slots[xslot].value;
   n.saved[0] = ub;
   n.rows = M; n.n_in = K; n.n_out = N;
@@ -544,7 +582,8 @@ int op_attention(fl_layer *L, int qslot, int *oslot) {
   }
   const double fl = 4.0 * D * L->T * (double)M, by = 4.0 * M * D * e + 4.0 * L->B * H * L->T;
   hipError_t he = timed(FL_K_ATTN_FWD, fl, by, st, [&] {
-    return launch_attention_fwd(L->dt, tp.slots[qslot].value, L->lengths, L->cfg.causal, L->B, L->T, H, dh, ob->ptr,
+    return launch_attention_fwd(L->dt, tp.slots[qslot].value, L->lengths, L->cfg.causal,
+                                make_drop_spec(L->rec_p_attn, L->rec_seed, 1), L->B, L->T, H, dh, ob->ptr,
                                 static_cast<float *>(lb->ptr), st);
   });
   if (he != hipSuccess) {
@@ -638,6 +677,7 @@ int forward_impl(fl_layer *L, const fl_layer_params_t *params, const void *X, co
   FL_TRY(check_ptrs(io, 2, "X/Y"));
   release_tape(L);
   L->B = B; L->T = T; L->M = B * T; L->stream = st; L->lengths = lengths;
+  L->rec_p_attn = L->p_attn; L->rec_p_hidden = L->p_hidden; L->rec_seed = L->seed;
   Tape &tp = L->tape;
   const int D = c.d_model, F = c.d_ffn;
   const int act = c.act == FL_ACT_RELU ? XF_RELU : XF_GELU;
@@ -646,22 +686,22 @@ int forward_impl(fl_layer *L, const fl_layer_params_t *params, const void *X, co
   L->slot_x = sx;
   int s_qkv, s_o, s_r1, s_y1, s_g, s_out, s_n1;
   if (c.norm == FL_NORM_POST) {
-    FL_TRY(op_linear(L, 0, sx, -1, XF_NONE, D, 3 * D, nullptr, &s_qkv));
+    FL_TRY(op_linear(L, 0, sx, -1, XF_NONE, D, 3 * D, nullptr, &s_qkv, 0));
     FL_TRY(op_attention(L, s_qkv, &s_o));
-    FL_TRY(op_linear(L, 1, s_o, sx, XF_NONE, D, D, nullptr, &s_r1));      // R1 = X + O Wo^T + bo
+    FL_TRY(op_linear(L, 1, s_o, sx, XF_NONE, D, D, nullptr, &s_r1, 2));   // R1 = X + drop(O Wo^T + bo)
     FL_TRY(op_layernorm(L, 0, s_r1, nullptr, &s_y1));                      // Y1 = LN1(R1)
-    FL_TRY(op_linear(L, 2, s_y1, -1, act, D, F, nullptr, &s_g));           // G = act(Y1 W1^T + b1)
+    FL_TRY(op_linear(L, 2, s_y1, -1, act, D, F, nullptr, &s_g, 3));        // G = drop(act(Y1 W1^T + b1))
     int s_r2;
-    FL_TRY(op_linear(L, 3, s_g, s_y1, XF_NONE, F, D, nullptr, &s_r2));     // R2 = Y1 + G W2^T + b2
+    FL_TRY(op_linear(L, 3, s_g, s_y1, XF_NONE, F, D, nullptr, &s_r2, 4));  // R2 = Y1 + drop(G W2^T + b2)
     FL_TRY(op_layernorm(L, 1, s_r2, Y, &s_out));                           // Y = LN2(R2)
   } else {
     FL_TRY(op_layernorm(L, 0, sx, nullptr, &s_n1));                        // N1 = LN1(X)
-    FL_TRY(op_linear(L, 0, s_n1, -1, XF_NONE, D, 3 * D, nullptr, &s_qkv));
+    FL_TRY(op_linear(L, 0, s_n1, -1, XF_NONE, D, 3 * D, nullptr, &s_qkv, 0));
     FL_TRY(op_attention(L, s_qkv, &s_o));
-    FL_TRY(op_linear(L, 1, s_o, sx, XF_NONE, D, D, nullptr, &s_r1));      // R1 = X + O Wo^T + bo
+    FL_TRY(op_linear(L, 1, s_o, sx, XF_NONE, D, D, nullptr, &s_r1, 2));   // R1 = X + drop(O Wo^T + bo)
     FL_TRY(op_layernorm(L, 1, s_r1, nullptr, &s_y1));                      // N2 = LN2(R1)
-    FL_TRY(op_linear(L, 2, s_y1, -1, act, D, F, nullptr, &s_g));
-    FL_TRY(op_linear(L, 3, s_g, s_r1, XF_NONE, F, D, Y, &s_out));          // Y = R1 + G W2^T + b2
+    FL_TRY(op_linear(L, 2, s_y1, -1, act, D, F, nullptr, &s_g, 3));
+    FL_TRY(op_linear(L, 3, s_g, s_r1, XF_NONE, F, D, Y, &s_out, 4));       // Y = R1 + drop(G W2^T + b2)
   }
   L->slot_y = s_out;
   tp.recorded = true;
@@ -744,6 +784,19 @@ fl_status_t fl_layer_forward(fl_layer_t *layer, const fl_layer_params_t *params,
   int rc = forward_impl(layer, params, X, lengths, B, T, Y, static_cast<hipStream_t>(hip_stream));
   if (rc) release_tape(layer);
   return (fl_status_t)rc;
+  FL_GUARD_END
+}
+
+fl_status_t fl_layer_set_dropout(fl_layer_t *layer, float p_attn, float p_hidden, uint64_t seed) {
+  FL_GUARD_BEGIN
+  if (!layer) return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "null argument");
+  if (!(p_attn >= 0.f && p_attn < 1.f) || !(p_hidden >= 0.f && p_hidden < 1.f))
+    return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "dropout rates must be in [0, 1) (got %g, %g)", (double)p_attn,
+                                  (double)p_hidden);
+  layer->p_attn = p_attn;
+  layer->p_hidden = p_hidden;
+  layer->seed = seed;
+  return FL_OK;
   FL_GUARD_END
 }
 

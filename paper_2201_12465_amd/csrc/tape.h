@@ -40,6 +40,7 @@ struct Slot {
   int32_t xform = XF_NONE;         // multiply the finished gradient by act'(aux)
   const void *xform_aux = nullptr;  // pre-activation (GELU) or activation output (ReLU)
   int32_t colsum_param = -1;        // also emit the gradient's column sums as this bias's gradient
+  int32_t xform_drop_site = 0;      // also multiply it by the dropout keep mask of this site (0 = none)
   // backward
   void *grad = nullptr;      // gradient accumulated so far (nullptr = none yet)
   Buf *grad_buf = nullptr;   // set if the library owns it

@@ -128,19 +128,29 @@ int32_t fl_test_colsum(int32_t dtype, const void *in, int32_t M, int32_t N, floa
                     "launch_colsum");
 }
 
-int32_t fl_test_attention_fwd(int32_t dtype, const void *qkv, const int32_t *lengths, int32_t causal, int32_t B,
-                              int32_t T, int32_t H, int32_t dh, void *o, float *lse, void *hip_stream) {
-  return hip_status(launch_attention_fwd(dtype == FL_F32 ? DT_F32 : DT_BF16, qkv, lengths, causal, B, T, H, dh, o, lse,
+int32_t fl_test_attention_fwd(int32_t dtype, const void *qkv, const int32_t *lengths, int32_t causal, float p_drop,
+                              uint64_t seed, int32_t B, int32_t T, int32_t H, int32_t dh, void *o, float *lse,
+                              void *hip_stream) {
+  return hip_status(launch_attention_fwd(dtype == FL_F32 ? DT_F32 : DT_BF16, qkv, lengths, causal,
+                                         make_drop_spec(p_drop, seed, 1), B, T, H, dh, o, lse,
                                          static_cast<hipStream_t>(hip_stream)),
                     "launch_attention_fwd");
 }
 
 int32_t fl_test_attention_bwd(int32_t dtype, const void *qkv, const void *o, const void *dout, const float *lse,
-                              const int32_t *lengths, int32_t causal, int32_t B, int32_t T, int32_t H, int32_t dh,
-                              void *dqkv, float *delta, void *hip_stream) {
-  return hip_status(launch_attention_bwd(dtype == FL_F32 ? DT_F32 : DT_BF16, qkv, o, dout, lse, lengths, causal, B, T,
-                                         H, dh, dqkv, delta, static_cast<hipStream_t>(hip_stream)),
+                              const int32_t *lengths, int32_t causal, float p_drop, uint64_t seed, int32_t B,
+                              int32_t T, int32_t H, int32_t dh, void *dqkv, float *delta, void *hip_stream) {
+  return hip_status(launch_attention_bwd(dtype == FL_F32 ? DT_F32 : DT_BF16, qkv, o, dout, lse, lengths, causal,
+                                         make_drop_spec(p_drop, seed, 1), B, T, H, dh, dqkv, delta,
+                                         static_cast<hipStream_t>(hip_stream)),
                     "launch_attention_bwd");
+}
+
+int32_t fl_test_dropout_mul(int32_t dtype, const void *in, void *out, int32_t M, int32_t N, int32_t site, float p,
+                            uint64_t seed, void *hip_stream) {
+  return hip_status(launch_dropout_mul(dtype == FL_F32 ? DT_F32 : DT_BF16, in, out, M, N,
+                                       make_drop_spec(p, seed, (uint32_t)site), static_cast<hipStream_t>(hip_stream)),
+                    "launch_dropout_mul");
 }
 
 void fl_test_attention_force_general(int32_t on) { attention_force_general(on != 0); }

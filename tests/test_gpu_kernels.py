@@ -236,29 +236,36 @@ ATTN_CASES = [  # B, T, H, dh, lengths
 ]
 
 
-@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("causal,p_drop", [(False, 0.0), (True, 0.0), (False, 0.2), (True, 0.35)])
 @pytest.mark.parametrize("dtype", ["f32", "bf16", "bf16-general"])
 @pytest.mark.parametrize("case", ATTN_CASES)
-def test_attention_forward_backward(dtype, case, causal):
-    """bf16 runs the MFMA kernels where the head size allows; "bf16-general" forces the general ones."""
+def test_attention_forward_backward(dtype, case, causal, p_drop):
+    """bf16 runs the MFMA kernels where the head size allows; "bf16-general" forces the general ones.
+    With p_drop > 0 the oracle regenerates the identical keep mask from the same seed."""
     b = _lib()
     general = dtype == "bf16-general"
     dtype = dtype.split("-")[0]
     b.lib().fl_test_attention_force_general(1 if general else 0)
     try:
-        _attention_case(b, dtype, case, causal)
+        _attention_case(b, dtype, case, causal, p_drop)
     finally:
         b.lib().fl_test_attention_force_general(0)
 
 
-def _attention_case(b, dtype, case, causal=False):
+def _attention_case(b, dtype, case, causal=False, p_drop=0.0):
     B, T, H, dh, lengths = case
+    seed = (0x9E3779B9 << 32) | (B * 7919 + T)
+    keep = None
+    p_drop = float(np.float32(p_drop))       # the ABI takes a C float: the oracle gets the same value
+    if p_drop > 0:
+        from oracle import dropout as odr
+        keep = odr.keep_mask_attention(B, H, T, p_drop, seed)
     D = H * dh
     rng = np.random.default_rng(B * 1000 + T)
     qkv = quantise(rng.standard_normal((B, T, 3 * D)), dtype)
     dO = quantise(rng.standard_normal((B, T, D)), dtype)
     Q, K, V = (orc.split_heads(qkv[..., i * D:(i + 1) * D].astype(np.float64), H) for i in range(3))
-    Oh, P = orc.attention_fwd(Q, K, V, lengths, causal)
+    Oh, P = orc.attention_fwd(Q, K, V, lengths, causal, keep)
     O = orc.merge_heads(Oh)
     S = (Q @ K.transpose(0, 1, 3, 2)) / math.sqrt(dh)
     if lengths is not None:
@@ -266,14 +273,15 @@ def _attention_case(b, dtype, case, causal=False):
     if causal:
         S = np.where(np.triu(np.ones((T, T), bool), 1)[None, None], -np.inf, S)
     lse_ref = np.log(np.exp(S - S.max(-1, keepdims=True)).sum(-1)) + S.max(-1)
-    dQ, dK, dV = orc.attention_bwd(orc.split_heads(dO.astype(np.float64), H), Q, K, V, P)
+    dQ, dK, dV = orc.attention_bwd(orc.split_heads(dO.astype(np.float64), H), Q, K, V, P, keep)
     dqkv_ref = np.concatenate([orc.merge_heads(dQ), orc.merge_heads(dK), orc.merge_heads(dV)], -1)
     torch = torch_mod()
     dl = torch.tensor(lengths, dtype=torch.int32, device="cuda") if lengths is not None else None
     dqkv_in = to_dev(qkv, dtype)
     o, lse = empty_dev((B, T, D), dtype), empty_dev((B, H, T), "f32")
     b.check(b.lib().fl_test_attention_fwd(dt_code(dtype), dqkv_in.data_ptr(), dl.data_ptr() if dl is not None else None,
-                                          int(causal), B, T, H, dh, o.data_ptr(), lse.data_ptr(), stream_ptr()))
+                                          int(causal), p_drop, seed, B, T, H, dh, o.data_ptr(), lse.data_ptr(),
+                                          stream_ptr()))
     torch.cuda.synchronize()
     assert rel_err(to_np(o), O) <= _tol(dtype)
     assert rel_err(to_np(lse), lse_ref) <= 1e-5
@@ -282,11 +290,36 @@ def _attention_case(b, dtype, case, causal=False):
     tdo = to_dev(dO, dtype)
     b.check(b.lib().fl_test_attention_bwd(dt_code(dtype), dqkv_in.data_ptr(), o.data_ptr(), tdo.data_ptr(),
                                           lse.data_ptr(), dl.data_ptr() if dl is not None else None, int(causal),
-                                          B, T, H, dh, dqkv.data_ptr(), delta.data_ptr(), stream_ptr()))
+                                          p_drop, seed, B, T, H, dh, dqkv.data_ptr(), delta.data_ptr(),
+                                          stream_ptr()))
     torch.cuda.synchronize()
     got = to_np(dqkv)
+    # delta_i = sum_j P_ij dP_ij is taken as dO_i . O_i from the stored (rounded) O; dropout scales the
+    # probabilities, and with them that rounding noise, by 1/(1-p)
+    gtol = _tol(dtype) * 2 / (1.0 - p_drop)
     for i, name in enumerate("qkv"):
-        assert rel_err(got[..., i * D:(i + 1) * D], dqkv_ref[..., i * D:(i + 1) * D]) <= _tol(dtype) * 2, name
+        assert rel_err(got[..., i * D:(i + 1) * D], dqkv_ref[..., i * D:(i + 1) * D]) <= gtol, name
     if lengths is not None:      # masked keys: exactly zero gradient rows
         for bi, n in enumerate(lengths):
             assert np.all(got[bi, n:, D:] == 0.0)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("M,N,site,p", [(37, 64, 2, 0.1), (300, 776, 3, 0.5), (1, 8, 4, 0.9), (513, 3072, 3, 0.25)])
+def test_dropout_mask_is_bit_identical_to_the_oracle(dtype, M, N, site, p):
+    """The device generator (Philox4x32-10) and the keep decision are integer work: applied to ones, the
+    kernel must reproduce the oracle's mask exactly (0 or the scale 1/(1-p) rounded to the storage type)."""
+    from oracle import dropout as odr
+    b = _lib()
+    seed = (0xC0FFEE << 32) | 0xDEADBEEF
+    ones = to_dev(np.ones((M, N), np.float32), dtype)
+    out = empty_dev((M, N), dtype)
+    b.check(b.lib().fl_test_dropout_mul(dt_code(dtype), ones.data_ptr(), out.data_ptr(), M, N, site, p, seed,
+                                        stream_ptr()))
+    torch_mod().cuda.synchronize()
+    got = to_np(out)
+    p = float(np.float32(p))                 # the ABI takes a C float
+    want = odr.keep_mask_rows(M, N, site, p, seed)
+    assert np.array_equal(got != 0, want != 0)
+    scale = quantise(np.array([np.float32(1.0 / (1.0 - p))]), dtype)[0]
+    assert np.all(got[got != 0] == scale)

@@ -11,13 +11,16 @@ from workloads import CONFIGS, PARAM_NAMES, make_inputs, make_stack_inputs
 pytestmark = pytest.mark.gpu
 
 
-def run_layer_gpu(cfg, inp, layer=None, keep=False):
+def run_layer_gpu(cfg, inp, layer=None, keep=False, dropout=None):
+    """dropout: None or (p_attn, p_hidden, seed)."""
     from paper_2201_12465_amd import binding as b
     torch = torch_mod()
     dt = cfg.dtype
     own = layer is None
     if own:
         layer = b.Layer(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F, cfg.act, cfg.norm, dt, cfg.eps, cfg.causal)
+    if dropout is not None:
+        layer.set_dropout(*dropout)
     p = {k: to_dev(v, dt) for k, v in inp["params"].items()}
     g = {k: empty_dev(v.shape, dt) for k, v in inp["params"].items()}
     X, dY = to_dev(inp["X"], dt), to_dev(inp["dY"], dt)
@@ -33,7 +36,7 @@ def run_layer_gpu(cfg, inp, layer=None, keep=False):
     return to_np(Y), to_np(dX), {k: to_np(v) for k, v in g.items()}
 
 
-def avoid_relu_kink(cfg, inp, margin=2e-5):
+def avoid_relu_kink(cfg, inp, margin=2e-5, masks=None):
     """relu'(u) jumps at u = 0, so a pre-activation that the fp64 oracle and the fp32 kernel place on
     opposite sides of 0 (they differ by rounding, ~1e-6) would make the two gradients differ by a
     whole term although both are right.  For the fp32 ReLU cases the inputs are therefore moved off
@@ -42,7 +45,7 @@ def avoid_relu_kink(cfg, inp, margin=2e-5):
     pre-activations carry bf16 rounding of their inputs; its tolerance absorbs the effect.)"""
     if cfg.act != "relu" or cfg.dtype != "f32":
         return inp
-    kw = dict(heads=cfg.H, act=cfg.act, norm=cfg.norm, eps=cfg.eps, causal=cfg.causal)
+    kw = dict(heads=cfg.H, act=cfg.act, norm=cfg.norm, eps=cfg.eps, causal=cfg.causal, masks=masks)
     for _ in range(50):
         _, c = orc.layer_forward(inp["params"], inp["X"], inp["lengths"], **kw)
         cols = np.unique(np.nonzero(np.abs(c["ffn"]["U"]) < margin)[-1])
@@ -79,10 +82,16 @@ def relu_kink_allowance(cfg, inp, cache, base, samples=3):
     return allow, float(amb.mean())
 
 
-def check_against_oracle(cfg, inp, tol):
-    inp = avoid_relu_kink(cfg, inp)
-    Y, dX, g = run_layer_gpu(cfg, inp)
-    kw = dict(heads=cfg.H, act=cfg.act, norm=cfg.norm, eps=cfg.eps, causal=cfg.causal)
+def check_against_oracle(cfg, inp, tol, dropout=None):
+    masks = None
+    if dropout is not None:
+        from oracle import dropout as odr
+        # the ABI takes the rates as C floats: the oracle gets the same (float32-rounded) values
+        dropout = (float(np.float32(dropout[0])), float(np.float32(dropout[1])), dropout[2])
+        masks = odr.layer_masks(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F, *dropout)
+    inp = avoid_relu_kink(cfg, inp, masks=masks)
+    Y, dX, g = run_layer_gpu(cfg, inp, dropout=dropout)
+    kw = dict(heads=cfg.H, act=cfg.act, norm=cfg.norm, eps=cfg.eps, causal=cfg.causal, masks=masks)
     rY, cache = orc.layer_forward(inp["params"], inp["X"], inp["lengths"], **kw)
     rdX, rg = orc.layer_backward(inp["params"], cache, inp["dY"])
     base = {"dX": rdX, **{"d" + k: rg[k] for k in PARAM_NAMES}}
@@ -158,6 +167,57 @@ def test_causal_rows_do_not_see_the_future():
     Y2 = run_layer_gpu(cfg, inp2)[0]
     assert np.array_equal(Y1[:, :t0], Y2[:, :t0])
     assert not np.array_equal(Y1[:, t0:], Y2[:, t0:])
+
+
+@pytest.mark.parametrize("dtype,norm,act,masked,causal", [("f32", "post", "relu", False, False),
+                                                          ("f32", "pre", "gelu", True, True),
+                                                          ("bf16", "post", "gelu", True, False),
+                                                          ("bf16", "pre", "relu", False, True)])
+def test_dropout_variants_ragged(dtype, norm, act, masked, causal):
+    """All four dropout sites on, ragged shapes spanning several tiles; the oracle regenerates the same
+    masks from the seed, so outputs and every gradient must agree to the usual tolerance."""
+    cfg = CONFIGS["cfg2_small_f32"].with_(B=3, T=203, D=192, H=3, F=392, dtype=dtype, norm=norm, act=act,
+                                          causal=causal, len_lo=70 if masked else 0, len_hi=203 if masked else 0,
+                                          init="normal0.02" if dtype == "bf16" else "xavier")
+    check_against_oracle(cfg, make_inputs(cfg, seed=6, nontrivial=True), _tol(cfg), dropout=(0.15, 0.3, 0xABCDEF0123456789))
+
+
+def test_dropout_config3_full_size():
+    """Config 3's shape in training mode (rate 0.1 at every site)."""
+    cfg = CONFIGS["cfg3_bert_base_bf16"]
+    check_against_oracle(cfg, make_inputs(cfg, seed=0, nontrivial=True), _tol(cfg), dropout=(0.1, 0.1, 2026))
+
+
+def test_dropout_settings_belong_to_the_recorded_forward():
+    """Changing the settings between a forward and its backward must not affect that backward; rate 0
+    is bit-identical to a layer that never heard of dropout; a new seed changes the result."""
+    from paper_2201_12465_amd import binding as b
+    cfg = CONFIGS["cfg2_small_f32"].with_(dtype="bf16", act="gelu", init="normal0.02")
+    inp = make_inputs(cfg, seed=2, nontrivial=True)
+    ref = run_layer_gpu(cfg, inp, dropout=(0.2, 0.2, 11))
+    torch = torch_mod()
+    layer = b.Layer(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F, cfg.act, cfg.norm, cfg.dtype, cfg.eps)
+    p = {k: to_dev(v, cfg.dtype) for k, v in inp["params"].items()}
+    g = {k: empty_dev(v.shape, cfg.dtype) for k, v in inp["params"].items()}
+    X, dY = to_dev(inp["X"], cfg.dtype), to_dev(inp["dY"], cfg.dtype)
+    Y, dX = empty_dev(X.shape, cfg.dtype), empty_dev(X.shape, cfg.dtype)
+    layer.set_dropout(0.2, 0.2, 11)
+    layer.forward(p, X, None, cfg.B, cfg.T, Y, stream_ptr())
+    layer.set_dropout(0.5, 0.0, 99)                     # must only affect the NEXT forward
+    layer.backward(p, dY, dX, g, stream_ptr())
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(Y), ref[0]) and np.array_equal(to_np(dX), ref[1])
+    for k in PARAM_NAMES:
+        assert np.array_equal(to_np(g[k]), ref[2][k]), k
+    layer.destroy()
+    off = run_layer_gpu(cfg, inp, dropout=(0.0, 0.0, 5))
+    plain = run_layer_gpu(cfg, inp)
+    assert np.array_equal(off[0], plain[0]) and np.array_equal(off[1], plain[1])
+    other = run_layer_gpu(cfg, inp, dropout=(0.2, 0.2, 12))
+    assert not np.array_equal(other[0], ref[0])
+    with pytest.raises(b.FlError) as e:
+        b.Layer(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F).set_dropout(1.0, 0.0, 0)
+    assert e.value.status == b.FL_ERR_INVALID_ARG
 
 
 def test_config4_full_size():
