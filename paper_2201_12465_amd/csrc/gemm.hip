@@ -280,7 +280,7 @@ hipError_t launch_gemm(int dt, const GemmArgs &a, hipStream_t stream) {
   if ((long)(splits - 1) * kps >= a.K) return hipErrorInvalidValue;
   if (dt == DT_BF16 && gemm_pipe_eligible(a, kps)) {
     int variant = gemm_pipe_pick_variant(a.a_kc, a.b_kc, a.M, a.N, a.K);
-    if (variant == 7 && d.drop_where) variant = 0;  // with the dropout steps the 256x192 instance spills
+    if (variant > 0 && d.drop_where) variant = 0;  // the dropout steps exist in the 128x128 / 2-stage instance only
     if (variant >= 0) return launch_gemm_bf16_pipe(a, &d, splits, variant, stream);
   }
   // fewer than 1.5 full tiles per CU: halve the tile height so that twice as many workgroups run

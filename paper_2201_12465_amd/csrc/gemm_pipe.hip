@@ -86,10 +86,15 @@ __device__ __forceinline__ bf16x8_t frag(const unsigned char *stage, int r0, int
   }
 }
 
-// WM x WN wavefronts share a BM x BN tile; each owns TM x TN MFMA tiles of 32x32.
-template <bool AKC, bool BKC, int BM, int BN, int NS, int WM, int WN, bool DROP>
-__global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_pipe(GemmDev p) {
-  constexpr int NW = WM * WN;
+// WM x WN wavefronts share a BM x BN tile; each owns TM x TN MFMA tiles of 32x32.  KG > 1: KG such
+// groups of wavefronts work on the same tile, group g taking the g-th part of every k-tile, and their
+// accumulators are added through LDS at the end.  For outputs with few tiles (one workgroup per CU)
+// this puts two wavefronts on every SIMD, so that one's LDS reads overlap the other's MFMAs.
+template <bool AKC, bool BKC, int BM, int BN, int NS, int WM, int WN, bool DROP, int KG>
+__global__ __launch_bounds__(WM *WN *KG * 64) void gemm_bf16_pipe(GemmDev p) {
+  constexpr int NW = WM * WN * KG;
+  constexpr int KKS = KT / 16 / KG;  // 16-wide k-steps of a k-tile per group
+  static_assert(KKS >= 1 && KKS * KG * 16 == KT, "k-groups must divide the k-tile");
   constexpr int TM = BM / (32 * WM), TN = BN / (32 * WN);
   constexpr int A_BYTES = BM * 128, STAGE = (BM + BN) * 128;
   constexpr int OPS = Stager<AKC, BM, NW>::NOPS + Stager<BKC, BN, NW>::NOPS;  // loads per wave per k-tile
@@ -105,7 +110,8 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_pipe(GemmDev p) {
   const bf16_t *A = static_cast<const bf16_t *>(p.A);
   const bf16_t *B = static_cast<const bf16_t *>(p.B);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave / WN, wn = wave % WN;
+  const int kg = wave / (WM * WN), wpos = wave % (WM * WN);  // k-group, position in the tile
+  const int wm = wpos / WN, wn = wpos % WN;
 
   Stager<AKC, BM, NW> sa;
   Stager<BKC, BN, NW> sb;
@@ -147,17 +153,20 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_pipe(GemmDev p) {
     const unsigned char *sA = smem + (kt % NS) * STAGE, *sB = sA + A_BYTES;
     // fragments of k-step kk+1 are requested before the MFMAs of k-step kk are issued
     bf16x8_t fa[2][TM], fb[2][TN];
+    const int kk0 = kg * KKS;
 #pragma unroll
-    for (int i = 0; i < TM; ++i) fa[0][i] = frag<AKC, BM>(sA, wm * (BM / WM) + i * 32, 0, lane);
+    for (int i = 0; i < TM; ++i) fa[0][i] = frag<AKC, BM>(sA, wm * (BM / WM) + i * 32, kk0, lane);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) fb[0][j] = frag<BKC, BN>(sB, wn * (BN / WN) + j * 32, 0, lane);
+    for (int j = 0; j < TN; ++j) fb[0][j] = frag<BKC, BN>(sB, wn * (BN / WN) + j * 32, kk0, lane);
 #pragma unroll
-    for (int kk = 0; kk < KT / 16; ++kk) {
-      if (kk + 1 < KT / 16) {
+    for (int kk = 0; kk < KKS; ++kk) {
+      if (kk + 1 < KKS) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) fa[(kk + 1) & 1][i] = frag<AKC, BM>(sA, wm * (BM / WM) + i * 32, kk + 1, lane);
+        for (int i = 0; i < TM; ++i)
+          fa[(kk + 1) & 1][i] = frag<AKC, BM>(sA, wm * (BM / WM) + i * 32, kk0 + kk + 1, lane);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) fb[(kk + 1) & 1][j] = frag<BKC, BN>(sB, wn * (BN / WN) + j * 32, kk + 1, lane);
+        for (int j = 0; j < TN; ++j)
+          fb[(kk + 1) & 1][j] = frag<BKC, BN>(sB, wn * (BN / WN) + j * 32, kk0 + kk + 1, lane);
       }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
@@ -171,17 +180,47 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_pipe(GemmDev p) {
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();  // every wave is done reading the operand stages
   asm volatile("" ::: "memory");
-  float *cw = reinterpret_cast<float *>(smem) + (size_t)wave * 32 * (TN * 32 + 4);
+  if constexpr (KG > 1) {
+    // groups 1.. park their accumulators in LDS ([group-1][position][register][lane]: lane-contiguous,
+    // no bank conflicts), group 0 adds them up and goes on alone
+    float *red = reinterpret_cast<float *>(smem);
+    constexpr int PER_WAVE = TM * TN * 16 * 64;
+    if (kg > 0) {
+      float *dst = red + ((size_t)(kg - 1) * (WM * WN) + wpos) * PER_WAVE + lane;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) dst[((i * TN + j) * 16 + r) * 64] = acc[i][j][r];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int g = 1; g < KG && kg == 0; ++g) {
+      const float *src = red + ((size_t)(g - 1) * (WM * WN) + wpos) * PER_WAVE + lane;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[i][j][r] += src[((i * TN + j) * 16 + r) * 64];
+    }
+    __syncthreads();  // the epilogue's staging area overlaps what other wavefronts have just read
+    if (kg > 0) return;  // no barrier follows: group 0 finishes alone
+  }
+  float *cw = reinterpret_cast<float *>(smem) + (size_t)wpos * 32 * (TN * 32 + 4);
   gemm_staged_epilogue<bf16_t, TM, TN, DROP>(p, acc, cw, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane);
 }
 
-template <bool AKC, bool BKC, int BM, int BN, int NS, int WM, int WN, bool DROP>
+template <bool AKC, bool BKC, int BM, int BN, int NS, int WM, int WN, bool DROP, int KG>
 hipError_t launch_cfg_d(GemmDev d, int splits, hipStream_t s) {
   constexpr size_t stage_lds = (size_t)NS * (BM + BN) * 128;
   constexpr size_t epi_lds = (size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float);
-  constexpr size_t lds = stage_lds > epi_lds ? stage_lds : epi_lds;
+  constexpr size_t red_lds = (size_t)(KG - 1) * BM * BN * sizeof(float);
+  constexpr size_t lds0 = stage_lds > epi_lds ? stage_lds : epi_lds;
+  constexpr size_t lds = lds0 > red_lds ? lds0 : red_lds;
   static_assert(lds <= 160 * 1024, "stages do not fit in LDS");
-  auto kern = gemm_bf16_pipe<AKC, BKC, BM, BN, NS, WM, WN, DROP>;
+  auto kern = gemm_bf16_pipe<AKC, BKC, BM, BN, NS, WM, WN, DROP, KG>;
   if (lds > 64 * 1024) {
     static bool raised = false;
     if (!raised) {
@@ -195,20 +234,20 @@ hipError_t launch_cfg_d(GemmDev d, int splits, hipStream_t s) {
   d.tiles_n = (d.N + BN - 1) / BN;
   d.splits = splits;
   dim3 grid(d.tiles_m * d.tiles_n * splits);
-  hipLaunchKernelGGL(kern, grid, dim3(WM * WN * 64), lds, s, d);
+  hipLaunchKernelGGL(kern, grid, dim3(WM * WN * KG * 64), lds, s, d);
   return hipGetLastError();
 }
 
 // Dropout in the epilogue exists for the 128x128 / 2-stage variant (the forward GEMMs in training mode).
-template <bool AKC, bool BKC, int BM, int BN, int NS, int WM = 2, int WN = 2>
+template <bool AKC, bool BKC, int BM, int BN, int NS, int WM = 2, int WN = 2, int KG = 1>
 hipError_t launch_cfg(const GemmDev &d, int splits, hipStream_t s) {
   if (d.drop_where) {
     if constexpr (AKC && BKC && NS == 2 && BM == 128 && BN == 128)
-      return launch_cfg_d<AKC, BKC, BM, BN, NS, WM, WN, true>(d, splits, s);
+      return launch_cfg_d<AKC, BKC, BM, BN, NS, WM, WN, true, KG>(d, splits, s);
     else
       return hipErrorInvalidValue;
   }
-  return launch_cfg_d<AKC, BKC, BM, BN, NS, WM, WN, false>(d, splits, s);
+  return launch_cfg_d<AKC, BKC, BM, BN, NS, WM, WN, false, KG>(d, splits, s);
 }
 
 template <bool AKC, bool BKC>
@@ -221,6 +260,8 @@ hipError_t launch_layout(const GemmDev &d, int splits, int variant, hipStream_t 
     case 4: return launch_cfg<AKC, BKC, 256, 256, 2>(d, splits, s);
     case 5: return launch_cfg<AKC, BKC, 256, 256, 2, 2, 4>(d, splits, s);
     case 6: return launch_cfg<AKC, BKC, 256, 128, 3, 4, 2>(d, splits, s);
+    case 8: return launch_cfg<AKC, BKC, 128, 128, 2, 2, 2, 2>(d, splits, s);
+    case 9: return launch_cfg<AKC, BKC, 128, 128, 3, 2, 2, 2>(d, splits, s);
     case 7:  // 192 columns: the k-major swizzle needs a power-of-two row length, so k-contiguous operands only
       if constexpr (AKC && BKC) return launch_cfg<AKC, BKC, 256, 192, 2, 4, 2>(d, splits, s);
       else return hipErrorInvalidValue;
@@ -242,7 +283,7 @@ bool gemm_pipe_eligible(const GemmArgs &a, int kps) {
 }
 
 void gemm_pipe_tile(int variant, int *bm, int *bn) {
-  static const int t[8][2] = {{128, 128}, {128, 128}, {256, 128}, {256, 128}, {256, 256}, {256, 256}, {256, 128}, {256, 192}};
+  static const int t[10][2] = {{128, 128}, {128, 128}, {256, 128}, {256, 128}, {256, 256}, {256, 256}, {256, 128}, {256, 192}, {128, 128}, {128, 128}};
   *bm = t[variant][0];
   *bn = t[variant][1];
 }
@@ -260,6 +301,9 @@ int gemm_pipe_pick_variant(bool a_kc, bool b_kc, int M, int N, int K) {
     const long rounds = (tiles + 255) / 256;
     if (tiles >= 160 && 100 * tiles >= 74 * rounds * 256) return 7;
   }
+  // few tiles and a long k-loop (FFN2): one workgroup per CU; three stages and two k-groups of
+  // wavefronts per tile keep more loads in flight (35 -> 32 us)
+  if ((long)((M + 127) / 128) * ((N + 127) / 128) <= 256 && K >= 2048) return 9;
   return 0;
 }
 

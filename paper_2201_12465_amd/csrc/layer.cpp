@@ -135,7 +135,7 @@ struct fl_layer {
   // valid during backward
   bool accumulate = false;  // parameter gradients are added to what the caller's buffers hold
   // Parameter-gradient work (bias sums, dW GEMMs, second-stage reductions) is enqueued on a side
-  // stream so that it runs beside the input-gradient chain; see side_fork() / side_join().
+  // stream so that it runs beside the input-gradient chain; see side_mark(), side_begin(), side_join().
   hipStream_t side = nullptr;          // non-null while this backward uses the side stream
   std::vector<hipEvent_t> fork_events; // one per fork, reused by the next backward
   size_t forks = 0;
@@ -212,19 +212,27 @@ hipStream_t side_stream() {
   }();
   return s;
 }
-// Makes the side stream wait for everything enqueued on the layer's stream so far and returns the
-// stream to launch the parameter-gradient kernels on (the layer's own stream when overlap is off).
-int side_fork(fl_layer *L, hipStream_t *out) {
-  *out = L->stream;
+// Fork in two steps, so that the host can enqueue the next kernel of the critical path on the layer's
+// stream BETWEEN them (enqueueing costs the host a few microseconds per call, and the GPU would wait):
+// side_mark() records "everything enqueued on the layer's stream so far" in an event; side_begin()
+// makes the side stream wait for that point and returns the stream to launch the parameter-gradient
+// kernels on (the layer's own stream when overlap is off).
+int side_mark(fl_layer *L, hipEvent_t *ev) {
+  *ev = nullptr;
   if (!L->side) return 0;
   if (L->forks == L->fork_events.size()) {
     hipEvent_t e = nullptr;
     FL_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
     L->fork_events.push_back(e);
   }
-  hipEvent_t e = L->fork_events[L->forks++];
-  FL_HIP(hipEventRecord(e, L->stream));
-  FL_HIP(hipStreamWaitEvent(L->side, e, 0));
+  *ev = L->fork_events[L->forks++];
+  FL_HIP(hipEventRecord(*ev, L->stream));
+  return 0;
+}
+int side_begin(fl_layer *L, hipEvent_t ev, hipStream_t *out) {
+  *out = L->stream;
+  if (!L->side) return 0;
+  FL_HIP(hipStreamWaitEvent(L->side, ev, 0));
   *out = L->side;
   return 0;
 }
@@ -317,42 +325,8 @@ int linear_backward(void *ctx, Tape *tape, const Node *n) {
     Buf *&b;
     ~Unref() { buf_unref(b); }
   } unref_gm{gm};
-  // The parameter gradients need gy and the saved input only and nobody waits for them before the
-  // backward pass ends: they go to the side stream, beside the input-gradient chain.
-  hipStream_t ps;
-  FL_TRY(side_fork(L, &ps));
-  side_hold(L, gm ? gm : ys.grad_buf);
-  side_hold(L, tape->slots[n->in0].value_buf);
-  // bias gradient, unless the kernel that finished gy already produced it
-  if (!ys.colsum_done) {
-    Scratch ws;
-    FL_TRY(ws.get(colsum_ws_floats(M, N) * sizeof(float), ps));
-    FL_HIP(timed(FL_K_COLSUM, 0, (double)M * N * e, ps,
-                 [&] { return launch_colsum(dt, gy, M, N, ws.f32(), L->grads[kLinear[n->param].b], ps, L->accumulate); }));
-  }
-  // weight gradient: dW[N,K] = sum_m gy[m,n] x[m,k]
-  {
-    GemmArgs a;
-    a.A = gy; a.lda = N; a.a_kc = false;
-    a.B = n->s0; a.ldb = K; a.b_kc = false;
-    a.M = N; a.N = K; a.K = M;
-    a.C = L->grads[kLinear[n->param].w]; a.ldc = K;
-    a.splits = gemm_pick_splits(dt, a.M, a.N, a.K);
-    const double fl = 2.0 * M * N * K, by = ((double)M * N + (double)M * K + (double)N * K) * e;
-    if (a.splits > 1) {
-      Scratch ws;
-      FL_TRY(ws.get((size_t)a.splits * N * K * sizeof(float), ps));
-      a.partial = ws.f32();
-      FL_HIP(timed(FL_K_GEMM_TN, fl, by, ps, [&] { return launch_gemm(dt, a, ps); }));
-      FL_HIP(timed(FL_K_SPLITK_REDUCE, 0, (double)(a.splits * 4 + e) * N * K, ps, [&] {
-        return launch_reduce_partials(dt, ws.f32(), a.splits, (size_t)N * K, (size_t)N * K, 1, a.C, nullptr, nullptr, ps,
-                                      L->accumulate);
-      }));
-    } else {
-      if (L->accumulate) a.residual = a.C;  // in place: each lane reads the elements it then writes
-      FL_HIP(timed(FL_K_GEMM_TN, fl, by, ps, [&] { return launch_gemm(dt, a, ps); }));
-    }
-  }
+  hipEvent_t forked;
+  FL_TRY(side_mark(L, &forked));   // gy is complete at this point of the layer's stream
   // input gradient: dx[M,K] = gy W (+ what other consumers of x already contributed)
   {
     Slot &xs = tape->slots[n->in0];
@@ -386,6 +360,43 @@ int linear_backward(void *ctx, Tape *tape, const Node *n) {
     }
     set_grad(xs, a.C, nb);
     if (a.dact) xs.xform_done = true;
+  }
+  // The parameter gradients need gy and the saved input only and nobody waits for them before the
+  // backward pass ends: they go to the side stream, beside the input-gradient chain (whose GEMM is
+  // already enqueued above).
+  hipStream_t ps;
+  FL_TRY(side_begin(L, forked, &ps));
+  side_hold(L, gm ? gm : ys.grad_buf);
+  side_hold(L, tape->slots[n->in0].value_buf);
+  // bias gradient, unless the kernel that finished gy already produced it
+  if (!ys.colsum_done) {
+    Scratch ws;
+    FL_TRY(ws.get(colsum_ws_floats(M, N) * sizeof(float), ps));
+    FL_HIP(timed(FL_K_COLSUM, 0, (double)M * N * e, ps,
+                 [&] { return launch_colsum(dt, gy, M, N, ws.f32(), L->grads[kLinear[n->param].b], ps, L->accumulate); }));
+  }
+  // weight gradient: dW[N,K] = sum_m gy[m,n] x[m,k]
+  {
+    GemmArgs a;
+    a.A = gy; a.lda = N; a.a_kc = false;
+    a.B = n->s0; a.ldb = K; a.b_kc = false;
+    a.M = N; a.N = K; a.K = M;
+    a.C = L->grads[kLinear[n->param].w]; a.ldc = K;
+    a.splits = gemm_pick_splits(dt, a.M, a.N, a.K);
+    const double fl = 2.0 * M * N * K, by = ((double)M * N + (double)M * K + (double)N * K) * e;
+    if (a.splits > 1) {
+      Scratch ws;
+      FL_TRY(ws.get((size_t)a.splits * N * K * sizeof(float), ps));
+      a.partial = ws.f32();
+      FL_HIP(timed(FL_K_GEMM_TN, fl, by, ps, [&] { return launch_gemm(dt, a, ps); }));
+      FL_HIP(timed(FL_K_SPLITK_REDUCE, 0, (double)(a.splits * 4 + e) * N * K, ps, [&] {
+        return launch_reduce_partials(dt, ws.f32(), a.splits, (size_t)N * K, (size_t)N * K, 1, a.C, nullptr, nullptr, ps,
+                                      L->accumulate);
+      }));
+    } else {
+      if (L->accumulate) a.residual = a.C;  // in place: each lane reads the elements it then writes
+      FL_HIP(timed(FL_K_GEMM_TN, fl, by, ps, [&] { return launch_gemm(dt, a, ps); }));
+    }
   }
   // residual input: the identity branch passes gy through unchanged
   if (n->in1 >= 0) {
@@ -481,8 +492,10 @@ int layernorm_backward(void *ctx, Tape *tape, const Node *n) {
   set_grad(xs, dst, nb);
   const bool want_bias = fin && xs.colsum_param >= 0;
   // second stage of the parameter-gradient sums: beside the input-gradient chain
+  hipEvent_t forked;
   hipStream_t ps;
-  FL_TRY(side_fork(L, &ps));
+  FL_TRY(side_mark(L, &forked));
+  FL_TRY(side_begin(L, forked, &ps));
   side_hold(L, ws.b);
   FL_HIP(timed(FL_K_COLSUM, 0, (double)parts * 3 * D * 4, ps, [&] {
     return launch_reduce_partials(dt, ws.f32(), parts, (size_t)3 * D, (size_t)D, want_bias ? 3 : 2, L->grads[gi],
