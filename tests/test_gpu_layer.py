@@ -137,6 +137,25 @@ def test_variants_ragged(dtype, norm, act, masked):
     check_against_oracle(cfg, inp, _tol(cfg))
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [
+    dict(B=1, T=1, D=64, H=4, F=64),              # a single token: attention is the identity on V
+    dict(B=4, T=1, D=128, H=2, F=256),            # sequences of one token
+    dict(B=2, T=9, D=4096, H=16, F=512),          # the largest d_model and head size (256) the layer accepts
+    dict(B=1, T=130, D=64, H=1, F=8),             # one head, smallest feed-forward width, two query blocks
+    dict(B=5, T=64, D=96, H=6, F=96),             # head size 16: the general attention kernels also in bf16
+])
+def test_edge_shapes(dtype, shape):
+    """Degenerate and extreme shapes, with every sequence but one cut to a single valid key."""
+    cfg = CONFIGS["cfg2_small_f32"].with_(name="edge", dtype=dtype, act="gelu", norm="pre",
+                                          init="normal0.02" if dtype == "bf16" else "xavier", **shape)
+    inp = make_inputs(cfg, seed=8, nontrivial=True)
+    lengths = np.ones(cfg.B, np.int32)
+    lengths[-1] = cfg.T
+    inp["lengths"] = lengths
+    check_against_oracle(cfg, inp, _tol(cfg))
+
+
 @pytest.mark.parametrize("dtype,norm,act,masked", [("f32", "post", "relu", False), ("f32", "pre", "gelu", True),
                                                    ("bf16", "post", "gelu", True), ("bf16", "pre", "relu", False)])
 def test_causal_variants_ragged(dtype, norm, act, masked):
