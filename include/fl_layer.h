@@ -137,7 +137,8 @@ const char *fl_last_error(void);
  * graph may run at the same time).  The side stream waits, through events, for the gradients it
  * reads, and the caller's stream waits for it before fl_layer_backward returns control of dX and
  * the gradient buffers to work enqueued later on that stream: the caller sees the same ordering
- * either way, and the results are bit-identical.  Process-wide; not thread-safe against
+ * either way, and the results are bit-identical.  Small problems (B*T*d_model < 2^18) always stay on
+ * one stream.  Process-wide; not thread-safe against
  * concurrent backward calls. */
 fl_status_t fl_set_grad_overlap(int32_t enabled);
 

@@ -737,7 +737,8 @@ int backward_impl(fl_layer *L, const fl_layer_params_t *params, const void *dY, 
   Tape &tp = L->tape;
   tp.slots[L->slot_y].grad = const_cast<void *>(dY);
   tp.slots[L->slot_x].grad_dst = dX;
-  L->side = g_overlap ? side_stream() : nullptr;
+  // the events of a fork cost the host more than tiny kernels take: small problems stay on one stream
+  L->side = g_overlap && (long)L->M * L->cfg.d_model >= (1l << 18) ? side_stream() : nullptr;
   L->forks = 0;
   int rc = tp.replay_reverse(L);
   const bool landed = rc == 0 && tp.slots[L->slot_x].grad == dX;
