@@ -38,10 +38,14 @@ def classify(name: str) -> str:
         m = re.search(r"gemm_kernelI\w+?Lb([01])ELb([01])E", n)
         if m:
             a, bb = m.group(1) == "1", m.group(2) == "1"
-        else:  # demangled; the element type may be printed oddly, the two booleans follow it
+        else:  # demangled: <T, AKC, BKC, tile height, dropout>
             bools = re.findall(r"\b(true|false)\b", n)
-            # some demanglers swallow the first boolean of <T, true, false, h>: then one is left
-            a, bb = (bools[0] == "true", bools[1] == "true") if len(bools) >= 2 else (True, bools[0] == "true")
+            if "bool, E" in n:
+                # a known demangler slip: "<__bf16, true, ..." comes out as "<bool _Accum, bool, E, ..."
+                # (the element type and AKC = true are swallowed); BKC is the first boolean that is left
+                a, bb = True, bools[0] == "true"
+            else:
+                a, bb = bools[0] == "true", bools[1] == "true"
         return {(True, True): "gemm_nt", (True, False): "gemm_nn", (False, False): "gemm_tn"}.get((a, bb), "gemm")
     table = (("reduce_partials", "splitk_reduce"), ("colsum", "colsum"), ("attn_fwd", "attn_fwd"),
              ("attn_bwd", "attn_bwd"), ("attn_delta", "attn_bwd"), ("ln_fwd", "ln_fwd"), ("ln_bwd", "ln_bwd"),

@@ -325,6 +325,11 @@ def test_profile_summary_classifies_kernel_names():
         "_ZN2fl12_GLOBAL__N_111gemm_kernelIfLb1ELb1ELi2EEEvNS_7GemmDevE": "gemm_nt",
         "void fl::(anonymous namespace)::gemm_kernel<bool _Accum, bool, E, false, 1>(fl::GemmDev)": "gemm_nn",
         "void fl::(anonymous namespace)::gemm_kernel<float, false, false, 2>(fl::GemmDev)": "gemm_tn",
+        "void fl::(anonymous namespace)::gemm_kernel<bool _Accum, bool, E, false, 1, false>(fl::GemmDev)": "gemm_nn",
+        "void fl::(anonymous namespace)::gemm_kernel<float, true, true, 2, true>(fl::GemmDev)": "gemm_nt",
+        "_ZN2fl12_GLOBAL__N_111gemm_kernelIDF16bLb1ELb0ELi1ELb0EEEvNS_7GemmDevE": "gemm_nn",
+        "_ZN2fl12_GLOBAL__N_111gemm_kernelIDF16bLb0ELb0ELi2ELb0EEEvNS_7GemmDevE": "gemm_tn",
+        "void fl::(anonymous namespace)::gemm_bf16_pipe<true, true, 256, 192, 2, 4, 2, false, 1>(fl::GemmDev)": "gemm_nt",
         "void fl::(anonymous namespace)::gemm_bf16_pipe<true, true, 128, 128, 2>(fl::GemmDev)": "gemm_nt",
         "_ZN2fl12_GLOBAL__N_122reduce_partials_kernelIDF16bEEvPKfimmPT_S5_S5_": "splitk_reduce",
         "_ZN2fl12_GLOBAL__N_127reduce_partials_tall_kernelIDF16bEEvPKfimmPT_S5_S5_": "splitk_reduce",
