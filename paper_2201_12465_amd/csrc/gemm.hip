@@ -237,8 +237,15 @@ void gemm_force_tile_height(int tmw) { g_force_tmw = tmw; }
 int gemm_pick_splits(int dt, int M, int N, int K) {
   const int KT = dt == DT_F32 ? Tile<float>::KT : Tile<bf16_t>::KT;
   long tiles = (long)((M + BM - 1) / BM) * ((N + BN - 1) / BN);
-  int want = (int)((512 + tiles - 1) / tiles);
-  int maxs = (K + 4 * KT - 1) / (4 * KT);  // at least four k-tiles per range
+  int want, maxs = (K + 4 * KT - 1) / (4 * KT);  // at least four k-tiles per range
+  if (dt == DT_BF16) {
+    // measured on the dW shapes of the layer (k = 4096 tokens; 36, 108 and 144 tiles): about 430
+    // workgroups are the best trade between filling the chip and the fp32 partial sums' traffic
+    want = (int)((432 + tiles / 2) / tiles);
+    if (want > 6) want = 6;
+  } else {
+    want = (int)((512 + tiles - 1) / tiles);
+  }
   int s = want < maxs ? want : maxs;
   if (s > 32) s = 32;
   if (s < 1) s = 1;

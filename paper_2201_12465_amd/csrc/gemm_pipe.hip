@@ -291,8 +291,12 @@ void gemm_pipe_tile(int variant, int *bm, int *bn) {
 int gemm_pipe_pick_variant(bool a_kc, bool b_kc, int M, int N, int K) {
   if (g_variant != -1) return g_variant == 7 && !(a_kc && b_kc) ? -2 : g_variant;
   (void)K;
-  // Measured on the layer's shapes (M = 4096, N and K in {768, 2304, 3072}).  With a k-major operand
-  // the register-staged kernel in gemm.hip is at least as fast.  With both operands k-contiguous:
+  // Measured on the layer's shapes (M = 4096, N and K in {768, 2304, 3072}).  dy W (one k-major
+  // operand): the register-staged kernel in gemm.hip is at least as fast.  dy^T x (both k-major, split
+  // over the tokens): this kernel with two wavefront groups per tile is 10 % faster alone, but it runs
+  // beside the input-gradient GEMMs and, holding 64 KiB of LDS per workgroup, slows those down by more
+  // than it gains (0.460 against 0.444 ms per step): the register-staged kernel stays.
+  // With both operands k-contiguous:
   // 256x192 tiles on 8 wavefronts halve the L1 and LDS traffic per flop and win when they fill the
   // chip in whole rounds (one workgroup per CU); otherwise 128x128 / 2 stages, two workgroups per CU.
   if (!(a_kc && b_kc)) return -2;
