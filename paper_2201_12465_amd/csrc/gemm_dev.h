@@ -88,8 +88,10 @@ template <> struct Oct<float> {
   }
 };
 
-template <typename T, bool DROP>
-__device__ __forceinline__ void gemm_epilogue_oct(const GemmDev &p, int m, int n0, float (&v)[8]) {
+// PRE: the eight residual / aux values were already loaded by the caller (pre_res, pre_aux; bf16 only).
+template <typename T, bool DROP, bool PRE = false>
+__device__ __forceinline__ void gemm_epilogue_oct(const GemmDev &p, int m, int n0, float (&v)[8],
+                                                  bf16x8_t pre_res = bf16x8_t{}, bf16x8_t pre_aux = bf16x8_t{}) {
   if (p.partial) {
     Oct<float>::store(p.partial + (size_t)m * p.N + n0, v);
     return;
@@ -117,12 +119,22 @@ __device__ __forceinline__ void gemm_epilogue_oct(const GemmDev &p, int m, int n
     for (int e = 0; e < 4; ++e) v[e] *= k0[e], v[e + 4] *= k1[e];
   }
   if (p.residual) {
-    Oct<T>::load(static_cast<const T *>(p.residual) + off, t);
+    if constexpr (PRE) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) t[e] = static_cast<float>(pre_res[e]);
+    } else {
+      Oct<T>::load(static_cast<const T *>(p.residual) + off, t);
+    }
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] += t[e];
   }
   if (p.dact) {
-    Oct<T>::load(static_cast<const T *>(p.aux) + off, t);
+    if constexpr (PRE) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) t[e] = static_cast<float>(pre_aux[e]);
+    } else {
+      Oct<T>::load(static_cast<const T *>(p.aux) + off, t);
+    }
     if (p.dact == 1) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[e] = t[e] > 0.f ? v[e] : 0.f;
@@ -152,9 +164,32 @@ template <typename T, int TM, int TN, bool DROP>
 __device__ __forceinline__ void gemm_staged_epilogue(const GemmDev &p, const f32x16_t (&acc)[TM][TN], float *cw,
                                                      int mbase, int nbase, int lane) {
   constexpr int WC = TN * 32, CS = WC + 4;
-  constexpr int LPR = WC / 8, RPP = 64 / LPR;  // lanes per row, rows per pass
+  constexpr int LPR = WC / 8, RPP = 64 / LPR;  // lanes per row, rows per pass (lanes beyond LPR*RPP idle)
+  constexpr int PASSES = (32 + RPP - 1) / RPP;
+  // bf16: 4 registers per prefetched oct; the large wavefront tiles have no registers to spare
+  constexpr bool PRE = sizeof(T) == 2 && TM * TN <= 4;
   const int rl = lane / LPR, c8 = lane % LPR;
   const int n0 = nbase + c8 * 8;
+  const bool lane_ok = rl < RPP && n0 < p.N;
+  // The residual and the activation-derivative operand of every pass are requested up front: inside
+  // the pass loop each load would be waited for on its own, one memory latency per pass, with
+  // nothing left to overlap it at the end of the kernel.
+  bf16x8_t pre_res[PRE ? TM : 1][PRE ? PASSES : 1], pre_aux[PRE ? TM : 1][PRE ? PASSES : 1];
+  if constexpr (PRE) {
+    const bool has_res = p.residual && !p.partial, has_aux = p.dact && !p.partial;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int k = 0; k < PASSES; ++k) {
+        const int r = rl + k * RPP, m = mbase + i * 32 + r;
+        const bool ok = lane_ok && r < 32 && m < p.M;
+        const size_t off = (size_t)m * p.ldc + n0;
+        pre_res[i][k] = bf16x8_t{};
+        pre_aux[i][k] = bf16x8_t{};
+        if (has_res && ok) pre_res[i][k] = *reinterpret_cast<const bf16x8_t *>(static_cast<const bf16_t *>(p.residual) + off);
+        if (has_aux && ok) pre_aux[i][k] = *reinterpret_cast<const bf16x8_t *>(static_cast<const bf16_t *>(p.aux) + off);
+      }
+  }
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -165,13 +200,15 @@ __device__ __forceinline__ void gemm_staged_epilogue(const GemmDev &p, const f32
             make_float4(acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
     // the wave reads what its own lanes wrote: LDS operations of one wave complete in order
 #pragma unroll
-    for (int r = rl; r < 32; r += RPP) {
+    for (int k = 0; k < PASSES; ++k) {
+      const int r = rl + k * RPP;
       const int m = mbase + i * 32 + r;
-      const float4 lo = *reinterpret_cast<const float4 *>(cw + r * CS + c8 * 8);
-      const float4 hi = *reinterpret_cast<const float4 *>(cw + r * CS + c8 * 8 + 4);
-      if (m < p.M && n0 < p.N) {
+      if (lane_ok && r < 32 && m < p.M) {
+        const float4 lo = *reinterpret_cast<const float4 *>(cw + r * CS + c8 * 8);
+        const float4 hi = *reinterpret_cast<const float4 *>(cw + r * CS + c8 * 8 + 4);
         float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-        gemm_epilogue_oct<T, DROP>(p, m, n0, v);
+        if constexpr (PRE) gemm_epilogue_oct<T, DROP, true>(p, m, n0, v, pre_res[i][k], pre_aux[i][k]);
+        else gemm_epilogue_oct<T, DROP, false>(p, m, n0, v);
       }
     }
   }
