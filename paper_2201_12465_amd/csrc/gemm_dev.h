@@ -19,59 +19,8 @@ struct GemmDev {
 };
 
 
-// Epilogue on four consecutive outputs C[m, n0..n0+3] (see GemmArgs for the order of the steps).
-// DROP: the kernel instance was built with the dropout steps (they cost registers even when unused).
-template <typename T, bool DROP>
-__device__ __forceinline__ void gemm_epilogue_quad(const GemmDev &p, int m, int n0, float (&v)[4]) {
-  if (p.partial) {
-    float *dst = p.partial + (size_t)m * p.N + n0;  // the kernel has moved `partial` to its k-range's slab
-    *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-    return;
-  }
-  const size_t off = (size_t)m * p.ldc + n0;
-  float t[4];
-  if (p.bias) {
-    VecIO<T, 4>::load(static_cast<const T *>(p.bias) + n0, t);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] += t[e];
-  }
-  if (p.preact) VecIO<T, 4>::store(static_cast<T *>(p.preact) + off, v);
-  if (p.act == 1) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] = fmaxf(v[e], 0.f);
-  } else if (p.act == 2) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] = gelu_f(v[e]);
-  }
-  if (DROP && p.drop_where == 1) {
-    drop_keep4(p.drop, (uint32_t)n0 >> 2, (uint32_t)m, 0u, t);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] *= t[e];
-  }
-  if (p.residual) {
-    VecIO<T, 4>::load(static_cast<const T *>(p.residual) + off, t);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] += t[e];
-  }
-  if (p.dact) {
-    VecIO<T, 4>::load(static_cast<const T *>(p.aux) + off, t);
-    if (p.dact == 1) {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] = t[e] > 0.f ? v[e] : 0.f;
-    } else {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_f(t[e]);
-    }
-  }
-  if (DROP && p.drop_where == 2) {
-    drop_keep4(p.drop, (uint32_t)n0 >> 2, (uint32_t)m, 0u, t);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] *= t[e];
-  }
-  VecIO<T, 4>::store(static_cast<T *>(p.C) + off, v);
-}
-
-// The same steps on eight consecutive outputs C[m, n0..n0+7]: 16-byte (bf16) / 32-byte (fp32) accesses.
+// The epilogue steps (see GemmArgs for their order) on eight consecutive outputs C[m, n0..n0+7]:
+// 16-byte (bf16) / 32-byte (fp32) accesses.
 template <typename T> struct Oct;
 template <> struct Oct<bf16_t> {
   static __device__ __forceinline__ void load(const bf16_t *p, float *v) { VecIO<bf16_t, 8>::load(p, v); }
@@ -91,18 +40,16 @@ template <> struct Oct<float> {
 // PRE: the eight residual / aux values were already loaded by the caller (pre_res, pre_aux; bf16 only).
 template <typename T, bool DROP, bool PRE = false>
 __device__ __forceinline__ void gemm_epilogue_oct(const GemmDev &p, int m, int n0, float (&v)[8],
-                                                  bf16x8_t pre_res = bf16x8_t{}, bf16x8_t pre_aux = bf16x8_t{}) {
+                                                  const float (&bias8)[8], bf16x8_t pre_res = bf16x8_t{},
+                                                  bf16x8_t pre_aux = bf16x8_t{}) {
   if (p.partial) {
     Oct<float>::store(p.partial + (size_t)m * p.N + n0, v);
     return;
   }
   const size_t off = (size_t)m * p.ldc + n0;
   float t[8];
-  if (p.bias) {
-    Oct<T>::load(static_cast<const T *>(p.bias) + n0, t);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] += t[e];
-  }
+  for (int e = 0; e < 8; ++e) v[e] += bias8[e];  // zeros without a bias
   if (p.preact) Oct<T>::store(static_cast<T *>(p.preact) + off, v);
   if (p.act == 1) {
 #pragma unroll
@@ -174,6 +121,8 @@ __device__ __forceinline__ void gemm_staged_epilogue(const GemmDev &p, const f32
   // The residual and the activation-derivative operand of every pass are requested up front: inside
   // the pass loop each load would be waited for on its own, one memory latency per pass, with
   // nothing left to overlap it at the end of the kernel.
+  float bias8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};  // a lane's eight columns are the same in every pass
+  if (p.bias && !p.partial && lane_ok) Oct<T>::load(static_cast<const T *>(p.bias) + n0, bias8);
   bf16x8_t pre_res[PRE ? TM : 1][PRE ? PASSES : 1], pre_aux[PRE ? TM : 1][PRE ? PASSES : 1];
   if constexpr (PRE) {
     const bool has_res = p.residual && !p.partial, has_aux = p.dact && !p.partial;
@@ -207,8 +156,8 @@ __device__ __forceinline__ void gemm_staged_epilogue(const GemmDev &p, const f32
         const float4 lo = *reinterpret_cast<const float4 *>(cw + r * CS + c8 * 8);
         const float4 hi = *reinterpret_cast<const float4 *>(cw + r * CS + c8 * 8 + 4);
         float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-        if constexpr (PRE) gemm_epilogue_oct<T, DROP, true>(p, m, n0, v, pre_res[i][k], pre_aux[i][k]);
-        else gemm_epilogue_oct<T, DROP, false>(p, m, n0, v);
+        if constexpr (PRE) gemm_epilogue_oct<T, DROP, true>(p, m, n0, v, bias8, pre_res[i][k], pre_aux[i][k]);
+        else gemm_epilogue_oct<T, DROP, false>(p, m, n0, v, bias8);
       }
     }
   }
