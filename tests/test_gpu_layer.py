@@ -357,6 +357,35 @@ def test_side_stream_for_parameter_gradients_changes_no_bit(name):
     assert b.alloc_stats()["live_bytes"] == 0
 
 
+def test_side_stream_repeated_steps_stay_bit_identical():
+    """Thirty back-to-back training steps on one handle with the side stream on (events and cached
+    blocks of both streams are reused every step, nothing synchronises the host in between): every
+    step's gradients must equal the first step's."""
+    from paper_2201_12465_amd import binding as b
+    torch = torch_mod()
+    cfg = CONFIGS["cfg3_bert_base_bf16"].with_(B=8)
+    inp = make_inputs(cfg, seed=1, nontrivial=True)
+    dt = cfg.dtype
+    layer = b.Layer(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F, cfg.act, cfg.norm, dt, cfg.eps)
+    p = {k: to_dev(v, dt) for k, v in inp["params"].items()}
+    X, dY = to_dev(inp["X"], dt), to_dev(inp["dY"], dt)
+    L = torch.tensor(inp["lengths"], dtype=torch.int32, device="cuda")
+    outs = []
+    for it in range(30):
+        g = {k: empty_dev(v.shape, dt) for k, v in inp["params"].items()}
+        Y, dX = empty_dev(X.shape, dt), empty_dev(X.shape, dt)
+        layer.forward(p, X, L, cfg.B, cfg.T, Y, stream_ptr())
+        layer.backward(p, dY, dX, g, stream_ptr())
+        outs.append((Y, dX, g))                      # kept alive: no reuse of these buffers by torch
+    torch.cuda.synchronize()
+    layer.destroy()
+    ref = outs[0]
+    for it, (Y, dX, g) in enumerate(outs[1:], 1):
+        assert torch.equal(Y, ref[0]) and torch.equal(dX, ref[1]), it
+        for k in PARAM_NAMES:
+            assert torch.equal(g[k], ref[2][k]), (it, k)
+
+
 def test_allocation_trace_names_the_operator_of_every_buffer():
     """Section 5.2.2 telemetry: each intermediate buffer of one forward + backward is tied to the
     operator that asked for it, and everything handed out comes back."""
