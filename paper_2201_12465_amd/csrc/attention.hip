@@ -102,7 +102,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_rows(const T *__restrict__ qk
                                                         const T *__restrict__ dout, const float *__restrict__ lse,
                                                         const int32_t *__restrict__ lengths, int causal,
                                                         DropSpec drop, int Tn, int H, int dh, float scale,
-                                                        T *__restrict__ dqkv, float *__restrict__ delta) {
+                                                        T *__restrict__ dqkv, const float *__restrict__ delta) {
   __shared__ float sq[4][MAX_DH];
   __shared__ float sdo[4][MAX_DH];
   __shared__ float sp[4][64];
@@ -117,16 +117,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_rows(const T *__restrict__ qk
     const int i = active ? iw : Tn - 1;
     const size_t orow = ((size_t)b * Tn + i) * D + h * dh;
     __syncthreads();
-    float dl = 0.f;
     for (int d = lane; d < dh; d += 64) {
       sq[wave][d] = to_f32(base[(size_t)i * ld + h * dh + d]) * scale;
-      const float g = to_f32(dout[orow + d]);
-      sdo[wave][d] = g;
-      dl += g * to_f32(o[orow + d]);
+      sdo[wave][d] = to_f32(dout[orow + d]);
     }
-    dl = wave_sum(dl);
     const float L = lse[((size_t)b * H + h) * Tn + i];
-    if (active && lane == 0) delta[((size_t)b * H + h) * Tn + i] = dl;
+    const float dl = delta[((size_t)b * H + h) * Tn + i];
     __syncthreads();
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
     const int lim = causal ? min(len, i + 1) : len;
@@ -238,6 +234,39 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_rows(const T *__restrict__ q
   }
 }
 
+// delta[b, h, t] = sum_d dO[b, t, h*dh + d] * O[b, t, h*dh + d]: one wavefront per token row; a lane's
+// VEC consecutive elements lie in one head (dh is a multiple of 16); the lanes of a head meet in LDS.
+template <typename T>
+__global__ __launch_bounds__(256) void attn_delta_rows(const T *__restrict__ o, const T *__restrict__ dout, int rows,
+                                                       int Tn, int H, int dh, float *__restrict__ delta) {
+  constexpr int VEC = Elem<T>::VEC;
+  __shared__ float sp[4][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row = blockIdx.x * 4 + wave;
+  if (row >= rows) return;  // whole wavefronts leave; no workgroup barrier below
+  const int b = row / Tn, t = row - b * Tn, D = H * dh;
+  const int lph = dh / VEC;                    // lanes per head
+  const int chunk = (64 * VEC / dh) * dh;      // elements per step: as many whole heads as 64 lanes hold
+  for (int c0 = 0; c0 < D; c0 += chunk) {
+    const int col = c0 + lane * VEC;
+    float part = 0.f;
+    if (lane * VEC < chunk && col < D) {
+      float a[VEC], g[VEC];
+      VecIO<T, VEC>::load(o + (size_t)row * D + col, a);
+      VecIO<T, VEC>::load(dout + (size_t)row * D + col, g);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) part += a[e] * g[e];
+    }
+    sp[wave][lane] = part;  // LDS operations of one wavefront complete in order
+    const int heads_here = min(chunk, D - c0) / dh;
+    if (lane < heads_here) {
+      float sum = 0.f;
+      for (int k = 0; k < lph; ++k) sum += sp[wave][lane * lph + k];
+      delta[((size_t)b * H + (c0 / dh + lane)) * Tn + t] = sum;
+    }
+  }
+}
+
 bool attn_shape_ok(int B, int T, int H, int dh) {
   return B >= 1 && T >= 1 && H >= 1 && dh >= 16 && dh % 16 == 0 && dh <= MAX_DH && H <= 65535 && B <= 65535;
 }
@@ -264,28 +293,52 @@ hipError_t launch_attention_fwd(int dt, const void *qkv, const int32_t *lengths,
   return hipGetLastError();
 }
 
+bool attention_bwd_parts_independent(int dt, int dh) {
+  return !(dt == DT_BF16 && !g_force_general && attention_mfma_supported(dh));
+}
+
 hipError_t launch_attention_bwd(int dt, const void *qkv, const void *o, const void *do_, const float *lse,
                                 const int32_t *lengths, int causal, const DropSpec &drop, int B, int T, int H, int dh,
-                                void *dqkv, float *delta, hipStream_t stream) {
-  if (!qkv || !o || !do_ || !lse || !dqkv || !delta || !attn_shape_ok(B, T, H, dh)) return hipErrorInvalidValue;
-  if (dt == DT_BF16 && !g_force_general && attention_mfma_supported(dh))
-    return launch_attention_bwd_mfma(qkv, o, do_, lse, lengths, causal, drop, B, T, H, dh, dqkv, delta, stream);
+                                void *dqkv, float *delta, hipStream_t stream, int parts) {
+  if (!qkv || !o || !do_ || !lse || !dqkv || !delta || !attn_shape_ok(B, T, H, dh) || !(parts & ATTN_BWD_ALL))
+    return hipErrorInvalidValue;
+  if (!attention_bwd_parts_independent(dt, dh)) {  // matrix cores: delta is produced by the dQ kernel
+    if (!(parts & (ATTN_BWD_DQ | ATTN_BWD_DKV))) return hipSuccess;
+    return launch_attention_bwd_mfma(qkv, o, do_, lse, lengths, causal, drop, B, T, H, dh, dqkv, delta, stream, parts);
+  }
+  if (parts & ATTN_BWD_DELTA) {
+    const int rows = B * T;
+    dim3 grid((rows + 3) / 4), block(256);
+    if (dt == DT_F32)
+      hipLaunchKernelGGL(attn_delta_rows<float>, grid, block, 0, stream, static_cast<const float *>(o),
+                         static_cast<const float *>(do_), rows, T, H, dh, delta);
+    else
+      hipLaunchKernelGGL(attn_delta_rows<bf16_t>, grid, block, 0, stream, static_cast<const bf16_t *>(o),
+                         static_cast<const bf16_t *>(do_), rows, T, H, dh, delta);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  if (!(parts & (ATTN_BWD_DQ | ATTN_BWD_DKV))) return hipSuccess;
   const float scale = 1.0f / sqrtf((float)dh);
   dim3 grid((T + ROWS_PER_WG - 1) / ROWS_PER_WG, H, B), block(256);
   if (dt == DT_F32) {
-    hipLaunchKernelGGL(attn_bwd_dq_rows<float>, grid, block, 0, stream, static_cast<const float *>(qkv),
-                       static_cast<const float *>(o), static_cast<const float *>(do_), lse, lengths, causal, drop, T, H, dh,
-                       scale, static_cast<float *>(dqkv), delta);
-    hipLaunchKernelGGL(attn_bwd_dkv_rows<float>, grid, block, 0, stream, static_cast<const float *>(qkv),
-                       static_cast<const float *>(do_), lse, delta, lengths, causal, drop, T, H, dh, scale,
-                       static_cast<float *>(dqkv));
+    if (parts & ATTN_BWD_DQ)
+      hipLaunchKernelGGL(attn_bwd_dq_rows<float>, grid, block, 0, stream, static_cast<const float *>(qkv),
+                         static_cast<const float *>(o), static_cast<const float *>(do_), lse, lengths, causal, drop, T,
+                         H, dh, scale, static_cast<float *>(dqkv), delta);
+    if (parts & ATTN_BWD_DKV)
+      hipLaunchKernelGGL(attn_bwd_dkv_rows<float>, grid, block, 0, stream, static_cast<const float *>(qkv),
+                         static_cast<const float *>(do_), lse, delta, lengths, causal, drop, T, H, dh, scale,
+                         static_cast<float *>(dqkv));
   } else {
-    hipLaunchKernelGGL(attn_bwd_dq_rows<bf16_t>, grid, block, 0, stream, static_cast<const bf16_t *>(qkv),
-                       static_cast<const bf16_t *>(o), static_cast<const bf16_t *>(do_), lse, lengths, causal, drop, T, H,
-                       dh, scale, static_cast<bf16_t *>(dqkv), delta);
-    hipLaunchKernelGGL(attn_bwd_dkv_rows<bf16_t>, grid, block, 0, stream, static_cast<const bf16_t *>(qkv),
-                       static_cast<const bf16_t *>(do_), lse, delta, lengths, causal, drop, T, H, dh, scale,
-                       static_cast<bf16_t *>(dqkv));
+    if (parts & ATTN_BWD_DQ)
+      hipLaunchKernelGGL(attn_bwd_dq_rows<bf16_t>, grid, block, 0, stream, static_cast<const bf16_t *>(qkv),
+                         static_cast<const bf16_t *>(o), static_cast<const bf16_t *>(do_), lse, lengths, causal, drop,
+                         T, H, dh, scale, static_cast<bf16_t *>(dqkv), delta);
+    if (parts & ATTN_BWD_DKV)
+      hipLaunchKernelGGL(attn_bwd_dkv_rows<bf16_t>, grid, block, 0, stream, static_cast<const bf16_t *>(qkv),
+                         static_cast<const bf16_t *>(do_), lse, delta, lengths, causal, drop, T, H, dh, scale,
+                         static_cast<bf16_t *>(dqkv));
   }
   return hipGetLastError();
 }

@@ -496,13 +496,17 @@ hipError_t launch_dkv(dim3 grid, size_t lds, const void *qkv, const void *dout, 
 
 template <int DH, bool CAUSAL, bool DROP>
 hipError_t bwd_t(const void *qkv, const void *o, const void *dout, const float *lse, const int32_t *lengths,
-                 const DropSpec &drop, int B, int T, int H, float scale, void *dqkv, float *delta, hipStream_t s) {
+                 const DropSpec &drop, int B, int T, int H, float scale, void *dqkv, float *delta, hipStream_t s, int parts) {
   dim3 grid((T + ROWS_WG - 1) / ROWS_WG, H, B);
-  hipLaunchKernelGGL((attn_bwd_dq_mfma<DH, CAUSAL, DROP>), grid, dim3(NT), 0, s, static_cast<const bf16_t *>(qkv),
-                     static_cast<const bf16_t *>(o), static_cast<const bf16_t *>(dout), lse, lengths, drop, T, H, scale,
-                     static_cast<bf16_t *>(dqkv), delta);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  hipError_t e = hipSuccess;
+  if (parts & ATTN_BWD_DQ) {
+    hipLaunchKernelGGL((attn_bwd_dq_mfma<DH, CAUSAL, DROP>), grid, dim3(NT), 0, s, static_cast<const bf16_t *>(qkv),
+                       static_cast<const bf16_t *>(o), static_cast<const bf16_t *>(dout), lse, lengths, drop, T, H,
+                       scale, static_cast<bf16_t *>(dqkv), delta);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  if (!(parts & ATTN_BWD_DKV)) return e;
   const size_t lds = dkv_lds_bytes<DH>();
   e = launch_dkv<DH, DH >= 128 ? 1 : 0, CAUSAL, DROP>(grid, lds, qkv, dout, lse, delta, lengths, drop, T, H, scale, dqkv,
                                                       s);
@@ -522,12 +526,12 @@ hipError_t fwd_pick(int causal, const void *qkv, const int32_t *lengths, const D
 template <int DH>
 hipError_t bwd_pick(int causal, const void *qkv, const void *o, const void *dout, const float *lse,
                     const int32_t *lengths, const DropSpec &drop, int B, int T, int H, float scale, void *dqkv,
-                    float *delta, hipStream_t s) {
+                    float *delta, hipStream_t s, int parts) {
   if (causal)
-    return drop.thr ? bwd_t<DH, true, true>(qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s)
-                    : bwd_t<DH, true, false>(qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s);
-  return drop.thr ? bwd_t<DH, false, true>(qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s)
-                  : bwd_t<DH, false, false>(qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s);
+    return drop.thr ? bwd_t<DH, true, true>(qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts)
+                    : bwd_t<DH, true, false>(qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts);
+  return drop.thr ? bwd_t<DH, false, true>(qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts)
+                  : bwd_t<DH, false, false>(qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts);
 }
 
 }  // namespace
@@ -550,15 +554,15 @@ hipError_t launch_attention_fwd_mfma(const void *qkv, const int32_t *lengths, in
 
 hipError_t launch_attention_bwd_mfma(const void *qkv, const void *o, const void *dout, const float *lse,
                                      const int32_t *lengths, int causal, const DropSpec &drop, int B, int T, int H,
-                                     int dh, void *dqkv, float *delta, hipStream_t s) {
+                                     int dh, void *dqkv, float *delta, hipStream_t s, int parts) {
   const float scale = 1.0f / sqrtf((float)dh);
   switch (dh) {
-    case 32: return bwd_pick<32>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s);
-    case 64: return bwd_pick<64>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s);
-    case 96: return bwd_pick<96>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s);
-    case 128: return bwd_pick<128>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s);
-    case 192: return bwd_pick<192>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s);
-    case 256: return bwd_pick<256>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s);
+    case 32: return bwd_pick<32>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts);
+    case 64: return bwd_pick<64>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts);
+    case 96: return bwd_pick<96>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts);
+    case 128: return bwd_pick<128>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts);
+    case 192: return bwd_pick<192>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts);
+    case 256: return bwd_pick<256>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts);
   }
   return hipErrorInvalidValue;
 }

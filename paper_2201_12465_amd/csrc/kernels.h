@@ -96,9 +96,16 @@ hipError_t launch_attention_fwd(int dt, const void *qkv, const int32_t *lengths,
                                 int B, int T, int H, int dh, void *o, float *lse, hipStream_t stream);
 // Backward: dqkv[B*T, 3D] from do_[B*T, D]; delta is fp32 scratch [B,H,T]
 // (delta_i = sum_d dO_i O_i).  Rows of dk, dv at masked keys are written as 0.
+// `parts` selects the steps: ATTN_BWD_DELTA writes delta, ATTN_BWD_DQ the q slab of dqkv, ATTN_BWD_DKV
+// the k and v slabs (both read delta).  With the general kernels dQ and dK/dV do not depend on each
+// other, so a caller may enqueue them on different streams once ATTN_BWD_DELTA is complete
+// (attention_bwd_parts_independent says whether that holds); on the matrix-core path delta comes out of
+// the dQ kernel and the parts must run in order on one stream.
+enum { ATTN_BWD_DELTA = 1, ATTN_BWD_DQ = 2, ATTN_BWD_DKV = 4, ATTN_BWD_ALL = 7 };
 hipError_t launch_attention_bwd(int dt, const void *qkv, const void *o, const void *do_, const float *lse,
                                 const int32_t *lengths, int causal, const DropSpec &drop, int B, int T, int H, int dh,
-                                void *dqkv, float *delta, hipStream_t stream);
+                                void *dqkv, float *delta, hipStream_t stream, int parts = ATTN_BWD_ALL);
+bool attention_bwd_parts_independent(int dt, int dh);
 
 
 // bf16 attention on the matrix cores (attention_mfma.hip); the launchers above pick it when
@@ -109,7 +116,7 @@ hipError_t launch_attention_fwd_mfma(const void *qkv, const int32_t *lengths, in
                                      int T, int H, int dh, void *o, float *lse, hipStream_t s);
 hipError_t launch_attention_bwd_mfma(const void *qkv, const void *o, const void *dout, const float *lse,
                                      const int32_t *lengths, int causal, const DropSpec &drop, int B, int T, int H,
-                                     int dh, void *dqkv, float *delta, hipStream_t s);
+                                     int dh, void *dqkv, float *delta, hipStream_t s, int parts);
 
 // ---------------------------------------------------------------------------
 // Fused optimizer step over up to OPT_MAX_TENSORS tensors in one launch (optimizer.hip).

@@ -140,6 +140,7 @@ struct fl_layer {
   std::vector<hipEvent_t> fork_events; // one per fork, reused by the next backward
   size_t forks = 0;
   hipEvent_t join_event = nullptr;
+  hipEvent_t attn_join_event = nullptr;  // dK/dV kernels on the second side stream -> layer's stream
   std::vector<Buf *> held;             // buffers the side stream reads: released after the join
   const void *params[P_COUNT];
   void *grads[P_COUNT];
@@ -204,12 +205,19 @@ struct Scratch {
 // One stream per process, default priority, never destroyed.  It has no implicit ordering with
 // any other stream: every dependency is an event.
 bool g_overlap = true;
+hipStream_t make_side_stream() {
+  hipStream_t t = nullptr;
+  if (hipStreamCreateWithFlags(&t, hipStreamNonBlocking) != hipSuccess) t = nullptr;
+  return t;
+}
 hipStream_t side_stream() {
-  static hipStream_t s = [] {
-    hipStream_t t = nullptr;
-    if (hipStreamCreateWithFlags(&t, hipStreamNonBlocking) != hipSuccess) t = nullptr;
-    return t;
-  }();
+  static hipStream_t s = make_side_stream();
+  return s;
+}
+// A second one for the dK/dV kernels of the attention backward, which run beside the dQ kernel: on the
+// first side stream they would queue up behind the weight-gradient GEMMs.
+hipStream_t side_stream2() {
+  static hipStream_t s = make_side_stream();
   return s;
 }
 // Fork in two steps, so that the host can enqueue the next kernel of the critical path on the layer's
@@ -437,11 +445,32 @@ int attention_backward(void *ctx, Tape *tape, const Node *n) {
     return rc;
   }
   const double fl = 10.0 * D * L->T * (double)M, by = 8.0 * M * D * e + 8.0 * L->B * H * L->T;
-  hipError_t he = timed(FL_K_ATTN_BWD, fl, by, st, [&] {
+  const DropSpec drop = make_drop_spec(L->rec_p_attn, L->rec_seed, 1);
+  auto run = [&](int parts, hipStream_t s) {
     return launch_attention_bwd(L->dt, qs.value, os.value, os.grad, static_cast<const float *>(n->s0), L->lengths,
-                                L->cfg.causal, make_drop_spec(L->rec_p_attn, L->rec_seed, 1), L->B, L->T, H, dh, nb->ptr,
-                                delta.f32(), st);
-  });
+                                L->cfg.causal, drop, L->B, L->T, H, dh, nb->ptr, delta.f32(), s, parts);
+  };
+  // Worth a second stream only where dQ and dK/dV are independent kernels (the general path, whose
+  // grids leave much of the chip idle); next to the parameter-gradient stream the matrix-core kernels
+  // measured no gain from it.
+  hipStream_t s2 = L->side && attention_bwd_parts_independent(L->dt, dh) ? side_stream2() : nullptr;
+  hipError_t he;
+  if (!s2) {
+    he = timed(FL_K_ATTN_BWD, fl, by, st, [&] { return run(ATTN_BWD_ALL, st); });
+  } else {
+    // dQ and dK/dV only share their inputs (and delta): dK/dV go to the second side stream, and the
+    // layer's stream waits for them before this function returns, so no buffer outlives its readers.
+    he = timed(FL_K_ATTN_BWD, 0, 0, st, [&] { return run(ATTN_BWD_DELTA, st); });
+    hipEvent_t forked = nullptr;
+    if (he == hipSuccess && side_mark(L, &forked)) he = hipErrorUnknown;
+    if (he == hipSuccess) he = timed(FL_K_ATTN_BWD, 0.4 * fl, 0.5 * by, st, [&] { return run(ATTN_BWD_DQ, st); });
+    if (he == hipSuccess) he = hipStreamWaitEvent(s2, forked, 0);
+    if (he == hipSuccess) he = timed(FL_K_ATTN_BWD, 0.6 * fl, 0.5 * by, s2, [&] { return run(ATTN_BWD_DKV, s2); });
+    if (he == hipSuccess && !L->attn_join_event) he = hipEventCreateWithFlags(&L->attn_join_event, hipEventDisableTiming);
+    if (he == hipSuccess) he = hipEventRecord(L->attn_join_event, s2);
+    if (he == hipSuccess) he = hipStreamWaitEvent(st, L->attn_join_event, 0);
+    if (he != hipSuccess) hipStreamSynchronize(s2);  // nothing of this function may still run when its buffers go
+  }
   if (he != hipSuccess) {
     buf_unref(nb);
     FL_HIP(he);
@@ -877,6 +906,7 @@ fl_status_t fl_layer_destroy(fl_layer_t *layer) {
   release_tape(layer);
   for (hipEvent_t e : layer->fork_events) hipEventDestroy(e);  // work already enqueued against them still completes
   if (layer->join_event) hipEventDestroy(layer->join_event);
+  if (layer->attn_join_event) hipEventDestroy(layer->attn_join_event);
   delete layer;
   return FL_OK;
   FL_GUARD_END
