@@ -67,8 +67,10 @@ typedef struct {
 } fl_layer_config_t;
 
 /* Host structs of device pointers; all 12 must be non-null.  Parameters are
- * read during forward AND backward and are never copied: keep them unchanged
- * between a forward and its backward. */
+ * read during forward AND backward; the library keeps no copy of them beyond
+ * one backward pass (forward may leave transposed copies of the four weight
+ * matrices behind for its own backward): keep them unchanged between a forward
+ * and its backward. */
 typedef struct {
   const void *Wqkv, *bqkv, *Wo, *bo, *W1, *b1, *W2, *b2, *ln1_g, *ln1_b, *ln2_g, *ln2_b;
 } fl_layer_params_t;
@@ -229,7 +231,8 @@ fl_status_t fl_zero_grad(fl_dtype_t dtype, int32_t n, void *const *grads, const 
  * reading exceeds its kernel's duration by about this much).  Returns the number
  * of entries through *n. */
 typedef enum {
-  FL_K_GEMM_NT = 0,   /* y = x W^T (+bias, +activation, +residual)           */
+  FL_K_GEMM_NT = 0,   /* y = x W^T (+bias, +activation, +residual); also dx  */
+                      /* where forward left a transposed copy of W behind    */
   FL_K_GEMM_NN = 1,   /* dx = dy W (+activation derivative, +skip gradient)  */
   FL_K_GEMM_TN = 2,   /* dW = dy^T x (split over the token dimension)        */
   FL_K_SPLITK_REDUCE = 3,
@@ -238,7 +241,8 @@ typedef enum {
   FL_K_LN_FWD = 6,
   FL_K_LN_BWD = 7,
   FL_K_COLSUM = 8,    /* bias gradients and second-stage column reductions   */
-  FL_K_CLASS_COUNT = 9
+  FL_K_TRANSPOSE = 9, /* transposed weight copies made by forward            */
+  FL_K_CLASS_COUNT = 10
 } fl_kernel_class_t;
 typedef struct {
   int32_t kernel_class;

@@ -55,6 +55,12 @@ int32_t fl_test_colsum(int32_t dtype, const void *in, int32_t M, int32_t N, floa
  * written), against which the HBM byte counters are calibrated and copy bandwidth is measured. */
 int32_t fl_test_copy(const void *src, void *dst, uint64_t nbytes, void *hip_stream);
 
+/* dst[j] [cols[j], rows[j]] = transpose of src[j] [rows[j], cols[j]] for j < n <= 4: row-major bf16
+ * device matrices, sizes multiples of 8, 16-byte aligned, no overlap; src/dst/rows/cols are HOST arrays.
+ * The kernel that makes the layer's transposed weight copies. */
+int32_t fl_test_transpose_bf16(int32_t n, const void *const *src, void *const *dst, const int32_t *rows,
+                               const int32_t *cols, void *hip_stream);
+
 /* Masked scaled-dot-product attention on qkv[B*T, 3*H*dh]; lse and delta are fp32 [B,H,T];
  * causal != 0 adds the mask j > i; p_drop > 0 drops probabilities out (site 1 of fl_layer_set_dropout). */
 int32_t fl_test_attention_fwd(int32_t dtype, const void *qkv, const int32_t *lengths, int32_t causal, float p_drop,

@@ -20,7 +20,7 @@ FL_ACT_RELU, FL_ACT_GELU = 0, 1
 FL_NORM_POST, FL_NORM_PRE = 0, 1
 PARAM_FIELDS = ("Wqkv", "bqkv", "Wo", "bo", "W1", "b1", "W2", "b2", "ln1_g", "ln1_b", "ln2_g", "ln2_b")
 KERNEL_CLASSES = ("gemm_nt", "gemm_nn", "gemm_tn", "splitk_reduce", "attn_fwd", "attn_bwd",
-                  "ln_fwd", "ln_bwd", "colsum")
+                  "ln_fwd", "ln_bwd", "colsum", "wt_transpose")
 
 
 class FlError(RuntimeError):
@@ -114,6 +114,7 @@ def lib() -> C.CDLL:
             "fl_test_layernorm_bwd_ws_floats": (i32, [i32, i32]),
             "fl_test_layernorm_bwd": (i32, [i32, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp]),
             "fl_test_copy": (i32, [vp, vp, u64, vp]),
+            "fl_test_transpose_bf16": (i32, [i32, vp, vp, vp, vp, vp]),
             "fl_test_colsum_ws_floats": (i64, [i32, i32]),
             "fl_test_colsum": (i32, [i32, vp, i32, i32, vp, vp, vp]),
             "fl_test_attention_fwd": (i32, [i32, vp, vp, i32, f32, u64, i32, i32, i32, i32, vp, vp, vp]),

@@ -119,6 +119,13 @@ hipError_t launch_attention_bwd_mfma(const void *qkv, const void *o, const void 
                                      int dh, void *dqkv, float *delta, hipStream_t s, int parts);
 
 // ---------------------------------------------------------------------------
+// dst[j] [cols, rows] = transpose of src[j] [rows, cols] (row-major bf16; rows, cols multiples of 8;
+// 16-byte aligned; src and dst do not overlap) for j < n <= TRANSPOSE_MAX, in one launch (transpose.hip).
+constexpr int TRANSPOSE_MAX = 4;
+hipError_t launch_transpose_bf16(int n, const void *const *src, void *const *dst, const int *rows, const int *cols,
+                                 hipStream_t stream);
+
+// ---------------------------------------------------------------------------
 // Fused optimizer step over up to OPT_MAX_TENSORS tensors in one launch (optimizer.hip).
 // kind 0 = SGD (momentum buffer m used iff momentum != 0), 1 = Adam (m, v).  params/grads have
 // type dt, state is fp32; numel % 8 == 0; every pointer 16-byte aligned.  inv_bias1/2 are

@@ -142,6 +142,11 @@ struct fl_layer {
   hipEvent_t join_event = nullptr;
   hipEvent_t attn_join_event = nullptr;  // dK/dV kernels on the second side stream -> layer's stream
   std::vector<Buf *> held;             // buffers the side stream reads: released after the join
+  // Transposed copies of Wqkv, Wo, W1, W2 (in kLinear order), made by forward for the input-gradient
+  // GEMMs of its backward; see wt_make(), wt_acquire(), wt_release().
+  Buf *wt[4] = {nullptr, nullptr, nullptr, nullptr};
+  hipEvent_t wt_fork_event = nullptr, wt_event = nullptr;
+  bool wt_on_side = false;             // made on the side stream, and the layer's stream has not waited yet
   const void *params[P_COUNT];
   void *grads[P_COUNT];
 };
@@ -276,7 +281,19 @@ int side_join(fl_layer *L, bool wait_host) {
   return rc;
 }
 
-void release_tape(fl_layer *L) {
+// The transposed weights go back to the cache of the layer's stream: if they were written on the side
+// stream and nobody has waited for that yet, the layer's stream (or, when it may no longer exist, the
+// host) waits first, so that whatever the cache hands the memory to next is ordered after the writes.
+void wt_release(fl_layer *L, bool host_wait) {
+  if (L->wt_on_side) {
+    if (host_wait || hipStreamWaitEvent(L->stream, L->wt_event, 0) != hipSuccess) hipEventSynchronize(L->wt_event);
+    L->wt_on_side = false;
+  }
+  for (Buf *&b : L->wt) buf_unref(b);
+}
+
+void release_tape(fl_layer *L, bool host_wait = false) {
+  wt_release(L, host_wait);
   for (Slot &s : L->tape.slots) {
     buf_unref(s.value_buf);
     buf_unref(s.grad_buf);
@@ -295,12 +312,73 @@ void set_grad(Slot &s, void *ptr, Buf *buf) {
   s.grad_buf = buf;
 }
 
-// ---- gradient functions ---------------------------------------------------------------
-
 struct LinearShape {
   int w, b;  // parameter ids
 };
 const LinearShape kLinear[4] = {{P_WQKV, P_BQKV}, {P_WO, P_BO}, {P_W1, P_B1}, {P_W2, P_B2}};
+
+// ---- transposed weight copies ----------------------------------------------------------------
+// dx = dy W contracts over the rows of W [out, in].  With bf16 operands the GEMM kernels are fastest
+// when the contraction index is contiguous in both operands (direct-to-LDS staging, 16-byte fragment
+// reads), so forward leaves W^T [in, out] of the four weight matrices behind for its backward: one
+// launch, on the side stream while that is idle (forward has no other use for it), else on the layer's
+// stream.  Small problems, very large ones (see below) and fp32 keep the general path.
+int wt_make(fl_layer *L) {
+  const int D = L->cfg.d_model, F = L->cfg.d_ffn;
+  if (L->dt != DT_BF16 || (long)L->M * D < (1l << 18) || D % 64 || F % 64) return 0;
+  // Measured: with more than about 512 output tiles of 128 x 128 in the d_model-wide gradients the general
+  // kernel is as fast on W as the pipelined one on W^T, and the copies only cost their own time.
+  if ((long)((L->M + 127) / 128) * ((D + 127) / 128) > 512) return 0;
+  OpTag tag(FL_OP_LINEAR_FWD, 0);
+  const int rows[4] = {3 * D, D, F, D}, cols[4] = {D, D, D, F};
+  const void *src[4];
+  void *dst[4];
+  double bytes = 0;
+  for (int i = 0; i < 4; ++i) {
+    const size_t nb = (size_t)rows[i] * cols[i] * esize(L);
+    L->wt[i] = buf_new(nb, L->stream);
+    if (!L->wt[i]) {
+      wt_release(L, false);
+      return set_error(FL_ERR_OOM, "device allocation of %zu bytes failed", nb);
+    }
+    src[i] = L->params[kLinear[i].w];
+    dst[i] = L->wt[i]->ptr;
+    bytes += 2.0 * nb;
+  }
+  hipStream_t s = L->stream;
+  hipStream_t side = g_overlap ? side_stream() : nullptr;
+  hipError_t he = hipSuccess;
+  if (side) {  // the parameters (and the memory just taken from the cache) are ready at this point of the layer's stream
+    if (!L->wt_fork_event) he = hipEventCreateWithFlags(&L->wt_fork_event, hipEventDisableTiming);
+    if (he == hipSuccess && !L->wt_event) he = hipEventCreateWithFlags(&L->wt_event, hipEventDisableTiming);
+    if (he == hipSuccess) he = hipEventRecord(L->wt_fork_event, L->stream);
+    if (he == hipSuccess) he = hipStreamWaitEvent(side, L->wt_fork_event, 0);
+    s = side;
+  }
+  if (he == hipSuccess)
+    he = timed(FL_K_TRANSPOSE, 0, bytes, s, [&] { return launch_transpose_bf16(4, src, dst, rows, cols, s); });
+  if (he == hipSuccess && side) {
+    he = hipEventRecord(L->wt_event, side);
+    L->wt_on_side = he == hipSuccess;
+  }
+  if (he != hipSuccess) {
+    if (side) hipStreamSynchronize(side);
+    wt_release(L, false);
+    FL_HIP(he);
+  }
+  return 0;
+}
+// Before the layer's stream reads the copies.
+int wt_acquire(fl_layer *L) {
+  if (L->wt_on_side) {
+    FL_HIP(hipStreamWaitEvent(L->stream, L->wt_event, 0));
+    L->wt_on_side = false;
+  }
+  return 0;
+}
+
+// ---- gradient functions ---------------------------------------------------------------
+
 
 // y = x W^T + b (+act) (+residual):  db = colsum(gy), dW = gy^T x, dx += gy W, dresidual += gy.
 int linear_backward(void *ctx, Tape *tape, const Node *n) {
@@ -343,6 +421,12 @@ int linear_backward(void *ctx, Tape *tape, const Node *n) {
     a.A = gy; a.lda = N; a.a_kc = true;
     a.B = W; a.ldb = K; a.b_kc = false;
     a.M = M; a.N = K; a.K = N; a.ldc = K;
+    int cls = FL_K_GEMM_NN;
+    if (const Buf *wt = L->wt[n->param]) {  // W^T [K, N]: the contraction index is contiguous in both operands
+      FL_TRY(wt_acquire(L));
+      a.B = wt->ptr; a.ldb = N; a.b_kc = true;
+      cls = FL_K_GEMM_NT;
+    }
     a.residual = xs.grad;
     if (fin && xs.xform != XF_NONE) {
       a.dact = xs.xform;
@@ -360,7 +444,7 @@ int linear_backward(void *ctx, Tape *tape, const Node *n) {
       if (!nb) return set_error(FL_ERR_OOM, "device allocation of %zu bytes failed", (size_t)M * K * e);
       a.C = nb->ptr;
     }
-    hipError_t he = timed(FL_K_GEMM_NN, 2.0 * M * N * K, ((double)M * N + (double)M * K + (double)N * K) * e, st,
+    hipError_t he = timed(cls, 2.0 * M * N * K, ((double)M * N + (double)M * K + (double)N * K) * e, st,
                           [&] { return launch_gemm(dt, a, st); });
     if (he != hipSuccess) {
       buf_unref(nb);
@@ -720,6 +804,7 @@ int forward_impl(fl_layer *L, const fl_layer_params_t *params, const void *X, co
   release_tape(L);
   L->B = B; L->T = T; L->M = B * T; L->stream = st; L->lengths = lengths;
   L->rec_p_attn = L->p_attn; L->rec_p_hidden = L->p_hidden; L->rec_seed = L->seed;
+  FL_TRY(wt_make(L));
   Tape &tp = L->tape;
   const int D = c.d_model, F = c.d_ffn;
   const int act = c.act == FL_ACT_RELU ? XF_RELU : XF_GELU;
@@ -903,7 +988,9 @@ fl_status_t fl_zero_grad(fl_dtype_t dtype, int32_t n, void *const *grads, const 
 fl_status_t fl_layer_destroy(fl_layer_t *layer) {
   FL_GUARD_BEGIN
   if (!layer) return FL_OK;
-  release_tape(layer);
+  release_tape(layer, true);  // the caller's stream may be gone by now
+  if (layer->wt_fork_event) hipEventDestroy(layer->wt_fork_event);
+  if (layer->wt_event) hipEventDestroy(layer->wt_event);
   for (hipEvent_t e : layer->fork_events) hipEventDestroy(e);  // work already enqueued against them still completes
   if (layer->join_event) hipEventDestroy(layer->join_event);
   if (layer->attn_join_event) hipEventDestroy(layer->attn_join_event);

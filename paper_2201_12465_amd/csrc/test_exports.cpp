@@ -120,6 +120,12 @@ int32_t fl_test_copy(const void *src, void *dst, uint64_t nbytes, void *hip_stre
   return hip_status(launch_copy(src, dst, (size_t)nbytes, static_cast<hipStream_t>(hip_stream)), "launch_copy");
 }
 
+int32_t fl_test_transpose_bf16(int32_t n, const void *const *src, void *const *dst, const int32_t *rows,
+                               const int32_t *cols, void *hip_stream) {
+  return hip_status(launch_transpose_bf16(n, src, dst, rows, cols, static_cast<hipStream_t>(hip_stream)),
+                    "launch_transpose_bf16");
+}
+
 int64_t fl_test_colsum_ws_floats(int32_t M, int32_t N) { return (int64_t)colsum_ws_floats(M, N); }
 
 int32_t fl_test_colsum(int32_t dtype, const void *in, int32_t M, int32_t N, float *ws, void *out, void *hip_stream) {

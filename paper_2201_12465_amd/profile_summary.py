@@ -49,7 +49,7 @@ def classify(name: str) -> str:
         return {(True, True): "gemm_nt", (True, False): "gemm_nn", (False, False): "gemm_tn"}.get((a, bb), "gemm")
     table = (("reduce_partials", "splitk_reduce"), ("colsum", "colsum"), ("attn_fwd", "attn_fwd"),
              ("attn_bwd", "attn_bwd"), ("attn_delta", "attn_bwd"), ("ln_fwd", "ln_fwd"), ("ln_bwd", "ln_bwd"),
-             ("opt_step", "optimizer"), ("zero_tensors", "optimizer"))
+             ("opt_step", "optimizer"), ("zero_tensors", "optimizer"), ("transpose_tiles", "wt_transpose"))
     for key, cls in table:
         if key in n:
             return cls

@@ -223,6 +223,38 @@ def test_colsum(dtype, shape):
     assert rel_err(to_np(out), a.astype(np.float64).sum(0)) <= _tol(dtype)
 
 
+@pytest.mark.parametrize("shapes", [[(8, 8)], [(64, 64), (72, 200)], [(2304, 768), (768, 768), (3072, 768), (768, 3072)],
+                                    [(136, 8), (8, 1000), (200, 328)]])
+def test_transposed_weight_copies_are_exact(shapes):
+    """Data movement only: every element must arrive unchanged, also in ragged edge tiles and with
+    several matrices in one launch."""
+    import ctypes
+    b = _lib()
+    rng = np.random.default_rng(len(shapes) * 1000 + shapes[0][0])
+    src_np = [quantise(rng.standard_normal(sh), "bf16") for sh in shapes]
+    src = [to_dev(a, "bf16") for a in src_np]
+    dst = [empty_dev((sh[1], sh[0]), "bf16") for sh in shapes]
+    n = len(shapes)
+    arr_p = ctypes.c_void_p * n
+    arr_i = ctypes.c_int32 * n
+    b.check(b.lib().fl_test_transpose_bf16(n, arr_p(*[t.data_ptr() for t in src]), arr_p(*[t.data_ptr() for t in dst]),
+                                           arr_i(*[sh[0] for sh in shapes]), arr_i(*[sh[1] for sh in shapes]),
+                                           stream_ptr()))
+    torch_mod().cuda.synchronize()
+    for a, d in zip(src_np, dst):
+        assert np.array_equal(to_np(d), a.T)
+
+
+def test_transpose_rejects_sizes_that_are_not_multiples_of_eight():
+    import ctypes
+    b = _lib()
+    t = empty_dev((16, 12), "bf16")
+    o = empty_dev((12, 16), "bf16")
+    rc = b.lib().fl_test_transpose_bf16(1, (ctypes.c_void_p * 1)(t.data_ptr()), (ctypes.c_void_p * 1)(o.data_ptr()),
+                                        (ctypes.c_int32 * 1)(16), (ctypes.c_int32 * 1)(12), stream_ptr())
+    assert rc != 0
+
+
 ATTN_CASES = [  # B, T, H, dh, lengths
     (2, 16, 4, 16, None),
     (2, 200, 2, 32, [200, 65]),

@@ -332,6 +332,65 @@ def test_steady_state_has_no_device_mallocs_and_is_deterministic():
             assert np.array_equal(o[2][k], outs[0][2][k]), k
 
 
+def _classes_of_one_step(cfg, inp, layer=None):
+    from paper_2201_12465_amd import binding as b
+    b.prof_enable("all")
+    try:
+        res = run_layer_gpu(cfg, inp, layer=layer)
+        prof = b.prof_collect()
+    finally:
+        b.prof_enable(None)
+    return res, {k: v["launches"] for k, v in prof.items()}
+
+
+@pytest.mark.parametrize("overlap", [True, False])
+def test_input_gradients_take_transposed_weight_copies_where_it_pays(overlap):
+    """bf16 layers of middling size leave W^T behind in forward and run dx = dy (W^T)^T on the kernel for
+    operands that are contiguous along the contraction; results stay within the oracle's tolerance
+    (ragged token count, so edge tiles are exercised), small and fp32 layers keep dx = dy W."""
+    from paper_2201_12465_amd import binding as b
+    cfg = CONFIGS["cfg3_bert_base_bf16"].with_(B=5, T=120, D=512, H=8, F=1088, len_lo=30, len_hi=120)
+    inp = make_inputs(cfg, seed=11, nontrivial=True)
+    b.set_grad_overlap(overlap)
+    try:
+        _, launches = _classes_of_one_step(cfg, inp)
+        check_against_oracle(cfg, inp, _tol(cfg))
+    finally:
+        b.set_grad_overlap(True)
+    assert launches.get("wt_transpose") == 1 and "gemm_nn" not in launches and launches["gemm_nt"] == 8
+    small = CONFIGS["cfg3_bert_base_bf16"].with_(B=2, T=64, D=256, H=4, F=512, len_lo=10, len_hi=64)
+    _, launches = _classes_of_one_step(small, make_inputs(small, seed=2))
+    assert "wt_transpose" not in launches and launches["gemm_nn"] == 4
+    _, launches = _classes_of_one_step(CONFIGS["cfg2_small_f32"], make_inputs(CONFIGS["cfg2_small_f32"], seed=2))
+    assert "wt_transpose" not in launches and launches["gemm_nn"] == 4
+    assert b.alloc_stats()["live_bytes"] == 0
+
+
+def test_forward_without_backward_releases_the_transposed_copies():
+    """Two forwards in a row on one handle (the first recording is dropped while its copies may still be
+    in flight on the side stream), then a backward: same result as a fresh handle, nothing left allocated."""
+    from paper_2201_12465_amd import binding as b
+    cfg = CONFIGS["cfg3_bert_base_bf16"].with_(B=8)
+    inp = make_inputs(cfg, seed=4, nontrivial=True)
+    ref = run_layer_gpu(cfg, inp)
+    torch = torch_mod()
+    dt = cfg.dtype
+    layer = b.Layer(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F, cfg.act, cfg.norm, dt, cfg.eps)
+    p = {k: to_dev(v, dt) for k, v in inp["params"].items()}
+    X = to_dev(inp["X"], dt)
+    Y = empty_dev(X.shape, dt)
+    L = torch.tensor(inp["lengths"], dtype=torch.int32, device="cuda")
+    layer.forward(p, X, L, cfg.B, cfg.T, Y, stream_ptr())
+    res = run_layer_gpu(cfg, inp, layer=layer)
+    layer.forward(p, X, L, cfg.B, cfg.T, Y, stream_ptr())   # recorded, never replayed: destroy must clean up
+    layer.destroy()
+    torch.cuda.synchronize()
+    assert np.array_equal(res[0], ref[0]) and np.array_equal(res[1], ref[1])
+    for k in PARAM_NAMES:
+        assert np.array_equal(res[2][k], ref[2][k]), k
+    assert b.alloc_stats()["live_bytes"] == 0
+
+
 @pytest.mark.parametrize("name", ["cfg2_small_f32", "cfg3_bert_base_bf16"])
 def test_side_stream_for_parameter_gradients_changes_no_bit(name):
     """The parameter-gradient kernels run beside the input-gradient chain on a side stream; with that
