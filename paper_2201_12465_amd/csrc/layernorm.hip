@@ -75,14 +75,19 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T *__restrict__ x, co
 // Workgroup b walks rows b*rows_per_wg .. ; wave w takes rows w, w+nw, ... of that range, two at a
 // time so that twice as many loads are in flight.  The three column partials live in registers and
 // are folded across the waves through LDS, one quantity at a time, by all threads.
+// Rows wider than 1024 elements (ln_bwd_wide) run with four wavefronts per workgroup and one row per
+// wavefront in flight: a lane then holds up to 64 elements of each of seven row-length quantities, which
+// needs the register budget of one wavefront per SIMD.
+template <typename T, int NCH> constexpr bool ln_bwd_wide() { return NCH * Elem<T>::VEC > 16; }
+
 template <typename T, int NCH>
-__global__ __launch_bounds__(512) void ln_bwd_kernel(const T *__restrict__ dy, const T *__restrict__ x,
+__global__ __launch_bounds__((NCH * Elem<T>::VEC > 16) ? 256 : 512) void ln_bwd_kernel(const T *__restrict__ dy, const T *__restrict__ x,
                                                      const float *__restrict__ mean, const float *__restrict__ rstd,
                                                      const T *__restrict__ gamma, const T *__restrict__ add, int M,
                                                      int D, int rows_per_wg, T *__restrict__ dx,
                                                      float *__restrict__ ws) {
   constexpr int VEC = Elem<T>::VEC;
-  constexpr int R = 2;
+  constexpr int R = ln_bwd_wide<T, NCH>() ? 1 : 2;
   extern __shared__ float red[];  // [nw][D]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   const int nchunks = D / VEC;
@@ -185,7 +190,7 @@ __global__ __launch_bounds__(512) void ln_bwd_kernel(const T *__restrict__ dy, c
   }
 }
 
-int ln_waves(int D) { return D <= 2048 ? 8 : 4; }
+int ln_waves(int D) { return D <= 1024 ? 8 : 4; }  // must match ln_bwd_wide: 256 threads for wide rows
 
 template <typename T>
 hipError_t ln_fwd_t(const void *x, const void *g, const void *b, float eps, int M, int D, void *y, float *mean,

@@ -168,7 +168,7 @@ def test_gemm_rejects_bad_shapes():
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("shape", [(32, 64), (203, 768), (1024, 256), (7, 1032), (5, 4096)])
+@pytest.mark.parametrize("shape", [(32, 64), (203, 768), (1024, 256), (7, 1032), (5, 4096), (300, 2048), (70, 4096)])
 def test_layernorm_forward_backward(dtype, shape):
     b = _lib()
     M, D = shape
