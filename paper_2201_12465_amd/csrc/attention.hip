@@ -12,8 +12,8 @@
 // dS = P (dP - delta), delta_i = sum_d dO_i O_i, dQ = dS K / sqrt(dh),
 // dK = dS^T Q / sqrt(dh).
 //
-// This file holds the general kernels (any element type, fp32 arithmetic on the
-// vector ALUs): one wavefront per query row (forward, dQ) or per key row (dK, dV).
+// This file holds the general kernels (any element type and head size, fp32 arithmetic on
+// the vector ALUs; the matrix-core kernels of attention_mfma*.hip take the common cases): one wavefront per query row (forward, dQ) or per key row (dK, dV).
 #include "devutil.h"
 #include "kernels.h"
 #include "philox.h"
@@ -282,6 +282,8 @@ hipError_t launch_attention_fwd(int dt, const void *qkv, const int32_t *lengths,
   if (!qkv || !o || !lse || !attn_shape_ok(B, T, H, dh)) return hipErrorInvalidValue;
   if (dt == DT_BF16 && !g_force_general && attention_mfma_supported(dh))
     return launch_attention_fwd_mfma(qkv, lengths, causal, drop, B, T, H, dh, o, lse, stream);
+  if (dt == DT_F32 && !g_force_general && attention_mfma_f32_supported(dh))
+    return launch_attention_fwd_mfma_f32(qkv, lengths, causal, drop, B, T, H, dh, o, lse, stream);
   const float scale = 1.0f / sqrtf((float)dh);
   dim3 grid((T + ROWS_PER_WG - 1) / ROWS_PER_WG, H, B), block(256);
   if (dt == DT_F32)
@@ -294,7 +296,8 @@ hipError_t launch_attention_fwd(int dt, const void *qkv, const int32_t *lengths,
 }
 
 bool attention_bwd_parts_independent(int dt, int dh) {
-  return !(dt == DT_BF16 && !g_force_general && attention_mfma_supported(dh));
+  if (g_force_general) return true;
+  return !(dt == DT_BF16 ? attention_mfma_supported(dh) : attention_mfma_f32_supported(dh));
 }
 
 hipError_t launch_attention_bwd(int dt, const void *qkv, const void *o, const void *do_, const float *lse,
@@ -304,6 +307,9 @@ hipError_t launch_attention_bwd(int dt, const void *qkv, const void *o, const vo
     return hipErrorInvalidValue;
   if (!attention_bwd_parts_independent(dt, dh)) {  // matrix cores: delta is produced by the dQ kernel
     if (!(parts & (ATTN_BWD_DQ | ATTN_BWD_DKV))) return hipSuccess;
+    if (dt == DT_F32)
+      return launch_attention_bwd_mfma_f32(qkv, o, do_, lse, lengths, causal, drop, B, T, H, dh, dqkv, delta, stream,
+                                           parts);
     return launch_attention_bwd_mfma(qkv, o, do_, lse, lengths, causal, drop, B, T, H, dh, dqkv, delta, stream, parts);
   }
   if (parts & ATTN_BWD_DELTA) {

@@ -269,13 +269,13 @@ ATTN_CASES = [  # B, T, H, dh, lengths
 
 
 @pytest.mark.parametrize("causal,p_drop", [(False, 0.0), (True, 0.0), (False, 0.2), (True, 0.35)])
-@pytest.mark.parametrize("dtype", ["f32", "bf16", "bf16-general"])
+@pytest.mark.parametrize("dtype", ["f32", "f32-general", "bf16", "bf16-general"])
 @pytest.mark.parametrize("case", ATTN_CASES)
 def test_attention_forward_backward(dtype, case, causal, p_drop):
-    """bf16 runs the MFMA kernels where the head size allows; "bf16-general" forces the general ones.
+    """Both types run the MFMA kernels where the head size allows; "-general" forces the general ones.
     With p_drop > 0 the oracle regenerates the identical keep mask from the same seed."""
     b = _lib()
-    general = dtype == "bf16-general"
+    general = dtype.endswith("-general")
     dtype = dtype.split("-")[0]
     b.lib().fl_test_attention_force_general(1 if general else 0)
     try:
