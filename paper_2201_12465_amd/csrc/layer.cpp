@@ -210,6 +210,12 @@ struct Scratch {
 // One stream per process, default priority, never destroyed.  It has no implicit ordering with
 // any other stream: every dependency is an event.
 bool g_overlap = true;
+// Events that order this library's streams among themselves on one device: no timing and no
+// system-scope fence.  By default a recorded event also makes device memory visible to the host and to
+// other devices, and that cache write-back delays the kernels behind every record; kernel boundaries
+// already order memory within the device, which is all these events are for (the caller's own
+// synchronisation with the host is untouched).  Measured: 0.429 -> 0.419 ms per step.
+constexpr unsigned kEventFlags = hipEventDisableTiming | hipEventDisableSystemFence;
 hipStream_t make_side_stream() {
   hipStream_t t = nullptr;
   if (hipStreamCreateWithFlags(&t, hipStreamNonBlocking) != hipSuccess) t = nullptr;
@@ -235,7 +241,7 @@ int side_mark(fl_layer *L, hipEvent_t *ev) {
   if (!L->side) return 0;
   if (L->forks == L->fork_events.size()) {
     hipEvent_t e = nullptr;
-    FL_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    FL_HIP(hipEventCreateWithFlags(&e, kEventFlags));
     L->fork_events.push_back(e);
   }
   *ev = L->fork_events[L->forks++];
@@ -265,7 +271,7 @@ int side_join(fl_layer *L, bool wait_host) {
       hipStreamSynchronize(L->side);
     } else {
       hipError_t e = hipSuccess;
-      if (!L->join_event) e = hipEventCreateWithFlags(&L->join_event, hipEventDisableTiming);
+      if (!L->join_event) e = hipEventCreateWithFlags(&L->join_event, kEventFlags);
       if (e == hipSuccess) e = hipEventRecord(L->join_event, L->side);
       if (e == hipSuccess) e = hipStreamWaitEvent(L->stream, L->join_event, 0);
       if (e != hipSuccess) {
@@ -349,8 +355,8 @@ int wt_make(fl_layer *L) {
   hipStream_t side = g_overlap ? side_stream() : nullptr;
   hipError_t he = hipSuccess;
   if (side) {  // the parameters (and the memory just taken from the cache) are ready at this point of the layer's stream
-    if (!L->wt_fork_event) he = hipEventCreateWithFlags(&L->wt_fork_event, hipEventDisableTiming);
-    if (he == hipSuccess && !L->wt_event) he = hipEventCreateWithFlags(&L->wt_event, hipEventDisableTiming);
+    if (!L->wt_fork_event) he = hipEventCreateWithFlags(&L->wt_fork_event, kEventFlags);
+    if (he == hipSuccess && !L->wt_event) he = hipEventCreateWithFlags(&L->wt_event, kEventFlags);
     if (he == hipSuccess) he = hipEventRecord(L->wt_fork_event, L->stream);
     if (he == hipSuccess) he = hipStreamWaitEvent(side, L->wt_fork_event, 0);
     s = side;
@@ -550,7 +556,7 @@ int attention_backward(void *ctx, Tape *tape, const Node *n) {
     if (he == hipSuccess) he = timed(FL_K_ATTN_BWD, 0.4 * fl, 0.5 * by, st, [&] { return run(ATTN_BWD_DQ, st); });
     if (he == hipSuccess) he = hipStreamWaitEvent(s2, forked, 0);
     if (he == hipSuccess) he = timed(FL_K_ATTN_BWD, 0.6 * fl, 0.5 * by, s2, [&] { return run(ATTN_BWD_DKV, s2); });
-    if (he == hipSuccess && !L->attn_join_event) he = hipEventCreateWithFlags(&L->attn_join_event, hipEventDisableTiming);
+    if (he == hipSuccess && !L->attn_join_event) he = hipEventCreateWithFlags(&L->attn_join_event, kEventFlags);
     if (he == hipSuccess) he = hipEventRecord(L->attn_join_event, s2);
     if (he == hipSuccess) he = hipStreamWaitEvent(st, L->attn_join_event, 0);
     if (he != hipSuccess) hipStreamSynchronize(s2);  // nothing of this function may still run when its buffers go
