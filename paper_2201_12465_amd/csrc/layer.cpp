@@ -468,10 +468,15 @@ int linear_backward(void *ctx, Tape *tape, const Node *n) {
   side_hold(L, tape->slots[n->in0].value_buf);
   // bias gradient, unless the kernel that finished gy already produced it
   if (!ys.colsum_done) {
+    // The first node of the tape is replayed last: nothing follows its input-gradient GEMM on the layer's
+    // stream, while the side stream still has this node's weight gradient to do, so the bias sums go
+    // behind the GEMM instead (measured: 0.420 -> 0.417 ms per step; for any other node they would delay
+    // the chain and cost more than they save)
+    hipStream_t cs = self == 0 ? st : ps;
     Scratch ws;
-    FL_TRY(ws.get(colsum_ws_floats(M, N) * sizeof(float), ps));
-    FL_HIP(timed(FL_K_COLSUM, 0, (double)M * N * e, ps,
-                 [&] { return launch_colsum(dt, gy, M, N, ws.f32(), L->grads[kLinear[n->param].b], ps, L->accumulate); }));
+    FL_TRY(ws.get(colsum_ws_floats(M, N) * sizeof(float), cs));
+    FL_HIP(timed(FL_K_COLSUM, 0, (double)M * N * e, cs,
+                 [&] { return launch_colsum(dt, gy, M, N, ws.f32(), L->grads[kLinear[n->param].b], cs, L->accumulate); }));
   }
   // weight gradient: dW[N,K] = sum_m gy[m,n] x[m,k]
   {
