@@ -391,6 +391,58 @@ def test_forward_without_backward_releases_the_transposed_copies():
     assert b.alloc_stats()["live_bytes"] == 0
 
 
+@pytest.mark.parametrize("name", ["cfg1_tiny_f32", "cfg3_bert_base_bf16"])
+def test_step_can_be_captured_in_a_graph_and_replayed(name):
+    """A caller may capture forward + backward in a HIP graph once the allocator's cache is warm (no
+    device allocation happens during capture; the side streams join the capture through the fork
+    events).  Every replay, with eager work and synchronisation in between, must reproduce the eager
+    result bit for bit."""
+    from paper_2201_12465_amd import binding as b
+    torch = torch_mod()
+    cfg = CONFIGS[name].with_(B=min(CONFIGS[name].B, 8))
+    inp = make_inputs(cfg, seed=6, nontrivial=True)
+    dt = cfg.dtype
+    layer = b.Layer(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F, cfg.act, cfg.norm, dt, cfg.eps)
+    p = {k: to_dev(v, dt) for k, v in inp["params"].items()}
+    g = {k: empty_dev(v.shape, dt) for k, v in inp["params"].items()}
+    X, dY = to_dev(inp["X"], dt), to_dev(inp["dY"], dt)
+    Y, dX = empty_dev(X.shape, dt), empty_dev(X.shape, dt)
+    L = torch.tensor(inp["lengths"], dtype=torch.int32, device="cuda") if inp["lengths"] is not None else None
+    s = torch.cuda.Stream()
+
+    def step():
+        layer.forward(p, X, L, cfg.B, cfg.T, Y, s.cuda_stream)
+        layer.backward(p, dY, dX, g, s.cuda_stream)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [Y.clone(), dX.clone()] + [g[k].clone() for k in PARAM_NAMES]
+
+    with torch.cuda.stream(s):
+        for _ in range(3):          # warms the cache of this stream and of the side streams
+            step()
+        ref = snapshot()
+        mallocs = b.alloc_stats()["backing_mallocs"]
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=s):
+            step()
+        assert b.alloc_stats()["backing_mallocs"] == mallocs
+        for rep in range(3):
+            for t in [Y, dX] + list(g.values()):
+                t.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            got = snapshot()
+            assert all(torch.equal(a, r) for a, r in zip(got, ref)), rep
+            (X.float() @ X.float().transpose(1, 2)).sum().item()     # unrelated eager work between replays
+        step()                       # and the handle still works eagerly afterwards
+        got = snapshot()
+        assert all(torch.equal(a, r) for a, r in zip(got, ref))
+    del graph
+    layer.destroy()
+    assert b.alloc_stats()["live_bytes"] == 0
+
+
 @pytest.mark.parametrize("name", ["cfg2_small_f32", "cfg3_bert_base_bf16"])
 def test_side_stream_for_parameter_gradients_changes_no_bit(name):
     """The parameter-gradient kernels run beside the input-gradient chain on a side stream; with that
