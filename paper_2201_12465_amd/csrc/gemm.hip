@@ -243,6 +243,10 @@ int gemm_pick_splits(int dt, int M, int N, int K) {
     // workgroups are the best trade between filling the chip and the fp32 partial sums' traffic
     want = (int)((432 + tiles / 2) / tiles);
     if (want > 6) want = 6;
+  } else if (gemm_f32_small_applies(M, N)) {
+    // 32 x 32 tiles with k split inside the workgroup: a wavefront's chain is K/8 MFMAs of 64 clocks
+    // (3.4 us at K = 1024), less than a second-stage launch costs, until K gets long
+    want = (K + 4095) / 4096;
   } else {
     want = (int)((512 + tiles - 1) / tiles);
   }
@@ -290,6 +294,7 @@ hipError_t launch_gemm(int dt, const GemmArgs &a, hipStream_t stream) {
     if (variant > 0 && d.drop_where) variant = 0;  // the dropout steps exist in the 128x128 / 2-stage instance only
     if (variant >= 0) return launch_gemm_bf16_pipe(a, &d, splits, variant, stream);
   }
+  if (dt == DT_F32 && !g_force_tmw && gemm_f32_small_applies(a.M, a.N)) return launch_gemm_f32_small(a, &d, splits, stream);
   // fewer than 1.5 full tiles per CU: halve the tile height so that twice as many workgroups run
   int tmw = (long)d.tiles_m * d.tiles_n * splits < 384 && a.M > 64 ? 1 : 2;
   if (g_force_tmw) tmw = g_force_tmw;

@@ -47,6 +47,11 @@ hipError_t launch_gemm(int dt, const GemmArgs &a, hipStream_t stream);
 int gemm_pick_splits(int dt, int M, int N, int K);
 void gemm_force_tile_height(int tmw);  // gemm.hip kernel: 0 automatic, 1 = 64x128 tiles, 2 = 128x128 tiles
 
+// fp32 outputs with few tiles (gemm_f32_small.hip): 32 x 32 tiles, the four wavefronts of a workgroup
+// split k.  launch_gemm uses it when gemm_f32_small_applies and no tile height is forced.
+bool gemm_f32_small_applies(int M, int N);
+hipError_t launch_gemm_f32_small(const GemmArgs &a, const void *gemm_dev, int splits, hipStream_t s);
+
 // The pipelined bf16 kernel (gemm_pipe.hip); launch_gemm uses it whenever the problem is eligible.
 bool gemm_pipe_eligible(const GemmArgs &a, int k_per_split);
 int gemm_pipe_pick_variant(bool a_kc, bool b_kc, int M, int N, int K);  // < 0: use the kernel in gemm.hip
