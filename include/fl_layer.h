@@ -140,8 +140,14 @@ const char *fl_last_error(void);
  * reads, and the caller's stream waits for it before fl_layer_backward returns control of dX and
  * the gradient buffers to work enqueued later on that stream: the caller sees the same ordering
  * either way, and the results are bit-identical.  Small problems (B*T*d_model < 2^18) always stay on
- * one stream.  Process-wide; not thread-safe against
- * concurrent backward calls. */
+ * one stream.  The same switch decides where forward writes the transposed weight copies it leaves for
+ * its backward (bf16 layers of middling size): on the side stream, or in order on the caller's.
+ * Process-wide; not thread-safe against concurrent forward or backward calls.
+ *
+ * Graph capture: once calls with the same sizes have warmed the allocator's cache (so that no device
+ * allocation happens), fl_layer_forward + fl_layer_backward on a capturing stream record a valid
+ * graph -- the side streams enter the capture through the fork events and leave it at the join --
+ * and replays reproduce the eager results bit for bit.  Timing (fl_prof_enable) must be off. */
 fl_status_t fl_set_grad_overlap(int32_t enabled);
 
 /* Caching device allocator telemetry (Section 4.1.2; Section 5.2.2 describes
