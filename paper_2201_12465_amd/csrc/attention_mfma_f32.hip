@@ -1,5 +1,6 @@
 // Fused masked attention in fp32 on the matrix cores (v_mfma_f32_32x32x2_f32), forward and
-// backward, for head sizes 32, 64, 96 and 128.
+// backward, for head sizes up to 128 (multiples of 16; a kernel instance is built for each multiple of
+// 32 and the next smaller size runs on it with its upper 16 columns read as zeros and never stored).
 //
 // Same operator, same decomposition and same orientation of the score blocks as the bf16 kernels
 // in attention_mfma.hip (the paper's matmul / exp / max / sum primitives, Section 4.1.1, fused with
@@ -48,11 +49,12 @@ template <int DH> struct TileRegsF {
   static constexpr int TILE = tile_rows(DH), CPR = DH / 4, N = TILE * CPR / NT;
   static_assert(TILE * CPR % NT == 0, "tile must divide among the threads");
   float4 r[N];
-  __device__ __forceinline__ void load(const float *src, size_t ld, int nvalid) {
+  __device__ __forceinline__ void load(const float *src, size_t ld, int nvalid, int dh) {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       const int c = threadIdx.x + NT * i, row = c / CPR, ch = c % CPR;
-      r[i] = row < nvalid ? *reinterpret_cast<const float4 *>(src + (size_t)row * ld + ch * 4) : make_float4(0, 0, 0, 0);
+      r[i] = row < nvalid && ch * 4 < dh ? *reinterpret_cast<const float4 *>(src + (size_t)row * ld + ch * 4)
+                                         : make_float4(0, 0, 0, 0);
     }
   }
   __device__ __forceinline__ void store(float *dst) const {
@@ -65,28 +67,28 @@ template <int DH> struct TileRegsF {
 };
 
 // this lane's operand values of its own row: element 2*kk + lane/32 for every k-step kk (zeros without a row)
-template <int DH> __device__ __forceinline__ void own_row(const float *row, int h2, float (&f)[DH / 2]) {
+template <int DH> __device__ __forceinline__ void own_row(const float *row, int h2, int dh, float (&f)[DH / 2]) {
 #pragma unroll
-  for (int kk = 0; kk < DH / 2; ++kk) f[kk] = row ? row[2 * kk + h2] : 0.f;
+  for (int kk = 0; kk < DH / 2; ++kk) f[kk] = row && 2 * kk < dh ? row[2 * kk + h2] : 0.f;
 }
 
 // ------------------------------------------------------------------------------------------ forward
 template <int DH, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(NT) void attn_fwd_mfma_f32(const float *__restrict__ qkv, const int32_t *__restrict__ lengths,
-                                                        DropSpec drop, int Tn, int H, float scale,
+                                                        DropSpec drop, int Tn, int H, int dh, float scale,
                                                         float *__restrict__ o, float *__restrict__ lse) {
   constexpr int TILE = tile_rows(DH), ST = row_stride(DH), NB = DH / 32;
   __shared__ __attribute__((aligned(16))) float sK[TILE * ST];
   __shared__ __attribute__((aligned(16))) float sV[TILE * ST];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5, l32 = lane & 31;
   const int b = blockIdx.z, hd = blockIdx.y;
-  const int D = H * DH;
+  const int D = H * dh;
   const size_t ld = (size_t)3 * D;
   const int len = lengths ? lengths[b] : Tn;
-  const float *base = qkv + (size_t)b * Tn * ld + hd * DH;
+  const float *base = qkv + (size_t)b * Tn * ld + hd * dh;
   const int q = blockIdx.x * ROWS_WG + wave * 32 + l32;
   float qf[DH / 2];
-  own_row<DH>(q < Tn ? base + (size_t)q * ld : nullptr, h2, qf);
+  own_row<DH>(q < Tn ? base + (size_t)q * ld : nullptr, h2, dh, qf);
   const float c = scale * LOG2E;
   float m = -INFINITY, l = 0.f;
   f32x16_t oacc[NB];
@@ -97,16 +99,16 @@ __global__ __launch_bounds__(NT) void attn_fwd_mfma_f32(const float *__restrict_
   const int kend = CAUSAL ? min(len, (int)(blockIdx.x * ROWS_WG + ROWS_WG)) : len;
   const int wend = CAUSAL ? min(len, (int)(blockIdx.x * ROWS_WG + wave * 32 + 32)) : len;
   TileRegsF<DH> tk, tv;
-  tk.load(base + D, ld, min(TILE, Tn));
-  tv.load(base + 2 * D, ld, min(TILE, Tn));
+  tk.load(base + D, ld, min(TILE, Tn), dh);
+  tv.load(base + 2 * D, ld, min(TILE, Tn), dh);
   for (int k0 = 0; k0 < kend; k0 += TILE) {
     __syncthreads();
     tk.store(sK);
     tv.store(sV);
     __syncthreads();
     if (k0 + TILE < kend) {
-      tk.load(base + (size_t)(k0 + TILE) * ld + D, ld, min(TILE, Tn - k0 - TILE));
-      tv.load(base + (size_t)(k0 + TILE) * ld + 2 * D, ld, min(TILE, Tn - k0 - TILE));
+      tk.load(base + (size_t)(k0 + TILE) * ld + D, ld, min(TILE, Tn - k0 - TILE), dh);
+      tv.load(base + (size_t)(k0 + TILE) * ld + 2 * D, ld, min(TILE, Tn - k0 - TILE), dh);
     }
 #pragma unroll
     for (int kb = 0; kb < TILE / 32; ++kb) {
@@ -156,14 +158,14 @@ __global__ __launch_bounds__(NT) void attn_fwd_mfma_f32(const float *__restrict_
   }
   if (q < Tn) {
     const float inv = 1.0f / l;
-    float *orow = o + ((size_t)b * Tn + q) * D + hd * DH;
+    float *orow = o + ((size_t)b * Tn + q) * D + hd * dh;
 #pragma unroll
     for (int db = 0; db < NB; ++db)
 #pragma unroll
       for (int qd = 0; qd < 4; ++qd) {
         float v[4] = {oacc[db][qd * 4] * inv, oacc[db][qd * 4 + 1] * inv, oacc[db][qd * 4 + 2] * inv,
                       oacc[db][qd * 4 + 3] * inv};
-        VecIO<float, 4>::store(orow + db * 32 + qd * 8 + h2 * 4, v);
+        if (db * 32 + qd * 8 + h2 * 4 < dh) VecIO<float, 4>::store(orow + db * 32 + qd * 8 + h2 * 4, v);
       }
     if (h2 == 0) lse[((size_t)b * H + hd) * Tn + q] = (m + log2f(l)) * LN2;
   }
@@ -175,26 +177,26 @@ __global__ __launch_bounds__(NT) void attn_bwd_dq_mfma_f32(const float *__restri
                                                            const float *__restrict__ dout,
                                                            const float *__restrict__ lse,
                                                            const int32_t *__restrict__ lengths, DropSpec drop, int Tn,
-                                                           int H, float scale, float *__restrict__ dqkv,
+                                                           int H, int dh, float scale, float *__restrict__ dqkv,
                                                            float *__restrict__ delta) {
   constexpr int TILE = tile_rows(DH), ST = row_stride(DH), NB = DH / 32;
   __shared__ __attribute__((aligned(16))) float sK[TILE * ST];
   __shared__ __attribute__((aligned(16))) float sV[TILE * ST];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5, l32 = lane & 31;
   const int b = blockIdx.z, hd = blockIdx.y;
-  const int D = H * DH;
+  const int D = H * dh;
   const size_t ld = (size_t)3 * D;
   const int len = lengths ? lengths[b] : Tn;
-  const float *base = qkv + (size_t)b * Tn * ld + hd * DH;
+  const float *base = qkv + (size_t)b * Tn * ld + hd * dh;
   const int q = blockIdx.x * ROWS_WG + wave * 32 + l32;
   const bool qok = q < Tn;
   float qf[DH / 2], dof[DH / 2];
-  own_row<DH>(qok ? base + (size_t)q * ld : nullptr, h2, qf);
-  own_row<DH>(qok ? dout + ((size_t)b * Tn + q) * D + hd * DH : nullptr, h2, dof);
+  own_row<DH>(qok ? base + (size_t)q * ld : nullptr, h2, dh, qf);
+  own_row<DH>(qok ? dout + ((size_t)b * Tn + q) * D + hd * dh : nullptr, h2, dh, dof);
   float dl = 0.f;
   {
     float of[DH / 2];
-    own_row<DH>(qok ? o + ((size_t)b * Tn + q) * D + hd * DH : nullptr, h2, of);
+    own_row<DH>(qok ? o + ((size_t)b * Tn + q) * D + hd * dh : nullptr, h2, dh, of);
 #pragma unroll
     for (int kk = 0; kk < DH / 2; ++kk) dl += dof[kk] * of[kk];
   }
@@ -210,16 +212,16 @@ __global__ __launch_bounds__(NT) void attn_bwd_dq_mfma_f32(const float *__restri
   const int kend = CAUSAL ? min(len, (int)(blockIdx.x * ROWS_WG + ROWS_WG)) : len;       // as in the forward kernel
   const int wend = CAUSAL ? min(len, (int)(blockIdx.x * ROWS_WG + wave * 32 + 32)) : len;
   TileRegsF<DH> tk, tv;
-  tk.load(base + D, ld, min(TILE, Tn));
-  tv.load(base + 2 * D, ld, min(TILE, Tn));
+  tk.load(base + D, ld, min(TILE, Tn), dh);
+  tv.load(base + 2 * D, ld, min(TILE, Tn), dh);
   for (int k0 = 0; k0 < kend; k0 += TILE) {
     __syncthreads();
     tk.store(sK);
     tv.store(sV);
     __syncthreads();
     if (k0 + TILE < kend) {
-      tk.load(base + (size_t)(k0 + TILE) * ld + D, ld, min(TILE, Tn - k0 - TILE));
-      tv.load(base + (size_t)(k0 + TILE) * ld + 2 * D, ld, min(TILE, Tn - k0 - TILE));
+      tk.load(base + (size_t)(k0 + TILE) * ld + D, ld, min(TILE, Tn - k0 - TILE), dh);
+      tv.load(base + (size_t)(k0 + TILE) * ld + 2 * D, ld, min(TILE, Tn - k0 - TILE), dh);
     }
 #pragma unroll
     for (int kb = 0; kb < TILE / 32; ++kb) {
@@ -257,14 +259,14 @@ __global__ __launch_bounds__(NT) void attn_bwd_dq_mfma_f32(const float *__restri
     }
   }
   if (qok) {
-    float *drow = dqkv + ((size_t)b * Tn + q) * ld + hd * DH;
+    float *drow = dqkv + ((size_t)b * Tn + q) * ld + hd * dh;
 #pragma unroll
     for (int db = 0; db < NB; ++db)
 #pragma unroll
       for (int qd = 0; qd < 4; ++qd) {
         float v[4] = {acc[db][qd * 4] * scale, acc[db][qd * 4 + 1] * scale, acc[db][qd * 4 + 2] * scale,
                       acc[db][qd * 4 + 3] * scale};
-        VecIO<float, 4>::store(drow + db * 32 + qd * 8 + h2 * 4, v);
+        if (db * 32 + qd * 8 + h2 * 4 < dh) VecIO<float, 4>::store(drow + db * 32 + qd * 8 + h2 * 4, v);
       }
   }
 }
@@ -276,22 +278,22 @@ __global__ __launch_bounds__(NT) void attn_bwd_dkv_mfma_f32(const float *__restr
                                                             const float *__restrict__ lse,
                                                             const float *__restrict__ delta,
                                                             const int32_t *__restrict__ lengths, DropSpec drop, int Tn,
-                                                            int H, float scale, float *__restrict__ dqkv) {
+                                                            int H, int dh, float scale, float *__restrict__ dqkv) {
   constexpr int TILE = tile_rows(DH), ST = row_stride(DH), NB = DH / 32;
   __shared__ __attribute__((aligned(16))) float sQ[TILE * ST];
   __shared__ __attribute__((aligned(16))) float sDO[TILE * ST];
   __shared__ float sL[TILE], sDl[TILE];   // lse*log2(e) and delta of the tile's queries
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5, l32 = lane & 31;
   const int b = blockIdx.z, hd = blockIdx.y;
-  const int D = H * DH;
+  const int D = H * dh;
   const size_t ld = (size_t)3 * D;
   const int len = lengths ? lengths[b] : Tn;
-  const float *base = qkv + (size_t)b * Tn * ld + hd * DH;
+  const float *base = qkv + (size_t)b * Tn * ld + hd * dh;
   const int key = blockIdx.x * ROWS_WG + wave * 32 + l32;
   const bool kok = key < Tn;
   float kf[DH / 2], vf[DH / 2];
-  own_row<DH>(kok ? base + (size_t)key * ld + D : nullptr, h2, kf);
-  own_row<DH>(kok ? base + (size_t)key * ld + 2 * D : nullptr, h2, vf);
+  own_row<DH>(kok ? base + (size_t)key * ld + D : nullptr, h2, dh, kf);
+  own_row<DH>(kok ? base + (size_t)key * ld + 2 * D : nullptr, h2, dh, vf);
   const float c = scale * LOG2E;
   const bool live = key < len;   // a masked key has probability 0 against every query
   f32x16_t dk[NB], dv[NB];
@@ -302,14 +304,14 @@ __global__ __launch_bounds__(NT) void attn_bwd_dkv_mfma_f32(const float *__restr
   }
   const bool wg_live = blockIdx.x * ROWS_WG < len;   // a workgroup whose keys are all masked only writes zeros
   const size_t stat0 = ((size_t)b * H + hd) * Tn;
-  const float *dobase = dout + (size_t)b * Tn * D + hd * DH;
+  const float *dobase = dout + (size_t)b * Tn * D + hd * dh;
 
   TileRegsF<DH> tq, tdo;
   float rl = INFINITY, rd = 0.f;   // this thread's lse / delta entry of the tile (threads < TILE)
   auto load_tile = [&](int q0) {
     const int nvalid = min(TILE, Tn - q0);
-    tq.load(base + (size_t)q0 * ld, ld, nvalid);
-    tdo.load(dobase + (size_t)q0 * D, (size_t)D, nvalid);
+    tq.load(base + (size_t)q0 * ld, ld, nvalid, dh);
+    tdo.load(dobase + (size_t)q0 * D, (size_t)D, nvalid, dh);
     if (threadIdx.x < TILE) {
       const bool ok = (int)threadIdx.x < nvalid;
       rl = ok ? lse[stat0 + q0 + threadIdx.x] * LOG2E : INFINITY;   // exp2(-inf) = 0 beyond T
@@ -364,7 +366,7 @@ __global__ __launch_bounds__(NT) void attn_bwd_dkv_mfma_f32(const float *__restr
     }
   }
   if (kok) {
-    float *dkrow = dqkv + ((size_t)b * Tn + key) * ld + D + hd * DH;
+    float *dkrow = dqkv + ((size_t)b * Tn + key) * ld + D + hd * dh;
     float *dvrow = dkrow + D;
 #pragma unroll
     for (int db = 0; db < NB; ++db)
@@ -372,35 +374,37 @@ __global__ __launch_bounds__(NT) void attn_bwd_dkv_mfma_f32(const float *__restr
       for (int qd = 0; qd < 4; ++qd) {
         float a[4] = {dk[db][qd * 4] * scale, dk[db][qd * 4 + 1] * scale, dk[db][qd * 4 + 2] * scale,
                       dk[db][qd * 4 + 3] * scale};
-        VecIO<float, 4>::store(dkrow + db * 32 + qd * 8 + h2 * 4, a);
         float v[4] = {dv[db][qd * 4], dv[db][qd * 4 + 1], dv[db][qd * 4 + 2], dv[db][qd * 4 + 3]};
-        VecIO<float, 4>::store(dvrow + db * 32 + qd * 8 + h2 * 4, v);
+        if (db * 32 + qd * 8 + h2 * 4 < dh) {
+          VecIO<float, 4>::store(dkrow + db * 32 + qd * 8 + h2 * 4, a);
+          VecIO<float, 4>::store(dvrow + db * 32 + qd * 8 + h2 * 4, v);
+        }
       }
   }
 }
 
 template <int DH, bool CAUSAL, bool DROP>
-hipError_t fwd_t(const float *qkv, const int32_t *lengths, const DropSpec &drop, int B, int T, int H, float scale,
+hipError_t fwd_t(const float *qkv, const int32_t *lengths, const DropSpec &drop, int B, int T, int H, int dh, float scale,
                  float *o, float *lse, hipStream_t s) {
   dim3 grid((T + ROWS_WG - 1) / ROWS_WG, H, B);
-  hipLaunchKernelGGL((attn_fwd_mfma_f32<DH, CAUSAL, DROP>), grid, dim3(NT), 0, s, qkv, lengths, drop, T, H, scale, o, lse);
+  hipLaunchKernelGGL((attn_fwd_mfma_f32<DH, CAUSAL, DROP>), grid, dim3(NT), 0, s, qkv, lengths, drop, T, H, dh, scale, o, lse);
   return hipGetLastError();
 }
 
 template <int DH, bool CAUSAL, bool DROP>
 hipError_t bwd_t(const float *qkv, const float *o, const float *dout, const float *lse, const int32_t *lengths,
-                 const DropSpec &drop, int B, int T, int H, float scale, float *dqkv, float *delta, hipStream_t s,
-                 int parts) {
+                 const DropSpec &drop, int B, int T, int H, int dh, float scale, float *dqkv, float *delta,
+                 hipStream_t s, int parts) {
   dim3 grid((T + ROWS_WG - 1) / ROWS_WG, H, B);
   if (parts & ATTN_BWD_DQ) {
     hipLaunchKernelGGL((attn_bwd_dq_mfma_f32<DH, CAUSAL, DROP>), grid, dim3(NT), 0, s, qkv, o, dout, lse, lengths, drop,
-                       T, H, scale, dqkv, delta);
+                       T, H, dh, scale, dqkv, delta);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   if (parts & ATTN_BWD_DKV) {
     hipLaunchKernelGGL((attn_bwd_dkv_mfma_f32<DH, CAUSAL, DROP>), grid, dim3(NT), 0, s, qkv, dout, lse, delta, lengths,
-                       drop, T, H, scale, dqkv);
+                       drop, T, H, dh, scale, dqkv);
     return hipGetLastError();
   }
   return hipSuccess;
@@ -408,39 +412,40 @@ hipError_t bwd_t(const float *qkv, const float *o, const float *dout, const floa
 
 template <int DH>
 hipError_t fwd_pick(int causal, const float *qkv, const int32_t *lengths, const DropSpec &drop, int B, int T, int H,
-                    float scale, float *o, float *lse, hipStream_t s) {
+                    int dh, float scale, float *o, float *lse, hipStream_t s) {
   if (causal)
-    return drop.thr ? fwd_t<DH, true, true>(qkv, lengths, drop, B, T, H, scale, o, lse, s)
-                    : fwd_t<DH, true, false>(qkv, lengths, drop, B, T, H, scale, o, lse, s);
-  return drop.thr ? fwd_t<DH, false, true>(qkv, lengths, drop, B, T, H, scale, o, lse, s)
-                  : fwd_t<DH, false, false>(qkv, lengths, drop, B, T, H, scale, o, lse, s);
+    return drop.thr ? fwd_t<DH, true, true>(qkv, lengths, drop, B, T, H, dh, scale, o, lse, s)
+                    : fwd_t<DH, true, false>(qkv, lengths, drop, B, T, H, dh, scale, o, lse, s);
+  return drop.thr ? fwd_t<DH, false, true>(qkv, lengths, drop, B, T, H, dh, scale, o, lse, s)
+                  : fwd_t<DH, false, false>(qkv, lengths, drop, B, T, H, dh, scale, o, lse, s);
 }
 
 template <int DH>
 hipError_t bwd_pick(int causal, const float *qkv, const float *o, const float *dout, const float *lse,
-                    const int32_t *lengths, const DropSpec &drop, int B, int T, int H, float scale, float *dqkv,
-                    float *delta, hipStream_t s, int parts) {
+                    const int32_t *lengths, const DropSpec &drop, int B, int T, int H, int dh, float scale,
+                    float *dqkv, float *delta, hipStream_t s, int parts) {
   if (causal)
-    return drop.thr ? bwd_t<DH, true, true>(qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts)
-                    : bwd_t<DH, true, false>(qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts);
-  return drop.thr ? bwd_t<DH, false, true>(qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts)
-                  : bwd_t<DH, false, false>(qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts);
+    return drop.thr ? bwd_t<DH, true, true>(qkv, o, dout, lse, lengths, drop, B, T, H, dh, scale, dqkv, delta, s, parts)
+                    : bwd_t<DH, true, false>(qkv, o, dout, lse, lengths, drop, B, T, H, dh, scale, dqkv, delta, s, parts);
+  return drop.thr ? bwd_t<DH, false, true>(qkv, o, dout, lse, lengths, drop, B, T, H, dh, scale, dqkv, delta, s, parts)
+                  : bwd_t<DH, false, false>(qkv, o, dout, lse, lengths, drop, B, T, H, dh, scale, dqkv, delta, s, parts);
 }
 
 }  // namespace
 
-bool attention_mfma_f32_supported(int dh) { return dh == 32 || dh == 64 || dh == 96 || dh == 128; }
+bool attention_mfma_f32_supported(int dh) { return dh >= 16 && dh <= 128 && dh % 16 == 0; }
 
 hipError_t launch_attention_fwd_mfma_f32(const void *qkv, const int32_t *lengths, int causal, const DropSpec &drop,
                                          int B, int T, int H, int dh, void *o, float *lse, hipStream_t s) {
   const float scale = 1.0f / sqrtf((float)dh);
   const float *x = static_cast<const float *>(qkv);
   float *y = static_cast<float *>(o);
-  switch (dh) {
-    case 32: return fwd_pick<32>(causal, x, lengths, drop, B, T, H, scale, y, lse, s);
-    case 64: return fwd_pick<64>(causal, x, lengths, drop, B, T, H, scale, y, lse, s);
-    case 96: return fwd_pick<96>(causal, x, lengths, drop, B, T, H, scale, y, lse, s);
-    case 128: return fwd_pick<128>(causal, x, lengths, drop, B, T, H, scale, y, lse, s);
+  if (!attention_mfma_f32_supported(dh)) return hipErrorInvalidValue;
+  switch ((dh + 31) / 32) {
+    case 1: return fwd_pick<32>(causal, x, lengths, drop, B, T, H, dh, scale, y, lse, s);
+    case 2: return fwd_pick<64>(causal, x, lengths, drop, B, T, H, dh, scale, y, lse, s);
+    case 3: return fwd_pick<96>(causal, x, lengths, drop, B, T, H, dh, scale, y, lse, s);
+    case 4: return fwd_pick<128>(causal, x, lengths, drop, B, T, H, dh, scale, y, lse, s);
   }
   return hipErrorInvalidValue;
 }
@@ -452,11 +457,12 @@ hipError_t launch_attention_bwd_mfma_f32(const void *qkv, const void *o, const v
   const float *x = static_cast<const float *>(qkv), *oo = static_cast<const float *>(o);
   const float *g = static_cast<const float *>(dout);
   float *dx = static_cast<float *>(dqkv);
-  switch (dh) {
-    case 32: return bwd_pick<32>(causal, x, oo, g, lse, lengths, drop, B, T, H, scale, dx, delta, s, parts);
-    case 64: return bwd_pick<64>(causal, x, oo, g, lse, lengths, drop, B, T, H, scale, dx, delta, s, parts);
-    case 96: return bwd_pick<96>(causal, x, oo, g, lse, lengths, drop, B, T, H, scale, dx, delta, s, parts);
-    case 128: return bwd_pick<128>(causal, x, oo, g, lse, lengths, drop, B, T, H, scale, dx, delta, s, parts);
+  if (!attention_mfma_f32_supported(dh)) return hipErrorInvalidValue;
+  switch ((dh + 31) / 32) {
+    case 1: return bwd_pick<32>(causal, x, oo, g, lse, lengths, drop, B, T, H, dh, scale, dx, delta, s, parts);
+    case 2: return bwd_pick<64>(causal, x, oo, g, lse, lengths, drop, B, T, H, dh, scale, dx, delta, s, parts);
+    case 3: return bwd_pick<96>(causal, x, oo, g, lse, lengths, drop, B, T, H, dh, scale, dx, delta, s, parts);
+    case 4: return bwd_pick<128>(causal, x, oo, g, lse, lengths, drop, B, T, H, dh, scale, dx, delta, s, parts);
   }
   return hipErrorInvalidValue;
 }

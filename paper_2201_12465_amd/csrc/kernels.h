@@ -123,8 +123,8 @@ hipError_t launch_attention_bwd_mfma(const void *qkv, const void *o, const void 
                                      const int32_t *lengths, int causal, const DropSpec &drop, int B, int T, int H,
                                      int dh, void *dqkv, float *delta, hipStream_t s, int parts);
 
-// fp32 attention on the matrix cores (attention_mfma_f32.hip), picked for dt fp32 and head sizes
-// 32, 64, 96, 128 unless the general kernels are forced.  As on the bf16 path, delta comes out of the
+// fp32 attention on the matrix cores (attention_mfma_f32.hip), picked for dt fp32 and head sizes up
+// to 128 (multiples of 16) unless the general kernels are forced.  As on the bf16 path, delta comes out of the
 // dQ kernel: ATTN_BWD_DQ before ATTN_BWD_DKV on one stream.
 bool attention_mfma_f32_supported(int dh);
 hipError_t launch_attention_fwd_mfma_f32(const void *qkv, const int32_t *lengths, int causal, const DropSpec &drop,
