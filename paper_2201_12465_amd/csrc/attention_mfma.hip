@@ -113,6 +113,13 @@ __device__ __forceinline__ int acc_row(int r, int h) { return (r >> 2) * 8 + h *
 // unrolling; small heads do not need that many, and a second to fourth resident wavefront hides the
 // LDS and exp latencies of the first (head size 64, B*H*T/128 = 384 workgroups: dK/dV 23.7 -> 15.7 us).
 // The values are the largest that compile without scratch.
+// Large heads: the two 32-row blocks of a tile are NOT unrolled into one body (the `#pragma unroll (...)`
+// in front of the block loops).  Unrolled, the scheduler keeps both blocks' fragments and scores live,
+// runs out of the 512 registers and spills (head size 192: 136-232 bytes per lane in the dK pass, head
+// size 256: up to 720); rolled, every instance compiles without scratch (dK pass at head size 192 and
+// T = 1000: 150 -> 99 us).
+// dK and dV in one pass up to head size 192 (rolled, that fits the register file); above, two passes.
+constexpr bool dkv_two_passes(int dh) { return dh > 192; }
 constexpr int fwd_waves(int dh, bool drop) { return dh <= 64 ? (drop ? 3 : 4) : dh <= 128 ? 2 : 1; }
 constexpr int dq_waves(int dh, bool drop) { return dh <= 64 ? (drop ? 2 : 3) : dh <= 96 ? 2 : 1; }
 constexpr int dkv_waves(int dh) { return dh <= 64 ? 2 : 1; }
@@ -161,7 +168,7 @@ __global__ __launch_bounds__(NT, fwd_waves(DH, DROP)) void attn_fwd_mfma(const b
       tk.load(base + (size_t)(k0 + TILE) * ld + D, ld, min(TILE, Tn - k0 - TILE));
       tv.load(base + (size_t)(k0 + TILE) * ld + 2 * D, ld, min(TILE, Tn - k0 - TILE));
     }
-#pragma unroll
+#pragma unroll (DH >= 192 ? 1 : 2)
     for (int kb = 0; kb < 2; ++kb) {
       if (k0 + kb * 32 >= wend) break;
       f32x16_t s;
@@ -283,7 +290,7 @@ __global__ __launch_bounds__(NT, dq_waves(DH, DROP)) void attn_bwd_dq_mfma(const
       tk.load(base + (size_t)(k0 + TILE) * ld + D, ld, min(TILE, Tn - k0 - TILE));
       tv.load(base + (size_t)(k0 + TILE) * ld + 2 * D, ld, min(TILE, Tn - k0 - TILE));
     }
-#pragma unroll
+#pragma unroll (DH >= 256 ? 1 : 2)
     for (int kb = 0; kb < 2; ++kb) {
       if (k0 + kb * 32 >= wend) break;
       f32x16_t s, dp;
@@ -332,7 +339,7 @@ __global__ __launch_bounds__(NT, dq_waves(DH, DROP)) void attn_bwd_dq_mfma(const
 }
 
 // ------------------------------------------------------------------------------------------ dK, dV
-// MODE 0 computes both; MODE 1 only dV, MODE 2 only dK.  Large heads run it twice (1 then 2): two
+// MODE 0 computes both; MODE 1 only dV, MODE 2 only dK.  Head size 256 runs it twice (1 then 2): two
 // accumulator sets of DH/32 x 16 registers plus the K and V fragments do not fit the register file.
 template <int DH, int MODE, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(NT, dkv_waves(DH)) void attn_bwd_dkv_mfma(const bf16_t *__restrict__ qkv,
@@ -409,7 +416,7 @@ __global__ __launch_bounds__(NT, dkv_waves(DH)) void attn_bwd_dkv_mfma(const bf1
     }
     __syncthreads();
     if (q0 + TILE < Tn) load_tile(q0 + TILE);
-#pragma unroll
+#pragma unroll (DH >= 128 ? 1 : 2)
     for (int qb = 0; qb < 2; ++qb) {
       if (q0 + qb * 32 >= Tn) break;
       if (CAUSAL && q0 + qb * 32 + 31 < wkey0) continue;
@@ -517,9 +524,9 @@ hipError_t bwd_t(const void *qkv, const void *o, const void *dout, const float *
   }
   if (!(parts & ATTN_BWD_DKV)) return e;
   const size_t lds = dkv_lds_bytes<DH>();
-  e = launch_dkv<DH, DH >= 128 ? 1 : 0, CAUSAL, DROP>(grid, lds, qkv, dout, lse, delta, lengths, drop, T, H, scale, dqkv,
+  e = launch_dkv<DH, dkv_two_passes(DH) ? 1 : 0, CAUSAL, DROP>(grid, lds, qkv, dout, lse, delta, lengths, drop, T, H, scale, dqkv,
                                                       s);
-  if (e != hipSuccess || DH < 128) return e;
+  if (e != hipSuccess || !dkv_two_passes(DH)) return e;
   return launch_dkv<DH, 2, CAUSAL, DROP>(grid, lds, qkv, dout, lse, delta, lengths, drop, T, H, scale, dqkv, s);
 }
 
