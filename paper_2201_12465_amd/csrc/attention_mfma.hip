@@ -121,7 +121,7 @@ __device__ __forceinline__ int acc_row(int r, int h) { return (r >> 2) * 8 + h *
 // dK and dV in one pass up to head size 192 (rolled, that fits the register file); above, two passes.
 constexpr bool dkv_two_passes(int dh) { return dh > 192; }
 constexpr int fwd_waves(int dh, bool drop) { return dh <= 64 ? (drop ? 3 : 4) : dh <= 128 ? 2 : 1; }
-constexpr int dq_waves(int dh, bool drop) { return dh <= 64 ? (drop ? 2 : 3) : dh <= 96 ? 2 : 1; }
+constexpr int dq_waves(int dh, bool drop) { return dh <= 64 ? (drop ? 2 : 3) : dh <= 96 ? 2 : dh <= 128 ? (drop ? 1 : 2) : 1; }
 constexpr int dkv_waves(int dh) { return dh <= 64 ? 2 : 1; }
 
 // ------------------------------------------------------------------------------------------ forward
@@ -290,7 +290,7 @@ __global__ __launch_bounds__(NT, dq_waves(DH, DROP)) void attn_bwd_dq_mfma(const
       tk.load(base + (size_t)(k0 + TILE) * ld + D, ld, min(TILE, Tn - k0 - TILE));
       tv.load(base + (size_t)(k0 + TILE) * ld + 2 * D, ld, min(TILE, Tn - k0 - TILE));
     }
-#pragma unroll (DH >= 256 ? 1 : 2)
+#pragma unroll (DH >= 256 || DH == 128 ? 1 : 2)
     for (int kb = 0; kb < 2; ++kb) {
       if (k0 + kb * 32 >= wend) break;
       f32x16_t s, dp;
