@@ -1,5 +1,7 @@
 // Fused masked attention on the matrix cores (bf16 in, fp32 accumulate), forward
-// and backward, for head sizes that are multiples of 32.
+// and backward, for head sizes up to 256 that are multiples of 16 (kernel instances exist for 32, 64, 96,
+// 128, 192 and 256; a smaller size runs on the next instance with the missing columns read as zeros and
+// never stored).
 //
 // Same operator as attention.hip (the paper's matmul / exp / max / sum primitives,
 // Section 4.1.1, fused into one operator with a pre-fused gradient function,
@@ -68,8 +70,8 @@ __device__ __forceinline__ bf16x8_t zero_frag() {
 }
 
 // Same layout straight from global memory (row pointer of this lane's row, or nullptr -> zeros).
-__device__ __forceinline__ bf16x8_t g_frag(const bf16_t *row, int kk, int lane) {
-  if (!row) return zero_frag();
+__device__ __forceinline__ bf16x8_t g_frag(const bf16_t *row, int kk, int lane, int dh) {
+  if (!row || kk * 16 >= dh) return zero_frag();   // dh is a multiple of 16: both lane halves agree
   return *reinterpret_cast<const bf16x8_t *>(row + kk * 16 + (lane >> 5) * 8);
 }
 
@@ -88,11 +90,12 @@ __device__ __forceinline__ bf16x8_t pack8(const f32x16_t &v, int s) {
 template <int DH> struct TileRegs {
   static constexpr int CPR = DH / 8, N = TILE * CPR / NT;  // 16-byte chunks per row, per thread
   uint4 r[N];
-  __device__ __forceinline__ void load(const bf16_t *src, size_t ld, int nvalid) {
+  __device__ __forceinline__ void load(const bf16_t *src, size_t ld, int nvalid, int dh) {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       const int c = threadIdx.x + NT * i, row = c / CPR, ch = c % CPR;
-      r[i] = row < nvalid ? *reinterpret_cast<const uint4 *>(src + (size_t)row * ld + ch * 8) : make_uint4(0, 0, 0, 0);
+      r[i] = row < nvalid && ch * 8 < dh ? *reinterpret_cast<const uint4 *>(src + (size_t)row * ld + ch * 8)
+                                         : make_uint4(0, 0, 0, 0);
     }
   }
   __device__ __forceinline__ void store(bf16_t *dst0, int stride0, bf16_t *dst1, int stride1) const {
@@ -127,22 +130,22 @@ constexpr int dkv_waves(int dh) { return dh <= 64 ? 2 : 1; }
 // ------------------------------------------------------------------------------------------ forward
 template <int DH, bool CAUSAL, bool DROP>
 __global__ __launch_bounds__(NT, fwd_waves(DH, DROP)) void attn_fwd_mfma(const bf16_t *__restrict__ qkv, const int32_t *__restrict__ lengths,
-                                                    DropSpec drop, int Tn, int H, float scale,
+                                                    DropSpec drop, int Tn, int H, int dh, float scale,
                                                     bf16_t *__restrict__ o, float *__restrict__ lse) {
   constexpr int KS = kc_stride(DH), VS = tr_stride(DH), NK = DH / 16, NB = DH / 32;
   __shared__ __attribute__((aligned(16))) bf16_t sK[TILE * KS];
   __shared__ __attribute__((aligned(16))) bf16_t sV[TILE * VS];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5;
   const int b = blockIdx.z, hd = blockIdx.y;
-  const int D = H * DH;
+  const int D = H * dh;
   const size_t ld = (size_t)3 * D;
   const int len = lengths ? lengths[b] : Tn;
-  const bf16_t *base = qkv + (size_t)b * Tn * ld + hd * DH;
+  const bf16_t *base = qkv + (size_t)b * Tn * ld + hd * dh;
   const int q = blockIdx.x * ROWS_WG + wave * 32 + (lane & 31);
   const bf16_t *qrow = q < Tn ? base + (size_t)q * ld : nullptr;
   bf16x8_t qf[NK];
 #pragma unroll
-  for (int kk = 0; kk < NK; ++kk) qf[kk] = g_frag(qrow, kk, lane);
+  for (int kk = 0; kk < NK; ++kk) qf[kk] = g_frag(qrow, kk, lane, dh);
   const float c = scale * LOG2E;
   float m = -INFINITY, l = 0.f;
   f32x16_t oacc[NB];
@@ -157,16 +160,16 @@ __global__ __launch_bounds__(NT, fwd_waves(DH, DROP)) void attn_fwd_mfma(const b
   const int kend = CAUSAL ? min(len, (int)(blockIdx.x * ROWS_WG + ROWS_WG)) : len;
   const int wend = CAUSAL ? min(len, (int)(blockIdx.x * ROWS_WG + wave * 32 + 32)) : len;
   TileRegs<DH> tk, tv;
-  tk.load(base + D, ld, min(TILE, Tn));
-  tv.load(base + 2 * D, ld, min(TILE, Tn));
+  tk.load(base + D, ld, min(TILE, Tn), dh);
+  tv.load(base + 2 * D, ld, min(TILE, Tn), dh);
   for (int k0 = 0; k0 < kend; k0 += TILE) {
     __syncthreads();
     tk.store(sK, KS, nullptr, 0);
     tv.store(sV, VS, nullptr, 0);
     __syncthreads();
     if (k0 + TILE < kend) {
-      tk.load(base + (size_t)(k0 + TILE) * ld + D, ld, min(TILE, Tn - k0 - TILE));
-      tv.load(base + (size_t)(k0 + TILE) * ld + 2 * D, ld, min(TILE, Tn - k0 - TILE));
+      tk.load(base + (size_t)(k0 + TILE) * ld + D, ld, min(TILE, Tn - k0 - TILE), dh);
+      tv.load(base + (size_t)(k0 + TILE) * ld + 2 * D, ld, min(TILE, Tn - k0 - TILE), dh);
     }
 #pragma unroll (DH >= 192 ? 1 : 2)
     for (int kb = 0; kb < 2; ++kb) {
@@ -219,14 +222,14 @@ __global__ __launch_bounds__(NT, fwd_waves(DH, DROP)) void attn_fwd_mfma(const b
   }
   if (q < Tn) {
     const float inv = 1.0f / l;
-    bf16_t *orow = o + ((size_t)b * Tn + q) * D + hd * DH;
+    bf16_t *orow = o + ((size_t)b * Tn + q) * D + hd * dh;
 #pragma unroll
     for (int db = 0; db < NB; ++db)
 #pragma unroll
       for (int qd = 0; qd < 4; ++qd) {
         float v[4] = {oacc[db][qd * 4] * inv, oacc[db][qd * 4 + 1] * inv, oacc[db][qd * 4 + 2] * inv,
                       oacc[db][qd * 4 + 3] * inv};
-        VecIO<bf16_t, 4>::store(orow + db * 32 + qd * 8 + h2 * 4, v);
+        if (db * 32 + qd * 8 + h2 * 4 < dh) VecIO<bf16_t, 4>::store(orow + db * 32 + qd * 8 + h2 * 4, v);
       }
     if (h2 == 0) lse[((size_t)b * H + hd) * Tn + q] = (m + log2f(l)) * LN2;
   }
@@ -238,7 +241,7 @@ __global__ __launch_bounds__(NT, dq_waves(DH, DROP)) void attn_bwd_dq_mfma(const
                                                        const bf16_t *__restrict__ dout,
                                                        const float *__restrict__ lse,
                                                        const int32_t *__restrict__ lengths, DropSpec drop, int Tn,
-                                                       int H, float scale, bf16_t *__restrict__ dqkv,
+                                                       int H, int dh, float scale, bf16_t *__restrict__ dqkv,
                                                        float *__restrict__ delta) {
   constexpr int KS = kc_stride(DH), TS = tr_stride(DH), NK = DH / 16, NB = DH / 32;
   __shared__ __attribute__((aligned(16))) bf16_t sK[TILE * KS];   // K rows for S^T = K Q^T
@@ -246,22 +249,22 @@ __global__ __launch_bounds__(NT, dq_waves(DH, DROP)) void attn_bwd_dq_mfma(const
   __shared__ __attribute__((aligned(16))) bf16_t sV[TILE * KS];   // V rows for dP^T = V dO^T
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5;
   const int b = blockIdx.z, hd = blockIdx.y;
-  const int D = H * DH;
+  const int D = H * dh;
   const size_t ld = (size_t)3 * D;
   const int len = lengths ? lengths[b] : Tn;
-  const bf16_t *base = qkv + (size_t)b * Tn * ld + hd * DH;
+  const bf16_t *base = qkv + (size_t)b * Tn * ld + hd * dh;
   const int q = blockIdx.x * ROWS_WG + wave * 32 + (lane & 31);
   const bool qok = q < Tn;
   const bf16_t *qrow = qok ? base + (size_t)q * ld : nullptr;
-  const bf16_t *dorow = qok ? dout + ((size_t)b * Tn + q) * D + hd * DH : nullptr;
-  const bf16_t *orow = qok ? o + ((size_t)b * Tn + q) * D + hd * DH : nullptr;
+  const bf16_t *dorow = qok ? dout + ((size_t)b * Tn + q) * D + hd * dh : nullptr;
+  const bf16_t *orow = qok ? o + ((size_t)b * Tn + q) * D + hd * dh : nullptr;
   bf16x8_t qf[NK], dof[NK];
   float dl = 0.f;
 #pragma unroll
   for (int kk = 0; kk < NK; ++kk) {
-    qf[kk] = g_frag(qrow, kk, lane);
-    dof[kk] = g_frag(dorow, kk, lane);
-    bf16x8_t of = g_frag(orow, kk, lane);
+    qf[kk] = g_frag(qrow, kk, lane, dh);
+    dof[kk] = g_frag(dorow, kk, lane, dh);
+    bf16x8_t of = g_frag(orow, kk, lane, dh);
 #pragma unroll
     for (int e = 0; e < 8; ++e) dl += static_cast<float>(dof[kk][e]) * static_cast<float>(of[e]);
   }
@@ -279,16 +282,16 @@ __global__ __launch_bounds__(NT, dq_waves(DH, DROP)) void attn_bwd_dq_mfma(const
   const int kend = CAUSAL ? min(len, (int)(blockIdx.x * ROWS_WG + ROWS_WG)) : len;       // as in the forward kernel
   const int wend = CAUSAL ? min(len, (int)(blockIdx.x * ROWS_WG + wave * 32 + 32)) : len;
   TileRegs<DH> tk, tv;
-  tk.load(base + D, ld, min(TILE, Tn));
-  tv.load(base + 2 * D, ld, min(TILE, Tn));
+  tk.load(base + D, ld, min(TILE, Tn), dh);
+  tv.load(base + 2 * D, ld, min(TILE, Tn), dh);
   for (int k0 = 0; k0 < kend; k0 += TILE) {
     __syncthreads();
     tk.store(sK, KS, sKt, TS);
     tv.store(sV, KS, nullptr, 0);
     __syncthreads();
     if (k0 + TILE < kend) {
-      tk.load(base + (size_t)(k0 + TILE) * ld + D, ld, min(TILE, Tn - k0 - TILE));
-      tv.load(base + (size_t)(k0 + TILE) * ld + 2 * D, ld, min(TILE, Tn - k0 - TILE));
+      tk.load(base + (size_t)(k0 + TILE) * ld + D, ld, min(TILE, Tn - k0 - TILE), dh);
+      tv.load(base + (size_t)(k0 + TILE) * ld + 2 * D, ld, min(TILE, Tn - k0 - TILE), dh);
     }
 #pragma unroll (DH >= 256 || DH == 128 ? 1 : 2)
     for (int kb = 0; kb < 2; ++kb) {
@@ -326,14 +329,14 @@ __global__ __launch_bounds__(NT, dq_waves(DH, DROP)) void attn_bwd_dq_mfma(const
     }
   }
   if (qok) {
-    bf16_t *drow = dqkv + ((size_t)b * Tn + q) * ld + hd * DH;
+    bf16_t *drow = dqkv + ((size_t)b * Tn + q) * ld + hd * dh;
 #pragma unroll
     for (int db = 0; db < NB; ++db)
 #pragma unroll
       for (int qd = 0; qd < 4; ++qd) {
         float v[4] = {acc[db][qd * 4] * scale, acc[db][qd * 4 + 1] * scale, acc[db][qd * 4 + 2] * scale,
                       acc[db][qd * 4 + 3] * scale};
-        VecIO<bf16_t, 4>::store(drow + db * 32 + qd * 8 + h2 * 4, v);
+        if (db * 32 + qd * 8 + h2 * 4 < dh) VecIO<bf16_t, 4>::store(drow + db * 32 + qd * 8 + h2 * 4, v);
       }
   }
 }
@@ -347,7 +350,7 @@ __global__ __launch_bounds__(NT, dkv_waves(DH)) void attn_bwd_dkv_mfma(const bf1
                                                         const float *__restrict__ lse,
                                                         const float *__restrict__ delta,
                                                         const int32_t *__restrict__ lengths, DropSpec drop, int Tn,
-                                                        int H, float scale, bf16_t *__restrict__ dqkv) {
+                                                        int H, int dh, float scale, bf16_t *__restrict__ dqkv) {
   constexpr bool DO_DV = MODE != 2, DO_DK = MODE != 1;
   constexpr int KS = kc_stride(DH), TS = tr_stride(DH), NK = DH / 16, NB = DH / 32;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -359,10 +362,10 @@ __global__ __launch_bounds__(NT, dkv_waves(DH)) void attn_bwd_dkv_mfma(const bf1
   float *sDl = sL + TILE;                                   // delta of the tile's queries
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5;
   const int b = blockIdx.z, hd = blockIdx.y;
-  const int D = H * DH;
+  const int D = H * dh;
   const size_t ld = (size_t)3 * D;
   const int len = lengths ? lengths[b] : Tn;
-  const bf16_t *base = qkv + (size_t)b * Tn * ld + hd * DH;
+  const bf16_t *base = qkv + (size_t)b * Tn * ld + hd * dh;
   const int key = blockIdx.x * ROWS_WG + wave * 32 + (lane & 31);
   const bool kok = key < Tn;
   const bf16_t *krow = kok ? base + (size_t)key * ld + D : nullptr;
@@ -370,8 +373,8 @@ __global__ __launch_bounds__(NT, dkv_waves(DH)) void attn_bwd_dkv_mfma(const bf1
   bf16x8_t kf[NK], vf[DO_DK ? NK : 1];
 #pragma unroll
   for (int kk = 0; kk < NK; ++kk) {
-    kf[kk] = g_frag(krow, kk, lane);
-    if constexpr (DO_DK) vf[kk] = g_frag(vrow, kk, lane);
+    kf[kk] = g_frag(krow, kk, lane, dh);
+    if constexpr (DO_DK) vf[kk] = g_frag(vrow, kk, lane, dh);
   }
   const float c = scale * LOG2E;
   const bool live = key < len;   // a masked key has probability 0 against every query
@@ -386,14 +389,14 @@ __global__ __launch_bounds__(NT, dkv_waves(DH)) void attn_bwd_dkv_mfma(const bf1
   // a workgroup whose keys are all masked only writes zeros
   const bool wg_live = blockIdx.x * ROWS_WG < len;
   const size_t stat0 = ((size_t)b * H + hd) * Tn;
-  const bf16_t *dobase = dout + (size_t)b * Tn * D + hd * DH;
+  const bf16_t *dobase = dout + (size_t)b * Tn * D + hd * dh;
 
   TileRegs<DH> tq, tdo;
   float rl = INFINITY, rd = 0.f;   // this thread's lse / delta entry of the tile (threads < TILE)
   auto load_tile = [&](int q0) {
     const int nvalid = min(TILE, Tn - q0);
-    tq.load(base + (size_t)q0 * ld, ld, nvalid);
-    tdo.load(dobase + (size_t)q0 * D, (size_t)D, nvalid);
+    tq.load(base + (size_t)q0 * ld, ld, nvalid, dh);
+    tdo.load(dobase + (size_t)q0 * D, (size_t)D, nvalid, dh);
     if (threadIdx.x < TILE) {
       const bool ok = (int)threadIdx.x < nvalid;
       rl = ok ? lse[stat0 + q0 + threadIdx.x] * LOG2E : INFINITY;   // exp2(-inf) = 0 beyond T
@@ -459,7 +462,7 @@ __global__ __launch_bounds__(NT, dkv_waves(DH)) void attn_bwd_dkv_mfma(const bf1
     }
   }
   if (kok) {
-    bf16_t *dkrow = dqkv + ((size_t)b * Tn + key) * ld + D + hd * DH;
+    bf16_t *dkrow = dqkv + ((size_t)b * Tn + key) * ld + D + hd * dh;
     bf16_t *dvrow = dkrow + D;
 #pragma unroll
     for (int db = 0; db < NB; ++db)
@@ -468,11 +471,11 @@ __global__ __launch_bounds__(NT, dkv_waves(DH)) void attn_bwd_dkv_mfma(const bf1
         if constexpr (DO_DK) {
           float a[4] = {dk[db][qd * 4] * scale, dk[db][qd * 4 + 1] * scale, dk[db][qd * 4 + 2] * scale,
                         dk[db][qd * 4 + 3] * scale};
-          VecIO<bf16_t, 4>::store(dkrow + db * 32 + qd * 8 + h2 * 4, a);
+          if (db * 32 + qd * 8 + h2 * 4 < dh) VecIO<bf16_t, 4>::store(dkrow + db * 32 + qd * 8 + h2 * 4, a);
         }
         if constexpr (DO_DV) {
           float v[4] = {dv[db][qd * 4], dv[db][qd * 4 + 1], dv[db][qd * 4 + 2], dv[db][qd * 4 + 3]};
-          VecIO<bf16_t, 4>::store(dvrow + db * 32 + qd * 8 + h2 * 4, v);
+          if (db * 32 + qd * 8 + h2 * 4 < dh) VecIO<bf16_t, 4>::store(dvrow + db * 32 + qd * 8 + h2 * 4, v);
         }
       }
   }
@@ -483,17 +486,17 @@ template <int DH> size_t dkv_lds_bytes() {
 }
 
 template <int DH, bool CAUSAL, bool DROP>
-hipError_t fwd_t(const void *qkv, const int32_t *lengths, const DropSpec &drop, int B, int T, int H, float scale,
+hipError_t fwd_t(const void *qkv, const int32_t *lengths, const DropSpec &drop, int B, int T, int H, int dh, float scale,
                  void *o, float *lse, hipStream_t s) {
   dim3 grid((T + ROWS_WG - 1) / ROWS_WG, H, B);
   hipLaunchKernelGGL((attn_fwd_mfma<DH, CAUSAL, DROP>), grid, dim3(NT), 0, s, static_cast<const bf16_t *>(qkv), lengths,
-                     drop, T, H, scale, static_cast<bf16_t *>(o), lse);
+                     drop, T, H, dh, scale, static_cast<bf16_t *>(o), lse);
   return hipGetLastError();
 }
 
 template <int DH, int MODE, bool CAUSAL, bool DROP>
 hipError_t launch_dkv(dim3 grid, size_t lds, const void *qkv, const void *dout, const float *lse, const float *delta,
-                      const int32_t *lengths, const DropSpec &drop, int T, int H, float scale, void *dqkv,
+                      const int32_t *lengths, const DropSpec &drop, int T, int H, int dh, float scale, void *dqkv,
                       hipStream_t s) {
   if (lds > 64 * 1024) {
     static bool raised = false;   // allow more than the default 64 KiB of dynamic LDS, once
@@ -506,64 +509,70 @@ hipError_t launch_dkv(dim3 grid, size_t lds, const void *qkv, const void *dout, 
   }
   hipLaunchKernelGGL((attn_bwd_dkv_mfma<DH, MODE, CAUSAL, DROP>), grid, dim3(NT), lds, s,
                      static_cast<const bf16_t *>(qkv), static_cast<const bf16_t *>(dout), lse, delta, lengths, drop, T, H,
-                     scale, static_cast<bf16_t *>(dqkv));
+                     dh, scale, static_cast<bf16_t *>(dqkv));
   return hipGetLastError();
 }
 
 template <int DH, bool CAUSAL, bool DROP>
 hipError_t bwd_t(const void *qkv, const void *o, const void *dout, const float *lse, const int32_t *lengths,
-                 const DropSpec &drop, int B, int T, int H, float scale, void *dqkv, float *delta, hipStream_t s, int parts) {
+                 const DropSpec &drop, int B, int T, int H, int dh, float scale, void *dqkv, float *delta, hipStream_t s, int parts) {
   dim3 grid((T + ROWS_WG - 1) / ROWS_WG, H, B);
   hipError_t e = hipSuccess;
   if (parts & ATTN_BWD_DQ) {
     hipLaunchKernelGGL((attn_bwd_dq_mfma<DH, CAUSAL, DROP>), grid, dim3(NT), 0, s, static_cast<const bf16_t *>(qkv),
                        static_cast<const bf16_t *>(o), static_cast<const bf16_t *>(dout), lse, lengths, drop, T, H,
-                       scale, static_cast<bf16_t *>(dqkv), delta);
+                       dh, scale, static_cast<bf16_t *>(dqkv), delta);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   if (!(parts & ATTN_BWD_DKV)) return e;
   const size_t lds = dkv_lds_bytes<DH>();
-  e = launch_dkv<DH, dkv_two_passes(DH) ? 1 : 0, CAUSAL, DROP>(grid, lds, qkv, dout, lse, delta, lengths, drop, T, H, scale, dqkv,
+  e = launch_dkv<DH, dkv_two_passes(DH) ? 1 : 0, CAUSAL, DROP>(grid, lds, qkv, dout, lse, delta, lengths, drop, T, H, dh, scale, dqkv,
                                                       s);
   if (e != hipSuccess || !dkv_two_passes(DH)) return e;
-  return launch_dkv<DH, 2, CAUSAL, DROP>(grid, lds, qkv, dout, lse, delta, lengths, drop, T, H, scale, dqkv, s);
+  return launch_dkv<DH, 2, CAUSAL, DROP>(grid, lds, qkv, dout, lse, delta, lengths, drop, T, H, dh, scale, dqkv, s);
 }
 
 // the four (causal, dropout) instances of one head size
 template <int DH>
 hipError_t fwd_pick(int causal, const void *qkv, const int32_t *lengths, const DropSpec &drop, int B, int T, int H,
-                    float scale, void *o, float *lse, hipStream_t s) {
-  if (causal) return drop.thr ? fwd_t<DH, true, true>(qkv, lengths, drop, B, T, H, scale, o, lse, s)
-                              : fwd_t<DH, true, false>(qkv, lengths, drop, B, T, H, scale, o, lse, s);
-  return drop.thr ? fwd_t<DH, false, true>(qkv, lengths, drop, B, T, H, scale, o, lse, s)
-                  : fwd_t<DH, false, false>(qkv, lengths, drop, B, T, H, scale, o, lse, s);
+                    int dh, float scale, void *o, float *lse, hipStream_t s) {
+  if (causal) return drop.thr ? fwd_t<DH, true, true>(qkv, lengths, drop, B, T, H, dh, scale, o, lse, s)
+                              : fwd_t<DH, true, false>(qkv, lengths, drop, B, T, H, dh, scale, o, lse, s);
+  return drop.thr ? fwd_t<DH, false, true>(qkv, lengths, drop, B, T, H, dh, scale, o, lse, s)
+                  : fwd_t<DH, false, false>(qkv, lengths, drop, B, T, H, dh, scale, o, lse, s);
 }
 template <int DH>
 hipError_t bwd_pick(int causal, const void *qkv, const void *o, const void *dout, const float *lse,
-                    const int32_t *lengths, const DropSpec &drop, int B, int T, int H, float scale, void *dqkv,
+                    const int32_t *lengths, const DropSpec &drop, int B, int T, int H, int dh, float scale, void *dqkv,
                     float *delta, hipStream_t s, int parts) {
   if (causal)
-    return drop.thr ? bwd_t<DH, true, true>(qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts)
-                    : bwd_t<DH, true, false>(qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts);
-  return drop.thr ? bwd_t<DH, false, true>(qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts)
-                  : bwd_t<DH, false, false>(qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts);
+    return drop.thr ? bwd_t<DH, true, true>(qkv, o, dout, lse, lengths, drop, B, T, H, dh, scale, dqkv, delta, s, parts)
+                    : bwd_t<DH, true, false>(qkv, o, dout, lse, lengths, drop, B, T, H, dh, scale, dqkv, delta, s, parts);
+  return drop.thr ? bwd_t<DH, false, true>(qkv, o, dout, lse, lengths, drop, B, T, H, dh, scale, dqkv, delta, s, parts)
+                  : bwd_t<DH, false, false>(qkv, o, dout, lse, lengths, drop, B, T, H, dh, scale, dqkv, delta, s, parts);
 }
 
 }  // namespace
 
-bool attention_mfma_supported(int dh) { return dh == 32 || dh == 64 || dh == 96 || dh == 128 || dh == 192 || dh == 256; }
+bool attention_mfma_supported(int dh) { return dh >= 16 && dh <= 256 && dh % 16 == 0; }
+
+namespace {
+// the kernel instance a head size runs on
+int instance_of(int dh) { return dh <= 128 ? (dh + 31) / 32 * 32 : dh <= 192 ? 192 : 256; }
+}  // namespace
 
 hipError_t launch_attention_fwd_mfma(const void *qkv, const int32_t *lengths, int causal, const DropSpec &drop, int B,
                                      int T, int H, int dh, void *o, float *lse, hipStream_t s) {
   const float scale = 1.0f / sqrtf((float)dh);
-  switch (dh) {
-    case 32: return fwd_pick<32>(causal, qkv, lengths, drop, B, T, H, scale, o, lse, s);
-    case 64: return fwd_pick<64>(causal, qkv, lengths, drop, B, T, H, scale, o, lse, s);
-    case 96: return fwd_pick<96>(causal, qkv, lengths, drop, B, T, H, scale, o, lse, s);
-    case 128: return fwd_pick<128>(causal, qkv, lengths, drop, B, T, H, scale, o, lse, s);
-    case 192: return fwd_pick<192>(causal, qkv, lengths, drop, B, T, H, scale, o, lse, s);
-    case 256: return fwd_pick<256>(causal, qkv, lengths, drop, B, T, H, scale, o, lse, s);
+  if (!attention_mfma_supported(dh)) return hipErrorInvalidValue;
+  switch (instance_of(dh)) {
+    case 32: return fwd_pick<32>(causal, qkv, lengths, drop, B, T, H, dh, scale, o, lse, s);
+    case 64: return fwd_pick<64>(causal, qkv, lengths, drop, B, T, H, dh, scale, o, lse, s);
+    case 96: return fwd_pick<96>(causal, qkv, lengths, drop, B, T, H, dh, scale, o, lse, s);
+    case 128: return fwd_pick<128>(causal, qkv, lengths, drop, B, T, H, dh, scale, o, lse, s);
+    case 192: return fwd_pick<192>(causal, qkv, lengths, drop, B, T, H, dh, scale, o, lse, s);
+    case 256: return fwd_pick<256>(causal, qkv, lengths, drop, B, T, H, dh, scale, o, lse, s);
   }
   return hipErrorInvalidValue;
 }
@@ -572,13 +581,14 @@ hipError_t launch_attention_bwd_mfma(const void *qkv, const void *o, const void 
                                      const int32_t *lengths, int causal, const DropSpec &drop, int B, int T, int H,
                                      int dh, void *dqkv, float *delta, hipStream_t s, int parts) {
   const float scale = 1.0f / sqrtf((float)dh);
-  switch (dh) {
-    case 32: return bwd_pick<32>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts);
-    case 64: return bwd_pick<64>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts);
-    case 96: return bwd_pick<96>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts);
-    case 128: return bwd_pick<128>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts);
-    case 192: return bwd_pick<192>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts);
-    case 256: return bwd_pick<256>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, scale, dqkv, delta, s, parts);
+  if (!attention_mfma_supported(dh)) return hipErrorInvalidValue;
+  switch (instance_of(dh)) {
+    case 32: return bwd_pick<32>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, dh, scale, dqkv, delta, s, parts);
+    case 64: return bwd_pick<64>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, dh, scale, dqkv, delta, s, parts);
+    case 96: return bwd_pick<96>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, dh, scale, dqkv, delta, s, parts);
+    case 128: return bwd_pick<128>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, dh, scale, dqkv, delta, s, parts);
+    case 192: return bwd_pick<192>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, dh, scale, dqkv, delta, s, parts);
+    case 256: return bwd_pick<256>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, dh, scale, dqkv, delta, s, parts);
   }
   return hipErrorInvalidValue;
 }

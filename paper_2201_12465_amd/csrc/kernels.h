@@ -113,8 +113,8 @@ hipError_t launch_attention_bwd(int dt, const void *qkv, const void *o, const vo
 bool attention_bwd_parts_independent(int dt, int dh);
 
 
-// bf16 attention on the matrix cores (attention_mfma.hip); the launchers above pick it when
-// dt is bf16 and the head size is one it is built for, unless the general kernels are forced.
+// bf16 attention on the matrix cores (attention_mfma.hip); the launchers above pick it when dt is
+// bf16 and the head size is at most 256 (multiples of 16), unless the general kernels are forced.
 bool attention_mfma_supported(int dh);
 void attention_force_general(bool on);
 hipError_t launch_attention_fwd_mfma(const void *qkv, const int32_t *lengths, int causal, const DropSpec &drop, int B,

@@ -265,7 +265,7 @@ ATTN_CASES = [  # B, T, H, dh, lengths
     (2, 197, 2, 64, None),
     (1, 300, 2, 192, [171]),
     (2, 70, 1, 256, [70, 33]),
-    (2, 75, 2, 48, [75, 9]),      # head sizes between the multiples of 32: padded instances (fp32), general kernels (bf16)
+    (2, 75, 2, 48, [75, 9]),      # head sizes between the multiples of 32: padded kernel instances
     (1, 45, 1, 112, None),
 ]
 
