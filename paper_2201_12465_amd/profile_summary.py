@@ -34,6 +34,12 @@ def classify(name: str) -> str:
             a, bb = (x in ("true", "1") for x in m.groups())
             return {(True, True): "gemm_nt", (True, False): "gemm_nn", (False, False): "gemm_tn"}.get((a, bb), "gemm")
         return "gemm_nt"
+    if "gemm_f32_small" in n:
+        m = re.search(r"gemm_f32_small(?:<|ILb)(true|false|1|0)(?:, |ELb)(true|false|1|0)", n)
+        if m:
+            a, bb = (x in ("true", "1") for x in m.groups())
+            return {(True, True): "gemm_nt", (True, False): "gemm_nn", (False, False): "gemm_tn"}.get((a, bb), "gemm")
+        return "gemm"
     if "gemm_kernel" in n:
         m = re.search(r"gemm_kernelI\w+?Lb([01])ELb([01])E", n)
         if m:

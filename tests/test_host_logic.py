@@ -339,6 +339,12 @@ def test_profile_summary_classifies_kernel_names():
         "_ZN2fl12_GLOBAL__N_113ln_fwd_kernelIDF16bLi2EEEvPKT_S4_S4_fiiPS2_PfS6_": "ln_fwd",
         "_ZN2fl12_GLOBAL__N_120colsum_stage1_kernelIDF16bEEvPKT_iiPf": "colsum",
         "fl::(anonymous namespace)::copy_kernel(HIP_vector_type<unsigned int, 4u> const*, ...)": "copy",
+        "void fl::(anonymous namespace)::gemm_f32_small<true, false, false>(fl::GemmDev)": "gemm_nn",
+        "void fl::(anonymous namespace)::gemm_f32_small<false, false, true>(fl::GemmDev)": "gemm_tn",
+        "_ZN2fl12_GLOBAL__N_114gemm_f32_smallILb1ELb1ELb0EEEvNS_7GemmDevE": "gemm_nt",
+        "void fl::(anonymous namespace)::attn_bwd_dq_mfma_f32<64, false, false>(float const*, float const*)": "attn_bwd",
+        "fl::(anonymous namespace)::transpose_tiles_kernel(fl::(anonymous namespace)::TransposeJobs)": "wt_transpose",
+        "_ZN2fl12_GLOBAL__N_115attn_delta_rowsIDF16bEEvPKT_S4_iiiiPf": "attn_bwd",
     }
     for name, cls in cases.items():
         assert classify(name) == cls, name
