@@ -343,13 +343,14 @@ def _classes_of_one_step(cfg, inp, layer=None):
     return res, {k: v["launches"] for k, v in prof.items()}
 
 
+@pytest.mark.parametrize("norm", ["post", "pre"])
 @pytest.mark.parametrize("overlap", [True, False])
-def test_input_gradients_take_transposed_weight_copies_where_it_pays(overlap):
+def test_input_gradients_take_transposed_weight_copies_where_it_pays(overlap, norm):
     """bf16 layers of middling size leave W^T behind in forward and run dx = dy (W^T)^T on the kernel for
     operands that are contiguous along the contraction; results stay within the oracle's tolerance
     (ragged token count, so edge tiles are exercised), small and fp32 layers keep dx = dy W."""
     from paper_2201_12465_amd import binding as b
-    cfg = CONFIGS["cfg3_bert_base_bf16"].with_(B=5, T=120, D=512, H=8, F=1088, len_lo=30, len_hi=120)
+    cfg = CONFIGS["cfg3_bert_base_bf16"].with_(B=5, T=120, D=512, H=8, F=1088, len_lo=30, len_hi=120, norm=norm)
     inp = make_inputs(cfg, seed=11, nontrivial=True)
     b.set_grad_overlap(overlap)
     try:
