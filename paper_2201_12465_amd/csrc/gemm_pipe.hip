@@ -303,7 +303,10 @@ int gemm_pipe_pick_variant(bool a_kc, bool b_kc, int M, int N, int K) {
   if (N % 192 == 0) {
     const long tiles = (long)((M + 255) / 256) * (N / 192);
     const long rounds = (tiles + 255) / 256;
-    if (tiles >= 160 && 100 * tiles >= 74 * rounds * 256) return 7;
+    // one round of tiles: worth it from 160 tiles up; several rounds: only if the last one is nearly full
+    // (12608 x 3072, 800 tiles = 3.1 rounds: 88 us against 81 with 128x128 tiles; 8000 x 3072, 512 tiles: 47.5
+    // against 51)
+    if (tiles >= 160 && 100 * tiles >= (rounds == 1 ? 74 : 90) * rounds * 256) return 7;
   }
   // few tiles and a long k-loop (FFN2): one workgroup per CU; three stages and two k-groups of
   // wavefronts per tile keep more loads in flight (35 -> 32 us)
