@@ -20,8 +20,11 @@
  *   - Element type of every activation, parameter and gradient is `dtype`
  *     (FL_F32: float; FL_BF16: bfloat16 storage, fp32 accumulation and fp32
  *     softmax / LayerNorm statistics).  Device pointers must be 16-byte aligned.
- *   - `hip_stream` is the caller's hipStream_t (0 = the null stream).  Every
- *     kernel is enqueued there; forward/backward never synchronise the device.
+ *   - `hip_stream` is the caller's hipStream_t (0 = the null stream).  All work
+ *     is ordered on it: kernels are enqueued there or on library-owned streams
+ *     that wait for it and that it waits for (see fl_set_grad_overlap), so work
+ *     the caller enqueues afterwards sees every result.  forward/backward never
+ *     synchronise the device.
  *   - Every call returns fl_status_t; no exception or abort crosses this ABI.
  *     fl_last_error() returns a thread-local message for the last failure.
  *     After an error outputs are unspecified; the handle stays destroyable.
