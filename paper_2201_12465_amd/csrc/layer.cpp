@@ -843,9 +843,6 @@ int forward_impl(fl_layer *L, const fl_layer_params_t *params, const void *X, co
   }
   L->slot_y = s_out;
   tp.recorded = true;
-  // The copies were written beside the kernels above; joining here (they finished long ago) means that
-  // whatever the caller enqueues, or frees after synchronising its stream, comes after all of forward's work.
-  FL_TRY(wt_acquire(L));
   return 0;
 }
 
