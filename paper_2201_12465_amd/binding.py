@@ -114,6 +114,9 @@ def lib() -> C.CDLL:
             "fl_test_layernorm_bwd_ws_floats": (i32, [i32, i32]),
             "fl_test_layernorm_bwd": (i32, [i32, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp]),
             "fl_test_copy": (i32, [vp, vp, u64, vp]),
+            "fl_test_gemm_variant": (i32, [i32, i32, i32, i32, i32]),
+            "fl_test_gemm_f32_small": (i32, [i32, i32]),
+            "fl_test_attention_path": (i32, [i32, i32]),
             "fl_test_transpose_bf16": (i32, [i32, vp, vp, vp, vp, vp]),
             "fl_test_colsum_ws_floats": (i64, [i32, i32]),
             "fl_test_colsum": (i32, [i32, vp, i32, i32, vp, vp, vp]),

@@ -348,3 +348,33 @@ def test_profile_summary_classifies_kernel_names():
     }
     for name, cls in cases.items():
         assert classify(name) == cls, name
+
+
+def test_kernel_selection_rules():
+    """The host-side rules that pick a kernel for a problem, on the shapes they were measured on: a change
+    of a rule shows up here before it shows up as a slower benchmark."""
+    from paper_2201_12465_amd import binding as b
+    lib = b.lib()
+    D, F = 768, 3072
+    nt = lambda M, N, K: lib.fl_test_gemm_variant(1, 1, M, N, K)
+    # BERT-base-shaped layer (M = 4096): wide outputs fill the chip in one round of 256x192 tiles; narrow
+    # outputs run 128x128 tiles, with two k-groups of wavefronts per tile when the k-loop is long
+    assert [nt(4096, 3 * D, D), nt(4096, D, D), nt(4096, F, D), nt(4096, D, F), nt(4096, D, 3 * D)] == [7, 0, 7, 9, 9]
+    # ViT-shaped stack (M = 12608): 3.1 rounds of 256x192 tiles are not worth it, one round for N = 768 is
+    assert [nt(12608, 3 * D, D), nt(12608, D, D), nt(12608, F, D), nt(12608, D, F)] == [0, 7, 0, 7]
+    # speech-shaped layer (M = 8000): two full rounds are
+    assert nt(8000, F, D) == 7 and nt(8000, D, F) == 0
+    # operands that are not contiguous along k stay on the register-staged kernel
+    assert lib.fl_test_gemm_variant(1, 0, 4096, D, F) == -2 and lib.fl_test_gemm_variant(0, 0, D, F, 4096) == -2
+    # weight gradients of the BERT-base layer: about 430 workgroups
+    splits = lambda M, N, K: lib.fl_test_gemm_splits(b.FL_BF16, M, N, K)
+    assert [splits(D, F, 4096), splits(F, D, 4096), splits(D, D, 4096), splits(3 * D, D, 4096)] == [3, 3, 6, 4]
+    # fp32: few-tile outputs run on 32x32 tiles and do not split k below 4096
+    assert lib.fl_test_gemm_f32_small(1024, 1024) == 1 and lib.fl_test_gemm_f32_small(4096, 3072) == 0
+    assert lib.fl_test_gemm_splits(b.FL_F32, 256, 1024, 1024) == 1 and lib.fl_test_gemm_splits(b.FL_F32, 256, 1024, 8192) == 2
+    # attention: every head size the layer accepts has matrix-core kernels, except fp32 above 128
+    for dh in range(16, 257, 16):
+        assert lib.fl_test_attention_path(b.FL_BF16, dh) == 1
+        assert lib.fl_test_attention_path(b.FL_F32, dh) == (2 if dh <= 128 else 0)
+    assert lib.fl_test_attention_path(b.FL_BF16, 24) == 0 and lib.fl_test_attention_path(b.FL_F32, 8) == 0
+
