@@ -156,6 +156,34 @@ def test_edge_shapes(dtype, shape):
     check_against_oracle(cfg, inp, _tol(cfg))
 
 
+def _random_case(k):
+    """Case k of a seeded sweep over shapes, types and options (sizes the oracle handles in about a second)."""
+    rng = np.random.default_rng(1000 + k)
+    dh = int(rng.choice([16, 32, 48, 64, 80, 96, 128]))
+    H = int(rng.choice([h for h in (1, 2, 3, 4, 6, 8, 12) if h * dh <= 768]))
+    dtype = "bf16" if k % 2 else "f32"
+    cfg = CONFIGS["cfg2_small_f32"].with_(
+        name=f"random{k}", dtype=dtype, B=int(rng.integers(1, 7)), T=int(rng.integers(1, 301)), D=H * dh, H=H,
+        F=8 * int(rng.integers(8, 193)), act=str(rng.choice(["relu", "gelu"])), norm=str(rng.choice(["post", "pre"])),
+        init="normal0.02" if dtype == "bf16" else "xavier", causal=bool(rng.integers(0, 2)))
+    inp = make_inputs(cfg, seed=2000 + k, nontrivial=True)
+    if rng.integers(0, 2):
+        inp["lengths"] = rng.integers(1, cfg.T + 1, size=cfg.B).astype(np.int32)
+    dropout = (float(rng.choice([0.0, 0.1, 0.3])), float(rng.choice([0.0, 0.1])), 77 + k) if k % 3 == 0 else None
+    if dropout is not None and dropout[0] == 0.0 and dropout[1] == 0.0:
+        dropout = None
+    return cfg, inp, dropout
+
+
+@pytest.mark.parametrize("k", range(60))
+def test_random_shapes_types_and_options(k):
+    """A seeded sweep across head sizes (all multiples of 16 up to 128), ragged token counts, both types,
+    both activations and norm placements, causal / padding masks and dropout: whatever kernel the
+    selection rules pick for a shape, the layer must match the oracle."""
+    cfg, inp, dropout = _random_case(k)
+    check_against_oracle(cfg, inp, _tol(cfg), dropout=dropout)
+
+
 @pytest.mark.parametrize("dtype,norm,act,masked", [("f32", "post", "relu", False), ("f32", "pre", "gelu", True),
                                                    ("bf16", "post", "gelu", True), ("bf16", "pre", "relu", False)])
 def test_causal_variants_ragged(dtype, norm, act, masked):
