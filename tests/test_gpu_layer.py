@@ -175,6 +175,22 @@ def _random_case(k):
     return cfg, inp, dropout
 
 
+@pytest.mark.parametrize("k", range(8))
+def test_random_midsize_bf16(k):
+    """Sizes at which the side stream, the transposed weight copies, the pipelined GEMM variants and the
+    split weight-gradient GEMMs are all in play, with ragged token counts."""
+    rng = np.random.default_rng(3000 + k)
+    D = int(rng.choice([512, 768, 1024]))
+    dh = int(rng.choice([64, 128]))
+    cfg = CONFIGS["cfg3_bert_base_bf16"].with_(
+        name=f"mid{k}", B=int(rng.integers(3, 9)), T=int(rng.integers(150, 400)), D=D, H=D // dh,
+        F=64 * int(rng.integers(12, 49)), act=str(rng.choice(["relu", "gelu"])), norm=str(rng.choice(["post", "pre"])),
+        causal=bool(rng.integers(0, 2)), len_lo=20, len_hi=150)
+    inp = make_inputs(cfg, seed=4000 + k, nontrivial=True)
+    dropout = (0.1, 0.1, 5 + k) if k % 4 == 0 else None
+    check_against_oracle(cfg, inp, _tol(cfg), dropout=dropout)
+
+
 @pytest.mark.parametrize("k", range(60))
 def test_random_shapes_types_and_options(k):
     """A seeded sweep across head sizes (all multiples of 16 up to 128), ragged token counts, both types,
