@@ -157,6 +157,39 @@ def test_gemm_backward_epilogue(dtype, dact):
     assert rel_err(to_np(dC), ref) <= _tol(dtype)
 
 
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9])
+def test_gemm_epilogues_on_every_pipelined_variant(variant):
+    """Bias, pre-activation copy, GELU and residual (forward form), and skip + GELU' (backward form), through
+    the staged epilogue of every tile shape of the pipelined kernel; ragged M and N, several tiles."""
+    b = _lib()
+    M, N, K = 520, 392, 128
+    rng = np.random.default_rng(40 + variant)
+    x = quantise(rng.standard_normal((M, K)), "bf16")
+    W = quantise(rng.standard_normal((N, K)) * 0.2, "bf16")
+    bias = quantise(rng.standard_normal(N), "bf16")
+    res = quantise(rng.standard_normal((M, N)), "bf16")
+    u_saved = quantise(rng.standard_normal((M, N)), "bf16")
+    u = orc.linear_fwd(x, W, bias)
+    ref_fwd = orc.act_fwd(u, "gelu") + res
+    ref_bwd = orc.act_bwd(x.astype(np.float64) @ W.astype(np.float64).T + res, u_saved, "gelu")
+    tx, tW, tb, tr, tu = (to_dev(a, "bf16") for a in (x, W, bias, res, u_saved))
+    b.lib().fl_test_gemm_force_variant(variant)
+    try:
+        dC, dU = empty_dev((M, N), "bf16"), empty_dev((M, N), "bf16")
+        b.check(b.lib().fl_test_gemm(1, 1, 1, tx.data_ptr(), tW.data_ptr(), dC.data_ptr(), M, N, K, tb.data_ptr(),
+                                     tr.data_ptr(), 2, dU.data_ptr(), 0, None, 1, None, stream_ptr()))
+        torch_mod().cuda.synchronize()
+        assert rel_err(to_np(dC), ref_fwd) <= BF16_KERNEL_TOL, variant
+        assert rel_err(to_np(dU), u) <= BF16_KERNEL_TOL, variant
+        dC = empty_dev((M, N), "bf16")
+        b.check(b.lib().fl_test_gemm(1, 1, 1, tx.data_ptr(), tW.data_ptr(), dC.data_ptr(), M, N, K, None,
+                                     tr.data_ptr(), 0, None, 2, tu.data_ptr(), 1, None, stream_ptr()))
+        torch_mod().cuda.synchronize()
+        assert rel_err(to_np(dC), ref_bwd) <= BF16_KERNEL_TOL, variant
+    finally:
+        b.lib().fl_test_gemm_force_variant(-1)
+
+
 def test_gemm_rejects_bad_shapes():
     b = _lib()
     d = empty_dev((64 * 64,), "f32")
