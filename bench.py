@@ -58,6 +58,23 @@ def copy_run(b, torch, stream, launches: int):
     return 2.0 * COPY_BYTES * launches / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
+def mfma_probe_run(b, torch, stream, dtype: str, launches: int = 3):
+    """TFLOP/s of an MFMA-only loop (operands in registers) of the workload's type on this GPU."""
+    import ctypes
+    wgs, iters = 256 * 16, 1000 if dtype == "bf16" else 250   # four wavefronts per SIMD, about 2 ms per launch
+    sink = torch.empty(wgs * 256, dtype=torch.float32, device="cuda")
+    flops = ctypes.c_double(0.0)
+    dt = b.FL_BF16 if dtype == "bf16" else b.FL_F32
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    b.check(b.lib().fl_test_mfma_probe(dt, wgs, iters, sink.data_ptr(), ctypes.byref(flops), stream))
+    e0.record()
+    for _ in range(launches):
+        b.check(b.lib().fl_test_mfma_probe(dt, wgs, iters, sink.data_ptr(), ctypes.byref(flops), stream))
+    e1.record()
+    torch.cuda.synchronize()
+    return flops.value * launches / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -204,6 +221,11 @@ def main() -> int:
         out["roofline"] = roof
         out["kernels"] = kernels
         out["hbm_copy_gbs"] = copy_run(b, torch, stream, 10)   # what a plain copy reaches on this GPU
+        out["mfma_probe_tflops"] = mfma_probe_run(b, torch, stream, cfg.dtype)   # and an MFMA-only loop
+        # the same fraction against what the probes reach on this GPU (the datasheet peak stays in `frac`)
+        measured = out["mfma_probe_tflops"] if roof["bound"] == "mfma" else out["hbm_copy_gbs"]
+        roof["peak_measured"] = measured
+        roof["frac_of_measured"] = roof["achieved"] / measured
 
     # ---- the fused optimizer step (NOT part of `value`: the metric is the layer's forward + backward)
     if not a.no_kernel_timing:

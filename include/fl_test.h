@@ -62,6 +62,12 @@ int32_t fl_test_colsum(int32_t dtype, const void *in, int32_t M, int32_t N, floa
  * written), against which the HBM byte counters are calibrated and copy bandwidth is measured. */
 int32_t fl_test_copy(const void *src, void *dst, uint64_t nbytes, void *hip_stream);
 
+/* Matrix-core ceiling of this GPU: `workgroups` x 4 wavefronts issue iters x 8 independent 32x32 MFMAs of
+ * `dtype` (fl_dtype_t) on register operands.  out: device, workgroups * 256 floats (written, content
+ * irrelevant); *flops: host, receives the floating-point operations one launch performs (may be NULL).
+ * The caller times the launch; the benchmark reports the rate beside the datasheet peak. */
+int32_t fl_test_mfma_probe(int32_t dtype, int32_t workgroups, int32_t iters, float *out, double *flops, void *hip_stream);
+
 /* dst[j] [cols[j], rows[j]] = transpose of src[j] [rows[j], cols[j]] for j < n <= 4: row-major bf16
  * device matrices, sizes multiples of 8, 16-byte aligned, no overlap; src/dst/rows/cols are HOST arrays.
  * The kernel that makes the layer's transposed weight copies. */

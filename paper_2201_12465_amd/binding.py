@@ -114,6 +114,7 @@ def lib() -> C.CDLL:
             "fl_test_layernorm_bwd_ws_floats": (i32, [i32, i32]),
             "fl_test_layernorm_bwd": (i32, [i32, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp]),
             "fl_test_copy": (i32, [vp, vp, u64, vp]),
+            "fl_test_mfma_probe": (i32, [i32, i32, i32, vp, C.POINTER(C.c_double), vp]),
             "fl_test_gemm_variant": (i32, [i32, i32, i32, i32, i32]),
             "fl_test_gemm_f32_small": (i32, [i32, i32]),
             "fl_test_attention_path": (i32, [i32, i32]),

@@ -75,6 +75,10 @@ hipError_t launch_dropout_mul(int dt, const void *in, void *out, int M, int N, c
 // dst[0..nbytes) = src[0..nbytes): nbytes % 16 == 0, both pointers 16-byte aligned.
 hipError_t launch_copy(const void *src, void *dst, size_t nbytes, hipStream_t stream);
 
+// `workgroups` x 4 wavefronts each issue iters x 8 independent 32x32 MFMAs of type dt on register operands;
+// out receives workgroups * 256 floats; *flops (host, may be null) = the floating-point operations launched.
+hipError_t launch_mfma_probe(int dt, int workgroups, int iters, float *out, double *flops, hipStream_t stream);
+
 // ---------------------------------------------------------------------------
 // LayerNorm over the last dimension D of x[M,D] (biased variance, eps inside the
 // square root).  Forward writes y and the per-row mean / reciprocal std (fp32).

@@ -169,4 +169,44 @@ hipError_t launch_copy(const void *src, void *dst, size_t nbytes, hipStream_t st
   return hipGetLastError();
 }
 
+// Matrix-core ceiling of the GPU this runs on: every wavefront issues `iters` rounds of eight independent
+// 32x32 MFMAs (bf16: k = 16, fp32: k = 2) on operands that stay in registers, so nothing but the MFMA
+// pipes limits it.  One float per thread is written so that the loop cannot be dropped.
+namespace {
+constexpr int PROBE_MFMAS = 8;
+template <bool BF16> __global__ __launch_bounds__(256) void mfma_probe_kernel(int iters, float *out) {
+  f32x16_t acc[PROBE_MFMAS];
+#pragma unroll
+  for (int j = 0; j < PROBE_MFMAS; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+  const float seed = 1.f / (float)(1 + (threadIdx.x & 63));
+  bf16x8_t a8, b8;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) a8[e] = (__bf16)(seed + (float)e * 0.125f), b8[e] = (__bf16)(0.5f - seed);
+  const float a1 = seed, b1 = 0.5f - seed;
+  for (int i = 0; i < iters; ++i) {
+#pragma unroll
+    for (int j = 0; j < PROBE_MFMAS; ++j) {
+      if constexpr (BF16) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a8, b8, acc[j], 0, 0, 0);
+      else acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[j], 0, 0, 0);
+    }
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int j = 0; j < PROBE_MFMAS; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sum += acc[j][r];
+  out[(size_t)blockIdx.x * 256 + threadIdx.x] = sum;
+}
+}  // namespace
+
+hipError_t launch_mfma_probe(int dt, int workgroups, int iters, float *out, double *flops, hipStream_t stream) {
+  if (workgroups < 1 || workgroups > (1 << 20) || iters < 1 || !out) return hipErrorInvalidValue;
+  if (dt == DT_BF16) mfma_probe_kernel<true><<<workgroups, 256, 0, stream>>>(iters, out);
+  else mfma_probe_kernel<false><<<workgroups, 256, 0, stream>>>(iters, out);
+  if (flops) *flops = (double)workgroups * 4 * iters * PROBE_MFMAS * 2.0 * 32 * 32 * (dt == DT_BF16 ? 16 : 2);
+  return hipGetLastError();
+}
+
 }  // namespace fl

@@ -129,6 +129,12 @@ int32_t fl_test_copy(const void *src, void *dst, uint64_t nbytes, void *hip_stre
   return hip_status(launch_copy(src, dst, (size_t)nbytes, static_cast<hipStream_t>(hip_stream)), "launch_copy");
 }
 
+int32_t fl_test_mfma_probe(int32_t dtype, int32_t workgroups, int32_t iters, float *out, double *flops, void *hip_stream) {
+  if (dtype != DT_F32 && dtype != DT_BF16) return set_error(FL_ERR_INVALID_ARG, "fl_test_mfma_probe: unknown dtype %d", dtype);
+  return hip_status(launch_mfma_probe(dtype, workgroups, iters, out, flops, static_cast<hipStream_t>(hip_stream)),
+                    "launch_mfma_probe");
+}
+
 int32_t fl_test_transpose_bf16(int32_t n, const void *const *src, void *const *dst, const int32_t *rows,
                                const int32_t *cols, void *hip_stream) {
   return hip_status(launch_transpose_bf16(n, src, dst, rows, cols, static_cast<hipStream_t>(hip_stream)),

@@ -190,6 +190,22 @@ def test_gemm_epilogues_on_every_pipelined_variant(variant):
         b.lib().fl_test_gemm_force_variant(-1)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_mfma_probe_runs_and_reports_its_work(dtype):
+    """The MFMA-only loop behind the benchmark's measured matrix-core ceiling: it runs, writes every output
+    and reports the operations it launched."""
+    import ctypes
+    b = _lib()
+    wgs, iters = 64, 10
+    out = torch_mod().full((wgs * 256,), float("nan"), dtype=torch_mod().float32, device="cuda")
+    flops = ctypes.c_double(0.0)
+    b.check(b.lib().fl_test_mfma_probe(dt_code(dtype), wgs, iters, out.data_ptr(), ctypes.byref(flops), stream_ptr()))
+    torch_mod().cuda.synchronize()
+    assert bool(torch_mod().isfinite(out).all())
+    assert flops.value == wgs * 4 * iters * 8 * 2.0 * 32 * 32 * (16 if dtype == "bf16" else 2)
+    assert b.lib().fl_test_mfma_probe(dt_code(dtype), 0, iters, out.data_ptr(), None, stream_ptr()) != 0
+
+
 def test_gemm_rejects_bad_shapes():
     b = _lib()
     d = empty_dev((64 * 64,), "f32")
