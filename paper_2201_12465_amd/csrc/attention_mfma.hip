@@ -36,6 +36,7 @@ constexpr int NT = 256;        // threads per workgroup (4 wavefronts)
 constexpr int ROWS_WG = 128;   // rows owned by a workgroup (32 per wavefront)
 constexpr int TILE = 64;       // rows of the walked dimension per LDS tile
 constexpr float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;
+constexpr float RESCALE_SLACK = 8.f;  // see attn_fwd_mfma
 
 // Row stride (elements) of a tile read with 16-byte row-fragment loads: 16 bytes of padding.
 constexpr int kc_stride(int dh) { return dh + 8; }
@@ -74,6 +75,16 @@ __device__ __forceinline__ bf16x8_t g_frag(const bf16_t *row, int kk, int lane, 
   if (!row || kk * 16 >= dh) return zero_frag();   // dh is a multiple of 16: both lane halves agree
   return *reinterpret_cast<const bf16x8_t *>(row + kk * 16 + (lane >> 5) * 8);
 }
+
+// Marks the point by which two fragments must be in registers.  Placed after a run of LDS reads it keeps
+// the compiler from sinking each read to just in front of the MFMA that uses it (which it does under
+// register pressure, and which makes every MFMA wait out an LDS round trip of its own).
+__device__ __forceinline__ void keep_requested(bf16x8_t &a, bf16x8_t &b) { asm volatile("" : "+v"(a), "+v"(b)); }
+
+// 2^x as the bare v_exp_f32: the arguments here are at most RESCALE_SLACK and results below the smallest
+// normal number may become 0 (probabilities under 1e-38), so the library function's range handling
+// (four more instructions per value) buys nothing.
+__device__ __forceinline__ float exp2_raw(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // registers 8s..8s+7 of a score block, rounded to bf16: the B operand of the next MFMA
 __device__ __forceinline__ bf16x8_t pack8(const f32x16_t &v, int s) {
@@ -133,6 +144,10 @@ __global__ __launch_bounds__(NT, fwd_waves(DH, DROP)) void attn_fwd_mfma(const b
                                                     DropSpec drop, int Tn, int H, int dh, float scale,
                                                     bf16_t *__restrict__ o, float *__restrict__ lse) {
   constexpr int KS = kc_stride(DH), VS = tr_stride(DH), NK = DH / 16, NB = DH / 32;
+  // K fragments in flight at one time (4 registers each); small heads run several wavefronts per SIMD
+  // instead and have no registers to spare
+  constexpr int KBATCH = DH <= 64 ? 1 : NK > 8 ? NK / 2 : NK;
+  constexpr bool LAZY = DH > 64;   // rescale the output accumulators only when a row's reference maximum moves
   __shared__ __attribute__((aligned(16))) bf16_t sK[TILE * KS];
   __shared__ __attribute__((aligned(16))) bf16_t sV[TILE * VS];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5;
@@ -177,9 +192,16 @@ __global__ __launch_bounds__(NT, fwd_waves(DH, DROP)) void attn_fwd_mfma(const b
       f32x16_t s;
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = 0.f;
+      // The K fragments are requested in batches ahead of the MFMAs that consume them: one at a time,
+      // every MFMA of the chain would wait out an LDS round trip of its own.
 #pragma unroll
-      for (int kk = 0; kk < NK; ++kk)
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc_frag(sK, KS, kb * 32, kk, lane), qf[kk], s, 0, 0, 0);
+      for (int kh = 0; kh < NK; kh += KBATCH) {
+        bf16x8_t kf[KBATCH];
+#pragma unroll
+        for (int kk = 0; kk < KBATCH; ++kk) kf[kk] = kc_frag(sK, KS, kb * 32, kh + kk, lane);
+#pragma unroll
+        for (int kk = 0; kk < KBATCH; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kh + kk], s, 0, 0, 0);
+      }
       float mloc = -INFINITY;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -188,15 +210,22 @@ __global__ __launch_bounds__(NT, fwd_waves(DH, DROP)) void attn_fwd_mfma(const b
         mloc = fmaxf(mloc, s[r]);
       }
       mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
-      const float mnew = fmaxf(m, mloc);
+      // The reference maximum m moves only when a block's maximum exceeds it by more than RESCALE_SLACK
+      // (in units of log2): probabilities are then at most 2^RESCALE_SLACK instead of 1, which changes
+      // neither O / l nor the log-sum-exp, and the accumulators are rescaled only in the blocks where some
+      // row's reference moved (the first block, and rarely again) instead of in every block.
+      // Heads up to 64 keep the plain rule (32 multiplications per block, and no registers for this).
+      const bool moved = !LAZY || mloc > m + RESCALE_SLACK;   // first block: m = -inf
+      const float mnew = LAZY ? (moved ? mloc : m) : fmaxf(m, mloc);
       float rs = 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        s[r] = exp2f(s[r] - mnew);
+        s[r] = exp2_raw(s[r] - mnew);
         rs += s[r];
       }
       rs += __shfl_xor(rs, 32, 64);
-      const float corr = exp2f(m - mnew);
+      const bool rescale = !LAZY || __any(moved);    // wave-uniform
+      const float corr = (LAZY && !moved) ? 1.f : exp2_raw(m - mnew);
       l = l * corr + rs;   // the softmax denominator ignores dropout
       m = mnew;
       if constexpr (DROP) {  // registers 4g..4g+3 hold four consecutive keys: one generator call
@@ -209,10 +238,14 @@ __global__ __launch_bounds__(NT, fwd_waves(DH, DROP)) void attn_fwd_mfma(const b
         }
       }
       bf16x8_t pf[2] = {pack8(s, 0), pack8(s, 1)};
+      if (rescale) {
+#pragma unroll
+        for (int db = 0; db < NB; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[db][r] *= corr;
+      }
 #pragma unroll
       for (int db = 0; db < NB; ++db) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[db][r] *= corr;
 #pragma unroll
         for (int st = 0; st < 2; ++st)
           oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(sV, VS, db * 32, kb * 32 + 16 * st, lane),
@@ -247,6 +280,9 @@ __global__ __launch_bounds__(NT, dq_waves(DH, DROP)) void attn_bwd_dq_mfma(const
   __shared__ __attribute__((aligned(16))) bf16_t sK[TILE * KS];   // K rows for S^T = K Q^T
   __shared__ __attribute__((aligned(16))) bf16_t sKt[TILE * TS];  // K again, for K^T in dQ^T = K^T dS^T
   __shared__ __attribute__((aligned(16))) bf16_t sV[TILE * KS];   // V rows for dP^T = V dO^T
+  constexpr int KBATCH = DH <= 64 ? 1 : DH <= 128 ? 2 : NK % 3 == 0 ? 3 : 4;   // K and V fragments in flight (8 registers per step)
+  constexpr int TBATCH = DH <= 64 ? 1 : NB % 3 == 0 ? 3 : 2;   // K^T fragment pairs in flight
+  static_assert(NK % KBATCH == 0 && NB % TBATCH == 0, "batches must divide the head size");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5;
   const int b = blockIdx.z, hd = blockIdx.y;
   const int D = H * dh;
@@ -299,10 +335,24 @@ __global__ __launch_bounds__(NT, dq_waves(DH, DROP)) void attn_bwd_dq_mfma(const
       f32x16_t s, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = 0.f, dp[r] = 0.f;
+      // fragments are requested in batches ahead of the MFMAs (see the forward kernel)
 #pragma unroll
-      for (int kk = 0; kk < NK; ++kk) {
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc_frag(sK, KS, kb * 32, kk, lane), qf[kk], s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc_frag(sV, KS, kb * 32, kk, lane), dof[kk], dp, 0, 0, 0);
+      for (int kh = 0; kh < NK; kh += KBATCH) {
+        bf16x8_t kfr[KBATCH], vfr[KBATCH];
+#pragma unroll
+        for (int kk = 0; kk < KBATCH; ++kk) {
+          kfr[kk] = kc_frag(sK, KS, kb * 32, kh + kk, lane);
+          vfr[kk] = kc_frag(sV, KS, kb * 32, kh + kk, lane);
+        }
+        if constexpr (KBATCH > 1) {
+#pragma unroll
+          for (int kk = 0; kk < KBATCH; ++kk) keep_requested(kfr[kk], vfr[kk]);
+        }
+#pragma unroll
+        for (int kk = 0; kk < KBATCH; ++kk) {
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[kk], qf[kh + kk], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[kk], dof[kh + kk], dp, 0, 0, 0);
+        }
       }
       if constexpr (DROP) {  // dP = (dO V^T) * keep
 #pragma unroll
@@ -316,16 +366,23 @@ __global__ __launch_bounds__(NT, dq_waves(DH, DROP)) void attn_bwd_dq_mfma(const
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int key = k0 + kb * 32 + acc_row(r, h2);
-        const float p = (key < len && (!CAUSAL || key <= q)) ? exp2f(s[r] * c - L2) : 0.f;
+        const float p = (key < len && (!CAUSAL || key <= q)) ? exp2_raw(s[r] * c - L2) : 0.f;
         s[r] = p * (dp[r] - dl);   // dS^T
       }
       bf16x8_t dsf[2] = {pack8(s, 0), pack8(s, 1)};
 #pragma unroll
-      for (int db = 0; db < NB; ++db)
+      for (int d0 = 0; d0 < NB; d0 += TBATCH) {
+        bf16x8_t tf[TBATCH][2];
 #pragma unroll
-        for (int st = 0; st < 2; ++st)
-          acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(sKt, TS, db * 32, kb * 32 + 16 * st, lane),
-                                                            dsf[st], acc[db], 0, 0, 0);
+        for (int db = 0; db < TBATCH; ++db)
+#pragma unroll
+          for (int st = 0; st < 2; ++st) tf[db][st] = tr_frag(sKt, TS, (d0 + db) * 32, kb * 32 + 16 * st, lane);
+#pragma unroll
+        for (int db = 0; db < TBATCH; ++db)
+#pragma unroll
+          for (int st = 0; st < 2; ++st)
+            acc[d0 + db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[db][st], dsf[st], acc[d0 + db], 0, 0, 0);
+      }
     }
   }
   if (qok) {
@@ -360,6 +417,9 @@ __global__ __launch_bounds__(NT, dkv_waves(DH)) void attn_bwd_dkv_mfma(const bf1
   bf16_t *sDOt = sDO + TILE * KS;                      // dO again, for dO^T in dV^T = dO^T P
   float *sL = reinterpret_cast<float *>(sDOt + TILE * TS);  // lse*log2(e) of the tile's queries
   float *sDl = sL + TILE;                                   // delta of the tile's queries
+  constexpr int KBATCH = DH <= 64 ? 1 : 2;   // Q and dO fragments in flight (8 registers per step)
+  constexpr int TBATCH = DH <= 64 ? 1 : NB % 3 == 0 ? 3 : 2;   // transposed dO / Q fragment pairs in flight
+  static_assert(NK % KBATCH == 0 && NB % TBATCH == 0, "batches must divide the head size");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5;
   const int b = blockIdx.z, hd = blockIdx.y;
   const int D = H * dh;
@@ -426,16 +486,29 @@ __global__ __launch_bounds__(NT, dkv_waves(DH)) void attn_bwd_dkv_mfma(const bf1
       f32x16_t s, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = 0.f, dp[r] = 0.f;
+      // fragments are requested in batches ahead of the MFMAs (see the forward kernel)
 #pragma unroll
-      for (int kk = 0; kk < NK; ++kk) {
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc_frag(sQ, KS, qb * 32, kk, lane), kf[kk], s, 0, 0, 0);
-        if (DO_DK)
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc_frag(sDO, KS, qb * 32, kk, lane), vf[kk], dp, 0, 0, 0);
+      for (int kh = 0; kh < NK; kh += KBATCH) {
+        bf16x8_t qfr[KBATCH], dofr[KBATCH];
+#pragma unroll
+        for (int kk = 0; kk < KBATCH; ++kk) {
+          qfr[kk] = kc_frag(sQ, KS, qb * 32, kh + kk, lane);
+          dofr[kk] = DO_DK ? kc_frag(sDO, KS, qb * 32, kh + kk, lane) : qfr[kk];
+        }
+        if constexpr (KBATCH > 1) {
+#pragma unroll
+          for (int kk = 0; kk < KBATCH; ++kk) keep_requested(qfr[kk], dofr[kk]);
+        }
+#pragma unroll
+        for (int kk = 0; kk < KBATCH; ++kk) {
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfr[kk], kf[kh + kk], s, 0, 0, 0);
+          if (DO_DK) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dofr[kk], vf[kh + kk], dp, 0, 0, 0);
+        }
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int qi = qb * 32 + acc_row(r, h2);
-        const float p = (live && (!CAUSAL || q0 + qi >= key)) ? exp2f(s[r] * c - sL[qi]) : 0.f;
+        const float p = (live && (!CAUSAL || q0 + qi >= key)) ? exp2_raw(s[r] * c - sL[qi]) : 0.f;
         float keep = 1.f;   // this lane's key against sixteen different queries: one generator call each
         if constexpr (DROP) keep = drop_keep1(drop, (uint32_t)key, (uint32_t)(q0 + qi), (uint32_t)(b * H + hd));
         if constexpr (DO_DK) dp[r] = p * (dp[r] * keep - sDl[qi]);   // dS
@@ -444,20 +517,42 @@ __global__ __launch_bounds__(NT, dkv_waves(DH)) void attn_bwd_dkv_mfma(const bf1
       if constexpr (DO_DV) {
         bf16x8_t pf[2] = {pack8(s, 0), pack8(s, 1)};
 #pragma unroll
-        for (int db = 0; db < NB; ++db)
+        for (int d0 = 0; d0 < NB; d0 += TBATCH) {
+          bf16x8_t tf[TBATCH][2];
 #pragma unroll
-          for (int st = 0; st < 2; ++st)
-            dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(sDOt, TS, db * 32, qb * 32 + 16 * st, lane),
-                                                             pf[st], dv[db], 0, 0, 0);
+          for (int db = 0; db < TBATCH; ++db)
+#pragma unroll
+            for (int st = 0; st < 2; ++st) tf[db][st] = tr_frag(sDOt, TS, (d0 + db) * 32, qb * 32 + 16 * st, lane);
+          if constexpr (TBATCH > 1) {
+#pragma unroll
+            for (int db = 0; db < TBATCH; ++db) keep_requested(tf[db][0], tf[db][1]);
+          }
+#pragma unroll
+          for (int db = 0; db < TBATCH; ++db)
+#pragma unroll
+            for (int st = 0; st < 2; ++st)
+              dv[d0 + db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[db][st], pf[st], dv[d0 + db], 0, 0, 0);
+        }
       }
       if constexpr (DO_DK) {
         bf16x8_t dsf[2] = {pack8(dp, 0), pack8(dp, 1)};
 #pragma unroll
-        for (int db = 0; db < NB; ++db)
+        for (int d0 = 0; d0 < NB; d0 += TBATCH) {
+          bf16x8_t tf[TBATCH][2];
 #pragma unroll
-          for (int st = 0; st < 2; ++st)
-            dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(sQt, TS, db * 32, qb * 32 + 16 * st, lane),
-                                                             dsf[st], dk[db], 0, 0, 0);
+          for (int db = 0; db < TBATCH; ++db)
+#pragma unroll
+            for (int st = 0; st < 2; ++st) tf[db][st] = tr_frag(sQt, TS, (d0 + db) * 32, qb * 32 + 16 * st, lane);
+          if constexpr (TBATCH > 1) {
+#pragma unroll
+            for (int db = 0; db < TBATCH; ++db) keep_requested(tf[db][0], tf[db][1]);
+          }
+#pragma unroll
+          for (int db = 0; db < TBATCH; ++db)
+#pragma unroll
+            for (int st = 0; st < 2; ++st)
+              dk[d0 + db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[db][st], dsf[st], dk[d0 + db], 0, 0, 0);
+        }
       }
     }
   }
