@@ -80,6 +80,8 @@ __device__ __forceinline__ bf16x8_t g_frag(const bf16_t *row, int kk, int lane, 
 // the compiler from sinking each read to just in front of the MFMA that uses it (which it does under
 // register pressure, and which makes every MFMA wait out an LDS round trip of its own).
 __device__ __forceinline__ void keep_requested(bf16x8_t &a, bf16x8_t &b) { asm volatile("" : "+v"(a), "+v"(b)); }
+// Memory operations written before this point are issued before it: LDS reads requested early stay early.
+__device__ __forceinline__ void issue_fence() { asm volatile("" ::: "memory"); }
 
 // 2^x as the bare v_exp_f32: the arguments here are at most RESCALE_SLACK and results below the smallest
 // normal number may become 0 (probabilities under 1e-38), so the library function's range handling
@@ -146,8 +148,11 @@ __global__ __launch_bounds__(NT, fwd_waves(DH, DROP)) void attn_fwd_mfma(const b
   constexpr int KS = kc_stride(DH), VS = tr_stride(DH), NK = DH / 16, NB = DH / 32;
   // K fragments in flight at one time (4 registers each); small heads run several wavefronts per SIMD
   // instead and have no registers to spare
-  constexpr int KBATCH = DH <= 64 ? 1 : NK > 8 ? NK / 2 : NK;
+  constexpr int KBATCH = DH <= 64 ? 1 : DH > 192 ? NK / 2 : NK;
   constexpr bool LAZY = DH > 64;   // rescale the output accumulators only when a row's reference maximum moves
+  // V^T fragments requested BEFORE the softmax arithmetic of a block, so that their LDS round trip runs
+  // under it (48 registers at head size 192; the largest head has none to spare)
+  constexpr int VEARLY = DH <= 64 || DH > 192 ? 0 : NB;
   __shared__ __attribute__((aligned(16))) bf16_t sK[TILE * KS];
   __shared__ __attribute__((aligned(16))) bf16_t sV[TILE * VS];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5;
@@ -199,8 +204,20 @@ __global__ __launch_bounds__(NT, fwd_waves(DH, DROP)) void attn_fwd_mfma(const b
         bf16x8_t kf[KBATCH];
 #pragma unroll
         for (int kk = 0; kk < KBATCH; ++kk) kf[kk] = kc_frag(sK, KS, kb * 32, kh + kk, lane);
+        if constexpr (KBATCH > 1) {
+#pragma unroll
+          for (int kk = 0; kk < KBATCH; kk += 2) keep_requested(kf[kk], kf[kk + 1]);
+        }
 #pragma unroll
         for (int kk = 0; kk < KBATCH; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kh + kk], s, 0, 0, 0);
+      }
+      bf16x8_t vt[VEARLY ? VEARLY : 1][2];
+      if constexpr (VEARLY > 0) {
+#pragma unroll
+        for (int db = 0; db < VEARLY; ++db)
+#pragma unroll
+          for (int st = 0; st < 2; ++st) vt[db][st] = tr_frag(sV, VS, db * 32, kb * 32 + 16 * st, lane);
+        issue_fence();
       }
       float mloc = -INFINITY;
 #pragma unroll
@@ -244,12 +261,16 @@ __global__ __launch_bounds__(NT, fwd_waves(DH, DROP)) void attn_fwd_mfma(const b
 #pragma unroll
           for (int r = 0; r < 16; ++r) oacc[db][r] *= corr;
       }
+      if constexpr (VEARLY > 0) {
+#pragma unroll
+        for (int db = 0; db < VEARLY; ++db) keep_requested(vt[db][0], vt[db][1]);
+      }
 #pragma unroll
       for (int db = 0; db < NB; ++db) {
 #pragma unroll
         for (int st = 0; st < 2; ++st)
-          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(sV, VS, db * 32, kb * 32 + 16 * st, lane),
-                                                             pf[st], oacc[db], 0, 0, 0);
+          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              db < VEARLY ? vt[db][st] : tr_frag(sV, VS, db * 32, kb * 32 + 16 * st, lane), pf[st], oacc[db], 0, 0, 0);
       }
     }
   }
@@ -280,7 +301,7 @@ __global__ __launch_bounds__(NT, dq_waves(DH, DROP)) void attn_bwd_dq_mfma(const
   __shared__ __attribute__((aligned(16))) bf16_t sK[TILE * KS];   // K rows for S^T = K Q^T
   __shared__ __attribute__((aligned(16))) bf16_t sKt[TILE * TS];  // K again, for K^T in dQ^T = K^T dS^T
   __shared__ __attribute__((aligned(16))) bf16_t sV[TILE * KS];   // V rows for dP^T = V dO^T
-  constexpr int KBATCH = DH <= 64 ? 1 : DH <= 128 ? 2 : NK % 3 == 0 ? 3 : 4;   // K and V fragments in flight (8 registers per step)
+  constexpr int KBATCH = DH <= 64 ? 1 : DH <= 128 ? 2 : NK % 3 == 0 ? 6 : 4;   // K and V fragments in flight (8 registers per step)
   constexpr int TBATCH = DH <= 64 ? 1 : NB % 3 == 0 ? 3 : 2;   // K^T fragment pairs in flight
   static_assert(NK % KBATCH == 0 && NB % TBATCH == 0, "batches must divide the head size");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5;
@@ -354,6 +375,17 @@ __global__ __launch_bounds__(NT, dq_waves(DH, DROP)) void attn_bwd_dq_mfma(const
           dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[kk], dof[kh + kk], dp, 0, 0, 0);
         }
       }
+      // the first K^T fragments are requested before the dS arithmetic, so that their LDS round trip runs under it
+      // (not with dropout at the large heads: the mask generator needs the registers)
+      constexpr bool EARLY = TBATCH > 1 && !(DROP && DH >= 192);
+      bf16x8_t tf0[TBATCH][2];
+      if constexpr (EARLY) {
+#pragma unroll
+        for (int db = 0; db < TBATCH; ++db)
+#pragma unroll
+          for (int st = 0; st < 2; ++st) tf0[db][st] = tr_frag(sKt, TS, db * 32, kb * 32 + 16 * st, lane);
+        issue_fence();
+      }
       if constexpr (DROP) {  // dP = (dO V^T) * keep
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
@@ -376,7 +408,12 @@ __global__ __launch_bounds__(NT, dq_waves(DH, DROP)) void attn_bwd_dq_mfma(const
 #pragma unroll
         for (int db = 0; db < TBATCH; ++db)
 #pragma unroll
-          for (int st = 0; st < 2; ++st) tf[db][st] = tr_frag(sKt, TS, (d0 + db) * 32, kb * 32 + 16 * st, lane);
+          for (int st = 0; st < 2; ++st)
+            tf[db][st] = (EARLY && d0 == 0) ? tf0[db][st] : tr_frag(sKt, TS, (d0 + db) * 32, kb * 32 + 16 * st, lane);
+        if constexpr (TBATCH > 1) {
+#pragma unroll
+          for (int db = 0; db < TBATCH; ++db) keep_requested(tf[db][0], tf[db][1]);
+        }
 #pragma unroll
         for (int db = 0; db < TBATCH; ++db)
 #pragma unroll
@@ -418,7 +455,7 @@ __global__ __launch_bounds__(NT, dkv_waves(DH)) void attn_bwd_dkv_mfma(const bf1
   float *sL = reinterpret_cast<float *>(sDOt + TILE * TS);  // lse*log2(e) of the tile's queries
   float *sDl = sL + TILE;                                   // delta of the tile's queries
   constexpr int KBATCH = DH <= 64 ? 1 : 2;   // Q and dO fragments in flight (8 registers per step)
-  constexpr int TBATCH = DH <= 64 ? 1 : NB % 3 == 0 ? 3 : 2;   // transposed dO / Q fragment pairs in flight
+  constexpr int TBATCH = DH <= 64 ? 1 : (NB % 3 == 0 && DH < 192) ? 3 : 2;   // transposed dO / Q fragment pairs in flight
   static_assert(NK % KBATCH == 0 && NB % TBATCH == 0, "batches must divide the head size");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5;
   const int b = blockIdx.z, hd = blockIdx.y;
@@ -505,6 +542,17 @@ __global__ __launch_bounds__(NT, dkv_waves(DH)) void attn_bwd_dkv_mfma(const bf1
           if (DO_DK) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dofr[kk], vf[kh + kk], dp, 0, 0, 0);
         }
       }
+      // the first transposed fragments of the stage after the dS arithmetic are requested before it
+      constexpr bool EARLY = TBATCH > 1 && !DROP;
+      bf16x8_t tf0[TBATCH][2];
+      if constexpr (EARLY) {
+#pragma unroll
+        for (int db = 0; db < TBATCH; ++db)
+#pragma unroll
+          for (int st = 0; st < 2; ++st)
+            tf0[db][st] = tr_frag(DO_DV ? sDOt : sQt, TS, db * 32, qb * 32 + 16 * st, lane);
+        issue_fence();
+      }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int qi = qb * 32 + acc_row(r, h2);
@@ -522,7 +570,8 @@ __global__ __launch_bounds__(NT, dkv_waves(DH)) void attn_bwd_dkv_mfma(const bf1
 #pragma unroll
           for (int db = 0; db < TBATCH; ++db)
 #pragma unroll
-            for (int st = 0; st < 2; ++st) tf[db][st] = tr_frag(sDOt, TS, (d0 + db) * 32, qb * 32 + 16 * st, lane);
+            for (int st = 0; st < 2; ++st)
+              tf[db][st] = (EARLY && d0 == 0) ? tf0[db][st] : tr_frag(sDOt, TS, (d0 + db) * 32, qb * 32 + 16 * st, lane);
           if constexpr (TBATCH > 1) {
 #pragma unroll
             for (int db = 0; db < TBATCH; ++db) keep_requested(tf[db][0], tf[db][1]);
@@ -542,7 +591,8 @@ __global__ __launch_bounds__(NT, dkv_waves(DH)) void attn_bwd_dkv_mfma(const bf1
 #pragma unroll
           for (int db = 0; db < TBATCH; ++db)
 #pragma unroll
-            for (int st = 0; st < 2; ++st) tf[db][st] = tr_frag(sQt, TS, (d0 + db) * 32, qb * 32 + 16 * st, lane);
+            for (int st = 0; st < 2; ++st)
+              tf[db][st] = (EARLY && !DO_DV && d0 == 0) ? tf0[db][st] : tr_frag(sQt, TS, (d0 + db) * 32, qb * 32 + 16 * st, lane);
           if constexpr (TBATCH > 1) {
 #pragma unroll
             for (int db = 0; db < TBATCH; ++db) keep_requested(tf[db][0], tf[db][1]);
