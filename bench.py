@@ -87,6 +87,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="skip the second, event-instrumented pass (used under rocprofv3)")
+    ap.add_argument("--no-deferred-join", action="store_true",
+                    help="multi-layer workloads: every layer's backward joins the side stream before it returns")
     ap.add_argument("--no-grad-overlap", action="store_true",
                     help="run the parameter-gradient kernels in order on the main stream instead of beside "
                          "the input-gradient chain (every kernel then runs alone: the mode for kernel traces)")
@@ -144,7 +146,14 @@ def main() -> int:
             layers[l].forward(P[l], acts[l], L, cfg.B, cfg.T, acts[l + 1], stream)
         for l in reversed(range(nl)):
             layers[l].backward(P[l], grads[l + 1], grads[l], G[l], stream)
+        if deferred:   # the parameter gradients of the whole stack are complete after these
+            for l in range(nl):
+                layers[l].join(stream)
 
+    # a stack joins its layers' side-stream work once, after the last backward, instead of after every layer
+    deferred = nl > 1 and not a.no_deferred_join
+    for ly in layers:
+        ly.set_deferred_join(deferred)
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()

@@ -157,6 +157,20 @@ const char *fl_last_error(void);
  * and replays reproduce the eager results bit for bit.  Timing (fl_prof_enable) must be off. */
 fl_status_t fl_set_grad_overlap(int32_t enabled);
 
+/* Deferred join, for stacks of layers (Section 4.2: a model is a sequence of modules whose backward
+ * passes run one after the other).  With it enabled (non-zero; default 0) fl_layer_backward no longer
+ * makes the caller's stream wait for the side stream before it returns: dX is complete in stream order
+ * as always (the input-gradient chain never leaves the caller's stream), so the backward pass of the
+ * layer below can start while this layer's last parameter-gradient kernels still run, but the buffers
+ * in `grads` are complete only after fl_layer_join(layer, stream), which makes `stream` (and the stream
+ * the layer ran on) wait for them.  The next fl_layer_forward on the handle and fl_layer_destroy join
+ * by themselves.  Until the join, the layer keeps the activations its side-stream kernels read.
+ * Without a side stream (small problems, fl_set_grad_overlap(0)) nothing is deferred and the join is a
+ * no-op.  Results are bit-identical either way.  Do not enable it under graph capture unless the
+ * captured region contains the join. */
+fl_status_t fl_layer_set_deferred_join(fl_layer_t *layer, int32_t enabled);
+fl_status_t fl_layer_join(fl_layer_t *layer, void *hip_stream);
+
 /* Caching device allocator telemetry (Section 4.1.2; Section 5.2.2 describes
  * size-bucketed caches, block splitting and allocation telemetry).
  * backing_mallocs / backing_bytes: calls to and bytes obtained from the device

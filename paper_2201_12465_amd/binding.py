@@ -102,6 +102,8 @@ def lib() -> C.CDLL:
             "fl_alloc_trace_read": (C.c_int, [C.POINTER(fl_alloc_event_t), i32, C.POINTER(i32)]),
             "fl_set_grad_overlap": (C.c_int, [i32]),
             "fl_alloc_trim": (C.c_int, []),
+            "fl_layer_set_deferred_join": (C.c_int, [vp, i32]),
+            "fl_layer_join": (C.c_int, [vp, vp]),
             "fl_alloc_set_split_limit": (C.c_int, [u64]),
             "fl_prof_enable": (C.c_int, [C.c_uint32]),
             "fl_prof_collect": (C.c_int, [C.POINTER(fl_prof_entry_t), i32, C.POINTER(i32)]),
@@ -191,6 +193,12 @@ class Layer:
             check(lib().fl_layer_backward_accumulate(self._h, C.byref(p), ptr(dY), ptr(dX), C.byref(g), 1, stream))
         else:
             check(lib().fl_layer_backward(self._h, C.byref(p), ptr(dY), ptr(dX), C.byref(g), stream))
+
+    def set_deferred_join(self, enabled: bool) -> None:
+        check(lib().fl_layer_set_deferred_join(self._h, 1 if enabled else 0))
+
+    def join(self, stream: int = 0) -> None:
+        check(lib().fl_layer_join(self._h, stream))
 
     def destroy(self) -> None:
         if self._h:

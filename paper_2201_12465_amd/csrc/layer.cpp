@@ -142,6 +142,8 @@ struct fl_layer {
   hipEvent_t join_event = nullptr;
   hipEvent_t attn_join_event = nullptr;  // dK/dV kernels on the second side stream -> layer's stream
   std::vector<Buf *> held;             // buffers the side stream reads: released after the join
+  bool defer_join = false;             // backward leaves the join to fl_layer_join() / the next call on the layer
+  bool join_pending = false;           // a backward has ended without the join: join_event marks its side-stream work
   // Transposed copies of Wqkv, Wo, W1, W2 (in kLinear order), made by forward for the input-gradient
   // GEMMs of its backward; see wt_make(), wt_acquire(), wt_release().
   Buf *wt[4] = {nullptr, nullptr, nullptr, nullptr};
@@ -264,8 +266,21 @@ void side_hold(fl_layer *L, Buf *b) {
 }
 // The layer's stream waits for the side stream; afterwards the held buffers may be reused.
 // wait_host: on an error path, where the order of what was enqueued is no longer known.
-int side_join(fl_layer *L, bool wait_host) {
+int side_join(fl_layer *L, bool wait_host, bool defer = false) {
   int rc = 0;
+  if (defer && !wait_host && L->side && L->forks) {
+    // Only mark the end of this backward's side-stream work; the held buffers stay held until
+    // finish_pending_join().  (A failure to record falls through to the immediate join.)
+    hipError_t e = hipSuccess;
+    if (!L->join_event) e = hipEventCreateWithFlags(&L->join_event, kEventFlags);
+    if (e == hipSuccess) e = hipEventRecord(L->join_event, L->side);
+    if (e == hipSuccess) {
+      L->join_pending = true;
+      L->forks = 0;
+      L->side = nullptr;
+      return 0;
+    }
+  }
   if (L->side && L->forks) {
     if (wait_host) {
       hipStreamSynchronize(L->side);
@@ -284,6 +299,25 @@ int side_join(fl_layer *L, bool wait_host) {
   L->held.clear();
   L->forks = 0;
   L->side = nullptr;
+  return rc;
+}
+
+// Completes a join that backward left open: the layer's stream (whose cache the held buffers return to)
+// waits for the marked point of the side stream, and so does `also` when it is another stream; with
+// wait_host the host waits instead (destroy, error paths).
+int finish_pending_join(fl_layer *L, hipStream_t also, bool wait_host) {
+  int rc = 0;
+  if (L->join_pending) {
+    hipError_t e = wait_host ? hipEventSynchronize(L->join_event) : hipStreamWaitEvent(L->stream, L->join_event, 0);
+    if (e == hipSuccess && !wait_host && also != L->stream) e = hipStreamWaitEvent(also, L->join_event, 0);
+    if (e != hipSuccess) {
+      hipStreamSynchronize(side_stream());
+      rc = set_error(FL_ERR_DEVICE, "joining the side stream failed: %s", hipGetErrorString(e));
+    }
+    L->join_pending = false;
+  }
+  for (Buf *&b : L->held) buf_unref(b);
+  L->held.clear();
   return rc;
 }
 
@@ -812,6 +846,7 @@ int forward_impl(fl_layer *L, const fl_layer_params_t *params, const void *X, co
   FL_TRY(check_ptrs(L->params, P_COUNT, "params"));
   const void *io[2] = {X, Y};
   FL_TRY(check_ptrs(io, 2, "X/Y"));
+  FL_TRY(finish_pending_join(L, st, false));
   release_tape(L);
   L->B = B; L->T = T; L->M = B * T; L->stream = st; L->lengths = lengths;
   L->rec_p_attn = L->p_attn; L->rec_p_hidden = L->p_hidden; L->rec_seed = L->seed;
@@ -867,7 +902,7 @@ int backward_impl(fl_layer *L, const fl_layer_params_t *params, const void *dY, 
   L->forks = 0;
   int rc = tp.replay_reverse(L);
   const bool landed = rc == 0 && tp.slots[L->slot_x].grad == dX;
-  const int jrc = side_join(L, rc != 0);
+  const int jrc = side_join(L, rc != 0, L->defer_join);
   release_tape(L);
   if (rc) return rc;
   if (jrc) return jrc;
@@ -952,6 +987,21 @@ fl_status_t fl_layer_backward_accumulate(fl_layer_t *layer, const fl_layer_param
   FL_GUARD_END
 }
 
+fl_status_t fl_layer_set_deferred_join(fl_layer_t *layer, int32_t enabled) {
+  FL_GUARD_BEGIN
+  if (!layer) return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "null argument");
+  layer->defer_join = enabled != 0;
+  return FL_OK;
+  FL_GUARD_END
+}
+
+fl_status_t fl_layer_join(fl_layer_t *layer, void *hip_stream) {
+  FL_GUARD_BEGIN
+  if (!layer) return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "null argument");
+  return (fl_status_t)finish_pending_join(layer, static_cast<hipStream_t>(hip_stream), false);
+  FL_GUARD_END
+}
+
 fl_status_t fl_opt_step(const fl_opt_config_t *cfg, fl_dtype_t dtype, int32_t n, void *const *params,
                         const void *const *grads, float *const *state_m, float *const *state_v, const int64_t *numel,
                         void *hip_stream) {
@@ -999,6 +1049,7 @@ fl_status_t fl_zero_grad(fl_dtype_t dtype, int32_t n, void *const *grads, const 
 fl_status_t fl_layer_destroy(fl_layer_t *layer) {
   FL_GUARD_BEGIN
   if (!layer) return FL_OK;
+  finish_pending_join(layer, nullptr, true);
   release_tape(layer, true);  // the caller's stream may be gone by now
   if (layer->wt_fork_event) hipEventDestroy(layer->wt_fork_event);
   if (layer->wt_event) hipEventDestroy(layer->wt_event);

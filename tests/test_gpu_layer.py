@@ -338,6 +338,52 @@ def _run_stack(cfg, nontrivial):
         L.destroy()
 
 
+@pytest.mark.parametrize("join", ["explicit", "next-forward", "other-stream"])
+def test_deferred_join_changes_no_bit(join):
+    """A stack whose layers leave the side-stream join to fl_layer_join (or to their next forward) produces
+    the same bits as one that joins in every backward; two steps, so that buffers are reused across them."""
+    from paper_2201_12465_amd import binding as b
+    torch = torch_mod()
+    cfg = CONFIGS["cfg5_vit_b16_bf16"].with_(B=8, layers=3)
+    inp = make_stack_inputs(cfg, seed=1, nontrivial=True)
+    dt = cfg.dtype
+
+    def run(deferred):
+        layers = [b.Layer(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F, cfg.act, cfg.norm, dt, cfg.eps) for _ in range(cfg.layers)]
+        for ly in layers:
+            ly.set_deferred_join(deferred)
+        P = [{k: to_dev(v, dt) for k, v in p.items()} for p in inp["params"]]
+        G = [{k: empty_dev(v.shape, dt) for k, v in p.items()} for p in inp["params"]]
+        acts = [to_dev(inp["X"], dt)] + [empty_dev(inp["X"].shape, dt) for _ in range(cfg.layers)]
+        grads = [empty_dev(inp["X"].shape, dt) for _ in range(cfg.layers)] + [to_dev(inp["dY"], dt)]
+        s = stream_ptr()
+        other = torch.cuda.Stream()
+        for step in range(2):
+            for l in range(cfg.layers):
+                layers[l].forward(P[l], acts[l], None, cfg.B, cfg.T, acts[l + 1], s)   # joins what step 0 left open
+            for l in reversed(range(cfg.layers)):
+                layers[l].backward(P[l], grads[l + 1], grads[l], G[l], s)
+            if deferred and join == "explicit":
+                for ly in layers:
+                    ly.join(s)
+            if deferred and join == "other-stream" and step == 1:
+                for ly in layers:
+                    ly.join(other.cuda_stream)
+                other.synchronize()
+        if deferred and join == "next-forward":
+            for ly in layers:   # destroy joins too; here the results are read first
+                ly.join(s)
+        torch.cuda.synchronize()
+        out = [to_np(acts[-1]), to_np(grads[0])] + [to_np(G[l][k]) for l in range(cfg.layers) for k in PARAM_NAMES]
+        for ly in layers:
+            ly.destroy()
+        return out
+
+    ref, got = run(False), run(True)
+    for i, (r, g) in enumerate(zip(ref, got)):
+        assert np.array_equal(r, g), (join, i)
+
+
 def test_masked_keys_get_exactly_zero_influence():
     """Changing X at a padded position changes only that position's output row."""
     cfg = CONFIGS["cfg2_small_f32"].with_(B=2, T=40, D=64, H=4, F=128)
