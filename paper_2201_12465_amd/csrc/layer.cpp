@@ -303,22 +303,22 @@ int side_join(fl_layer *L, bool wait_host, bool defer = false) {
 }
 
 // Completes a join that backward left open: the layer's stream (whose cache the held buffers return to)
-// waits for the marked point of the side stream, and so does `also` when it is another stream; with
-// wait_host the host waits instead (destroy, error paths).
+// waits for the marked point of the side stream, and so does `also` when it is another stream.  Where a
+// stream cannot wait (wait_host: destroy and error paths; or the caller has destroyed the stream since),
+// the host waits instead, as wt_release() does.
 int finish_pending_join(fl_layer *L, hipStream_t also, bool wait_host) {
-  int rc = 0;
   if (L->join_pending) {
-    hipError_t e = wait_host ? hipEventSynchronize(L->join_event) : hipStreamWaitEvent(L->stream, L->join_event, 0);
-    if (e == hipSuccess && !wait_host && also != L->stream) e = hipStreamWaitEvent(also, L->join_event, 0);
-    if (e != hipSuccess) {
-      hipStreamSynchronize(side_stream());
-      rc = set_error(FL_ERR_DEVICE, "joining the side stream failed: %s", hipGetErrorString(e));
+    bool ordered = !wait_host && hipStreamWaitEvent(L->stream, L->join_event, 0) == hipSuccess &&
+                   (also == L->stream || hipStreamWaitEvent(also, L->join_event, 0) == hipSuccess);
+    if (!ordered) {
+      (void)hipGetLastError();
+      if (hipEventSynchronize(L->join_event) != hipSuccess) hipStreamSynchronize(side_stream());
     }
     L->join_pending = false;
   }
   for (Buf *&b : L->held) buf_unref(b);
   L->held.clear();
-  return rc;
+  return 0;
 }
 
 // The transposed weights go back to the cache of the layer's stream: if they were written on the side
