@@ -302,40 +302,47 @@ def test_vit_stack_reduced():
 
 def test_config5_full_stack():
     """Config 5 as the benchmark spec states it: 12 pre-LN layers, B=64, T=197, final Y, dX at the stack
-    input and all 12 layers' parameter gradients against the oracle."""
-    _run_stack(CONFIGS["cfg5_vit_b16_bf16"], nontrivial=False)
+    input and all 12 layers' parameter gradients against the oracle; once with every backward joining the
+    side stream itself and once the way the benchmark runs the stack (one join per layer after the last
+    backward)."""
+    _run_stack(CONFIGS["cfg5_vit_b16_bf16"], nontrivial=False, deferred_too=True)
 
 
-def _run_stack(cfg, nontrivial):
+def _run_stack(cfg, nontrivial, deferred_too=False):
     from paper_2201_12465_amd import binding as b
     torch = torch_mod()
     inp = make_stack_inputs(cfg, seed=0, nontrivial=nontrivial)
     dt = cfg.dtype
-    layers = [b.Layer(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F, cfg.act, cfg.norm, dt, cfg.eps) for _ in range(cfg.layers)]
-    P = [{k: to_dev(v, dt) for k, v in p.items()} for p in inp["params"]]
-    G = [{k: empty_dev(v.shape, dt) for k, v in p.items()} for p in inp["params"]]
-    acts = [to_dev(inp["X"], dt)] + [empty_dev(inp["X"].shape, dt) for _ in range(cfg.layers)]
-    grads = [empty_dev(inp["X"].shape, dt) for _ in range(cfg.layers)] + [to_dev(inp["dY"], dt)]
-    s = stream_ptr()
-    for l in range(cfg.layers):
-        layers[l].forward(P[l], acts[l], None, cfg.B, cfg.T, acts[l + 1], s)
-    for l in reversed(range(cfg.layers)):
-        layers[l].backward(P[l], grads[l + 1], grads[l], G[l], s)
-    torch.cuda.synchronize()
     rY, rdX, rg = orc.stack_forward_backward(inp["params"], inp["X"], inp["dY"], None, heads=cfg.H, act=cfg.act,
                                              norm=cfg.norm, eps=cfg.eps)
-    errs = {"Y": rel_err(to_np(acts[-1]), rY), "dX": rel_err(to_np(grads[0]), rdX)}
-    for l in range(cfg.layers):
-        for k in PARAM_NAMES:
-            errs[f"L{l}.d{k}"] = rel_err(to_np(G[l][k]), rg[l][k])
-    # Every layer rounds its activations and gradients to bf16 on its own, so the single-layer bound
-    # compounds over the chain like independent errors: in quadrature.
-    tol = BF16_TOL * np.sqrt(cfg.layers)
-    bad = {k: v for k, v in errs.items() if not v <= tol}
-    assert not bad, (tol, bad)
-    print(f"stack of {cfg.layers}: largest error {max(errs.values()):.4f} (bound {tol:.4f})")
-    for L in layers:
-        L.destroy()
+    P = [{k: to_dev(v, dt) for k, v in p.items()} for p in inp["params"]]
+    for deferred in ([False, True] if deferred_too else [False]):
+        layers = [b.Layer(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F, cfg.act, cfg.norm, dt, cfg.eps) for _ in range(cfg.layers)]
+        G = [{k: empty_dev(v.shape, dt) for k, v in p.items()} for p in inp["params"]]
+        acts = [to_dev(inp["X"], dt)] + [empty_dev(inp["X"].shape, dt) for _ in range(cfg.layers)]
+        grads = [empty_dev(inp["X"].shape, dt) for _ in range(cfg.layers)] + [to_dev(inp["dY"], dt)]
+        s = stream_ptr()
+        for ly in layers:
+            ly.set_deferred_join(deferred)
+        for l in range(cfg.layers):
+            layers[l].forward(P[l], acts[l], None, cfg.B, cfg.T, acts[l + 1], s)
+        for l in reversed(range(cfg.layers)):
+            layers[l].backward(P[l], grads[l + 1], grads[l], G[l], s)
+        for ly in layers:
+            ly.join(s)   # nothing to do unless deferred
+        torch.cuda.synchronize()
+        errs = {"Y": rel_err(to_np(acts[-1]), rY), "dX": rel_err(to_np(grads[0]), rdX)}
+        for l in range(cfg.layers):
+            for k in PARAM_NAMES:
+                errs[f"L{l}.d{k}"] = rel_err(to_np(G[l][k]), rg[l][k])
+        # Every layer rounds its activations and gradients to bf16 on its own, so the single-layer bound
+        # compounds over the chain like independent errors: in quadrature.
+        tol = BF16_TOL * np.sqrt(cfg.layers)
+        bad = {k: v for k, v in errs.items() if not v <= tol}
+        assert not bad, (deferred, tol, bad)
+        print(f"stack of {cfg.layers} (deferred join: {deferred}): largest error {max(errs.values()):.4f} (bound {tol:.4f})")
+        for L in layers:
+            L.destroy()
 
 
 @pytest.mark.parametrize("join", ["explicit", "next-forward", "other-stream"])
