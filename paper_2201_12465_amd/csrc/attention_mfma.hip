@@ -149,6 +149,7 @@ __global__ __launch_bounds__(NT, fwd_waves(DH, DROP)) void attn_fwd_mfma(const b
   // K fragments in flight at one time (4 registers each); small heads run several wavefronts per SIMD
   // instead and have no registers to spare
   constexpr int KBATCH = DH <= 64 ? 1 : DH > 192 ? NK / 2 : NK;
+  static_assert(NK % KBATCH == 0 && (KBATCH == 1 || KBATCH % 2 == 0), "K fragments are pinned in pairs");
   constexpr bool LAZY = DH > 64;   // rescale the output accumulators only when a row's reference maximum moves
   // V^T fragments requested BEFORE the softmax arithmetic of a block, so that their LDS round trip runs
   // under it (48 registers at head size 192; the largest head has none to spare)
