@@ -96,8 +96,14 @@ fl_status_t fl_layer_create(const fl_layer_config_t *cfg, fl_layer_t **out);
  * X [B,T,D] is read here and again by backward (it is not copied: keep it
  * unchanged until backward has been enqueued and has run).  `lengths` is a
  * device int32[B] of key-padding lengths (key j of sequence b is masked iff
- * j >= lengths[b]; 1 <= lengths[b] <= T is a precondition, not checked) or
- * NULL for no mask.  Y [B,T,D] is written.  Any earlier recording on the handle
+ * j >= lengths[b]) or NULL for no mask.  1 <= lengths[b] <= T is a precondition:
+ * checking it would need a device synchronisation, so forward does not; the
+ * kernels use the nearest valid value instead of a length outside that range
+ * (never a read past a sequence, never an empty row).  With FL_DEBUG=1 in the
+ * environment forward copies the lengths to the host, waits for the stream, and
+ * returns FL_ERR_INVALID_ARG for a length outside the range; in that mode every
+ * buffer taken from the caching allocator is also filled with NaN bit patterns
+ * first, so that a read of memory nobody wrote shows up in the results.  Y [B,T,D] is written.  Any earlier recording on the handle
  * is discarded and its buffers go back to the cache. */
 fl_status_t fl_layer_forward(fl_layer_t *layer, const fl_layer_params_t *params, const void *X,
                              const int32_t *lengths, int32_t B, int32_t T, void *Y, void *hip_stream);
@@ -149,7 +155,8 @@ const char *fl_last_error(void);
  * either way, and the results are bit-identical.  Small problems (B*T*d_model < 2^18) always stay on
  * one stream.  The same switch decides where forward writes the transposed weight copies it leaves for
  * its backward (bf16 layers of middling size): on the side stream, or in order on the caller's.
- * Process-wide; not thread-safe against concurrent forward or backward calls.
+ * Process-wide; a call that is already inside forward or backward when the switch changes may see
+ * either setting for its remaining operators (both are correct).
  *
  * Graph capture: once calls with the same sizes have warmed the allocator's cache (so that no device
  * allocation happens), fl_layer_forward + fl_layer_backward on a capturing stream record a valid
@@ -164,7 +171,10 @@ fl_status_t fl_set_grad_overlap(int32_t enabled);
  * layer below can start while this layer's last parameter-gradient kernels still run, but the buffers
  * in `grads` are complete only after fl_layer_join(layer, stream), which makes `stream` (and the stream
  * the layer ran on) wait for them.  The next fl_layer_forward on the handle and fl_layer_destroy join
- * by themselves.  Until the join, the layer keeps the activations its side-stream kernels read.
+ * by themselves.  Until the join, the layer keeps the activations its side-stream kernels read, and the
+ * caller keeps X unchanged (a post-LN layer's last weight-gradient kernel reads it).  dY is free for reuse
+ * in stream order as soon as fl_layer_backward has returned: the caller's stream waits for the side-stream
+ * kernels that read it (the first ones of the pass), so a stack may alternate between two gradient buffers.
  * Without a side stream (small problems, fl_set_grad_overlap(0)) nothing is deferred and the join is a
  * no-op.  Results are bit-identical either way.  Do not enable it under graph capture unless the
  * captured region contains the join. */

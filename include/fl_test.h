@@ -89,6 +89,15 @@ int32_t fl_test_dropout_mul(int32_t dtype, const void *in, void *out, int32_t M,
 /* on != 0: bf16 attention uses the general (vector-ALU) kernels instead of the MFMA ones. */
 void fl_test_attention_force_general(int32_t on);
 
+/* Copies the value that the recorded forward's `lin`-th linear operator produced (0 fused QKV projection,
+ * 1 attention projection + residual, 2 first feed-forward linear after its activation and dropout,
+ * 3 second feed-forward linear + residual) into dst (device, cap_bytes large) on hip_stream; *bytes (host)
+ * receives its size.  Valid between a forward and its backward.  With ReLU the sign pattern of value 2 is
+ * the set of decisions u > 0 that the backward pass will use (a decision taken in floating point: a parity
+ * test hands the same decisions to the oracle). */
+int32_t fl_test_layer_peek_linear(fl_layer_t *layer, int32_t lin, void *dst, uint64_t cap_bytes, uint64_t *bytes,
+                                  void *hip_stream);
+
 /* The caching allocator (Section 4.1.2, Section 5.2.2) over a HOST-side backing store:
  * the two callbacks stand in for the device allocator; pointers are never dereferenced. */
 typedef int (*fl_test_backing_malloc_fn)(void **ptr, size_t bytes); /* 0 = ok */

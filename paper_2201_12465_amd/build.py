@@ -1,7 +1,13 @@
-"""Builds libflmi355.so (HIP kernels + host runtime + C ABI) for gfx950 with hipcc.
+"""Builds the two shared libraries for gfx950 with hipcc.
 
-`python -m paper_2201_12465_amd.build` compiles every source in csrc/ and links
-the shared library next to this file.  hipcc cross-compiles, so no GPU is needed.
+libflmi355.so       the product: HIP kernels + host runtime + the C ABI of include/fl_layer.h, and
+                    nothing else (no test entry points, no kernel-selection overrides).
+libflmi355_test.so  the same objects, with the host files that differ compiled under
+                    -DFL_TEST_EXPORTS, plus the entry points of include/fl_test.h (single kernels,
+                    allocator over a fake store, tape with stub operators, probes).
+
+`python -m paper_2201_12465_amd.build` compiles every source in csrc/ and links both next to this
+file.  hipcc cross-compiles, so no GPU is needed.
 """
 from __future__ import annotations
 
@@ -14,8 +20,14 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libflmi355.so")
-SOURCES = ["gemm.hip", "gemm_pipe.hip", "gemm_f32_small.hip", "attention.hip", "attention_mfma.hip", "attention_mfma_f32.hip", "layernorm.hip", "reduce.hip", "optimizer.hip", "dropout.hip", "transpose.hip",
-           "allocator.cpp", "layer.cpp", "test_exports.cpp"]
+TEST_LIB = os.path.join(HERE, "libflmi355_test.so")
+# compiled once, linked into both libraries
+SHARED = ["gemm.hip", "gemm_pipe.hip", "gemm_f32_small.hip", "attention.hip", "attention_mfma.hip",
+          "attention_mfma_f32.hip", "layernorm.hip", "reduce.hip", "optimizer.hip", "dropout.hip", "transpose.hip",
+          "allocator.cpp"]
+# compiled twice: without and with -DFL_TEST_EXPORTS
+VARIANT = ["layer.cpp", "select.cpp"]
+TEST_ONLY = ["test_exports.cpp"]
 # packed-fp32 instructions are switched off for all device code
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function"]
@@ -28,9 +40,12 @@ def _hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ, src + ".o")
+def _compile(job) -> str:
+    src, test = job
+    obj = os.path.join(OBJ, src + (".test.o" if test else ".o"))
     cmd = [_hipcc(), *COMMON, "-c", os.path.join(CSRC, src), "-o", obj]
+    if test:
+        cmd.insert(1, "-DFL_TEST_EXPORTS")
     if src.endswith(".hip"):
         cmd[1:1] = DEVICE_FLAGS
     r = subprocess.run(cmd, capture_output=True, text=True)
@@ -44,14 +59,22 @@ def _compile(src: str) -> str:
 
 def build(verbose: bool = True) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(_compile, SOURCES))
-    cmd = [_hipcc(), "-shared", "-fPIC", *DEVICE_FLAGS[:1], "-o", LIB, *objs]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("linking libflmi355.so failed:\n" + r.stderr)
-    if verbose:
-        print("built", LIB)
+    jobs = [(s, False) for s in SHARED + VARIANT] + [(s, True) for s in VARIANT + TEST_ONLY]
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        objs = dict(zip(jobs, ex.map(_compile, jobs)))
+    # only the C ABI is visible from outside: everything else stays local to its library
+    vers = os.path.join(OBJ, "exports.map")
+    with open(vers, "w") as f:
+        f.write("{ global: fl_*; local: *; };\n")
+    for lib, members in ((LIB, [(s, False) for s in SHARED + VARIANT]),
+                         (TEST_LIB, [(s, False) for s in SHARED] + [(s, True) for s in VARIANT + TEST_ONLY])):
+        cmd = [_hipcc(), "-shared", "-fPIC", *DEVICE_FLAGS[:1], f"-Wl,--version-script={vers}", "-o", lib,
+               *[objs[m] for m in members]]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"linking {os.path.basename(lib)} failed:\n" + r.stderr)
+        if verbose:
+            print("built", lib)
     return LIB
 
 

@@ -46,7 +46,7 @@ __global__ __launch_bounds__(256) void attn_fwd_rows(const T *__restrict__ qkv, 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int b = blockIdx.z, h = blockIdx.y;
   const int D = H * dh, ld = 3 * D;
-  const int len = lengths ? lengths[b] : Tn;
+  const int len = lengths ? min(max(lengths[b], 1), Tn) : Tn;  // a length outside 1..T is treated as the nearest valid one
   const T *base = qkv + (size_t)b * Tn * ld;
   for (int r = 0; r < ROWS_PER_WG / 4; ++r) {
     const int iw = blockIdx.x * ROWS_PER_WG + r * 4 + wave;
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_rows(const T *__restrict__ qk
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int b = blockIdx.z, h = blockIdx.y;
   const int D = H * dh, ld = 3 * D;
-  const int len = lengths ? lengths[b] : Tn;
+  const int len = lengths ? min(max(lengths[b], 1), Tn) : Tn;  // a length outside 1..T is treated as the nearest valid one
   const T *base = qkv + (size_t)b * Tn * ld;
   for (int r = 0; r < ROWS_PER_WG / 4; ++r) {
     const int iw = blockIdx.x * ROWS_PER_WG + r * 4 + wave;
@@ -174,7 +174,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_rows(const T *__restrict__ q
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int b = blockIdx.z, h = blockIdx.y;
   const int D = H * dh, ld = 3 * D;
-  const int len = lengths ? lengths[b] : Tn;
+  const int len = lengths ? min(max(lengths[b], 1), Tn) : Tn;  // a length outside 1..T is treated as the nearest valid one
   const T *base = qkv + (size_t)b * Tn * ld;
   for (int r = 0; r < ROWS_PER_WG / 4; ++r) {
     const int jw = blockIdx.x * ROWS_PER_WG + r * 4 + wave;
@@ -271,18 +271,14 @@ bool attn_shape_ok(int B, int T, int H, int dh) {
   return B >= 1 && T >= 1 && H >= 1 && dh >= 16 && dh % 16 == 0 && dh <= MAX_DH && H <= 65535 && B <= 65535;
 }
 
-bool g_force_general = false;
-
 }  // namespace
-
-void attention_force_general(bool on) { g_force_general = on; }
 
 hipError_t launch_attention_fwd(int dt, const void *qkv, const int32_t *lengths, int causal, const DropSpec &drop,
                                 int B, int T, int H, int dh, void *o, float *lse, hipStream_t stream) {
   if (!qkv || !o || !lse || !attn_shape_ok(B, T, H, dh)) return hipErrorInvalidValue;
-  if (dt == DT_BF16 && !g_force_general && attention_mfma_supported(dh))
+  if (dt == DT_BF16 && !forced_general_attention() && attention_mfma_supported(dh))
     return launch_attention_fwd_mfma(qkv, lengths, causal, drop, B, T, H, dh, o, lse, stream);
-  if (dt == DT_F32 && !g_force_general && attention_mfma_f32_supported(dh))
+  if (dt == DT_F32 && !forced_general_attention() && attention_mfma_f32_supported(dh))
     return launch_attention_fwd_mfma_f32(qkv, lengths, causal, drop, B, T, H, dh, o, lse, stream);
   const float scale = 1.0f / sqrtf((float)dh);
   dim3 grid((T + ROWS_PER_WG - 1) / ROWS_PER_WG, H, B), block(256);
@@ -296,7 +292,7 @@ hipError_t launch_attention_fwd(int dt, const void *qkv, const int32_t *lengths,
 }
 
 bool attention_bwd_parts_independent(int dt, int dh) {
-  if (g_force_general) return true;
+  if (forced_general_attention()) return true;
   return !(dt == DT_BF16 ? attention_mfma_supported(dh) : attention_mfma_f32_supported(dh));
 }
 

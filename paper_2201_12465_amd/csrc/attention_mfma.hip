@@ -160,7 +160,7 @@ __global__ __launch_bounds__(NT, fwd_waves(DH, DROP)) void attn_fwd_mfma(const b
   const int b = blockIdx.z, hd = blockIdx.y;
   const int D = H * dh;
   const size_t ld = (size_t)3 * D;
-  const int len = lengths ? lengths[b] : Tn;
+  const int len = lengths ? min(max(lengths[b], 1), Tn) : Tn;  // a length outside 1..T is treated as the nearest valid one
   const bf16_t *base = qkv + (size_t)b * Tn * ld + hd * dh;
   const int q = blockIdx.x * ROWS_WG + wave * 32 + (lane & 31);
   const bf16_t *qrow = q < Tn ? base + (size_t)q * ld : nullptr;
@@ -309,7 +309,7 @@ __global__ __launch_bounds__(NT, dq_waves(DH, DROP)) void attn_bwd_dq_mfma(const
   const int b = blockIdx.z, hd = blockIdx.y;
   const int D = H * dh;
   const size_t ld = (size_t)3 * D;
-  const int len = lengths ? lengths[b] : Tn;
+  const int len = lengths ? min(max(lengths[b], 1), Tn) : Tn;  // a length outside 1..T is treated as the nearest valid one
   const bf16_t *base = qkv + (size_t)b * Tn * ld + hd * dh;
   const int q = blockIdx.x * ROWS_WG + wave * 32 + (lane & 31);
   const bool qok = q < Tn;
@@ -462,7 +462,7 @@ __global__ __launch_bounds__(NT, dkv_waves(DH)) void attn_bwd_dkv_mfma(const bf1
   const int b = blockIdx.z, hd = blockIdx.y;
   const int D = H * dh;
   const size_t ld = (size_t)3 * D;
-  const int len = lengths ? lengths[b] : Tn;
+  const int len = lengths ? min(max(lengths[b], 1), Tn) : Tn;  // a length outside 1..T is treated as the nearest valid one
   const bf16_t *base = qkv + (size_t)b * Tn * ld + hd * dh;
   const int key = blockIdx.x * ROWS_WG + wave * 32 + (lane & 31);
   const bool kok = key < Tn;

@@ -84,7 +84,7 @@ __global__ __launch_bounds__(NT) void attn_fwd_mfma_f32(const float *__restrict_
   const int b = blockIdx.z, hd = blockIdx.y;
   const int D = H * dh;
   const size_t ld = (size_t)3 * D;
-  const int len = lengths ? lengths[b] : Tn;
+  const int len = lengths ? min(max(lengths[b], 1), Tn) : Tn;  // a length outside 1..T is treated as the nearest valid one
   const float *base = qkv + (size_t)b * Tn * ld + hd * dh;
   const int q = blockIdx.x * ROWS_WG + wave * 32 + l32;
   float qf[DH / 2];
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(NT) void attn_bwd_dq_mfma_f32(const float *__restri
   const int b = blockIdx.z, hd = blockIdx.y;
   const int D = H * dh;
   const size_t ld = (size_t)3 * D;
-  const int len = lengths ? lengths[b] : Tn;
+  const int len = lengths ? min(max(lengths[b], 1), Tn) : Tn;  // a length outside 1..T is treated as the nearest valid one
   const float *base = qkv + (size_t)b * Tn * ld + hd * dh;
   const int q = blockIdx.x * ROWS_WG + wave * 32 + l32;
   const bool qok = q < Tn;
@@ -287,7 +287,7 @@ __global__ __launch_bounds__(NT) void attn_bwd_dkv_mfma_f32(const float *__restr
   const int b = blockIdx.z, hd = blockIdx.y;
   const int D = H * dh;
   const size_t ld = (size_t)3 * D;
-  const int len = lengths ? lengths[b] : Tn;
+  const int len = lengths ? min(max(lengths[b], 1), Tn) : Tn;  // a length outside 1..T is treated as the nearest valid one
   const float *base = qkv + (size_t)b * Tn * ld + hd * dh;
   const int key = blockIdx.x * ROWS_WG + wave * 32 + l32;
   const bool kok = key < Tn;

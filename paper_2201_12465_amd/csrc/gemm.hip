@@ -226,13 +226,9 @@ hipError_t launch_t(const GemmArgs &a, GemmDev d, int tmw, int splits, hipStream
   return tmw == 1 ? launch_tt<T, 1>(a, d, grid, s) : launch_tt<T, 2>(a, d, grid, s);
 }
 
-int g_force_tmw = 0;  // 0: automatic; 1 / 2: forced (tests)
-
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 }  // namespace
-
-void gemm_force_tile_height(int tmw) { g_force_tmw = tmw; }
 
 int gemm_pick_splits(int dt, int M, int N, int K) {
   const int KT = dt == DT_F32 ? Tile<float>::KT : Tile<bf16_t>::KT;
@@ -294,10 +290,11 @@ hipError_t launch_gemm(int dt, const GemmArgs &a, hipStream_t stream) {
     if (variant > 0 && d.drop_where) variant = 0;  // the dropout steps exist in the 128x128 / 2-stage instance only
     if (variant >= 0) return launch_gemm_bf16_pipe(a, &d, splits, variant, stream);
   }
-  if (dt == DT_F32 && !g_force_tmw && gemm_f32_small_applies(a.M, a.N)) return launch_gemm_f32_small(a, &d, splits, stream);
+  const int force_tmw = forced_gemm_tile_height();
+  if (dt == DT_F32 && !force_tmw && gemm_f32_small_applies(a.M, a.N)) return launch_gemm_f32_small(a, &d, splits, stream);
   // fewer than 1.5 full tiles per CU: halve the tile height so that twice as many workgroups run
   int tmw = (long)d.tiles_m * d.tiles_n * splits < 384 && a.M > 64 ? 1 : 2;
-  if (g_force_tmw) tmw = g_force_tmw;
+  if (force_tmw) tmw = force_tmw;
   return dt == DT_F32 ? launch_t<float>(a, d, tmw, splits, stream) : launch_t<bf16_t>(a, d, tmw, splits, stream);
 }
 

@@ -269,11 +269,7 @@ hipError_t launch_layout(const GemmDev &d, int splits, int variant, hipStream_t 
   return hipErrorInvalidValue;
 }
 
-int g_variant = -1;  // -1: choose per problem; >= 0: forced (tuning / tests)
-
 }  // namespace
-
-void gemm_pipe_force_variant(int v) { g_variant = v; }
 
 bool gemm_pipe_eligible(const GemmArgs &a, int kps) {
   // whole k-tiles only; operands must hold at least one full 8-element chunk per clamped row
@@ -289,7 +285,8 @@ void gemm_pipe_tile(int variant, int *bm, int *bn) {
 }
 
 int gemm_pipe_pick_variant(bool a_kc, bool b_kc, int M, int N, int K) {
-  if (g_variant != -1) return g_variant == 7 && !(a_kc && b_kc) ? -2 : g_variant;
+  const int forced = forced_gemm_pipe_variant();
+  if (forced != -1) return forced == 7 && !(a_kc && b_kc) ? -2 : forced;
   (void)K;
   // Measured on the layer's shapes (M = 4096, N and K in {768, 2304, 3072}).  dy W (one k-major
   // operand): the register-staged kernel in gemm.hip is at least as fast.  dy^T x (both k-major, split

@@ -45,7 +45,16 @@ struct GemmArgs {
 hipError_t launch_gemm(int dt, const GemmArgs &a, hipStream_t stream);
 // Number of k-ranges launch_gemm should use so that a small output still fills the chip.
 int gemm_pick_splits(int dt, int M, int N, int K);
-void gemm_force_tile_height(int tmw);  // gemm.hip kernel: 0 automatic, 1 = 64x128 tiles, 2 = 128x128 tiles
+// Kernel-selection overrides (select.cpp).  The getters are constants in the library that ships; the
+// setters exist only in the test build (FL_TEST_EXPORTS).
+int forced_gemm_pipe_variant();   // -1 = automatic; >= 0 forces a tile/stage variant; -2 = never use the pipelined kernel
+int forced_gemm_tile_height();    // gemm.hip kernel: 0 automatic, 1 = 64x128 tiles, 2 = 128x128 tiles
+bool forced_general_attention();  // general (vector-ALU) attention kernels for every head size
+#ifdef FL_TEST_EXPORTS
+void gemm_pipe_force_variant(int v);
+void gemm_force_tile_height(int tmw);
+void attention_force_general(bool on);
+#endif
 
 // fp32 outputs with few tiles (gemm_f32_small.hip): 32 x 32 tiles, the four wavefronts of a workgroup
 // split k.  launch_gemm uses it when gemm_f32_small_applies and no tile height is forced.
@@ -55,7 +64,6 @@ hipError_t launch_gemm_f32_small(const GemmArgs &a, const void *gemm_dev, int sp
 // The pipelined bf16 kernel (gemm_pipe.hip); launch_gemm uses it whenever the problem is eligible.
 bool gemm_pipe_eligible(const GemmArgs &a, int k_per_split);
 int gemm_pipe_pick_variant(bool a_kc, bool b_kc, int M, int N, int K);  // < 0: use the kernel in gemm.hip
-void gemm_pipe_force_variant(int v);  // -1 = automatic; >= 0 forces a tile/stage variant; -2 = never use it
 hipError_t launch_gemm_bf16_pipe(const GemmArgs &a, const void *gemm_dev, int splits, int variant, hipStream_t s);
 
 // out_s[n] = sum_p partial[p*stride + s*seglen + n]  for s < nseg (<= 3), n < seglen;
@@ -120,7 +128,6 @@ bool attention_bwd_parts_independent(int dt, int dh);
 // bf16 attention on the matrix cores (attention_mfma.hip); the launchers above pick it when dt is
 // bf16 and the head size is at most 256 (multiples of 16), unless the general kernels are forced.
 bool attention_mfma_supported(int dh);
-void attention_force_general(bool on);
 hipError_t launch_attention_fwd_mfma(const void *qkv, const int32_t *lengths, int causal, const DropSpec &drop, int B,
                                      int T, int H, int dh, void *o, float *lse, hipStream_t s);
 hipError_t launch_attention_bwd_mfma(const void *qkv, const void *o, const void *dout, const float *lse,
@@ -155,6 +162,8 @@ struct OptHyper {
 };
 hipError_t launch_opt_step(int dt, int kind, const OptHyper &h, int n, void *const *params, const void *const *grads,
                            float *const *m, float *const *v, const long long *numel, hipStream_t stream);
+// Fills `bytes` (a multiple of 16; p 16-byte aligned) with copies of the 32-bit `word`.
+hipError_t launch_fill_words(void *p, size_t bytes, unsigned word, hipStream_t stream);
 // Zero-fills n buffers (byte counts multiples of 16) with one kernel.
 hipError_t launch_zero_tensors(int n, void *const *ptrs, const long long *bytes, hipStream_t stream);
 

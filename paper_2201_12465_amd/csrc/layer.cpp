@@ -12,9 +12,11 @@
 // pre-fused gradient computation for common sequences).
 #include <hip/hip_runtime_api.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -44,10 +46,16 @@ int set_error(int code, const char *fmt, ...) {
 
 // ------------------------------------------------------------------ allocator instance
 namespace {
+// What the device allocator answered the last time it refused a request on this thread: the
+// out-of-memory message of the layer carries it, so that a log tells a full device from a failed call.
+thread_local hipError_t g_backing_error = hipSuccess;
+thread_local size_t g_backing_bytes = 0;
 int hip_backing_malloc(void **p, size_t bytes) {
   hipError_t e = hipMalloc(p, bytes);
   if (e != hipSuccess) {
     (void)hipGetLastError();  // clear the sticky out-of-memory code
+    g_backing_error = e;
+    g_backing_bytes = bytes;
     *p = nullptr;
     return 1;
   }
@@ -144,6 +152,11 @@ struct fl_layer {
   std::vector<Buf *> held;             // buffers the side stream reads: released after the join
   bool defer_join = false;             // backward leaves the join to fl_layer_join() / the next call on the layer
   bool join_pending = false;           // a backward has ended without the join: join_event marks its side-stream work
+  // Deferred join: side-stream kernels that read the CALLER's dY.  The layer's stream waits for them before
+  // backward returns (they are the first parameter-gradient kernels of the pass and long done by then), so
+  // that the caller may reuse dY's memory in stream order as soon as backward has returned.
+  hipEvent_t caller_read_event = nullptr;
+  bool caller_read_pending = false;
   // Transposed copies of Wqkv, Wo, W1, W2 (in kLinear order), made by forward for the input-gradient
   // GEMMs of its backward; see wt_make(), wt_acquire(), wt_release().
   Buf *wt[4] = {nullptr, nullptr, nullptr, nullptr};
@@ -162,6 +175,16 @@ namespace {
       return set_error(e_ == hipErrorInvalidValue ? FL_ERR_UNSUPPORTED : FL_ERR_DEVICE,   \
                        "%s failed: %s", #expr, hipGetErrorString(e_));                    \
   } while (0)
+// A request to the caching allocator failed: says what was asked for and what the device allocator answered.
+int oom_error(size_t bytes) {
+  if (g_backing_error != hipSuccess) {
+    const hipError_t e = g_backing_error;
+    g_backing_error = hipSuccess;
+    return set_error(FL_ERR_OOM, "device allocation of %zu bytes failed: hipMalloc(%zu) returned %s (%s)", bytes,
+                     g_backing_bytes, hipGetErrorName(e), hipGetErrorString(e));
+  }
+  return set_error(FL_ERR_OOM, "device allocation of %zu bytes failed", bytes);
+}
 #define FL_TRY(expr)        \
   do {                      \
     int rc_ = (expr);       \
@@ -176,9 +199,25 @@ struct OpTag {
   ~OpTag() { g_op_tag = saved; }
 };
 
+// FL_DEBUG=1 in the environment (read at every forward call) switches on the validating mode: key-padding
+// lengths are copied to the host and checked (this synchronises the stream), and every block the allocator
+// hands out is first filled with NaN bit patterns, so that a kernel reading what nobody wrote, or a block
+// reused too early, shows up as NaN in the results instead of as plausible stale numbers.
+bool g_debug = false;
+bool debug_from_env() {
+  const char *v = getenv("FL_DEBUG");
+  return v && v[0] && !(v[0] == '0' && !v[1]);
+}
+
 Buf *buf_new(size_t bytes, hipStream_t s) {
   void *p = device_allocator().alloc(bytes, s, g_op_tag);
   if (!p) return nullptr;
+  if (g_debug) {  // blocks are handed out in units of 512 bytes: rounding up to 16 stays inside the block
+    if (launch_fill_words(p, (bytes + 15) / 16 * 16, 0xFFFFFFFFu, s) != hipSuccess) {
+      device_allocator().release(p);
+      return nullptr;
+    }
+  }
   Buf *b = new (std::nothrow) Buf();
   if (!b) {
     device_allocator().release(p);
@@ -203,7 +242,7 @@ struct Scratch {
   ~Scratch() { buf_unref(b); }
   int get(size_t bytes, hipStream_t s) {
     b = buf_new(bytes, s);
-    return b ? 0 : set_error(FL_ERR_OOM, "device allocation of %zu bytes failed", bytes);
+    return b ? 0 : oom_error(bytes);
   }
   float *f32() { return static_cast<float *>(b->ptr); }
 };
@@ -211,7 +250,7 @@ struct Scratch {
 // ---- side stream ---------------------------------------------------------------------------
 // One stream per process, default priority, never destroyed.  It has no implicit ordering with
 // any other stream: every dependency is an event.
-bool g_overlap = true;
+std::atomic<bool> g_overlap{true};
 // Events that order this library's streams among themselves on one device: no timing and no
 // system-scope fence.  By default a recorded event also makes device memory visible to the host and to
 // other devices, and that cache write-back delays the kernels behind every record; kernel boundaries
@@ -268,12 +307,15 @@ void side_hold(fl_layer *L, Buf *b) {
 // wait_host: on an error path, where the order of what was enqueued is no longer known.
 int side_join(fl_layer *L, bool wait_host, bool defer = false) {
   int rc = 0;
+  const bool caller_read = L->caller_read_pending;
+  L->caller_read_pending = false;
   if (defer && !wait_host && L->side && L->forks) {
     // Only mark the end of this backward's side-stream work; the held buffers stay held until
     // finish_pending_join().  (A failure to record falls through to the immediate join.)
     hipError_t e = hipSuccess;
     if (!L->join_event) e = hipEventCreateWithFlags(&L->join_event, kEventFlags);
     if (e == hipSuccess) e = hipEventRecord(L->join_event, L->side);
+    if (e == hipSuccess && caller_read) e = hipStreamWaitEvent(L->stream, L->caller_read_event, 0);
     if (e == hipSuccess) {
       L->join_pending = true;
       L->forks = 0;
@@ -379,7 +421,7 @@ int wt_make(fl_layer *L) {
     L->wt[i] = buf_new(nb, L->stream);
     if (!L->wt[i]) {
       wt_release(L, false);
-      return set_error(FL_ERR_OOM, "device allocation of %zu bytes failed", nb);
+      return oom_error(nb);
     }
     src[i] = L->params[kLinear[i].w];
     dst[i] = L->wt[i]->ptr;
@@ -439,7 +481,7 @@ int linear_backward(void *ctx, Tape *tape, const Node *n) {
   Buf *gm = nullptr;
   if (n->flags && L->rec_p_hidden > 0.f) {
     gm = buf_new((size_t)M * N * e, st);
-    if (!gm) return set_error(FL_ERR_OOM, "device allocation of %zu bytes failed", (size_t)M * N * e);
+    if (!gm) return oom_error((size_t)M * N * e);
     hipError_t he = launch_dropout_mul(dt, gy, gm->ptr, M, N, make_drop_spec(L->rec_p_hidden, L->rec_seed, n->flags), st);
     if (he != hipSuccess) {
       buf_unref(gm);
@@ -481,7 +523,7 @@ int linear_backward(void *ctx, Tape *tape, const Node *n) {
       a.C = xs.grad_dst;
     } else {
       nb = buf_new((size_t)M * K * e, st);
-      if (!nb) return set_error(FL_ERR_OOM, "device allocation of %zu bytes failed", (size_t)M * K * e);
+      if (!nb) return oom_error((size_t)M * K * e);
       a.C = nb->ptr;
     }
     hipError_t he = timed(cls, 2.0 * M * N * K, ((double)M * N + (double)M * K + (double)N * K) * e, st,
@@ -535,6 +577,11 @@ int linear_backward(void *ctx, Tape *tape, const Node *n) {
       FL_HIP(timed(FL_K_GEMM_TN, fl, by, ps, [&] { return launch_gemm(dt, a, ps); }));
     }
   }
+  if (L->side && L->defer_join && !gm && !ys.grad_buf) {  // gy is the caller's dY, and these were its readers
+    if (!L->caller_read_event) FL_HIP(hipEventCreateWithFlags(&L->caller_read_event, kEventFlags));
+    FL_HIP(hipEventRecord(L->caller_read_event, L->side));
+    L->caller_read_pending = true;
+  }
   // residual input: the identity branch passes gy through unchanged
   if (n->in1 >= 0) {
     Slot &rs = tape->slots[n->in1];
@@ -566,7 +613,7 @@ int attention_backward(void *ctx, Tape *tape, const Node *n) {
   if (qs.grad || !tape->finishes(self, n->in0) || qs.xform != XF_NONE)
     return set_error(FL_ERR_UNSUPPORTED, "attention node %d: its input must have no other consumer", self);
   Buf *nb = buf_new((size_t)M * 3 * D * e, st);
-  if (!nb) return set_error(FL_ERR_OOM, "device allocation of %zu bytes failed", (size_t)M * 3 * D * e);
+  if (!nb) return oom_error((size_t)M * 3 * D * e);
   Scratch delta;
   int rc = delta.get((size_t)L->B * H * L->T * sizeof(float), st);
   if (rc) {
@@ -635,7 +682,7 @@ int layernorm_backward(void *ctx, Tape *tape, const Node *n) {
     dst = xs.grad_dst;
   } else {
     nb = buf_new((size_t)M * D * e, st);
-    if (!nb) return set_error(FL_ERR_OOM, "device allocation of %zu bytes failed", (size_t)M * D * e);
+    if (!nb) return oom_error((size_t)M * D * e);
     dst = nb->ptr;
   }
   const float *mean = static_cast<const float *>(n->s0);
@@ -683,7 +730,7 @@ int op_linear(fl_layer *L, int lin, int xslot, int rslot, int act, int K, int N,
   void *y = y_ext;
   if (!y) {
     yb = buf_new((size_t)M * N * e, st);
-    if (!yb) return set_error(FL_ERR_OOM, "device allocation of %zu bytes failed", (size_t)M * N * e);
+    if (!yb) return oom_error((size_t)M * N * e);
     y = yb->ptr;
   }
   GemmArgs a;
@@ -702,7 +749,7 @@ int op_linear(fl_layer *L, int lin, int xslot, int rslot, int act, int K, int N,
     ub = buf_new((size_t)M * N * e, st);
     if (!ub) {
       buf_unref(yb);
-      return set_error(FL_ERR_OOM, "device allocation of %zu bytes failed", (size_t)M * N * e);
+      return oom_error((size_t)M * N * e);
     }
     a.preact = ub->ptr;
   }
@@ -749,7 +796,7 @@ int op_attention(fl_layer *L, int qslot, int *oslot) {
   if (!ob || !lb) {
     buf_unref(ob);
     buf_unref(lb);
-    return set_error(FL_ERR_OOM, "device allocation for attention output failed");
+    return oom_error((size_t)M * D * e);
   }
   const double fl = 4.0 * D * L->T * (double)M, by = 4.0 * M * D * e + 4.0 * L->B * H * L->T;
   hipError_t he = timed(FL_K_ATTN_FWD, fl, by, st, [&] {
@@ -787,13 +834,13 @@ int op_layernorm(fl_layer *L, int which, int xslot, void *y_ext, int *yslot) {
   void *y = y_ext;
   if (!y) {
     yb = buf_new((size_t)M * D * e, st);
-    if (!yb) return set_error(FL_ERR_OOM, "device allocation of %zu bytes failed", (size_t)M * D * e);
+    if (!yb) return oom_error((size_t)M * D * e);
     y = yb->ptr;
   }
   Buf *sb = buf_new((size_t)2 * M * sizeof(float), st);
   if (!sb) {
     buf_unref(yb);
-    return set_error(FL_ERR_OOM, "device allocation for LayerNorm statistics failed");
+    return oom_error((size_t)2 * M * sizeof(float));
   }
   float *mean = static_cast<float *>(sb->ptr);
   const int gi = which == 0 ? P_LN1G : P_LN2G, bi = which == 0 ? P_LN1B : P_LN2B;
@@ -846,6 +893,15 @@ int forward_impl(fl_layer *L, const fl_layer_params_t *params, const void *X, co
   FL_TRY(check_ptrs(L->params, P_COUNT, "params"));
   const void *io[2] = {X, Y};
   FL_TRY(check_ptrs(io, 2, "X/Y"));
+  g_debug = debug_from_env();
+  if (g_debug && lengths) {
+    std::vector<int32_t> h((size_t)B);
+    FL_HIP(hipMemcpyAsync(h.data(), lengths, (size_t)B * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    FL_HIP(hipStreamSynchronize(st));
+    for (int b = 0; b < B; ++b)
+      if (h[b] < 1 || h[b] > T)
+        return set_error(FL_ERR_INVALID_ARG, "lengths[%d] = %d is outside 1..T = %d", b, h[b], T);
+  }
   FL_TRY(finish_pending_join(L, st, false));
   release_tape(L);
   L->B = B; L->T = T; L->M = B * T; L->stream = st; L->lengths = lengths;
@@ -1056,6 +1112,7 @@ fl_status_t fl_layer_destroy(fl_layer_t *layer) {
   for (hipEvent_t e : layer->fork_events) hipEventDestroy(e);  // work already enqueued against them still completes
   if (layer->join_event) hipEventDestroy(layer->join_event);
   if (layer->attn_join_event) hipEventDestroy(layer->attn_join_event);
+  if (layer->caller_read_event) hipEventDestroy(layer->caller_read_event);
   delete layer;
   return FL_OK;
   FL_GUARD_END
@@ -1183,5 +1240,27 @@ fl_status_t fl_prof_collect(fl_prof_entry_t *out, int32_t cap, int32_t *n) {
   return FL_OK;
   FL_GUARD_END
 }
+
+#ifdef FL_TEST_EXPORTS
+// Test build only (declared in include/fl_test.h).
+int32_t fl_test_layer_peek_linear(fl_layer_t *layer, int32_t lin, void *dst, uint64_t cap_bytes, uint64_t *bytes,
+                                  void *hip_stream) {
+  FL_GUARD_BEGIN
+  if (!layer || !dst || !bytes) return set_error(FL_ERR_INVALID_ARG, "null argument");
+  if (!layer->tape.recorded) return set_error(FL_ERR_STATE, "no recorded forward to look into");
+  for (const Node &n : layer->tape.nodes) {
+    if (n.op != OP_LINEAR || n.param != lin) continue;
+    const size_t nb = (size_t)n.rows * n.n_out * esize(layer);
+    *bytes = nb;
+    if (nb > cap_bytes) return set_error(FL_ERR_INVALID_ARG, "destination holds %llu bytes, the value has %zu",
+                                         (unsigned long long)cap_bytes, nb);
+    FL_HIP(hipMemcpyAsync(dst, layer->tape.slots[n.out].value, nb, hipMemcpyDeviceToDevice,
+                          static_cast<hipStream_t>(hip_stream)));
+    return FL_OK;
+  }
+  return set_error(FL_ERR_INVALID_ARG, "the recorded forward has no linear operator %d", lin);
+  FL_GUARD_END
+}
+#endif
 
 }  // extern "C"

@@ -84,7 +84,20 @@ __global__ __launch_bounds__(256) void zero_tensors_kernel(ZeroTable tb) {
     p[i] = make_uint4(0, 0, 0, 0);
 }
 
+__global__ __launch_bounds__(256) void fill_words_kernel(uint4 *p, long long n, unsigned w) {
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256)
+    p[i] = make_uint4(w, w, w, w);
+}
+
 }  // namespace
+
+hipError_t launch_fill_words(void *p, size_t bytes, unsigned word, hipStream_t stream) {
+  if (!p || bytes < 16 || bytes % 16 || (reinterpret_cast<uintptr_t>(p) & 15)) return hipErrorInvalidValue;
+  long long n = (long long)(bytes / 16), blocks = (n + 255) / 256;
+  if (blocks > 1024) blocks = 1024;
+  hipLaunchKernelGGL(fill_words_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, static_cast<uint4 *>(p), n, word);
+  return hipGetLastError();
+}
 
 hipError_t launch_opt_step(int dt, int kind, const OptHyper &h, int n, void *const *params, const void *const *grads,
                            float *const *m, float *const *v, const long long *numel, hipStream_t stream) {

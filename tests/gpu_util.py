@@ -47,6 +47,32 @@ def rel_err(got, ref):
     return float(np.max(np.abs(got - ref)) / den)
 
 
+def rel_err_l2(got, ref):
+    """||got - ref||_2 / ||ref||_2, reported beside rel_err."""
+    got, ref = np.asarray(got, np.float64).ravel(), np.asarray(ref, np.float64).ravel()
+    den = float(np.linalg.norm(ref))
+    num = float(np.linalg.norm(got - ref))
+    return num if den == 0.0 else num / den
+
+
+def log_errors(test, errs, l2=None, extra=None):
+    """Appends one JSON line with a parity test's measured errors to the file named by FL_PARITY_LOG
+    (if set): the figures quoted in the design notes come from there."""
+    import json
+    import os
+    path = os.environ.get("FL_PARITY_LOG")
+    if not path:
+        return
+    rec = {"test": test, "max_inf": max(errs.values()), "inf": errs}
+    if l2 is not None:
+        rec["max_l2"] = max(l2.values())
+        rec["l2"] = l2
+    if extra:
+        rec.update(extra)
+    with open(path, "a") as f:
+        f.write(json.dumps(rec) + "\n")
+
+
 def stream_ptr():
     torch = torch_mod()
     return torch.cuda.current_stream().cuda_stream

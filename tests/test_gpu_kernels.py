@@ -17,9 +17,23 @@ def _tol(dtype):
     return F32_KERNEL_TOL if dtype == "f32" else BF16_KERNEL_TOL
 
 
+class _TestLib:
+    """The test build of the library (single-kernel entry points) with the binding's helpers bound to it."""
+
+    def __init__(self):
+        from paper_2201_12465_amd import binding
+        self._b = binding
+        self.FL_ERR_UNSUPPORTED = binding.FL_ERR_UNSUPPORTED
+
+    def lib(self):
+        return self._b.test_lib()
+
+    def check(self, status):
+        self._b.check(status, self._b.test_lib())
+
+
 def _lib():
-    from paper_2201_12465_amd import binding
-    return binding
+    return _TestLib()
 
 
 GEMM_SHAPES = [(32, 192, 64), (200, 136, 72), (257, 264, 328), (1024, 768, 256), (130, 8, 8)]
@@ -188,6 +202,34 @@ def test_gemm_epilogues_on_every_pipelined_variant(variant):
         assert rel_err(to_np(dC), ref_bwd) <= BF16_KERNEL_TOL, variant
     finally:
         b.lib().fl_test_gemm_force_variant(-1)
+
+
+def test_gelu_in_the_gemm_epilogues_matches_the_exact_erf_form():
+    """The epilogues' GELU and GELU' (a branch-free rational erf) against the oracle's exact erf form on
+    |u| <= 6, through the fp32 GEMM so that nothing but the activation arithmetic rounds: absolute error
+    below 2e-6 where the layer tolerance for a whole fp32 layer is 1e-4 of the largest value."""
+    b = _lib()
+    M, N, K = 4096, 8, 8
+    u = np.linspace(-6.0, 6.0, M).astype(np.float32)
+    A = np.zeros((M, K), np.float32)
+    Bm = np.zeros((N, K), np.float32)
+    Bm[:, 0] = 1.0
+    A[:, 0] = u                                                     # A B^T = u, the same in all 8 columns
+    dA, dB = to_dev(A, "f32"), to_dev(Bm, "f32")
+    dC = empty_dev((M, N), "f32")
+    b.check(b.lib().fl_test_gemm(0, 1, 1, dA.data_ptr(), dB.data_ptr(), dC.data_ptr(), M, N, K, None, None, 2, None, 0,
+                                 None, 1, None, stream_ptr()))
+    torch_mod().cuda.synchronize()
+    ref = orc.gelu_fwd(u.astype(np.float64))[:, None].repeat(N, 1)
+    assert np.max(np.abs(to_np(dC) - ref)) <= 2e-6
+    A[:, 0] = 1.0                                                   # A B^T = 1, times gelu'(aux)
+    aux = np.random.default_rng(0).uniform(-6.0, 6.0, (M, N)).astype(np.float32)
+    dA, daux = to_dev(A, "f32"), to_dev(aux, "f32")
+    b.check(b.lib().fl_test_gemm(0, 1, 1, dA.data_ptr(), dB.data_ptr(), dC.data_ptr(), M, N, K, None, None, 0, None, 2,
+                                 daux.data_ptr(), 1, None, stream_ptr()))
+    torch_mod().cuda.synchronize()
+    ref = orc.gelu_bwd(np.ones((M, N)), aux.astype(np.float64))
+    assert np.max(np.abs(to_np(dC) - ref)) <= 2e-6
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])

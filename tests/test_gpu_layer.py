@@ -5,20 +5,23 @@ import numpy as np
 import pytest
 
 from oracle import oracle as orc
-from gpu_util import BF16_TOL, F32_TOL, empty_dev, rel_err, stream_ptr, to_dev, to_np, torch_mod
+from gpu_util import (BF16_TOL, F32_TOL, empty_dev, log_errors, rel_err, rel_err_l2, stream_ptr, to_dev, to_np,
+                      torch_mod)
 from workloads import CONFIGS, PARAM_NAMES, make_inputs, make_stack_inputs
 
 pytestmark = pytest.mark.gpu
 
 
-def run_layer_gpu(cfg, inp, layer=None, keep=False, dropout=None):
-    """dropout: None or (p_attn, p_hidden, seed)."""
+def run_layer_gpu(cfg, inp, layer=None, keep=False, dropout=None, peek_act=False):
+    """dropout: None or (p_attn, p_hidden, seed).  peek_act: the layer runs on the test build of the library
+    and the feed-forward activation's output, as the recorded forward holds it, is returned as a fourth value."""
     from paper_2201_12465_amd import binding as b
     torch = torch_mod()
     dt = cfg.dtype
     own = layer is None
     if own:
-        layer = b.Layer(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F, cfg.act, cfg.norm, dt, cfg.eps, cfg.causal)
+        layer = b.Layer(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F, cfg.act, cfg.norm, dt, cfg.eps, cfg.causal,
+                        L=b.test_lib() if peek_act else None)
     if dropout is not None:
         layer.set_dropout(*dropout)
     p = {k: to_dev(v, dt) for k, v in inp["params"].items()}
@@ -29,11 +32,16 @@ def run_layer_gpu(cfg, inp, layer=None, keep=False, dropout=None):
     if inp["lengths"] is not None:
         L = torch.tensor(inp["lengths"], dtype=torch.int32, device="cuda")
     layer.forward(p, X, L, cfg.B, cfg.T, Y, stream_ptr())
+    G = None
+    if peek_act:
+        G = empty_dev((cfg.B, cfg.T, cfg.F), dt)
+        assert layer.peek_linear(2, G, stream_ptr()) == G.numel() * G.element_size()
     layer.backward(p, dY, dX, g, stream_ptr())
     torch.cuda.synchronize()
     if own and not keep:
         layer.destroy()
-    return to_np(Y), to_np(dX), {k: to_np(v) for k, v in g.items()}
+    res = (to_np(Y), to_np(dX), {k: to_np(v) for k, v in g.items()})
+    return res + (to_np(G),) if peek_act else res
 
 
 def avoid_relu_kink(cfg, inp, margin=2e-5, masks=None):
@@ -41,8 +49,9 @@ def avoid_relu_kink(cfg, inp, margin=2e-5, masks=None):
     opposite sides of 0 (they differ by rounding, ~1e-6) would make the two gradients differ by a
     whole term although both are right.  For the fp32 ReLU cases the inputs are therefore moved off
     the kink: bias b1 of every column holding a pre-activation with |u| < margin is shifted by
-    4*margin until none is left.  Uses the oracle only.  (The bf16 path cannot avoid this: its
-    pre-activations carry bf16 rounding of their inputs; its tolerance absorbs the effect.)"""
+    4*margin until none is left.  Uses the oracle only.  (The bf16 path cannot avoid this by choosing
+    inputs: its pre-activations carry the bf16 rounding of the tensors before them; there the comparison
+    is made under the GPU's own decisions, see relu_decisions_of_the_gpu.)"""
     if cfg.act != "relu" or cfg.dtype != "f32":
         return inp
     kw = dict(heads=cfg.H, act=cfg.act, norm=cfg.norm, eps=cfg.eps, causal=cfg.causal, masks=masks)
@@ -55,34 +64,37 @@ def avoid_relu_kink(cfg, inp, margin=2e-5, masks=None):
     raise AssertionError("could not move the pre-activations off the ReLU kink")
 
 
-def relu_kink_allowance(cfg, inp, cache, base, samples=3):
-    """How far ambiguous ReLU decisions can move each gradient tensor (bf16 + ReLU only).
+def relu_decisions_of_the_gpu(cfg, inp, cache, G_gpu):
+    """The bf16 path's ReLU decisions, validated, as a stand-in pre-activation for the oracle's backward.
 
-    The bf16 path takes the decision u > 0 on its own pre-activation, which differs from the
-    fp64 oracle's by the bf16 rounding of the tensors stored before it (a few 2^-9 relative
-    steps of the terms of the dot product).  Where |u| is below that uncertainty, both decisions
-    are valid results of the method.  Every gradient is linear in the 0/1 decisions, so the test
-    re-runs the oracle's backward pass with the ambiguous decisions drawn at random and reports,
-    per tensor, the largest deviation from the unmodified oracle: the comparison tolerates that
-    much on top of the stated tolerance.  Uses the oracle only."""
+    relu'(u) = 1[u > 0] is a decision taken in floating point: the bf16 path takes it on its own
+    pre-activation, which differs from the fp64 oracle's by the bf16 rounding of the tensors stored before
+    it.  Where |u| is below that uncertainty both decisions are valid results of the method, and a single
+    flipped decision changes a gradient by a whole term.  So the comparison is made under the GPU's own
+    decisions (the sign pattern of the activation output its forward pass recorded), after checking that
+    they are valid: a decision may differ from the oracle's only where the oracle's |u| is smaller than
+    2^-6 * sqrt(sum_k x_k^2 W_k^2) -- about four standard deviations of what rounding x to bf16 (2^-9
+    relative, independent per term) does to the dot product -- and only on a small share of the elements.
+    Elements that dropout removed carry no decision (their gradient is zero either way).
+    Returns (cache with the decisions put in place of U, share of flipped decisions)."""
     U = cache["ffn"]["U"]
     x, W1 = cache["ffn"]["x"], np.asarray(inp["params"]["W1"], np.float64)
-    delta = 2.0 ** -6 * np.sqrt((x * x) @ (W1 * W1).T)       # ~4 sigma of the pre-activation's uncertainty
-    amb = np.abs(U) < delta
-    rng = np.random.default_rng(123)
-    allow = {k: 0.0 for k in base}
-    for _ in range(samples):
-        Umod = np.where(amb, np.where(rng.random(U.shape) < 0.5, 1e-30, -1e-30), U)
-        c2 = dict(cache)
-        c2["ffn"] = dict(cache["ffn"], U=Umod)
-        dX, g = orc.layer_backward(inp["params"], c2, inp["dY"])
-        alt = {"dX": dX, **{"d" + k: g[k] for k in PARAM_NAMES}}
-        for k in alt:
-            allow[k] = max(allow[k], float(np.max(np.abs(alt[k] - base[k])) / np.max(np.abs(base[k]))))
-    return allow, float(amb.mean())
+    delta = 2.0 ** -6 * np.sqrt((x * x) @ (W1 * W1).T)
+    keep = cache["ffn"].get("keep")
+    decided = np.ones(U.shape, bool) if keep is None else np.asarray(keep) > 0
+    on_gpu = np.asarray(G_gpu).reshape(U.shape) > 0
+    flipped = decided & (on_gpu != (U > 0))
+    assert not np.any(flipped & ~(np.abs(U) < delta)), \
+        f"{cfg.name}: ReLU decisions differ where the pre-activation is not ambiguous (max |u| {np.abs(U[flipped]).max()})"
+    share = float(flipped.sum() / max(1, decided.sum()))
+    assert share <= 0.02, f"{cfg.name}: {share:.4f} of the ReLU decisions flipped"
+    Umod = np.where(decided, np.where(on_gpu, 1.0, -1.0), U)
+    c2 = dict(cache)
+    c2["ffn"] = dict(cache["ffn"], U=Umod)
+    return c2, share
 
 
-def check_against_oracle(cfg, inp, tol, dropout=None):
+def check_against_oracle(cfg, inp, tol, dropout=None, test=None):
     masks = None
     if dropout is not None:
         from oracle import dropout as odr
@@ -90,19 +102,22 @@ def check_against_oracle(cfg, inp, tol, dropout=None):
         dropout = (float(np.float32(dropout[0])), float(np.float32(dropout[1])), dropout[2])
         masks = odr.layer_masks(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F, *dropout)
     inp = avoid_relu_kink(cfg, inp, masks=masks)
-    Y, dX, g = run_layer_gpu(cfg, inp, dropout=dropout)
+    own_decisions = cfg.act == "relu" and cfg.dtype == "bf16"
+    res = run_layer_gpu(cfg, inp, dropout=dropout, peek_act=own_decisions)
+    Y, dX, g = res[:3]
     kw = dict(heads=cfg.H, act=cfg.act, norm=cfg.norm, eps=cfg.eps, causal=cfg.causal, masks=masks)
     rY, cache = orc.layer_forward(inp["params"], inp["X"], inp["lengths"], **kw)
+    extra = {}
+    if own_decisions:
+        cache, extra["relu_flipped_share"] = relu_decisions_of_the_gpu(cfg, inp, cache, res[3])
     rdX, rg = orc.layer_backward(inp["params"], cache, inp["dY"])
-    base = {"dX": rdX, **{"d" + k: rg[k] for k in PARAM_NAMES}}
-    got = {"dX": dX, **{"d" + k: g[k] for k in PARAM_NAMES}}
-    errs = {"Y": rel_err(Y, rY)}
-    errs.update({k: rel_err(got[k], base[k]) for k in base})
-    allow = {}
-    if cfg.act == "relu" and cfg.dtype == "bf16":
-        allow, frac = relu_kink_allowance(cfg, inp, cache, base)
-    bad = {k: (v, allow.get(k, 0.0)) for k, v in errs.items() if not v <= tol + allow.get(k, 0.0)}
-    assert not bad, f"{cfg.name}: above {tol} (+ReLU-kink allowance): {bad}; all: {errs}; allowances: {allow}"
+    base = {"Y": rY, "dX": rdX, **{"d" + k: rg[k] for k in PARAM_NAMES}}
+    got = {"Y": Y, "dX": dX, **{"d" + k: g[k] for k in PARAM_NAMES}}
+    errs = {k: rel_err(got[k], base[k]) for k in base}
+    l2 = {k: rel_err_l2(got[k], base[k]) for k in base}
+    log_errors(test or cfg.name, errs, l2, extra)
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, f"{cfg.name}: above {tol}: {bad}; all: {errs}; {extra}"
     return errs
 
 
@@ -297,24 +312,36 @@ def test_speech_shape_reduced():
 
 def test_vit_stack_reduced():
     """Config 5's chain (pre-LN, GELU, T=197) through the same layer calls: 3 layers, batch 4."""
-    _run_stack(CONFIGS["cfg5_vit_b16_bf16"].with_(B=4, layers=3), nontrivial=True)
+    _run_stack(CONFIGS["cfg5_vit_b16_bf16"].with_(B=4, layers=3), nontrivial=True, test="cfg5_reduced_3_layers")
 
 
 def test_config5_full_stack():
-    """Config 5 as the benchmark spec states it: 12 pre-LN layers, B=64, T=197, final Y, dX at the stack
-    input and all 12 layers' parameter gradients against the oracle; once with every backward joining the
-    side stream itself and once the way the benchmark runs the stack (one join per layer after the last
-    backward)."""
-    _run_stack(CONFIGS["cfg5_vit_b16_bf16"], nontrivial=False, deferred_too=True)
+    """Config 5 as the benchmark spec states it: 12 pre-LN layers, B=64, T=197.  Two comparisons, both at the
+    flat bf16 tolerance: (1) the chain end to end -- final Y, dX at the stack input and all 12 layers'
+    parameter gradients against the oracle's chain; (2) every layer on its own -- the oracle is given the
+    very input and upstream gradient the GPU's layer l received (the GPU's own bf16 tensors), so that each
+    layer's Y, dX and 12 gradients are checked without the error the chain has built up before it.
+    Run once with every backward joining the side stream itself and once the way the benchmark runs the
+    stack (one join per layer after the last backward)."""
+    _run_stack(CONFIGS["cfg5_vit_b16_bf16"], nontrivial=False, deferred_too=True, test="cfg5_vit_b16_bf16")
 
 
-def _run_stack(cfg, nontrivial, deferred_too=False):
+# The chain of 12 layer calls hands bf16 tensors from call to call: against the un-rounded fp64 chain the
+# residual stream and the gradient stream are each rounded 24 times, whatever the kernels do, and those
+# roundings add up like a random walk (per layer: 0.005; chain: 0.017 on Y).  One tensor of the full-size
+# chain ends above the flat tolerance, and is held to its measured value, reported as it is: dX at the
+# stack input, 0.0202.  Every other tensor of the chain, and every tensor of every single layer, is held
+# to the flat 2e-2.
+CHAIN_TOL = {"cfg5_vit_b16_bf16": {"dX": 2.05e-2}}
+
+
+def _run_stack(cfg, nontrivial, deferred_too=False, test=None):
     from paper_2201_12465_amd import binding as b
     torch = torch_mod()
     inp = make_stack_inputs(cfg, seed=0, nontrivial=nontrivial)
     dt = cfg.dtype
-    rY, rdX, rg = orc.stack_forward_backward(inp["params"], inp["X"], inp["dY"], None, heads=cfg.H, act=cfg.act,
-                                             norm=cfg.norm, eps=cfg.eps)
+    kw = dict(heads=cfg.H, act=cfg.act, norm=cfg.norm, eps=cfg.eps)
+    rY, rdX, rg = orc.stack_forward_backward(inp["params"], inp["X"], inp["dY"], None, **kw)
     P = [{k: to_dev(v, dt) for k, v in p.items()} for p in inp["params"]]
     for deferred in ([False, True] if deferred_too else [False]):
         layers = [b.Layer(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F, cfg.act, cfg.norm, dt, cfg.eps) for _ in range(cfg.layers)]
@@ -331,18 +358,35 @@ def _run_stack(cfg, nontrivial, deferred_too=False):
         for ly in layers:
             ly.join(s)   # nothing to do unless deferred
         torch.cuda.synchronize()
-        errs = {"Y": rel_err(to_np(acts[-1]), rY), "dX": rel_err(to_np(grads[0]), rdX)}
-        for l in range(cfg.layers):
-            for k in PARAM_NAMES:
-                errs[f"L{l}.d{k}"] = rel_err(to_np(G[l][k]), rg[l][k])
-        # Every layer rounds its activations and gradients to bf16 on its own, so the single-layer bound
-        # compounds over the chain like independent errors: in quadrature.
-        tol = BF16_TOL * np.sqrt(cfg.layers)
-        bad = {k: v for k, v in errs.items() if not v <= tol}
-        assert not bad, (deferred, tol, bad)
-        print(f"stack of {cfg.layers} (deferred join: {deferred}): largest error {max(errs.values()):.4f} (bound {tol:.4f})")
         for L in layers:
             L.destroy()
+        # (1) the chain end to end
+        pairs = {"Y": (to_np(acts[-1]), rY), "dX": (to_np(grads[0]), rdX)}
+        for l in range(cfg.layers):
+            for k in PARAM_NAMES:
+                pairs[f"L{l}.d{k}"] = (to_np(G[l][k]), rg[l][k])
+        errs = {k: rel_err(a, r) for k, (a, r) in pairs.items()}
+        l2 = {k: rel_err_l2(a, r) for k, (a, r) in pairs.items()}
+        log_errors(f"{test}/chain/deferred={deferred}", errs, l2)
+        print(f"stack of {cfg.layers} (deferred join: {deferred}): chain, largest error {max(errs.values()):.4f}")
+        bad = {k: v for k, v in errs.items() if not v <= CHAIN_TOL.get(test, {}).get(k, BF16_TOL)}
+        assert not bad, ("chain", deferred, BF16_TOL, bad)
+        if deferred:
+            continue   # same kernels, same bits (test_deferred_join_changes_no_bit): the per-layer pass is not repeated
+        # (2) every layer on its own, fed what the GPU's layer was fed
+        worst = {}
+        for l in range(cfg.layers):
+            x_l, dy_l = to_np(acts[l]), to_np(grads[l + 1])
+            oY, odX, og = orc.layer_forward_backward(inp["params"][l], x_l, dy_l, None, **kw)
+            pl = {"Y": (to_np(acts[l + 1]), oY), "dX": (to_np(grads[l]), odX)}
+            pl.update({"d" + k: (to_np(G[l][k]), og[k]) for k in PARAM_NAMES})
+            e_l = {k: rel_err(a, r) for k, (a, r) in pl.items()}
+            l2_l = {k: rel_err_l2(a, r) for k, (a, r) in pl.items()}
+            log_errors(f"{test}/layer{l}", e_l, l2_l)
+            bad = {k: v for k, v in e_l.items() if not v <= BF16_TOL}
+            assert not bad, ("layer", l, BF16_TOL, bad)
+            worst[l] = max(e_l.values())
+        print(f"stack of {cfg.layers}: per-layer largest errors {worst}")
 
 
 @pytest.mark.parametrize("join", ["explicit", "next-forward", "other-stream"])
@@ -389,6 +433,82 @@ def test_deferred_join_changes_no_bit(join):
     ref, got = run(False), run(True)
     for i, (r, g) in enumerate(zip(ref, got)):
         assert np.array_equal(r, g), (join, i)
+
+
+def test_deferred_join_lets_the_caller_reuse_the_upstream_gradient_buffer():
+    """A stack that ping-pongs TWO gradient buffers: layer l writes its dX into the buffer that held the dY of
+    layer l+1.  With the join deferred, layer l+1's weight-gradient kernels (which read that dY on the side
+    stream) must be done before layer l's chain overwrites it.  Same bits as the run that joins in every
+    backward and keeps one buffer per layer."""
+    from paper_2201_12465_amd import binding as b
+    torch = torch_mod()
+    cfg = CONFIGS["cfg5_vit_b16_bf16"].with_(B=16, layers=4)
+    inp = make_stack_inputs(cfg, seed=2, nontrivial=True)
+    dt = cfg.dtype
+
+    def run(deferred):
+        layers = [b.Layer(cfg.B, cfg.T, cfg.D, cfg.H, cfg.F, cfg.act, cfg.norm, dt, cfg.eps) for _ in range(cfg.layers)]
+        for ly in layers:
+            ly.set_deferred_join(deferred)
+        P = [{k: to_dev(v, dt) for k, v in p.items()} for p in inp["params"]]
+        G = [{k: empty_dev(v.shape, dt) for k, v in p.items()} for p in inp["params"]]
+        acts = [to_dev(inp["X"], dt)] + [empty_dev(inp["X"].shape, dt) for _ in range(cfg.layers)]
+        if deferred:
+            ping = [to_dev(inp["dY"], dt), empty_dev(inp["X"].shape, dt)]
+            grads = [ping[(cfg.layers - l) % 2] for l in range(cfg.layers + 1)]   # grads[layers] = dY
+        else:
+            grads = [empty_dev(inp["X"].shape, dt) for _ in range(cfg.layers)] + [to_dev(inp["dY"], dt)]
+        s = stream_ptr()
+        for step in range(2):
+            if deferred and step:
+                grads[cfg.layers].copy_(to_dev(inp["dY"], dt))   # the first step's chain has overwritten it
+            for l in range(cfg.layers):
+                layers[l].forward(P[l], acts[l], None, cfg.B, cfg.T, acts[l + 1], s)
+            for l in reversed(range(cfg.layers)):
+                layers[l].backward(P[l], grads[l + 1], grads[l], G[l], s)
+            for ly in layers:
+                ly.join(s)
+        torch.cuda.synchronize()
+        out = [to_np(grads[0])] + [to_np(G[l][k]) for l in range(cfg.layers) for k in PARAM_NAMES]
+        for ly in layers:
+            ly.destroy()
+        return out
+
+    ref, got = run(False), run(True)
+    for i, (r, g) in enumerate(zip(ref, got)):
+        assert np.array_equal(r, g), i
+
+
+def test_lengths_outside_the_valid_range():
+    """1 <= lengths[b] <= T is a precondition.  The kernels treat a length outside it as the nearest valid one
+    (no read past a sequence, no 0/0 row); with FL_DEBUG=1 in the environment forward checks the lengths on
+    the host and refuses them, and hands out NaN-filled buffers without changing any result."""
+    import os
+    from paper_2201_12465_amd import binding as b
+    torch = torch_mod()
+    for dtype in ("f32", "bf16"):
+        cfg = CONFIGS["cfg2_small_f32"].with_(B=3, T=70, D=128, H=2, F=256, dtype=dtype, act="gelu",
+                                              init="normal0.02" if dtype == "bf16" else "xavier")
+        inp = make_inputs(cfg, seed=9, nontrivial=True)
+        inp["lengths"] = np.array([0, 75, 33], np.int32)
+        clamped = dict(inp, lengths=np.array([1, 70, 33], np.int32))
+        got, want = run_layer_gpu(cfg, inp), run_layer_gpu(cfg, clamped)
+        assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1])
+        for k in PARAM_NAMES:
+            assert np.array_equal(got[2][k], want[2][k]), k
+        os.environ["FL_DEBUG"] = "1"
+        try:
+            with pytest.raises(b.FlError) as e:
+                run_layer_gpu(cfg, inp)
+            assert e.value.status == b.FL_ERR_INVALID_ARG and "lengths[0] = 0" in str(e.value)
+            poisoned = run_layer_gpu(cfg, clamped)
+        finally:
+            del os.environ["FL_DEBUG"]
+        assert np.array_equal(poisoned[0], want[0]) and np.array_equal(poisoned[1], want[1])
+        for k in PARAM_NAMES:
+            assert np.array_equal(poisoned[2][k], want[2][k]), k
+    torch.cuda.synchronize()
+    assert b.alloc_stats()["live_bytes"] == 0
 
 
 def test_masked_keys_get_exactly_zero_influence():
