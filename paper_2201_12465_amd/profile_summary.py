@@ -11,7 +11,13 @@ counter per run) around `python3 bench.py --no-kernel-timing --no-cpu-baseline .
 `python3 bench.py --copy-calibration`.  The counters are in KiB per dispatch; each is scaled by
 (bytes the plain copy kernel is known to move) / (what the same counter reads for it), and the
 per-class lines `traffic <class> bytes_per_launch <bytes>` are what bench.py reports as
-roofline.traffic.  Only text parsing happens here: nothing touches the GPU.
+roofline.traffic.
+    python -m paper_2201_12465_amd.profile_summary mfma <dir> [--workload NAME] > summary.txt
+mfma: <dir> is the -d directory of one counter run (SQ block + GRBM_GUI_ACTIVE, see MFMA_COUNTERS) around
+the same bench command; per kernel it prints the share of the chip's MFMA issue cycles that were busy
+(the matrix-core utilisation the roofline fraction is cross-checked against), the share of the
+wavefronts' resident cycles spent waiting, and LDS bank conflicts.
+Only text parsing happens here: nothing touches the GPU.
 """
 import argparse
 import collections
@@ -147,6 +153,75 @@ def traffic(args) -> int:
     return 0
 
 
+MFMA_COUNTERS = ("SQ_WAVES", "SQ_BUSY_CYCLES", "SQ_WAVE_CYCLES", "SQ_WAIT_INST_ANY", "SQ_WAIT_INST_LDS",
+                 "SQ_ACTIVE_INST_VALU", "SQ_VALU_MFMA_BUSY_CYCLES", "SQ_LDS_BANK_CONFLICT", "GRBM_GUI_ACTIVE")
+SIMDS = 1024          # 256 compute units x 4
+MFMA_CYCLES = {"bf16": 32, "f32": 64}      # issue cycles of one 32x32 MFMA (x16 bf16: 32768 flop; x2 f32: 4096 flop)
+MFMA_FLOP = {"bf16": 32768.0, "f32": 4096.0}
+
+
+def mfma(args) -> int:
+    acc = collections.defaultdict(lambda: collections.defaultdict(list))
+    info = {}
+    for f in glob.glob(args.dir + "/**/*counter_collection.csv", recursive=True):
+        for r in csv.DictReader(open(f)):
+            k = r["Kernel_Name"]
+            if not ours(k):
+                continue
+            acc[k][r["Counter_Name"]].append(float(r["Counter_Value"]))
+            info[k] = (r.get("Workgroup_Size", "?"), r.get("LDS_Block_Size", "?"), r.get("VGPR_Count", "?"),
+                       r.get("Accum_VGPR_Count", "?"), r.get("Scratch_Size", "?"))
+    if not acc:
+        print(f"no counter_collection.csv with this library's kernels under {args.dir}", file=sys.stderr)
+        return 1
+    # GRBM_GUI_ACTIVE arrives summed over the accelerator dies (XCCs), each of which counts its own clocks
+    xcc = 8
+    for f in glob.glob(args.dir + "/**/*agent_info.csv", recursive=True):
+        for r in csv.DictReader(open(f)):
+            if r.get("Agent_Type") == "GPU" and r.get("Num_Xcc", "").isdigit():
+                xcc = int(r["Num_Xcc"])
+    print("# made by (from /tmp, TMPDIR=/tmp, on one MI355X):")
+    print(f"#   rocprofv3 --pmc {' '.join(MFMA_COUNTERS)} --output-format csv -d <dir> -- python3 bench.py "
+          f"--workload {args.workload} --steps 3 --warmup 2 --no-cpu-baseline --no-kernel-timing --no-grad-overlap")
+    print(f"#   python3 -m paper_2201_12465_amd.profile_summary mfma <dir> --workload {args.workload}")
+    print("# Per dispatch, averaged over the launches of a kernel (each kernel runs alone under counter collection).")
+    print(f"# gui_cyc   GRBM_GUI_ACTIVE / {xcc} (the counter is the sum over the {xcc} dies): clocks the dispatch kept the GPU busy;")
+    print("#           under counter collection a dispatch lasts about 20 % longer than in the kernel trace")
+    print("# mfma_busy SQ_VALU_MFMA_BUSY_CYCLES summed over the SIMDs: issue cycles the matrix cores were occupied")
+    print(f"# mfma_util mfma_busy / (gui_cyc x {SIMDS} SIMDs): 1.0 = every matrix core busy on every clock, i.e. the")
+    print("#           dense peak (2.5 PFLOP/s bf16: 32768 flop per 32x32x16 MFMA, 32 issue cycles each)")
+    print("# wait      SQ_WAIT_INST_ANY / SQ_WAVE_CYCLES: share of the wavefronts' resident cycles spent at s_waitcnt")
+    print("# wait_lds  SQ_WAIT_INST_LDS / SQ_WAVE_CYCLES: the part of it waiting for LDS")
+    print("# valu      SQ_ACTIVE_INST_VALU / SQ_WAVE_CYCLES (counter units as delivered: compare kernels, not 1.0)")
+    print("# conflict  SQ_LDS_BANK_CONFLICT / SQ_BUSY_CYCLES: LDS bank-conflict cycles per busy SQ cycle")
+    print(f"workload {args.workload}")
+    print(f"{'class':13s} {'kernel':60s} {'n':>4s} {'wg':>4s} {'lds':>6s} {'vgpr':>4s} {'agpr':>4s} {'scr':>4s} "
+          f"{'gui_cyc':>9s} {'mfma_busy':>11s} {'mfma_util':>9s} {'wait':>6s} {'wait_lds':>8s} {'valu':>6s} {'conflict':>8s}")
+    per_class = collections.defaultdict(lambda: [0.0, 0.0])
+    rows = []
+    for k, cs in acc.items():
+        avg = {c: (sum(v) / len(v) if v else 0.0) for c, v in cs.items()}
+        g = avg.get("GRBM_GUI_ACTIVE", 0.0) / xcc
+        mb = avg.get("SQ_VALU_MFMA_BUSY_CYCLES", 0.0)
+        wc = avg.get("SQ_WAVE_CYCLES", 0.0) or 1.0
+        n = len(cs.get("GRBM_GUI_ACTIVE", [])) or len(next(iter(cs.values())))
+        rows.append((g * n, k, n, g, mb, avg, wc))
+        c = classify(k)
+        per_class[c][0] += mb * n
+        per_class[c][1] += g * n
+    for _, k, n, g, mb, avg, wc in sorted(rows, reverse=True):
+        wg, lds, vg, ag, scr = info[k]
+        print(f"{classify(k):13s} {short(k, 60):60s} {n:4d} {wg:>4s} {lds:>6s} {vg:>4s} {ag:>4s} {scr:>4s} "
+              f"{g:9.0f} {mb:11.0f} {mb / (g * SIMDS) if g else 0:9.3f} {avg.get('SQ_WAIT_INST_ANY', 0) / wc:6.2f} "
+              f"{avg.get('SQ_WAIT_INST_LDS', 0) / wc:8.2f} {avg.get('SQ_ACTIVE_INST_VALU', 0) / wc:6.2f} "
+              f"{avg.get('SQ_LDS_BANK_CONFLICT', 0) / (avg.get('SQ_BUSY_CYCLES', 0) or 1):8.3f}")
+    print()
+    for c, (mb, g) in sorted(per_class.items(), key=lambda kv: -kv[1][1]):
+        if mb:
+            print(f"mfma_util {c} {mb / (g * SIMDS):.3f}")
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -157,8 +232,11 @@ def main() -> int:
     for n in ("bench_fetch", "bench_write", "copy_fetch", "copy_write"):
         t.add_argument(n)
     t.add_argument("--workload", default="cfg3_bert_base_bf16")
+    m = sub.add_parser("mfma")
+    m.add_argument("dir")
+    m.add_argument("--workload", default="cfg3_bert_base_bf16")
     a = ap.parse_args()
-    return kernel_trace(a) if a.cmd == "kernel-trace" else traffic(a)
+    return {"kernel-trace": kernel_trace, "traffic": traffic, "mfma": mfma}[a.cmd](a)
 
 
 if __name__ == "__main__":
