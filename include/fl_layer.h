@@ -108,6 +108,26 @@ fl_status_t fl_layer_create(const fl_layer_config_t *cfg, fl_layer_t **out);
 fl_status_t fl_layer_forward(fl_layer_t *layer, const fl_layer_params_t *params, const void *X,
                              const int32_t *lengths, int32_t B, int32_t T, void *Y, void *hip_stream);
 
+/* For callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  The forward pass of fl_layer_forward in evaluation mode (no dropout,
+ * nothing recorded or kept for a backward pass), same kernels, same results bit for bit, with every
+ * intermediate (projections, attention output and row statistics, residual sums, LayerNorm outputs and
+ * statistics, the feed-forward hidden activation) placed in a fixed device array of 128 MiB that each GPU
+ * holds from the moment the library's code is loaded on it until the process ends.  The call allocates
+ * nothing: no hipMalloc / hipFree, no stream or event creation, not through the caching allocator either
+ * (fl_alloc_get_stats does not move).  Arguments, layouts and preconditions as for fl_layer_forward; every
+ * kernel runs on hip_stream.
+ * Limit: the intermediates alive at one time must fit the array,
+ *   max(2*M*D + M*F, 4*M*D) * sizeof(element) + small change <= 128 MiB,   M = B*T
+ * (all five benchmark shapes do; 12608 tokens of d_model 768, d_ffn 3072 in bf16 need 116 MB).  Beyond it
+ * the call returns FL_ERR_UNSUPPORTED and enqueues nothing.  FL_ERR_STATE if the handle holds a recorded
+ * forward whose backward has not run.
+ * Every call on one GPU uses the same array and leaves its contents behind: two calls that may overlap on
+ * a GPU (different streams without an event between them, different threads) race on it.  Calls on one
+ * stream are ordered and safe.  Nothing in the array needs to start at zero. */
+fl_status_t fl_layer_forward_static(fl_layer_t *layer, const fl_layer_params_t *params, const void *X,
+                                    const int32_t *lengths, int32_t B, int32_t T, void *Y, void *hip_stream);
+
 /* Backward pass (Variable::backward(), Section 4.2; the training-loop listing's
  * loss.backward()): replays the tape of the last forward in reverse order.
  * dY [B,T,D] is the upstream gradient; dX [B,T,D] and all 12 gradient tensors

@@ -91,6 +91,7 @@ def _signatures():
     product = {
         "fl_layer_create": (C.c_int, [C.POINTER(fl_layer_config_t), C.POINTER(vp)]),
         "fl_layer_forward": (C.c_int, [vp, C.POINTER(fl_layer_params_t), vp, vp, i32, i32, vp, vp]),
+        "fl_layer_forward_static": (C.c_int, [vp, C.POINTER(fl_layer_params_t), vp, vp, i32, i32, vp, vp]),
         "fl_layer_backward": (C.c_int, [vp, C.POINTER(fl_layer_params_t), vp, vp, C.POINTER(fl_layer_grads_t), vp]),
         "fl_layer_backward_accumulate": (C.c_int, [vp, C.POINTER(fl_layer_params_t), vp, vp,
                                                    C.POINTER(fl_layer_grads_t), i32, vp]),
@@ -216,6 +217,10 @@ class Layer:
     def forward(self, params: dict, X, lengths, B: int, T: int, Y, stream: int = 0) -> None:
         p = _pack(fl_layer_params_t, params)
         check(self._L.fl_layer_forward(self._h, C.byref(p), ptr(X), ptr(lengths), B, T, ptr(Y), stream), self._L)
+
+    def forward_static(self, params: dict, X, lengths, B: int, T: int, Y, stream: int = 0) -> None:
+        p = _pack(fl_layer_params_t, params)
+        check(self._L.fl_layer_forward_static(self._h, C.byref(p), ptr(X), ptr(lengths), B, T, ptr(Y), stream), self._L)
 
     def backward(self, params: dict, dY, dX, grads: dict, stream: int = 0, accumulate: bool = False) -> None:
         p = _pack(fl_layer_params_t, params)

@@ -24,7 +24,7 @@ TEST_LIB = os.path.join(HERE, "libflmi355_test.so")
 # compiled once, linked into both libraries
 SHARED = ["gemm.hip", "gemm_pipe.hip", "gemm_f32_small.hip", "attention.hip", "attention_mfma.hip",
           "attention_mfma_f32.hip", "layernorm.hip", "reduce.hip", "optimizer.hip", "dropout.hip", "transpose.hip",
-          "allocator.cpp"]
+          "static_scratch.hip", "allocator.cpp"]
 # compiled twice: without and with -DFL_TEST_EXPORTS
 VARIANT = ["layer.cpp", "select.cpp"]
 TEST_ONLY = ["test_exports.cpp"]

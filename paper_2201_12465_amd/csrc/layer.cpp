@@ -26,6 +26,7 @@
 #include "allocator.h"
 #include "kernels.h"
 #include "runtime.h"
+#include "static_scratch.h"
 #include "tape.h"
 
 using namespace fl;
@@ -101,11 +102,13 @@ Prof &prof() {
 }  // namespace
 
 namespace fl {
+// Set while this thread runs the allocation-free forward: nothing may create an event or take device memory.
+thread_local bool g_no_alloc = false;
 // Runs `launch` (which enqueues one kernel class on `s`), bracketed by events when that class is selected.
 template <typename F>
 hipError_t timed(int cls, double flops, double bytes, hipStream_t s, F &&launch) {
   Prof &P = prof();
-  if (!(P.mask & (1u << cls))) return launch();
+  if (g_no_alloc || !(P.mask & (1u << cls))) return launch();
   std::lock_guard<std::mutex> g(P.mu);
   ProfEvent ev{P.get(), P.get(), cls, flops, bytes};
   if (!ev.a || !ev.b) return hipErrorOutOfMemory;
@@ -162,6 +165,7 @@ struct fl_layer {
   Buf *wt[4] = {nullptr, nullptr, nullptr, nullptr};
   hipEvent_t wt_fork_event = nullptr, wt_event = nullptr;
   bool wt_on_side = false;             // made on the side stream, and the layer's stream has not waited yet
+  bool inference = false;              // forward keeps nothing for a backward pass (no pre-activation copy)
   const void *params[P_COUNT];
   void *grads[P_COUNT];
 };
@@ -175,8 +179,59 @@ namespace {
       return set_error(e_ == hipErrorInvalidValue ? FL_ERR_UNSUPPORTED : FL_ERR_DEVICE,   \
                        "%s failed: %s", #expr, hipGetErrorString(e_));                    \
   } while (0)
-// A request to the caching allocator failed: says what was asked for and what the device allocator answered.
+// First-fit allocator over the static scratch array, host-side bookkeeping only.  It lives for one call of
+// the allocation-free forward: every kernel of that call runs on one stream, so a range may be handed out
+// again as soon as its last reader has been enqueued.
+struct Arena {
+  struct Range {
+    size_t off, size;
+    bool free;
+  };
+  unsigned char *base = nullptr;
+  std::vector<Range> ranges;
+  size_t live = 0, peak = 0;
+  Arena(void *b, size_t bytes) : base(static_cast<unsigned char *>(b)) { ranges.push_back({0, bytes, true}); }
+  void *alloc(size_t bytes) {
+    const size_t need = (bytes + 255) / 256 * 256;
+    for (size_t i = 0; i < ranges.size(); ++i) {
+      if (!ranges[i].free || ranges[i].size < need) continue;
+      const size_t rest = ranges[i].size - need;
+      ranges[i].size = need;
+      ranges[i].free = false;
+      if (rest) ranges.insert(ranges.begin() + i + 1, Range{ranges[i].off + need, rest, true});
+      live += need;
+      if (live > peak) peak = live;
+      return base + ranges[i].off;
+    }
+    return nullptr;
+  }
+  void release(void *p) {
+    const size_t off = static_cast<unsigned char *>(p) - base;
+    for (size_t i = 0; i < ranges.size(); ++i) {
+      if (ranges[i].off != off || ranges[i].free) continue;
+      ranges[i].free = true;
+      live -= ranges[i].size;
+      if (i + 1 < ranges.size() && ranges[i + 1].free) {
+        ranges[i].size += ranges[i + 1].size;
+        ranges.erase(ranges.begin() + i + 1);
+      }
+      if (i > 0 && ranges[i - 1].free) {
+        ranges[i - 1].size += ranges[i].size;
+        ranges.erase(ranges.begin() + i);
+      }
+      return;
+    }
+  }
+};
+thread_local Arena *g_arena = nullptr;  // non-null while this thread runs the allocation-free forward
+
+// A request for device memory failed: says what was asked for and what the device allocator answered.
 int oom_error(size_t bytes) {
+  if (g_arena)
+    return set_error(FL_ERR_UNSUPPORTED,
+                     "the intermediates of this forward pass do not fit the static scratch: %zu more bytes wanted with "
+                     "%zu of %zu in use; use fl_layer_forward, or fewer tokens per call",
+                     bytes, g_arena->live, (size_t)kStaticScratchBytes);
   if (g_backing_error != hipSuccess) {
     const hipError_t e = g_backing_error;
     g_backing_error = hipSuccess;
@@ -210,6 +265,19 @@ bool debug_from_env() {
 }
 
 Buf *buf_new(size_t bytes, hipStream_t s) {
+  if (g_arena) {
+    void *p = g_arena->alloc(bytes);
+    Buf *b = p ? new (std::nothrow) Buf() : nullptr;
+    if (!b) {
+      if (p) g_arena->release(p);
+      return nullptr;
+    }
+    b->ptr = p;
+    b->bytes = bytes;
+    b->refs = 1;
+    b->from_arena = true;
+    return b;
+  }
   void *p = device_allocator().alloc(bytes, s, g_op_tag);
   if (!p) return nullptr;
   if (g_debug) {  // blocks are handed out in units of 512 bytes: rounding up to 16 stays inside the block
@@ -230,7 +298,11 @@ Buf *buf_new(size_t bytes, hipStream_t s) {
 }
 void buf_unref(Buf *&b) {
   if (b && --b->refs == 0) {
-    device_allocator().release(b->ptr);
+    if (b->from_arena) {
+      if (g_arena) g_arena->release(b->ptr);  // the arena is gone with its call otherwise
+    } else {
+      device_allocator().release(b->ptr);
+    }
     delete b;
   }
   b = nullptr;
@@ -745,7 +817,7 @@ int op_linear(fl_layer *L, int lin, int xslot, int rslot, int act, int K, int N,
     a.drop_where = 1;
     a.drop = make_drop_spec(L->rec_p_hidden, L->rec_seed, (uint32_t)site);
   }
-  if (act == XF_GELU) {  // the derivative needs the pre-activation
+  if (act == XF_GELU && !L->inference) {  // the derivative needs the pre-activation
     ub = buf_new((size_t)M * N * e, st);
     if (!ub) {
       buf_unref(yb);
@@ -769,7 +841,7 @@ int op_linear(fl_layer *L, int lin, int xslot, int rslot, int act, int K, int N,
   s.colsum_param = dropped && act == XF_NONE ? -1 : kLinear[lin].b;
   if (act != XF_NONE) {
     s.xform = act;
-    s.xform_aux = act == XF_GELU ? ub->ptr : y;  // ReLU: the output's sign is the pre-activation's
+    s.xform_aux = act == XF_GELU && ub ? ub->ptr : y;  // ReLU: the output's sign is the pre-activation's
     if (dropped) s.xform_drop_site = site;       // and the kept outputs were scaled: same mask on the way back
   }
   Node n;
@@ -937,6 +1009,93 @@ int forward_impl(fl_layer *L, const fl_layer_params_t *params, const void *X, co
   return 0;
 }
 
+// The allocation-free forward (fl_layer_forward_static): the same operators and kernels as forward_impl in
+// evaluation mode, with every intermediate carved out of the static scratch array and given back as soon as
+// its last reader is enqueued; nothing is kept for a backward pass and nothing is recorded.
+int forward_static_impl(fl_layer *L, const fl_layer_params_t *params, const void *X, const int32_t *lengths, int B,
+                        int T, void *Y, hipStream_t st) {
+  const fl_layer_config_t &c = L->cfg;
+  if (B < 1 || T < 1 || B > c.max_B || T > c.max_T)
+    return set_error(FL_ERR_INVALID_ARG, "B=%d T=%d outside 1..max_B=%d, 1..max_T=%d", B, T, c.max_B, c.max_T);
+  if ((long)B * T > (1l << 24)) return set_error(FL_ERR_UNSUPPORTED, "B*T too large");
+  if (L->tape.recorded || L->join_pending)
+    return set_error(FL_ERR_STATE, "the handle holds a recorded forward: run its backward (and join) first");
+  load_params(L, params);
+  FL_TRY(check_ptrs(L->params, P_COUNT, "params"));
+  const void *io[2] = {X, Y};
+  FL_TRY(check_ptrs(io, 2, "X/Y"));
+  const int D = c.d_model, F = c.d_ffn;
+  const size_t e = esize(L), M = (size_t)B * T;
+  // the largest set of intermediates alive at once: the feed-forward block (its input, the hidden
+  // activation and the residual sum around it)
+  // or the attention block (the fused projections, the attention output and its row statistics)
+  const size_t ffn = M * D * e * 2 + M * F * e, attn = M * D * e * 4 + M * c.n_heads * 4;
+  const size_t need = (ffn > attn ? ffn : attn) + M * 8 + 4096;
+  if (need > kStaticScratchBytes)
+    return set_error(FL_ERR_UNSUPPORTED,
+                     "B*T = %zu tokens need %zu bytes of intermediates, the static scratch holds %zu: use "
+                     "fl_layer_forward, or fewer tokens per call", M, need, (size_t)kStaticScratchBytes);
+  void *base = nullptr;
+  FL_HIP(static_scratch_base(&base));
+  Arena arena(base, kStaticScratchBytes);
+  struct Mode {  // evaluation mode on this thread for the length of the call
+    fl_layer *L;
+    Mode(fl_layer *l, Arena *a) : L(l) { g_arena = a; g_no_alloc = true; L->inference = true; }
+    ~Mode() {
+      release_tape(L);  // while the arena still exists
+      g_arena = nullptr; g_no_alloc = false; L->inference = false;
+    }
+  } mode(L, &arena);
+  L->B = B; L->T = T; L->M = B * T; L->stream = st; L->lengths = lengths;
+  L->rec_p_attn = 0.f; L->rec_p_hidden = 0.f; L->rec_seed = 0;  // evaluation mode: no dropout
+  Tape &tp = L->tape;
+  auto drop_value = [&](int slot) { buf_unref(tp.slots[slot].value_buf); };
+  auto drop_saved = [&]() {  // what the node recorded last keeps for its backward
+    for (Buf *&b : tp.nodes.back().saved) buf_unref(b);
+  };
+  const int act = c.act == FL_ACT_RELU ? XF_RELU : XF_GELU;
+  const int sx = tp.new_slot();
+  tp.slots[sx].value = X;
+  int s_qkv, s_o, s_r1, s_y1, s_g, s_out, s_n1;
+  if (c.norm == FL_NORM_POST) {
+    FL_TRY(op_linear(L, 0, sx, -1, XF_NONE, D, 3 * D, nullptr, &s_qkv, 0));
+    FL_TRY(op_attention(L, s_qkv, &s_o));
+    drop_saved();        // the log-sum-exp
+    drop_value(s_qkv);
+    FL_TRY(op_linear(L, 1, s_o, sx, XF_NONE, D, D, nullptr, &s_r1, 0));
+    drop_value(s_o);
+    FL_TRY(op_layernorm(L, 0, s_r1, nullptr, &s_y1));
+    drop_saved();        // mean / rstd
+    drop_value(s_r1);
+    FL_TRY(op_linear(L, 2, s_y1, -1, act, D, F, nullptr, &s_g, 0));
+    int s_r2;
+    FL_TRY(op_linear(L, 3, s_g, s_y1, XF_NONE, F, D, nullptr, &s_r2, 0));
+    drop_value(s_g);
+    drop_value(s_y1);
+    FL_TRY(op_layernorm(L, 1, s_r2, Y, &s_out));
+    drop_saved();
+    drop_value(s_r2);
+  } else {
+    FL_TRY(op_layernorm(L, 0, sx, nullptr, &s_n1));
+    drop_saved();
+    FL_TRY(op_linear(L, 0, s_n1, -1, XF_NONE, D, 3 * D, nullptr, &s_qkv, 0));
+    drop_value(s_n1);
+    FL_TRY(op_attention(L, s_qkv, &s_o));
+    drop_saved();
+    drop_value(s_qkv);
+    FL_TRY(op_linear(L, 1, s_o, sx, XF_NONE, D, D, nullptr, &s_r1, 0));
+    drop_value(s_o);
+    FL_TRY(op_layernorm(L, 1, s_r1, nullptr, &s_y1));
+    drop_saved();
+    FL_TRY(op_linear(L, 2, s_y1, -1, act, D, F, nullptr, &s_g, 0));
+    drop_value(s_y1);
+    FL_TRY(op_linear(L, 3, s_g, s_r1, XF_NONE, F, D, Y, &s_out, 0));
+    drop_value(s_g);
+    drop_value(s_r1);
+  }
+  return 0;  // ~Mode drops the recording: tape.recorded was never set
+}
+
 int backward_impl(fl_layer *L, const fl_layer_params_t *params, const void *dY, void *dX, fl_layer_grads_t *grads,
                   bool accumulate, hipStream_t st) {
   L->accumulate = accumulate;
@@ -1014,6 +1173,14 @@ fl_status_t fl_layer_forward(fl_layer_t *layer, const fl_layer_params_t *params,
   int rc = forward_impl(layer, params, X, lengths, B, T, Y, static_cast<hipStream_t>(hip_stream));
   if (rc) release_tape(layer);
   return (fl_status_t)rc;
+  FL_GUARD_END
+}
+
+fl_status_t fl_layer_forward_static(fl_layer_t *layer, const fl_layer_params_t *params, const void *X,
+                                    const int32_t *lengths, int32_t B, int32_t T, void *Y, void *hip_stream) {
+  FL_GUARD_BEGIN
+  if (!layer || !params || !X || !Y) return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "null argument");
+  return (fl_status_t)forward_static_impl(layer, params, X, lengths, B, T, Y, static_cast<hipStream_t>(hip_stream));
   FL_GUARD_END
 }
 

@@ -25,6 +25,7 @@ struct Buf {
   void *ptr = nullptr;
   size_t bytes = 0;
   int refs = 0;
+  bool from_arena = false;  // carved out of the static scratch array instead (allocation-free forward)
 };
 
 enum GradXform : int32_t { XF_NONE = 0, XF_RELU = 1, XF_GELU = 2 };
