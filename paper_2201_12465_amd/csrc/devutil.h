@@ -61,15 +61,29 @@ template <> struct VecIO<bf16_t, 8> {
   }
 };
 
+// Wavefront-wide reductions (every lane receives the result).  Inside a row of 16 lanes the partners come
+// through the data-parallel-primitive lane selects of the ALU (no LDS round trip as with a shuffle):
+// quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror; after them every lane of a row
+// holds its row's result, and the four rows meet through scalar reads of one lane each.
+template <int CTRL> __device__ __forceinline__ float dpp_lane(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float lane_value(float v, int lane) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  v += dpp_lane<0xB1>(v);
+  v += dpp_lane<0x4E>(v);
+  v += dpp_lane<0x141>(v);
+  v += dpp_lane<0x140>(v);
+  return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
+  v = fmaxf(v, dpp_lane<0xB1>(v));
+  v = fmaxf(v, dpp_lane<0x4E>(v));
+  v = fmaxf(v, dpp_lane<0x141>(v));
+  v = fmaxf(v, dpp_lane<0x140>(v));
+  return fmaxf(fmaxf(lane_value(v, 0), lane_value(v, 16)), fmaxf(lane_value(v, 32), lane_value(v, 48)));
 }
 
 // erf(x) and E = exp(-x^2) without branches: the rational approximation 7.1.26 of Abramowitz & Stegun,

@@ -72,8 +72,22 @@ hipError_t launch_reduce_partials(int dt, const float *partial, int P, size_t st
                                   int nseg, void *out0, void *out1, void *out2, hipStream_t stream,
                                   bool accumulate = false);  // accumulate: out_s += the sums
 
+// Up to REDUCE_MAX_JOBS such reductions in one launch, with the same summation order (bit-identical sums).
+constexpr int REDUCE_MAX_JOBS = 8;
+struct ReduceJob {
+  const float *partial;
+  int P, nseg;
+  size_t stride, seglen;
+  void *out[3];
+};
+hipError_t launch_reduce_batch(int dt, const ReduceJob *jobs, int n, hipStream_t stream, bool accumulate = false);
+
 // Column sums of in[M,N] (type dt) -> out[N] (type dt); ws must hold colsum_ws_floats(M,N) floats.
+// launch_colsum_stage1 runs the first stage alone: ws then holds colsum_stage1_rows(M) partial rows of N
+// floats, for a reduction the caller batches with others.
 size_t colsum_ws_floats(int M, int N);
+int colsum_stage1_rows(int M);
+hipError_t launch_colsum_stage1(int dt, const void *in, int M, int N, float *ws, hipStream_t stream);
 hipError_t launch_colsum(int dt, const void *in, int M, int N, float *ws, void *out, hipStream_t stream,
                          bool accumulate = false);
 

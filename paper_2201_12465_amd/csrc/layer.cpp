@@ -18,6 +18,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <functional>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -165,6 +166,19 @@ struct fl_layer {
   Buf *wt[4] = {nullptr, nullptr, nullptr, nullptr};
   hipEvent_t wt_fork_event = nullptr, wt_event = nullptr;
   bool wt_on_side = false;             // made on the side stream, and the layer's stream has not waited yet
+  // Second stages of the backward pass's two-stage reductions (split weight gradients, LayerNorm sums, bias
+  // sums): collected while the tape is replayed and run as ONE launch at the end of the parameter-gradient
+  // lane; the partial buffers are kept until then.
+  std::vector<ReduceJob> reduce_jobs;
+  std::vector<Buf *> reduce_bufs;
+  hipStream_t reduce_stream = nullptr;
+  bool reduce_has_side = false;        // some collected job's partial sums were written on the side stream
+  bool reduce_from_main = false;       // some collected job's partial sums were written on the layer's stream
+                                       // after the last fork: the side stream has not been told to wait for them
+  // Every fork puts a barrier on the layer's stream (the recorded event), a few microseconds in which the
+  // input-gradient chain stands still.  The first linear operator replayed therefore does not fork: its
+  // parameter-gradient work waits here for the next operator's fork and runs in front of that one's.
+  std::vector<std::function<int(hipStream_t)>> pending_side;
   bool inference = false;              // forward keeps nothing for a backward pass (no pre-activation copy)
   const void *params[P_COUNT];
   void *grads[P_COUNT];
@@ -366,6 +380,7 @@ int side_begin(fl_layer *L, hipEvent_t ev, hipStream_t *out) {
   if (!L->side) return 0;
   FL_HIP(hipStreamWaitEvent(L->side, ev, 0));
   *out = L->side;
+  L->reduce_from_main = false;  // whatever the layer's stream wrote before the event is ordered now
   return 0;
 }
 // A buffer that kernels on the side stream read must not go back to the cache of the layer's stream
@@ -531,6 +546,65 @@ int wt_acquire(fl_layer *L) {
   return 0;
 }
 
+// ---- batched second stages ---------------------------------------------------------------
+// Every job's partial sums are produced on `ps` (or, for the LayerNorm sums, made visible to it by a fork)
+// before anything enqueued later on `ps`: the batch launched at the end of the pass is ordered after them.
+int reduce_flush(fl_layer *L) {
+  int rc = 0;
+  if (!L->reduce_jobs.empty()) {
+    hipStream_t ps = L->reduce_stream;
+    if (L->reduce_from_main && ps != L->stream) {
+      if (!L->reduce_has_side) {
+        ps = L->stream;  // every partial sum was written on the layer's stream: reduce there, in order
+      } else {           // make the side stream wait for what the layer's stream wrote
+        hipEvent_t ev;
+        rc = side_mark(L, &ev);
+        if (!rc) rc = side_begin(L, ev, &ps);
+      }
+    }
+    if (!rc) {
+      double bytes = 0;
+      for (const ReduceJob &j : L->reduce_jobs) bytes += (double)(j.P * 4 + esize(L)) * j.seglen * j.nseg;
+      hipError_t he = timed(FL_K_SPLITK_REDUCE, 0, bytes, ps, [&] {
+        return launch_reduce_batch(L->dt, L->reduce_jobs.data(), (int)L->reduce_jobs.size(), ps, L->accumulate);
+      });
+      if (he != hipSuccess)
+        rc = set_error(FL_ERR_DEVICE, "the batched second-stage reduction failed: %s", hipGetErrorString(he));
+    }
+  }
+  for (Buf *&b : L->reduce_bufs) buf_unref(b);   // back to the cache of the stream that has just read them
+  L->reduce_bufs.clear();
+  L->reduce_jobs.clear();
+  L->reduce_from_main = false;
+  L->reduce_has_side = false;
+  return rc;
+}
+// ps: the stream the batch will run on (the side stream while there is one).  from_main: the partial sums were
+// written by a kernel on the layer's stream that no fork has covered yet.
+int reduce_later(fl_layer *L, hipStream_t ps, bool from_main, Buf *partial, int P, size_t stride, size_t seglen,
+                 int nseg, void *o0, void *o1, void *o2) {
+  if (!L->reduce_jobs.empty() && (L->reduce_stream != ps || (int)L->reduce_jobs.size() == REDUCE_MAX_JOBS))
+    FL_TRY(reduce_flush(L));
+  L->reduce_stream = ps;
+  if (from_main && ps != L->stream) L->reduce_from_main = true;
+  if (!from_main && ps != L->stream) L->reduce_has_side = true;
+  ReduceJob j;
+  j.partial = static_cast<const float *>(partial->ptr);
+  j.P = P; j.nseg = nseg; j.stride = stride; j.seglen = seglen;
+  j.out[0] = o0; j.out[1] = o1; j.out[2] = o2;
+  L->reduce_jobs.push_back(j);
+  partial->refs++;
+  L->reduce_bufs.push_back(partial);
+  return 0;
+}
+int run_pending_side(fl_layer *L, hipStream_t ps) {
+  int rc = 0;
+  for (auto &f : L->pending_side)
+    if (!rc) rc = f(ps);
+  L->pending_side.clear();
+  return rc;
+}
+
 // ---- gradient functions ---------------------------------------------------------------
 
 
@@ -565,8 +639,10 @@ int linear_backward(void *ctx, Tape *tape, const Node *n) {
     Buf *&b;
     ~Unref() { buf_unref(b); }
   } unref_gm{gm};
-  hipEvent_t forked;
-  FL_TRY(side_mark(L, &forked));   // gy is complete at this point of the layer's stream
+  // The first linear operator of the replay leaves its parameter-gradient work to the next fork (see pending_side).
+  const bool defer_side = L->side && L->forks == 0 && L->pending_side.empty() && self > 1;
+  hipEvent_t forked = nullptr;
+  if (!defer_side) FL_TRY(side_mark(L, &forked));   // gy is complete at this point of the layer's stream
   // input gradient: dx[M,K] = gy W (+ what other consumers of x already contributed)
   {
     Slot &xs = tape->slots[n->in0];
@@ -610,29 +686,30 @@ int linear_backward(void *ctx, Tape *tape, const Node *n) {
   // The parameter gradients need gy and the saved input only and nobody waits for them before the
   // backward pass ends: they go to the side stream, beside the input-gradient chain (whose GEMM is
   // already enqueued above).
-  hipStream_t ps;
-  FL_TRY(side_begin(L, forked, &ps));
   side_hold(L, gm ? gm : ys.grad_buf);
   side_hold(L, tape->slots[n->in0].value_buf);
-  // bias gradient, unless the kernel that finished gy already produced it
-  if (!ys.colsum_done) {
-    // The first node of the tape is replayed last: nothing follows its input-gradient GEMM on the layer's
-    // stream, while the side stream still has this node's weight gradient to do, so the bias sums go
-    // behind the GEMM instead (measured: 0.420 -> 0.417 ms per step; for any other node they would delay
-    // the chain and cost more than they save)
-    hipStream_t cs = self == 0 ? st : ps;
-    Scratch ws;
-    FL_TRY(ws.get(colsum_ws_floats(M, N) * sizeof(float), cs));
-    FL_HIP(timed(FL_K_COLSUM, 0, (double)M * N * e, cs,
-                 [&] { return launch_colsum(dt, gy, M, N, ws.f32(), L->grads[kLinear[n->param].b], cs, L->accumulate); }));
-  }
-  // weight gradient: dW[N,K] = sum_m gy[m,n] x[m,k]
-  {
+  const bool need_colsum = !ys.colsum_done;
+  const bool reads_callers_dy = L->side && L->defer_join && !gm && !ys.grad_buf;
+  const void *x_saved = n->s0;
+  const int lin = n->param;
+  auto side_work = [=](hipStream_t ps) -> int {
+    OpTag tag2(FL_OP_LINEAR_BWD, self);
+    // bias gradient, unless the kernel that finished gy already produced it: first stage here, second stage
+    // batched with the others
+    if (need_colsum) {
+      Scratch ws;
+      FL_TRY(ws.get(colsum_ws_floats(M, N) * sizeof(float), ps));
+      FL_HIP(timed(FL_K_COLSUM, 0, (double)M * N * e, ps,
+                   [&] { return launch_colsum_stage1(dt, gy, M, N, ws.f32(), ps); }));
+      FL_TRY(reduce_later(L, ps, false, ws.b, colsum_stage1_rows(M), (size_t)N, (size_t)N, 1,
+                          L->grads[kLinear[lin].b], nullptr, nullptr));
+    }
+    // weight gradient: dW[N,K] = sum_m gy[m,n] x[m,k]
     GemmArgs a;
     a.A = gy; a.lda = N; a.a_kc = false;
-    a.B = n->s0; a.ldb = K; a.b_kc = false;
+    a.B = x_saved; a.ldb = K; a.b_kc = false;
     a.M = N; a.N = K; a.K = M;
-    a.C = L->grads[kLinear[n->param].w]; a.ldc = K;
+    a.C = L->grads[kLinear[lin].w]; a.ldc = K;
     a.splits = gemm_pick_splits(dt, a.M, a.N, a.K);
     const double fl = 2.0 * M * N * K, by = ((double)M * N + (double)M * K + (double)N * K) * e;
     if (a.splits > 1) {
@@ -640,19 +717,30 @@ int linear_backward(void *ctx, Tape *tape, const Node *n) {
       FL_TRY(ws.get((size_t)a.splits * N * K * sizeof(float), ps));
       a.partial = ws.f32();
       FL_HIP(timed(FL_K_GEMM_TN, fl, by, ps, [&] { return launch_gemm(dt, a, ps); }));
-      FL_HIP(timed(FL_K_SPLITK_REDUCE, 0, (double)(a.splits * 4 + e) * N * K, ps, [&] {
-        return launch_reduce_partials(dt, ws.f32(), a.splits, (size_t)N * K, (size_t)N * K, 1, a.C, nullptr, nullptr, ps,
-                                      L->accumulate);
-      }));
+      FL_TRY(reduce_later(L, ps, false, ws.b, a.splits, (size_t)N * K, (size_t)N * K, 1, a.C, nullptr, nullptr));
     } else {
       if (L->accumulate) a.residual = a.C;  // in place: each lane reads the elements it then writes
       FL_HIP(timed(FL_K_GEMM_TN, fl, by, ps, [&] { return launch_gemm(dt, a, ps); }));
     }
-  }
-  if (L->side && L->defer_join && !gm && !ys.grad_buf) {  // gy is the caller's dY, and these were its readers
-    if (!L->caller_read_event) FL_HIP(hipEventCreateWithFlags(&L->caller_read_event, kEventFlags));
-    FL_HIP(hipEventRecord(L->caller_read_event, L->side));
-    L->caller_read_pending = true;
+    if (reads_callers_dy) {  // gy is the caller's dY, and these were its readers
+      if (!L->caller_read_event) FL_HIP(hipEventCreateWithFlags(&L->caller_read_event, kEventFlags));
+      FL_HIP(hipEventRecord(L->caller_read_event, L->side));
+      L->caller_read_pending = true;
+    }
+    return 0;
+  };
+  // The parameter gradients need gy and the saved input only and nobody waits for them before the
+  // backward pass ends: they go to the side stream, beside the input-gradient chain (whose GEMM is
+  // already enqueued above).
+  if (defer_side) {
+    L->pending_side.push_back(side_work);
+  } else {
+    hipStream_t ps;
+    FL_TRY(side_begin(L, forked, &ps));
+    FL_TRY(run_pending_side(L, ps));
+    FL_TRY(side_work(ps));
+    // (the second stages stay collected until the end of the pass: one launch there measured better than a
+    // launch after every operator, 0.408 against 0.413 ms per step on the BERT-base shape)
   }
   // residual input: the identity branch passes gy through unchanged
   if (n->in1 >= 0) {
@@ -768,16 +856,12 @@ int layernorm_backward(void *ctx, Tape *tape, const Node *n) {
   }
   set_grad(xs, dst, nb);
   const bool want_bias = fin && xs.colsum_param >= 0;
-  // second stage of the parameter-gradient sums: beside the input-gradient chain
-  hipEvent_t forked;
-  hipStream_t ps;
-  FL_TRY(side_mark(L, &forked));
-  FL_TRY(side_begin(L, forked, &ps));
+  // second stage of the parameter-gradient sums: batched with the others on the parameter-gradient lane (no
+  // fork of its own: the next linear operator's fork, or the one before the last batch, covers these sums)
+  hipStream_t ps = L->side ? L->side : st;
   side_hold(L, ws.b);
-  FL_HIP(timed(FL_K_COLSUM, 0, (double)parts * 3 * D * 4, ps, [&] {
-    return launch_reduce_partials(dt, ws.f32(), parts, (size_t)3 * D, (size_t)D, want_bias ? 3 : 2, L->grads[gi],
-                                  L->grads[bi], want_bias ? L->grads[xs.colsum_param] : nullptr, ps, L->accumulate);
-  }));
+  FL_TRY(reduce_later(L, ps, true, ws.b, parts, (size_t)3 * D, (size_t)D, want_bias ? 3 : 2, L->grads[gi], L->grads[bi],
+                      want_bias ? L->grads[xs.colsum_param] : nullptr));
   if (want_bias) xs.colsum_done = true;
   set_grad(ys, nullptr, nullptr);
   buf_unref(ys.value_buf);
@@ -1116,6 +1200,23 @@ int backward_impl(fl_layer *L, const fl_layer_params_t *params, const void *dY, 
   L->side = g_overlap && (long)L->M * L->cfg.d_model >= (1l << 18) ? side_stream() : nullptr;
   L->forks = 0;
   int rc = tp.replay_reverse(L);
+  if (!rc && !L->pending_side.empty()) {  // no later operator forked: fork now
+    hipEvent_t ev;
+    hipStream_t ps;
+    rc = side_mark(L, &ev);
+    if (!rc) rc = side_begin(L, ev, &ps);
+    if (!rc) rc = run_pending_side(L, ps);
+  }
+  if (rc) {   // drop what the failed pass has collected
+    L->pending_side.clear();
+    L->reduce_jobs.clear();
+    for (Buf *&b : L->reduce_bufs) buf_unref(b);
+    L->reduce_bufs.clear();
+    L->reduce_from_main = false;
+    L->reduce_has_side = false;
+  } else {
+    rc = reduce_flush(L);
+  }
   const bool landed = rc == 0 && tp.slots[L->slot_x].grad == dX;
   const int jrc = side_join(L, rc != 0, L->defer_join);
   release_tape(L);

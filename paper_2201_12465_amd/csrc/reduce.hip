@@ -72,6 +72,69 @@ __global__ __launch_bounds__(1024) void reduce_partials_tall_kernel(const float 
   }
 }
 
+// Several such reductions in one launch (the second stages a backward pass has collected).  A workgroup
+// of 16 waves serves one job: "flat" jobs (few partial rows) give every thread one float4 column and let it
+// walk the P rows; "tall" jobs (many partial rows, few columns) work as reduce_partials_tall_kernel.  Both
+// add in the order of the single-job kernels above, so the sums are bit-identical to theirs.
+struct ReduceTable {
+  ReduceJob job[REDUCE_MAX_JOBS];
+  int first_block[REDUCE_MAX_JOBS + 1];  // job j owns workgroups first_block[j] .. first_block[j+1]-1
+  int blocks_per_seg[REDUCE_MAX_JOBS];
+  int n;
+};
+template <typename T>
+__global__ __launch_bounds__(1024) void reduce_batch_kernel(ReduceTable tb, int accumulate) {
+  __shared__ float4 red[16][64];
+  int j = 0;
+  while (j + 1 < tb.n && (int)blockIdx.x >= tb.first_block[j + 1]) ++j;
+  const ReduceJob &J = tb.job[j];
+  const int local = blockIdx.x - tb.first_block[j];
+  const int s = local / tb.blocks_per_seg[j], blk = local - s * tb.blocks_per_seg[j];
+  T *out = static_cast<T *>(J.out[s]);
+  const float *src0 = J.partial + (size_t)s * J.seglen;
+  if (J.P < 32) {
+    const size_t n = ((size_t)blk * 1024 + threadIdx.x) * 4;
+    if (n >= J.seglen || !out) return;
+    float a[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int p = 0; p < J.P; ++p) {
+      float4 t = *reinterpret_cast<const float4 *>(src0 + n + (size_t)p * J.stride);
+      a[0] += t.x; a[1] += t.y; a[2] += t.z; a[3] += t.w;
+    }
+    if (accumulate) {
+      float o[4];
+      VecIO<T, 4>::load(out + n, o);
+      a[0] += o[0]; a[1] += o[1]; a[2] += o[2]; a[3] += o[3];
+    }
+    VecIO<T, 4>::store(out + n, a);
+    return;
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const size_t n = ((size_t)blk * 64 + lane) * 4;
+  float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (n < J.seglen) {
+    for (int p = wave; p < J.P; p += 16) {
+      float4 t = *reinterpret_cast<const float4 *>(src0 + n + (size_t)p * J.stride);
+      a.x += t.x; a.y += t.y; a.z += t.z; a.w += t.w;
+    }
+  }
+  red[wave][lane] = a;
+  __syncthreads();
+  if (wave == 0 && n < J.seglen && out) {
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+      float4 t = red[w][lane];
+      v[0] += t.x; v[1] += t.y; v[2] += t.z; v[3] += t.w;
+    }
+    if (accumulate) {
+      float o[4];
+      VecIO<T, 4>::load(out + n, o);
+      v[0] += o[0]; v[1] += o[1]; v[2] += o[2]; v[3] += o[3];
+    }
+    VecIO<T, 4>::store(out + n, v);
+  }
+}
+
 constexpr int CS_ROWS = 32;   // rows per first-stage block
 
 // ws[rb][n] = sum over the rows of block rb of in[m][n]; 64 lanes x VEC columns, 4 waves interleave rows
@@ -133,21 +196,53 @@ hipError_t launch_reduce_partials(int dt, const float *partial, int P, size_t st
   return hipGetLastError();
 }
 
+hipError_t launch_reduce_batch(int dt, const ReduceJob *jobs, int n, hipStream_t stream, bool accumulate) {
+  if (!jobs || n < 1 || n > REDUCE_MAX_JOBS) return hipErrorInvalidValue;
+  ReduceTable tb;
+  tb.n = n;
+  int total = 0;
+  for (int j = 0; j < n; ++j) {
+    const ReduceJob &J = jobs[j];
+    if (!J.partial || J.P < 1 || J.nseg < 1 || J.nseg > 3 || J.seglen == 0 || J.seglen % 4 || J.stride % 4)
+      return hipErrorInvalidValue;
+    if ((size_t)J.nseg * J.seglen > J.stride && J.P > 1) return hipErrorInvalidValue;
+    tb.job[j] = J;
+    const size_t cols4 = J.seglen / 4;
+    tb.blocks_per_seg[j] = (int)(J.P < 32 ? (cols4 + 1023) / 1024 : (cols4 + 63) / 64);
+    tb.first_block[j] = total;
+    total += tb.blocks_per_seg[j] * J.nseg;
+  }
+  tb.first_block[n] = total;
+  if (dt == DT_F32)
+    hipLaunchKernelGGL(reduce_batch_kernel<float>, dim3(total), dim3(1024), 0, stream, tb, accumulate ? 1 : 0);
+  else
+    hipLaunchKernelGGL(reduce_batch_kernel<bf16_t>, dim3(total), dim3(1024), 0, stream, tb, accumulate ? 1 : 0);
+  return hipGetLastError();
+}
+
 size_t colsum_ws_floats(int M, int N) { return (size_t)((M + CS_ROWS - 1) / CS_ROWS) * N; }
 
-hipError_t launch_colsum(int dt, const void *in, int M, int N, float *ws, void *out, hipStream_t stream,
-                         bool accumulate) {
-  if (!in || !ws || !out || M < 1 || N < 1 || N % 8) return hipErrorInvalidValue;
-  const int rb = (M + CS_ROWS - 1) / CS_ROWS;
+int colsum_stage1_rows(int M) { return (M + CS_ROWS - 1) / CS_ROWS; }
+
+hipError_t launch_colsum_stage1(int dt, const void *in, int M, int N, float *ws, hipStream_t stream) {
+  if (!in || !ws || M < 1 || N < 1 || N % 8) return hipErrorInvalidValue;
+  const int rb = colsum_stage1_rows(M);
   const int vec = dt == DT_F32 ? 4 : 8;
   dim3 grid((N + 64 * vec - 1) / (64 * vec), rb);
   if (dt == DT_F32)
     hipLaunchKernelGGL(colsum_stage1_kernel<float>, grid, dim3(256), 0, stream, static_cast<const float *>(in), M, N, ws);
   else
     hipLaunchKernelGGL(colsum_stage1_kernel<bf16_t>, grid, dim3(256), 0, stream, static_cast<const bf16_t *>(in), M, N, ws);
-  hipError_t e = hipGetLastError();
+  return hipGetLastError();
+}
+
+hipError_t launch_colsum(int dt, const void *in, int M, int N, float *ws, void *out, hipStream_t stream,
+                         bool accumulate) {
+  if (!out) return hipErrorInvalidValue;
+  hipError_t e = launch_colsum_stage1(dt, in, M, N, ws, stream);
   if (e != hipSuccess) return e;
-  return launch_reduce_partials(dt, ws, rb, (size_t)N, (size_t)N, 1, out, nullptr, nullptr, stream, accumulate);
+  return launch_reduce_partials(dt, ws, colsum_stage1_rows(M), (size_t)N, (size_t)N, 1, out, nullptr, nullptr, stream,
+                                accumulate);
 }
 
 // Plain copy of nbytes (a multiple of 16; 16-byte aligned): the reference for what one read plus one
