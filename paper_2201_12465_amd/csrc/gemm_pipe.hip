@@ -35,6 +35,23 @@ typedef __attribute__((address_space(3))) s16x4_t *lds_s16x4_ptr;
 
 template <int N> __device__ __forceinline__ void wait_vmcnt_le() { FL_WAIT_VMCNT(N); }
 
+// One wave-level direct-to-LDS load: lane l's 16 bytes at `src` land at LDS byte address lds_base + 16*l
+// (lds_base is wave-uniform and travels in M0).  Written as inline assembly on purpose: through the
+// compiler's builtin the instruction counts as a flat access that may touch LDS, and from then on every
+// wait the compiler inserts for an LDS read is a wait for ALL outstanding LDS reads (lgkmcnt(0)) -- the
+// fragment reads requested ahead for the next k-step included, which serialises the main loop.  The kernel
+// orders these loads itself (s_waitcnt vmcnt + s_barrier before any read of a stage), so the compiler has
+// nothing to track.  One wait state is required between the write of M0 and the load.
+__device__ __forceinline__ void lds_dma16(const void *src, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(src), "s"(lds_base)
+               : "memory", "m0");
+}
+__device__ __forceinline__ unsigned lds_address(const void *p) {
+  return (unsigned)(size_t)(__attribute__((address_space(3))) const unsigned char *)p;
+}
+
 // One operand's staging plan for this wave: element offsets (from the operand base) of the chunks
 // its lanes fetch, for each of its NOPS wave-level loads per k-tile.
 template <bool KC, int R, int NW> struct Stager {
@@ -56,11 +73,12 @@ template <bool KC, int R, int NW> struct Stager {
     }
     kstep = KC ? KT : KT * ld;
   }
-  __device__ __forceinline__ void issue(const bf16_t *base, int kt, unsigned char *stage, int wave) const {
+  // stage_lds: LDS byte address of the stage's first byte; wave: wave-uniform (a scalar)
+  __device__ __forceinline__ void issue(const bf16_t *base, int kt, unsigned stage_lds, int wave) const {
 #pragma unroll
     for (int j = 0; j < NOPS; ++j) {
       const bf16_t *src = base + (size_t)off[j] + (size_t)kt * kstep;
-      __builtin_amdgcn_global_load_lds((glb_void_ptr)src, (lds_void_ptr)(stage + (wave + NW * j) * 1024), 16, 0, 0);
+      lds_dma16(src, stage_lds + (unsigned)(wave + NW * j) * 1024u);
     }
   }
 };
@@ -109,7 +127,9 @@ __global__ __launch_bounds__(WM *WN *KG * 64) void gemm_bf16_pipe(GemmDev p) {
   const int nk = (kend - kbeg) / KT;
   const bf16_t *A = static_cast<const bf16_t *>(p.A);
   const bf16_t *B = static_cast<const bf16_t *>(p.B);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // in a scalar register: LDS addresses below are scalars too
+  const unsigned smem_lds = lds_address(smem);
   const int kg = wave / (WM * WN), wpos = wave % (WM * WN);  // k-group, position in the tile
   const int wm = wpos / WN, wn = wpos % WN;
 
@@ -130,8 +150,8 @@ __global__ __launch_bounds__(WM *WN *KG * 64) void gemm_bf16_pipe(GemmDev p) {
 #pragma unroll
   for (int s = 0; s < NS - 1; ++s) {
     if (s < nk) {
-      sa.issue(A, s, smem + s * STAGE, wave);
-      sb.issue(B, s, smem + s * STAGE + A_BYTES, wave);
+      sa.issue(A, s, smem_lds + s * STAGE, wave);
+      sb.issue(B, s, smem_lds + s * STAGE + A_BYTES, wave);
     }
   }
   for (int kt = 0; kt < nk; ++kt) {
@@ -146,12 +166,16 @@ __global__ __launch_bounds__(WM *WN *KG * 64) void gemm_bf16_pipe(GemmDev p) {
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     if (kt + NS - 1 < nk) {
-      unsigned char *st = smem + ((kt + NS - 1) % NS) * STAGE;
+      const unsigned st = smem_lds + ((kt + NS - 1) % NS) * STAGE;
       sa.issue(A, kt + NS - 1, st, wave);
       sb.issue(B, kt + NS - 1, st + A_BYTES, wave);
     }
     const unsigned char *sA = smem + (kt % NS) * STAGE, *sB = sA + A_BYTES;
-    // fragments of k-step kk+1 are requested before the MFMAs of k-step kk are issued
+    // fragments of k-step kk+1 are requested before the MFMAs of k-step kk are issued.  Left to itself the
+    // scheduler sinks those reads behind the MFMAs and into the registers the MFMAs have just read, so that
+    // every k-step waits out a full LDS round trip; the scheduling barriers keep the two groups apart where
+    // the wavefront tile is small enough for the second fragment set to cost no occupancy.
+    constexpr bool PIN = TM * TN <= 4;
     bf16x8_t fa[2][TM], fb[2][TN];
     const int kk0 = kg * KKS;
 #pragma unroll
@@ -168,11 +192,13 @@ __global__ __launch_bounds__(WM *WN *KG * 64) void gemm_bf16_pipe(GemmDev p) {
         for (int j = 0; j < TN; ++j)
           fb[(kk + 1) & 1][j] = frag<BKC, BN>(sB, wn * (BN / WN) + j * 32, kk0 + kk + 1, lane);
       }
+      if constexpr (PIN) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][j], fa[kk & 1][i], acc[i][j], 0, 0, 0);
+      if constexpr (PIN) __builtin_amdgcn_sched_barrier(0);
     }
   }
 
