@@ -17,6 +17,11 @@ mfma: <dir> is the -d directory of one counter run (SQ block + GRBM_GUI_ACTIVE, 
 the same bench command; per kernel it prints the share of the chip's MFMA issue cycles that were busy
 (the matrix-core utilisation the roofline fraction is cross-checked against), the share of the
 wavefronts' resident cycles spent waiting, and LDS bank conflicts.
+    python -m paper_2201_12465_amd.profile_summary l2 <dir> [--workload NAME] > summary.txt
+l2: <dir> is the -d directory of one counter run (L2_COUNTERS: the L2 and vector-L1 blocks) around the same
+bench command; per kernel it prints the L2 hit rate, the average latency of a vector-L1 read request to
+L2, and how much of the time the L1 had requests pending -- the evidence for where a GEMM's operand
+traffic waits.
 Only text parsing happens here: nothing touches the GPU.
 """
 import argparse
@@ -59,7 +64,7 @@ def classify(name: str) -> str:
             else:
                 a, bb = bools[0] == "true", bools[1] == "true"
         return {(True, True): "gemm_nt", (True, False): "gemm_nn", (False, False): "gemm_tn"}.get((a, bb), "gemm")
-    table = (("reduce_partials", "splitk_reduce"), ("colsum", "colsum"), ("attn_fwd", "attn_fwd"),
+    table = (("reduce_partials", "splitk_reduce"), ("reduce_batch", "splitk_reduce"), ("colsum", "colsum"), ("attn_fwd", "attn_fwd"),
              ("attn_bwd", "attn_bwd"), ("attn_delta", "attn_bwd"), ("ln_fwd", "ln_fwd"), ("ln_bwd", "ln_bwd"),
              ("opt_step", "optimizer"), ("zero_tensors", "optimizer"), ("transpose_tiles", "wt_transpose"))
     for key, cls in table:
@@ -222,6 +227,54 @@ def mfma(args) -> int:
     return 0
 
 
+L2_COUNTERS = ("TCC_HIT_sum", "TCC_MISS_sum", "TCC_EA0_RDREQ_sum", "TCP_TCC_READ_REQ_sum",
+               "TCP_TCC_READ_REQ_LATENCY_sum", "TCP_PENDING_STALL_CYCLES_sum", "GRBM_GUI_ACTIVE")
+
+
+def l2(args) -> int:
+    acc = collections.defaultdict(lambda: collections.defaultdict(list))
+    for f in glob.glob(args.dir + "/**/*counter_collection.csv", recursive=True):
+        for r in csv.DictReader(open(f)):
+            if ours(r["Kernel_Name"]):
+                acc[r["Kernel_Name"]][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    if not acc:
+        print(f"no counter_collection.csv with this library's kernels under {args.dir}", file=sys.stderr)
+        return 1
+    xcc = 8
+    for f in glob.glob(args.dir + "/**/*agent_info.csv", recursive=True):
+        for r in csv.DictReader(open(f)):
+            if r.get("Agent_Type") == "GPU" and r.get("Num_Xcc", "").isdigit():
+                xcc = int(r["Num_Xcc"])
+    print("# made by (from /tmp, TMPDIR=/tmp, on one MI355X):")
+    print(f"#   rocprofv3 --pmc {' '.join(L2_COUNTERS)} --output-format csv -d <dir> -- python3 bench.py "
+          f"--workload {args.workload} --steps 3 --warmup 2 --no-cpu-baseline --no-kernel-timing --no-grad-overlap")
+    print(f"#   python3 -m paper_2201_12465_amd.profile_summary l2 <dir> --workload {args.workload}")
+    print("# Per dispatch, averaged over the launches of a kernel (each kernel runs alone under counter collection).")
+    print(f"# gui_cyc      GRBM_GUI_ACTIVE / {xcc}: clocks the dispatch kept the GPU busy")
+    print("# l2_hit       TCC_HIT / (TCC_HIT + TCC_MISS): share of L2 requests served from the L2 of the requesting die")
+    print("# l2_req_MB    TCP_TCC_READ_REQ x 64 bytes: what the vector L1 caches asked the L2 for")
+    print("# mem_rd_MB    TCC_EA0_RDREQ x 64 bytes (upper bound: 32-byte requests count as one): L2 misses sent to the memory side")
+    print("# rd_latency   TCP_TCC_READ_REQ_LATENCY / TCP_TCC_READ_REQ: average clocks from an L1 read request to its answer")
+    print("# l1_pending   TCP_PENDING_STALL_CYCLES summed over the 256 L1s / (gui_cyc x 256)")
+    print(f"workload {args.workload}")
+    print(f"{'class':13s} {'kernel':60s} {'n':>4s} {'gui_cyc':>9s} {'l2_hit':>7s} {'l2_req_MB':>10s} {'mem_rd_MB':>10s} "
+          f"{'rd_latency':>10s} {'l1_pending':>10s}")
+    rows = []
+    for k, cs in acc.items():
+        a = {c: (sum(v) / len(v) if v else 0.0) for c, v in cs.items()}
+        g = a.get("GRBM_GUI_ACTIVE", 0.0) / xcc
+        n = len(cs.get("GRBM_GUI_ACTIVE", [])) or len(next(iter(cs.values())))
+        rows.append((g * n, k, n, g, a))
+    for _, k, n, g, a in sorted(rows, reverse=True):
+        hit, miss = a.get("TCC_HIT_sum", 0.0), a.get("TCC_MISS_sum", 0.0)
+        req = a.get("TCP_TCC_READ_REQ_sum", 0.0)
+        print(f"{classify(k):13s} {short(k, 60):60s} {n:4d} {g:9.0f} {hit / (hit + miss) if hit + miss else 0:7.3f} "
+              f"{req * 64 / 1e6:10.1f} {a.get('TCC_EA0_RDREQ_sum', 0.0) * 64 / 1e6:10.1f} "
+              f"{a.get('TCP_TCC_READ_REQ_LATENCY_sum', 0.0) / req if req else 0:10.0f} "
+              f"{a.get('TCP_PENDING_STALL_CYCLES_sum', 0.0) / (g * 256) if g else 0:10.2f}")
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -235,8 +288,11 @@ def main() -> int:
     m = sub.add_parser("mfma")
     m.add_argument("dir")
     m.add_argument("--workload", default="cfg3_bert_base_bf16")
+    q = sub.add_parser("l2")
+    q.add_argument("dir")
+    q.add_argument("--workload", default="cfg3_bert_base_bf16")
     a = ap.parse_args()
-    return {"kernel-trace": kernel_trace, "traffic": traffic, "mfma": mfma}[a.cmd](a)
+    return {"kernel-trace": kernel_trace, "traffic": traffic, "mfma": mfma, "l2": l2}[a.cmd](a)
 
 
 if __name__ == "__main__":
