@@ -265,7 +265,8 @@ fl_status_t fl_alloc_set_split_limit(uint64_t bytes);
  * 16-byte aligned).  state_m[i] (SGD momentum buffer / Adam m) and state_v[i] (Adam v) are device
  * fp32 buffers of numel[i] elements owned by the caller, zero before the first step; state_m may
  * be NULL for SGD without momentum, state_v for SGD.  The pointer arrays themselves are HOST
- * arrays.  Arithmetic is fp32; a bf16 parameter is rounded once when it is written back. */
+ * arrays.  Arithmetic is fp32; a bf16 parameter is rounded once when it is written back, and no
+ * higher-precision copy is kept: over many small steps that rounding accumulates (see fl_opt_step_master). */
 typedef enum { FL_OPT_SGD = 0, FL_OPT_ADAM = 1 } fl_opt_kind_t;
 typedef struct {
   fl_opt_kind_t kind;
@@ -275,6 +276,16 @@ typedef struct {
 fl_status_t fl_opt_step(const fl_opt_config_t *cfg, fl_dtype_t dtype, int32_t n, void *const *params,
                         const void *const *grads, float *const *state_m, float *const *state_v, const int64_t *numel,
                         void *hip_stream);
+/* The same step with full-precision master copies (Section 4.2: the optimizers act on the parameters' tensors;
+ * with bf16 storage a parameter of magnitude 0.02 has a spacing of 6e-5, so updates of the order lr = 1e-4 and
+ * below are largely rounded away when the bf16 value itself carries them).  master[i]: device fp32 buffer
+ * of numel[i] elements owned by the caller, initialised with the parameter's values, or NULL for a tensor
+ * without one (`master` itself may be NULL: then this is fl_opt_step).  Where given, the update reads and
+ * writes the master copy and params[i] receives its value rounded to `dtype`; 8 more bytes of traffic per
+ * element. */
+fl_status_t fl_opt_step_master(const fl_opt_config_t *cfg, fl_dtype_t dtype, int32_t n, void *const *params,
+                               float *const *master, const void *const *grads, float *const *state_m,
+                               float *const *state_v, const int64_t *numel, void *hip_stream);
 /* Sets n gradient tensors to zero with one kernel (safe inside a captured graph). */
 fl_status_t fl_zero_grad(fl_dtype_t dtype, int32_t n, void *const *grads, const int64_t *numel, void *hip_stream);
 

@@ -97,6 +97,8 @@ def _signatures():
                                                    C.POINTER(fl_layer_grads_t), i32, vp]),
         "fl_opt_step": (C.c_int, [C.POINTER(fl_opt_config_t), C.c_int, i32, C.POINTER(vp), C.POINTER(vp),
                                   C.POINTER(vp), C.POINTER(vp), C.POINTER(i64), vp]),
+        "fl_opt_step_master": (C.c_int, [C.POINTER(fl_opt_config_t), C.c_int, i32, C.POINTER(vp), C.POINTER(vp),
+                                         C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(i64), vp]),
         "fl_zero_grad": (C.c_int, [C.c_int, i32, C.POINTER(vp), C.POINTER(i64), vp]),
         "fl_layer_set_dropout": (C.c_int, [vp, f32, f32, u64]),
         "fl_layer_destroy": (C.c_int, [vp]),
@@ -265,12 +267,17 @@ def _ptr_array(items):
 
 
 def opt_step(kind: str, dtype: str, params, grads, state_m, state_v, numel, stream: int = 0, *, lr, momentum=0.0,
-             weight_decay=0.0, beta1=0.9, beta2=0.999, eps=1e-8, step=1) -> None:
-    """One fused optimizer step over lists of tensors (see fl_opt_step)."""
+             weight_decay=0.0, beta1=0.9, beta2=0.999, eps=1e-8, step=1, master=None) -> None:
+    """One fused optimizer step over lists of tensors (see fl_opt_step; with `master`, fl_opt_step_master)."""
     cfg = fl_opt_config_t({"sgd": FL_OPT_SGD, "adam": FL_OPT_ADAM}[kind], lr, momentum, weight_decay, beta1, beta2,
                           eps, step)
     n = len(params)
     ne = (C.c_int64 * n)(*[int(x) for x in numel])
+    if master is not None:
+        check(lib().fl_opt_step_master(C.byref(cfg), {"f32": FL_F32, "bf16": FL_BF16}[dtype], n, _ptr_array(params),
+                                       _ptr_array(master), _ptr_array(grads), _ptr_array(state_m),
+                                       _ptr_array(state_v), ne, stream))
+        return
     check(lib().fl_opt_step(C.byref(cfg), {"f32": FL_F32, "bf16": FL_BF16}[dtype], n, _ptr_array(params),
                             _ptr_array(grads), _ptr_array(state_m), _ptr_array(state_v), ne, stream))
 

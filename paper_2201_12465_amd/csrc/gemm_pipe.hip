@@ -314,15 +314,19 @@ int gemm_pipe_pick_variant(bool a_kc, bool b_kc, int M, int N, int K) {
   const int forced = forced_gemm_pipe_variant();
   if (forced != -1) return forced == 7 && !(a_kc && b_kc) ? -2 : forced;
   (void)K;
-  // Measured on the layer's shapes (M = 4096, N and K in {768, 2304, 3072}).  dy W (one k-major
-  // operand): the register-staged kernel in gemm.hip is at least as fast.  dy^T x (both k-major, split
-  // over the tokens): this kernel with two wavefront groups per tile is 10 % faster alone, but it runs
-  // beside the input-gradient GEMMs and, holding 64 KiB of LDS per workgroup, slows those down by more
-  // than it gains (0.460 against 0.444 ms per step): the register-staged kernel stays.
-  // With both operands k-contiguous:
+  // Measured inside the layer (whole training steps, same box, libraries alternating), since a loop over one
+  // launch flatters whatever profits most from warm caches.
+  // dy^T x (both operands k-major, split over the tokens) and dy W (one k-major operand, used where forward
+  // left no transposed weights behind): 128x128 tiles, 2 stages, two workgroups per CU.  2-3 % of a step
+  // against the register-staged kernel in gemm.hip on the BERT-base, speech and ViT shapes (0.404 -> 0.394,
+  // 0.799 -> 0.779, 12.03 -> 11.68 ms for dy^T x; 12.07 -> 11.75 ms for dy W); the variants with three
+  // stages or two wavefront groups per tile hold more LDS and slow the kernels they run beside.
+  if (!a_kc && !b_kc) return 0;
+  if (a_kc && !b_kc) return 0;
+  if (!(a_kc && b_kc)) return -2;
+  // Both operands k-contiguous:
   // 256x192 tiles on 8 wavefronts halve the L1 and LDS traffic per flop and win when they fill the
   // chip in whole rounds (one workgroup per CU); otherwise 128x128 / 2 stages, two workgroups per CU.
-  if (!(a_kc && b_kc)) return -2;
   if (N % 192 == 0) {
     const long tiles = (long)((M + 255) / 256) * (N / 192);
     const long rounds = (tiles + 255) / 256;

@@ -174,8 +174,11 @@ constexpr int OPT_MAX_TENSORS = 16;
 struct OptHyper {
   float lr, momentum, weight_decay, beta1, beta2, eps, inv_bias1, inv_bias2;
 };
+// master (may be null, and so may any entry): fp32 copies of the parameters; where given, the update is
+// applied to the copy and params[i] receives its rounded value.
 hipError_t launch_opt_step(int dt, int kind, const OptHyper &h, int n, void *const *params, const void *const *grads,
-                           float *const *m, float *const *v, const long long *numel, hipStream_t stream);
+                           float *const *m, float *const *v, const long long *numel, hipStream_t stream,
+                           float *const *master = nullptr);
 // Fills `bytes` (a multiple of 16; p 16-byte aligned) with copies of the 32-bit `word`.
 hipError_t launch_fill_words(void *p, size_t bytes, unsigned word, hipStream_t stream);
 // Zero-fills n buffers (byte counts multiples of 16) with one kernel.

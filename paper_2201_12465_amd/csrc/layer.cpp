@@ -1329,6 +1329,12 @@ fl_status_t fl_layer_join(fl_layer_t *layer, void *hip_stream) {
 fl_status_t fl_opt_step(const fl_opt_config_t *cfg, fl_dtype_t dtype, int32_t n, void *const *params,
                         const void *const *grads, float *const *state_m, float *const *state_v, const int64_t *numel,
                         void *hip_stream) {
+  return fl_opt_step_master(cfg, dtype, n, params, nullptr, grads, state_m, state_v, numel, hip_stream);
+}
+
+fl_status_t fl_opt_step_master(const fl_opt_config_t *cfg, fl_dtype_t dtype, int32_t n, void *const *params,
+                               float *const *master, const void *const *grads, float *const *state_m,
+                               float *const *state_v, const int64_t *numel, void *hip_stream) {
   FL_GUARD_BEGIN
   if (!cfg || !params || !grads || !numel) return (fl_status_t)set_error(FL_ERR_INVALID_ARG, "null argument");
   if (n < 1 || n > OPT_MAX_TENSORS)
@@ -1346,7 +1352,7 @@ fl_status_t fl_opt_step(const fl_opt_config_t *cfg, fl_dtype_t dtype, int32_t n,
   long long ne[OPT_MAX_TENSORS];
   for (int i = 0; i < n; ++i) ne[i] = (long long)numel[i];
   hipError_t e = launch_opt_step(dtype == FL_F32 ? DT_F32 : DT_BF16, cfg->kind == FL_OPT_SGD ? 0 : 1, h, n, params,
-                                 grads, state_m, state_v, ne, static_cast<hipStream_t>(hip_stream));
+                                 grads, state_m, state_v, ne, static_cast<hipStream_t>(hip_stream), master);
   if (e != hipSuccess)
     return (fl_status_t)set_error(e == hipErrorInvalidValue ? FL_ERR_UNSUPPORTED : FL_ERR_DEVICE,
                                   "optimizer step: %s (needs numel %% 8 == 0, 16-byte aligned pointers, state "

@@ -17,6 +17,7 @@ namespace fl {
 namespace {
 
 struct OptTable {
+  float *master[OPT_MAX_TENSORS];  // fp32 copy of the parameter that carries the update (or nullptr)
   void *p[OPT_MAX_TENSORS];
   const void *g[OPT_MAX_TENSORS];
   float *m[OPT_MAX_TENSORS];
@@ -31,10 +32,15 @@ __global__ __launch_bounds__(256) void opt_step_kernel(OptTable tb, OptHyper h) 
   const long long n = tb.n[t];
   T *p = static_cast<T *>(tb.p[t]);
   const T *g = static_cast<const T *>(tb.g[t]);
-  float *m = tb.m[t], *v = tb.v[t];
+  float *m = tb.m[t], *v = tb.v[t], *w = tb.master[t];
   for (long long i = ((long long)blockIdx.x * 256 + threadIdx.x) * VEC; i < n; i += (long long)gridDim.x * 256 * VEC) {
     float pv[VEC], gv[VEC], mv[VEC], vv[VEC];
-    VecIO<T, VEC>::load(p + i, pv);
+    if (w) {  // the full-precision copy is the parameter; p only receives its rounded value
+#pragma unroll
+      for (int e = 0; e < VEC; e += 4) VecIO<float, 4>::load(w + i + e, pv + e);
+    } else {
+      VecIO<T, VEC>::load(p + i, pv);
+    }
     VecIO<T, VEC>::load(g + i, gv);
     if (KIND == 1 || h.momentum != 0.f) {
 #pragma unroll
@@ -61,6 +67,10 @@ __global__ __launch_bounds__(256) void opt_step_kernel(OptTable tb, OptHyper h) 
       }
     }
     VecIO<T, VEC>::store(p + i, pv);
+    if (w) {
+#pragma unroll
+      for (int e = 0; e < VEC; e += 4) VecIO<float, 4>::store(w + i + e, pv + e);
+    }
     if (KIND == 1 || h.momentum != 0.f) {
 #pragma unroll
       for (int e = 0; e < VEC; e += 4) VecIO<float, 4>::store(m + i + e, mv + e);
@@ -100,7 +110,8 @@ hipError_t launch_fill_words(void *p, size_t bytes, unsigned word, hipStream_t s
 }
 
 hipError_t launch_opt_step(int dt, int kind, const OptHyper &h, int n, void *const *params, const void *const *grads,
-                           float *const *m, float *const *v, const long long *numel, hipStream_t stream) {
+                           float *const *m, float *const *v, const long long *numel, hipStream_t stream,
+                           float *const *master) {
   if (n < 1 || n > OPT_MAX_TENSORS || !params || !grads || !numel || (kind != 0 && kind != 1))
     return hipErrorInvalidValue;
   const bool need_m = kind == 1 || h.momentum != 0.f;
@@ -114,6 +125,8 @@ hipError_t launch_opt_step(int dt, int kind, const OptHyper &h, int n, void *con
     if ((reinterpret_cast<uintptr_t>(params[i]) | reinterpret_cast<uintptr_t>(grads[i]) |
          (need_m ? reinterpret_cast<uintptr_t>(m[i]) : 0) | (kind == 1 ? reinterpret_cast<uintptr_t>(v[i]) : 0)) & 15)
       return hipErrorInvalidValue;
+    tb.master[i] = master ? master[i] : nullptr;
+    if (tb.master[i] && (reinterpret_cast<uintptr_t>(tb.master[i]) & 15)) return hipErrorInvalidValue;
     tb.p[i] = params[i]; tb.g[i] = grads[i];
     tb.m[i] = need_m ? m[i] : nullptr; tb.v[i] = kind == 1 ? v[i] : nullptr;
     tb.n[i] = numel[i];

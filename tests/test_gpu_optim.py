@@ -53,6 +53,39 @@ def test_optimizer_steps_match_oracle(dtype, kind, hyper):
             ref_p[i] = got          # continue from the stored (rounded) parameter
 
 
+def test_master_copies_keep_small_adam_steps_that_bf16_storage_loses():
+    """100 Adam steps of lr = 1e-4 on bf16 weights ~ N(0, 0.02) (spacing 6e-5 near 0.02): with fp32 master
+    copies the parameters follow the fp64 oracle; without them most of every update is rounded away."""
+    from paper_2201_12465_amd import binding as b
+    torch = torch_mod()
+    rng = np.random.default_rng(11)
+    n, steps, hyper = 4096, 100, dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8)
+    p0 = quantise(0.02 * rng.standard_normal(n), "bf16")
+    grads = [quantise(rng.standard_normal(n) + 0.5, "bf16") for _ in range(steps)]   # a consistent drift plus noise
+    ref_p, ref_m, ref_v = p0.astype(np.float64), np.zeros(n), np.zeros(n)
+    for t, g in enumerate(grads, 1):
+        ref_p, ref_m, ref_v = oo.adam_step(ref_p, g, ref_m, ref_v, step=t, **hyper)
+    moved = float(np.max(np.abs(ref_p - p0)))
+    out = {}
+    for with_master in (True, False):
+        dp = to_dev(p0, "bf16")
+        master = torch.from_numpy(p0.astype(np.float32)).cuda() if with_master else None
+        dm, dv = torch.zeros(n, device="cuda"), torch.zeros(n, device="cuda")
+        for t, g in enumerate(grads, 1):
+            b.opt_step("adam", "bf16", [dp], [to_dev(g, "bf16")], [dm], [dv], [n], stream_ptr(), step=t,
+                       master=[master] if with_master else None, **hyper)
+        torch.cuda.synchronize()
+        out[with_master] = float(np.max(np.abs(to_np(dp) - ref_p))) / moved
+        if with_master:   # what is left is the one rounding of the result to bf16: half a spacing of the value
+            half_ulp = 2.0 ** (np.floor(np.log2(np.abs(ref_p))) - 8)
+            assert np.all(np.abs(to_np(dp) - ref_p) <= 1.02 * half_ulp)
+        if with_master:
+            assert float(np.max(np.abs(master.cpu().numpy().astype(np.float64) - ref_p))) / moved <= 1e-4
+            assert torch.equal(dp, master.to(torch.bfloat16))      # the bf16 parameter is the rounded master copy
+    assert out[True] <= 0.05        # that rounding (at most 4.9e-4 / 2 here) against a movement of ~1e-2
+    assert out[False] >= 5 * out[True], out
+
+
 def test_zero_grad_and_argument_checks():
     from paper_2201_12465_amd import binding as b
     torch = torch_mod()
