@@ -328,11 +328,8 @@ def test_config5_full_stack():
 
 # The chain of 12 layer calls hands bf16 tensors from call to call: against the un-rounded fp64 chain the
 # residual stream and the gradient stream are each rounded 24 times, whatever the kernels do, and those
-# roundings add up like a random walk (per layer: 0.005; chain: 0.017 on Y).  One tensor of the full-size
-# chain ends above the flat tolerance, and is held to its measured value, reported as it is: dX at the
-# stack input, 0.0202.  Every other tensor of the chain, and every tensor of every single layer, is held
-# to the flat 2e-2.
-CHAIN_TOL = {"cfg5_vit_b16_bf16": {"dX": 2.05e-2}}
+# roundings add up like a random walk (per layer: 0.005; chain: 0.017 on Y, 0.018 on dX).  The chain is held
+# to the same flat tolerance as a single layer; so is every tensor of every single layer.
 
 
 def _run_stack(cfg, nontrivial, deferred_too=False, test=None):
@@ -369,7 +366,7 @@ def _run_stack(cfg, nontrivial, deferred_too=False, test=None):
         l2 = {k: rel_err_l2(a, r) for k, (a, r) in pairs.items()}
         log_errors(f"{test}/chain/deferred={deferred}", errs, l2)
         print(f"stack of {cfg.layers} (deferred join: {deferred}): chain, largest error {max(errs.values()):.4f}")
-        bad = {k: v for k, v in errs.items() if not v <= CHAIN_TOL.get(test, {}).get(k, BF16_TOL)}
+        bad = {k: v for k, v in errs.items() if not v <= BF16_TOL}
         assert not bad, ("chain", deferred, BF16_TOL, bad)
         if deferred:
             continue   # same kernels, same bits (test_deferred_join_changes_no_bit): the per-layer pass is not repeated
