@@ -88,6 +88,9 @@ int32_t fl_test_dropout_mul(int32_t dtype, const void *in, void *out, int32_t M,
 
 /* on != 0: bf16 attention uses the general (vector-ALU) kernels instead of the MFMA ones. */
 void fl_test_attention_force_general(int32_t on);
+/* on != 0: bf16 attention backward always runs as the dQ kernel followed by the dK/dV kernel(s), also where
+ * the one-kernel backward (head size 64, T <= 224) would apply. */
+void fl_test_attention_force_unfused_bwd(int32_t on);
 
 /* Copies the value that the recorded forward's `lin`-th linear operator produced (0 fused QKV projection,
  * 1 attention projection + residual, 2 first feed-forward linear after its activation and dropout,

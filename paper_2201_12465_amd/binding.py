@@ -135,6 +135,7 @@ def _signatures():
         "fl_test_attention_bwd": (i32, [i32, vp, vp, vp, vp, vp, i32, f32, u64, i32, i32, i32, i32, vp, vp, vp]),
         "fl_test_dropout_mul": (i32, [i32, vp, vp, i32, i32, i32, f32, u64, vp]),
         "fl_test_attention_force_general": (None, [i32]),
+        "fl_test_attention_force_unfused_bwd": (None, [i32]),
         "fl_test_layer_peek_linear": (i32, [vp, i32, vp, u64, C.POINTER(u64), vp]),
         "fl_test_alloc_create": (vp, [BACKING_MALLOC, BACKING_FREE]),
         "fl_test_alloc_destroy": (None, [vp]),

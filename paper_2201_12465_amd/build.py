@@ -22,7 +22,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libflmi355.so")
 TEST_LIB = os.path.join(HERE, "libflmi355_test.so")
 # compiled once, linked into both libraries
-SHARED = ["gemm.hip", "gemm_pipe.hip", "gemm_f32_small.hip", "attention.hip", "attention_mfma.hip",
+SHARED = ["gemm.hip", "gemm_pipe.hip", "gemm_f32_small.hip", "attention.hip", "attention_mfma.hip", "attention_bwd_fused.hip",
           "attention_mfma_f32.hip", "layernorm.hip", "reduce.hip", "optimizer.hip", "dropout.hip", "transpose.hip",
           "static_scratch.hip", "allocator.cpp"]
 # compiled twice: without and with -DFL_TEST_EXPORTS

@@ -728,6 +728,8 @@ hipError_t launch_attention_bwd_mfma(const void *qkv, const void *o, const void 
                                      int dh, void *dqkv, float *delta, hipStream_t s, int parts) {
   const float scale = 1.0f / sqrtf((float)dh);
   if (!attention_mfma_supported(dh)) return hipErrorInvalidValue;
+  if ((parts & (ATTN_BWD_DQ | ATTN_BWD_DKV)) == (ATTN_BWD_DQ | ATTN_BWD_DKV) && attention_bwd_fused_applies(T, dh))
+    return launch_attention_bwd_fused(qkv, o, dout, lse, lengths, causal, drop, B, T, H, dh, dqkv, s);
   switch (instance_of(dh)) {
     case 32: return bwd_pick<32>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, dh, scale, dqkv, delta, s, parts);
     case 64: return bwd_pick<64>(causal, qkv, o, dout, lse, lengths, drop, B, T, H, dh, scale, dqkv, delta, s, parts);

@@ -50,10 +50,12 @@ int gemm_pick_splits(int dt, int M, int N, int K);
 int forced_gemm_pipe_variant();   // -1 = automatic; >= 0 forces a tile/stage variant; -2 = never use the pipelined kernel
 int forced_gemm_tile_height();    // gemm.hip kernel: 0 automatic, 1 = 64x128 tiles, 2 = 128x128 tiles
 bool forced_general_attention();  // general (vector-ALU) attention kernels for every head size
+bool forced_unfused_attention_bwd();  // never the one-kernel attention backward
 #ifdef FL_TEST_EXPORTS
 void gemm_pipe_force_variant(int v);
 void gemm_force_tile_height(int tmw);
 void attention_force_general(bool on);
+void attention_force_unfused_bwd(bool on);
 #endif
 
 // fp32 outputs with few tiles (gemm_f32_small.hip): 32 x 32 tiles, the four wavefronts of a workgroup
@@ -147,6 +149,14 @@ hipError_t launch_attention_fwd_mfma(const void *qkv, const int32_t *lengths, in
 hipError_t launch_attention_bwd_mfma(const void *qkv, const void *o, const void *dout, const float *lse,
                                      const int32_t *lengths, int causal, const DropSpec &drop, int B, int T, int H,
                                      int dh, void *dqkv, float *delta, hipStream_t s, int parts);
+
+// bf16 attention backward in one kernel (attention_bwd_fused.hip): head size 64 and T <= 224, where a
+// (sequence, head) pair fits one workgroup's LDS.  launch_attention_bwd_mfma hands it every such problem
+// whose dQ and dK/dV parts are requested together; delta stays inside the kernel.
+bool attention_bwd_fused_applies(int T, int dh);
+hipError_t launch_attention_bwd_fused(const void *qkv, const void *o, const void *dout, const float *lse,
+                                      const int32_t *lengths, int causal, const DropSpec &drop, int B, int T, int H,
+                                      int dh, void *dqkv, hipStream_t s);
 
 // fp32 attention on the matrix cores (attention_mfma_f32.hip), picked for dt fp32 and head sizes up
 // to 128 (multiples of 16) unless the general kernels are forced.  As on the bf16 path, delta comes out of the

@@ -175,6 +175,7 @@ int32_t fl_test_dropout_mul(int32_t dtype, const void *in, void *out, int32_t M,
 }
 
 void fl_test_attention_force_general(int32_t on) { attention_force_general(on != 0); }
+void fl_test_attention_force_unfused_bwd(int32_t on) { attention_force_unfused_bwd(on != 0); }
 
 // ---- allocator over a caller-supplied backing store -------------------------------------
 void *fl_test_alloc_create(fl_test_backing_malloc_fn m, fl_test_backing_free_fn f) {

@@ -377,7 +377,52 @@ def test_attention_forward_backward(dtype, case, causal, p_drop):
         b.lib().fl_test_attention_force_general(0)
 
 
-def _attention_case(b, dtype, case, causal=False, p_drop=0.0):
+ATTN_ONE_KERNEL_BWD_CASES = [  # head size 64 and T <= 224: the one-kernel backward (2, 4, 6 or 8 wavefronts)
+    (2, 1, 2, 64, None),
+    (2, 32, 1, 64, [32, 5]),
+    (1, 64, 3, 64, [33]),
+    (2, 65, 2, 64, [65, 64]),
+    (2, 100, 2, 64, [31, 100]),
+    (1, 130, 2, 64, [97]),
+    (2, 192, 1, 64, [192, 40]),
+    (2, 224, 2, 64, [224, 129]),
+    (1, 225, 1, 64, [200]),       # one row too long: falls back to the two-kernel path
+]
+
+
+@pytest.mark.parametrize("causal,p_drop", [(False, 0.0), (True, 0.0), (False, 0.2), (True, 0.35)])
+@pytest.mark.parametrize("unfused", [False, True])
+@pytest.mark.parametrize("case", ATTN_ONE_KERNEL_BWD_CASES + [c for c in ATTN_CASES if c[3] == 64])
+def test_attention_backward_in_one_kernel_and_in_two(case, unfused, causal, p_drop):
+    """Head size 64 with T <= 224 runs dQ, dK and dV in one kernel; `unfused` puts the same problem on the
+    dQ + dK/dV kernels.  Both are checked against the oracle."""
+    b = _lib()
+    b.lib().fl_test_attention_force_unfused_bwd(1 if unfused else 0)
+    try:
+        _attention_case(b, "bf16", case, causal, p_drop)
+    finally:
+        b.lib().fl_test_attention_force_unfused_bwd(0)
+
+
+@pytest.mark.parametrize("causal,p_drop", [(False, 0.0), (True, 0.3)])
+@pytest.mark.parametrize("case", [(2, 192, 1, 64, [192, 1]), (3, 128, 2, 64, [128, 64, 100]), (2, 197, 3, 64, None)])
+def test_one_kernel_attention_backward_agrees_with_the_two_kernel_path(case, causal, p_drop):
+    """Same inputs (the forward's own O and log-sum-exp), same mask: the two paths differ in the order
+    of their fp32 sums only.  Includes a sequence of length 1 under dropout, where the reference
+    gradient is exactly 0 and both paths return the rounding noise of the stored O (delta = dO . O), which
+    is why that case is compared between the paths and not with the oracle."""
+    b = _lib()
+    got = {}
+    for unfused in (False, True):
+        b.lib().fl_test_attention_force_unfused_bwd(1 if unfused else 0)
+        try:
+            got[unfused] = _attention_case(b, "bf16", case, causal, p_drop, check_backward=False)
+        finally:
+            b.lib().fl_test_attention_force_unfused_bwd(0)
+    assert rel_err(got[False], got[True]) <= 4e-3      # one bf16 rounding step of the largest element
+
+
+def _attention_case(b, dtype, case, causal=False, p_drop=0.0, check_backward=True):
     B, T, H, dh, lengths = case
     seed = (0x9E3779B9 << 32) | (B * 7919 + T)
     keep = None
@@ -419,6 +464,8 @@ def _attention_case(b, dtype, case, causal=False, p_drop=0.0):
                                           stream_ptr()))
     torch.cuda.synchronize()
     got = to_np(dqkv)
+    if not check_backward:
+        return got
     # delta_i = sum_j P_ij dP_ij is taken as dO_i . O_i from the stored (rounded) O; dropout scales the
     # probabilities, and with them that rounding noise, by 1/(1-p)
     gtol = _tol(dtype) * 2 / (1.0 - p_drop)
@@ -427,6 +474,7 @@ def _attention_case(b, dtype, case, causal=False, p_drop=0.0):
     if lengths is not None:      # masked keys: exactly zero gradient rows
         for bi, n in enumerate(lengths):
             assert np.all(got[bi, n:, D:] == 0.0)
+    return got
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
