@@ -311,13 +311,16 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bwd_fused64(const bf16_t *__r
     // register 4g+e of a lane half h holds query qb*32 + 8g + 4h + e
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      const float4 l4 = *reinterpret_cast<const float4 *>(pl + qb * 32 + g * 8);
-      const float4 d4 = *reinterpret_cast<const float4 *>(pdl + qb * 32 + g * 8);
+      float4 l4 = *reinterpret_cast<const float4 *>(pl + qb * 32 + g * 8);
+      float4 d4 = *reinterpret_cast<const float4 *>(pdl + qb * 32 + g * 8);
+      // pinned: otherwise the reads sink behind the `live` test, one LDS round trip per branch
+      asm volatile("" : "+v"(l4.x), "+v"(l4.y), "+v"(l4.z), "+v"(l4.w), "+v"(d4.x), "+v"(d4.y), "+v"(d4.z), "+v"(d4.w));
       const float lq[4] = {l4.x, l4.y, l4.z, l4.w}, dq[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int r = g * 4 + e, qi = qb * 32 + g * 8 + h2 * 4 + e;
-        const float p = (live && (!CAUSAL || qi >= key)) ? exp2_raw(s[r] * c - lq[e]) : 0.f;
+        const float ex = exp2_raw(s[r] * c - lq[e]);
+        const float p = (live && (!CAUSAL || qi >= key)) ? ex : 0.f;
         float keep = 1.f;
         if constexpr (DROP) keep = drop_keep1(drop, (uint32_t)key, (uint32_t)qi, (uint32_t)(b * H + hd));
         dp[r] = p * (dp[r] * keep - dq[e]);   // dS

@@ -28,6 +28,8 @@
 #include "devutil.h"
 #include "kernels.h"
 #include "philox.h"
+#include <type_traits>
+#include <utility>
 
 namespace fl {
 namespace {
@@ -82,6 +84,33 @@ __device__ __forceinline__ bf16x8_t g_frag(const bf16_t *row, int kk, int lane, 
 __device__ __forceinline__ void keep_requested(bf16x8_t &a, bf16x8_t &b) { asm volatile("" : "+v"(a), "+v"(b)); }
 // Memory operations written before this point are issued before it: LDS reads requested early stay early.
 __device__ __forceinline__ void issue_fence() { asm volatile("" ::: "memory"); }
+
+// f(integral_constant<int, 0>), f(integral_constant<int, 1>), ...: a loop whose index is a constant in every pass
+template <int... I, typename F> __device__ __forceinline__ void unrolled(std::integer_sequence<int, I...>, F &&f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+// N batches of LDS fragment reads, each followed by the MFMAs that consume it, with the reads of batch
+// i+1 issued BEFORE the MFMAs of batch i (two sets of fragment registers, picked by the slot argument).
+// Left alone the compiler gives consecutive batches the same registers, and every batch then waits out
+// its own LDS round trip with the matrix core idle -- which a kernel that runs one wavefront per SIMD
+// cannot hide behind another wavefront.  load(i, slot) and compute(i, slot) get integral constants.
+// AHEAD = false keeps one set of registers: batch after batch, for the instances that have none to spare.
+template <int N, bool AHEAD = true, typename L, typename C>
+__device__ __forceinline__ void pipelined(L &&load, C &&compute, bool first_loaded = false) {
+  if (!first_loaded) load(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+  unrolled(std::make_integer_sequence<int, N>{}, [&](auto i) {
+    constexpr int I = decltype(i)::value;
+    if constexpr (AHEAD) {
+      if constexpr (I + 1 < N) load(std::integral_constant<int, I + 1>{}, std::integral_constant<int, (I + 1) & 1>{});
+      __builtin_amdgcn_sched_barrier(0);
+      compute(i, std::integral_constant<int, I & 1>{});
+      __builtin_amdgcn_sched_barrier(0);
+    } else {
+      if constexpr (I > 0) load(i, std::integral_constant<int, 0>{});
+      compute(i, std::integral_constant<int, 0>{});
+    }
+  });
+}
 
 // 2^x as the bare v_exp_f32: the arguments here are at most RESCALE_SLACK and results below the smallest
 // normal number may become 0 (probabilities under 1e-38), so the library function's range handling
@@ -302,8 +331,8 @@ __global__ __launch_bounds__(NT, dq_waves(DH, DROP)) void attn_bwd_dq_mfma(const
   __shared__ __attribute__((aligned(16))) bf16_t sK[TILE * KS];   // K rows for S^T = K Q^T
   __shared__ __attribute__((aligned(16))) bf16_t sKt[TILE * TS];  // K again, for K^T in dQ^T = K^T dS^T
   __shared__ __attribute__((aligned(16))) bf16_t sV[TILE * KS];   // V rows for dP^T = V dO^T
-  constexpr int KBATCH = DH <= 64 ? 1 : DH <= 128 ? 2 : NK % 3 == 0 ? 6 : 4;   // K and V fragments in flight (8 registers per step)
-  constexpr int TBATCH = DH <= 64 ? 1 : NB % 3 == 0 ? 3 : 2;   // K^T fragment pairs in flight
+  constexpr int KBATCH = DH <= 128 ? 1 : 2;   // K and V fragments of a batch (8 registers per step, two batches in flight)
+  constexpr int TBATCH = DH <= 64 ? 1 : NB % 2 == 0 ? 2 : 3;   // K^T fragment pairs of a batch
   static_assert(NK % KBATCH == 0 && NB % TBATCH == 0, "batches must divide the head size");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5;
   const int b = blockIdx.z, hd = blockIdx.y;
@@ -357,34 +386,38 @@ __global__ __launch_bounds__(NT, dq_waves(DH, DROP)) void attn_bwd_dq_mfma(const
       f32x16_t s, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = 0.f, dp[r] = 0.f;
-      // fragments are requested in batches ahead of the MFMAs (see the forward kernel)
+      // K and V row fragments in batches, the next batch requested before the MFMAs of this one
+      bf16x8_t kfr[2][KBATCH], vfr[2][KBATCH];
+      pipelined<NK / KBATCH>(
+          [&](auto bi, auto sl) {
+            constexpr int kh = decltype(bi)::value * KBATCH, S = decltype(sl)::value;
 #pragma unroll
-      for (int kh = 0; kh < NK; kh += KBATCH) {
-        bf16x8_t kfr[KBATCH], vfr[KBATCH];
+            for (int kk = 0; kk < KBATCH; ++kk) {
+              kfr[S][kk] = kc_frag(sK, KS, kb * 32, kh + kk, lane);
+              vfr[S][kk] = kc_frag(sV, KS, kb * 32, kh + kk, lane);
+            }
+          },
+          [&](auto bi, auto sl) {
+            constexpr int kh = decltype(bi)::value * KBATCH, S = decltype(sl)::value;
 #pragma unroll
-        for (int kk = 0; kk < KBATCH; ++kk) {
-          kfr[kk] = kc_frag(sK, KS, kb * 32, kh + kk, lane);
-          vfr[kk] = kc_frag(sV, KS, kb * 32, kh + kk, lane);
-        }
-        if constexpr (KBATCH > 1) {
-#pragma unroll
-          for (int kk = 0; kk < KBATCH; ++kk) keep_requested(kfr[kk], vfr[kk]);
-        }
-#pragma unroll
-        for (int kk = 0; kk < KBATCH; ++kk) {
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[kk], qf[kh + kk], s, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[kk], dof[kh + kk], dp, 0, 0, 0);
-        }
-      }
+            for (int kk = 0; kk < KBATCH; ++kk) {
+              s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[S][kk], qf[kh + kk], s, 0, 0, 0);
+              dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[S][kk], dof[kh + kk], dp, 0, 0, 0);
+            }
+          });
       // the first K^T fragments are requested before the dS arithmetic, so that their LDS round trip runs under it
       // (not with dropout at the large heads: the mask generator needs the registers)
-      constexpr bool EARLY = TBATCH > 1 && !(DROP && DH >= 192);
-      bf16x8_t tf0[TBATCH][2];
-      if constexpr (EARLY) {
+      constexpr bool EARLY = !(DROP && DH >= 192);
+      bf16x8_t tf[2][TBATCH][2];
+      auto load_t = [&](auto bi, auto sl) {
+        constexpr int d0 = decltype(bi)::value * TBATCH, S = decltype(sl)::value;
 #pragma unroll
         for (int db = 0; db < TBATCH; ++db)
 #pragma unroll
-          for (int st = 0; st < 2; ++st) tf0[db][st] = tr_frag(sKt, TS, db * 32, kb * 32 + 16 * st, lane);
+          for (int st = 0; st < 2; ++st) tf[S][db][st] = tr_frag(sKt, TS, (d0 + db) * 32, kb * 32 + 16 * st, lane);
+      };
+      if constexpr (EARLY) {
+        load_t(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
         issue_fence();
       }
       if constexpr (DROP) {  // dP = (dO V^T) * keep
@@ -399,28 +432,22 @@ __global__ __launch_bounds__(NT, dq_waves(DH, DROP)) void attn_bwd_dq_mfma(const
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int key = k0 + kb * 32 + acc_row(r, h2);
-        const float p = (key < len && (!CAUSAL || key <= q)) ? exp2_raw(s[r] * c - L2) : 0.f;
+        const float e = exp2_raw(s[r] * c - L2);
+        const float p = (key < len && (!CAUSAL || key <= q)) ? e : 0.f;
         s[r] = p * (dp[r] - dl);   // dS^T
       }
-      bf16x8_t dsf[2] = {pack8(s, 0), pack8(s, 1)};
+      const bf16x8_t dsf[2] = {pack8(s, 0), pack8(s, 1)};
+      pipelined<NB / TBATCH>(
+          load_t,
+          [&](auto bi, auto sl) {
+            constexpr int d0 = decltype(bi)::value * TBATCH, S = decltype(sl)::value;
 #pragma unroll
-      for (int d0 = 0; d0 < NB; d0 += TBATCH) {
-        bf16x8_t tf[TBATCH][2];
+            for (int st = 0; st < 2; ++st)
 #pragma unroll
-        for (int db = 0; db < TBATCH; ++db)
-#pragma unroll
-          for (int st = 0; st < 2; ++st)
-            tf[db][st] = (EARLY && d0 == 0) ? tf0[db][st] : tr_frag(sKt, TS, (d0 + db) * 32, kb * 32 + 16 * st, lane);
-        if constexpr (TBATCH > 1) {
-#pragma unroll
-          for (int db = 0; db < TBATCH; ++db) keep_requested(tf[db][0], tf[db][1]);
-        }
-#pragma unroll
-        for (int db = 0; db < TBATCH; ++db)
-#pragma unroll
-          for (int st = 0; st < 2; ++st)
-            acc[d0 + db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[db][st], dsf[st], acc[d0 + db], 0, 0, 0);
-      }
+              for (int db = 0; db < TBATCH; ++db)
+                acc[d0 + db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[S][db][st], dsf[st], acc[d0 + db], 0, 0, 0);
+          },
+          EARLY);
     }
   }
   if (qok) {
@@ -524,87 +551,98 @@ __global__ __launch_bounds__(NT, dkv_waves(DH)) void attn_bwd_dkv_mfma(const bf1
       f32x16_t s, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = 0.f, dp[r] = 0.f;
-      // fragments are requested in batches ahead of the MFMAs (see the forward kernel)
+      // Q and dO row fragments in batches, the next batch requested before the MFMAs of this one
+      constexpr bool SAHEAD = !(DROP && DH >= 192);   // statistics one group ahead: not where the mask generator needs the registers
+      bf16x8_t qfr[2][KBATCH], dofr[2][KBATCH];
+      pipelined<NK / KBATCH>(
+          [&](auto bi, auto sl) {
+            constexpr int kh = decltype(bi)::value * KBATCH, S = decltype(sl)::value;
 #pragma unroll
-      for (int kh = 0; kh < NK; kh += KBATCH) {
-        bf16x8_t qfr[KBATCH], dofr[KBATCH];
+            for (int kk = 0; kk < KBATCH; ++kk) {
+              qfr[S][kk] = kc_frag(sQ, KS, qb * 32, kh + kk, lane);
+              dofr[S][kk] = DO_DK ? kc_frag(sDO, KS, qb * 32, kh + kk, lane) : qfr[S][kk];
+            }
+          },
+          [&](auto bi, auto sl) {
+            constexpr int kh = decltype(bi)::value * KBATCH, S = decltype(sl)::value;
 #pragma unroll
-        for (int kk = 0; kk < KBATCH; ++kk) {
-          qfr[kk] = kc_frag(sQ, KS, qb * 32, kh + kk, lane);
-          dofr[kk] = DO_DK ? kc_frag(sDO, KS, qb * 32, kh + kk, lane) : qfr[kk];
-        }
-        if constexpr (KBATCH > 1) {
-#pragma unroll
-          for (int kk = 0; kk < KBATCH; ++kk) keep_requested(qfr[kk], dofr[kk]);
-        }
-#pragma unroll
-        for (int kk = 0; kk < KBATCH; ++kk) {
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfr[kk], kf[kh + kk], s, 0, 0, 0);
-          if (DO_DK) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dofr[kk], vf[kh + kk], dp, 0, 0, 0);
-        }
-      }
-      // the first transposed fragments of the stage after the dS arithmetic are requested before it
-      constexpr bool EARLY = TBATCH > 1 && !DROP;
-      bf16x8_t tf0[TBATCH][2];
-      if constexpr (EARLY) {
+            for (int kk = 0; kk < KBATCH; ++kk) {
+              s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfr[S][kk], kf[kh + kk], s, 0, 0, 0);
+              if (DO_DK) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dofr[S][kk], vf[kh + kk], dp, 0, 0, 0);
+            }
+          });
+      // dV^T += dO^T P, then dK^T += Q^T dS: one sequence of batches of transposed fragments; the first
+      // batch is requested before the dS arithmetic (not with dropout: the mask generator needs the registers)
+      constexpr int NBV = DO_DV ? NB / TBATCH : 0, NBK = DO_DK ? NB / TBATCH : 0;
+      bf16x8_t tf[2][TBATCH][2];
+      auto load_t = [&](auto bi, auto sl) {
+        constexpr int J = decltype(bi)::value, S = decltype(sl)::value;
+        constexpr bool V = J < NBV;
+        constexpr int d0 = (V ? J : J - NBV) * TBATCH;
 #pragma unroll
         for (int db = 0; db < TBATCH; ++db)
 #pragma unroll
           for (int st = 0; st < 2; ++st)
-            tf0[db][st] = tr_frag(DO_DV ? sDOt : sQt, TS, db * 32, qb * 32 + 16 * st, lane);
+            tf[S][db][st] = tr_frag(V ? sDOt : sQt, TS, (d0 + db) * 32, qb * 32 + 16 * st, lane);
+      };
+      constexpr bool EARLY = !DROP;
+      if constexpr (EARLY) {
+        load_t(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
         issue_fence();
       }
+      // The statistics of the block's queries are read as whole 16-byte groups (registers 4g..4g+3 of a
+      // lane half hold four consecutive queries), one group ahead of their use, and pinned: read where they
+      // are used, each sits behind the `live` test in a branch of its own and costs a full LDS round trip,
+      // sixteen times per block.
+      auto stats = [&](int g, float4 &l4, float4 &d4) {
+        l4 = *reinterpret_cast<const float4 *>(sL + qb * 32 + g * 8 + h2 * 4);
+        d4 = *reinterpret_cast<const float4 *>(sDl + qb * 32 + g * 8 + h2 * 4);
+        asm volatile("" : "+v"(l4.x), "+v"(l4.y), "+v"(l4.z), "+v"(l4.w), "+v"(d4.x), "+v"(d4.y), "+v"(d4.z), "+v"(d4.w));
+      };
+      float4 l4n, d4n;
+      if constexpr (SAHEAD) stats(0, l4n, d4n);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int qi = qb * 32 + acc_row(r, h2);
-        const float p = (live && (!CAUSAL || q0 + qi >= key)) ? exp2_raw(s[r] * c - sL[qi]) : 0.f;
-        float keep = 1.f;   // this lane's key against sixteen different queries: one generator call each
-        if constexpr (DROP) keep = drop_keep1(drop, (uint32_t)key, (uint32_t)(q0 + qi), (uint32_t)(b * H + hd));
-        if constexpr (DO_DK) dp[r] = p * (dp[r] * keep - sDl[qi]);   // dS
-        s[r] = p * keep;   // dV sees the dropped-out probabilities
-      }
-      if constexpr (DO_DV) {
-        bf16x8_t pf[2] = {pack8(s, 0), pack8(s, 1)};
+      for (int g = 0; g < 4; ++g) {
+        float lq[4], dq[4];
+        if constexpr (SAHEAD) {
+          const float4 l4 = l4n, d4 = d4n;
+          if (g < 3) stats(g + 1, l4n, d4n);   // one group ahead
+          lq[0] = l4.x, lq[1] = l4.y, lq[2] = l4.z, lq[3] = l4.w;
+          dq[0] = d4.x, dq[1] = d4.y, dq[2] = d4.z, dq[3] = d4.w;
+        } else {
 #pragma unroll
-        for (int d0 = 0; d0 < NB; d0 += TBATCH) {
-          bf16x8_t tf[TBATCH][2];
-#pragma unroll
-          for (int db = 0; db < TBATCH; ++db)
-#pragma unroll
-            for (int st = 0; st < 2; ++st)
-              tf[db][st] = (EARLY && d0 == 0) ? tf0[db][st] : tr_frag(sDOt, TS, (d0 + db) * 32, qb * 32 + 16 * st, lane);
-          if constexpr (TBATCH > 1) {
-#pragma unroll
-            for (int db = 0; db < TBATCH; ++db) keep_requested(tf[db][0], tf[db][1]);
+          for (int e = 0; e < 4; ++e) {
+            lq[e] = sL[qb * 32 + g * 8 + h2 * 4 + e];
+            dq[e] = sDl[qb * 32 + g * 8 + h2 * 4 + e];
           }
+        }
 #pragma unroll
-          for (int db = 0; db < TBATCH; ++db)
-#pragma unroll
-            for (int st = 0; st < 2; ++st)
-              dv[d0 + db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[db][st], pf[st], dv[d0 + db], 0, 0, 0);
+        for (int e = 0; e < 4; ++e) {
+          const int r = g * 4 + e, qi = qb * 32 + acc_row(r, h2);
+          const float ex = exp2_raw(s[r] * c - lq[e]);
+          const float p = (live && (!CAUSAL || q0 + qi >= key)) ? ex : 0.f;
+          float keep = 1.f;   // this lane's key against sixteen different queries: one generator call each
+          if constexpr (DROP) keep = drop_keep1(drop, (uint32_t)key, (uint32_t)(q0 + qi), (uint32_t)(b * H + hd));
+          if constexpr (DO_DK) dp[r] = p * (dp[r] * keep - dq[e]);   // dS
+          s[r] = p * keep;   // dV sees the dropped-out probabilities
         }
       }
-      if constexpr (DO_DK) {
-        bf16x8_t dsf[2] = {pack8(dp, 0), pack8(dp, 1)};
+      const bf16x8_t pf[2] = {pack8(s, 0), pack8(s, 1)}, dsf[2] = {pack8(dp, 0), pack8(dp, 1)};
+      pipelined<NBV + NBK>(
+          load_t,
+          [&](auto bi, auto sl) {
+            constexpr int J = decltype(bi)::value, S = decltype(sl)::value;
+            constexpr bool V = J < NBV;
+            constexpr int d0 = (V ? J : J - NBV) * TBATCH;
 #pragma unroll
-        for (int d0 = 0; d0 < NB; d0 += TBATCH) {
-          bf16x8_t tf[TBATCH][2];
+            for (int db = 0; db < TBATCH; ++db)
 #pragma unroll
-          for (int db = 0; db < TBATCH; ++db)
-#pragma unroll
-            for (int st = 0; st < 2; ++st)
-              tf[db][st] = (EARLY && !DO_DV && d0 == 0) ? tf0[db][st] : tr_frag(sQt, TS, (d0 + db) * 32, qb * 32 + 16 * st, lane);
-          if constexpr (TBATCH > 1) {
-#pragma unroll
-            for (int db = 0; db < TBATCH; ++db) keep_requested(tf[db][0], tf[db][1]);
-          }
-#pragma unroll
-          for (int db = 0; db < TBATCH; ++db)
-#pragma unroll
-            for (int st = 0; st < 2; ++st)
-              dk[d0 + db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[db][st], dsf[st], dk[d0 + db], 0, 0, 0);
-        }
-      }
+              for (int st = 0; st < 2; ++st) {
+                if constexpr (V) dv[d0 + db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[S][db][st], pf[st], dv[d0 + db], 0, 0, 0);
+                else dk[d0 + db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[S][db][st], dsf[st], dk[d0 + db], 0, 0, 0);
+              }
+          },
+          EARLY);
     }
   }
   if (kok) {
