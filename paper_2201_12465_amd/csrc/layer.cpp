@@ -12,6 +12,7 @@
 // pre-fused gradient computation for common sequences).
 #include <hip/hip_runtime_api.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstdarg>
@@ -171,6 +172,12 @@ struct fl_layer {
   // lane; the partial buffers are kept until then.
   std::vector<ReduceJob> reduce_jobs;
   std::vector<Buf *> reduce_bufs;
+  std::vector<char> reduce_job_main;   // per job: its partial sums were written on the layer's stream
+  // The pass's last linear operator (see linear_backward): where the side stream stood when its work began.
+  int tail_node = -1;                  // tape index of that operator; -1 = the pass does not split its tail
+  bool tail_split = false;
+  size_t tail_jobs = 0;                // second stages collected before that point
+  hipEvent_t tail_event = nullptr;     // recorded on the side stream at that point
   hipStream_t reduce_stream = nullptr;
   bool reduce_has_side = false;        // some collected job's partial sums were written on the side stream
   bool reduce_from_main = false;       // some collected job's partial sums were written on the layer's stream
@@ -575,8 +582,47 @@ int reduce_flush(fl_layer *L) {
   for (Buf *&b : L->reduce_bufs) buf_unref(b);   // back to the cache of the stream that has just read them
   L->reduce_bufs.clear();
   L->reduce_jobs.clear();
+  L->reduce_job_main.clear();
   L->reduce_from_main = false;
   L->reduce_has_side = false;
+  L->tail_split = false;   // a flush in the middle of the pass: the tail is no longer what was counted
+  return rc;
+}
+// The end of a pass whose last linear operator marked the side stream (tail_split): the second stages
+// collected before the mark, and those whose partial sums the layer's stream wrote itself, run on the
+// LAYER's stream -- which has nothing left to do while the side stream still works on that operator's
+// weight gradient -- and only the rest behind that weight gradient on the side stream.  Same kernel,
+// same summation order: which launch a job is part of does not change its result.
+int reduce_flush_split(fl_layer *L) {
+  std::vector<ReduceJob> on_main, on_side;
+  for (size_t i = 0; i < L->reduce_jobs.size(); ++i)
+    (i < L->tail_jobs || L->reduce_job_main[i] ? on_main : on_side).push_back(L->reduce_jobs[i]);
+  int rc = 0;
+  auto launch = [&](std::vector<ReduceJob> &jobs, hipStream_t ps) {
+    for (size_t at = 0; at < jobs.size() && !rc; at += REDUCE_MAX_JOBS) {
+      const int n = (int)std::min<size_t>(REDUCE_MAX_JOBS, jobs.size() - at);
+      double bytes = 0;
+      for (int k = 0; k < n; ++k) bytes += (double)(jobs[at + k].P * 4 + esize(L)) * jobs[at + k].seglen * jobs[at + k].nseg;
+      hipError_t he = timed(FL_K_SPLITK_REDUCE, 0, bytes, ps,
+                            [&] { return launch_reduce_batch(L->dt, jobs.data() + at, n, ps, L->accumulate); });
+      if (he != hipSuccess)
+        rc = set_error(FL_ERR_DEVICE, "the batched second-stage reduction failed: %s", hipGetErrorString(he));
+    }
+  };
+  if (!on_main.empty()) {
+    hipError_t he = hipStreamWaitEvent(L->stream, L->tail_event, 0);
+    if (he != hipSuccess) rc = set_error(FL_ERR_DEVICE, "waiting for the side stream failed: %s", hipGetErrorString(he));
+    if (!rc) launch(on_main, L->stream);
+  }
+  if (!rc) launch(on_side, L->side);
+  // the partial sums came from either stream's cache and were read on either stream: they go back after the join
+  for (Buf *&b : L->reduce_bufs) L->held.push_back(b);
+  L->reduce_bufs.clear();
+  L->reduce_jobs.clear();
+  L->reduce_job_main.clear();
+  L->reduce_from_main = false;
+  L->reduce_has_side = false;
+  L->tail_split = false;
   return rc;
 }
 // ps: the stream the batch will run on (the side stream while there is one).  from_main: the partial sums were
@@ -593,6 +639,7 @@ int reduce_later(fl_layer *L, hipStream_t ps, bool from_main, Buf *partial, int 
   j.P = P; j.nseg = nseg; j.stride = stride; j.seglen = seglen;
   j.out[0] = o0; j.out[1] = o1; j.out[2] = o2;
   L->reduce_jobs.push_back(j);
+  L->reduce_job_main.push_back(from_main ? 1 : 0);
   partial->refs++;
   L->reduce_bufs.push_back(partial);
   return 0;
@@ -688,7 +735,14 @@ int linear_backward(void *ctx, Tape *tape, const Node *n) {
   // already enqueued above).
   side_hold(L, gm ? gm : ys.grad_buf);
   side_hold(L, tape->slots[n->in0].value_buf);
+  // The pass's last linear operator: nothing follows its input gradient on the layer's stream, while the
+  // side stream still has this operator's weight gradient and every second stage ahead of it.  So its
+  // bias sums run on the layer's stream behind the input gradient, and the second stages split (see
+  // reduce_flush_split).  Measured on the BERT-base shape: the side stream used to end 45 us after the
+  // layer's stream.
+  const bool tail = L->side && !defer_side && self == L->tail_node;
   const bool need_colsum = !ys.colsum_done;
+  const bool colsum_here = need_colsum && !tail;
   const bool reads_callers_dy = L->side && L->defer_join && !gm && !ys.grad_buf;
   const void *x_saved = n->s0;
   const int lin = n->param;
@@ -696,7 +750,7 @@ int linear_backward(void *ctx, Tape *tape, const Node *n) {
     OpTag tag2(FL_OP_LINEAR_BWD, self);
     // bias gradient, unless the kernel that finished gy already produced it: first stage here, second stage
     // batched with the others
-    if (need_colsum) {
+    if (colsum_here) {
       Scratch ws;
       FL_TRY(ws.get(colsum_ws_floats(M, N) * sizeof(float), ps));
       FL_HIP(timed(FL_K_COLSUM, 0, (double)M * N * e, ps,
@@ -738,6 +792,20 @@ int linear_backward(void *ctx, Tape *tape, const Node *n) {
     hipStream_t ps;
     FL_TRY(side_begin(L, forked, &ps));
     FL_TRY(run_pending_side(L, ps));
+    if (tail) {
+      if (!L->tail_event) FL_HIP(hipEventCreateWithFlags(&L->tail_event, kEventFlags));
+      FL_HIP(hipEventRecord(L->tail_event, ps));
+      L->tail_jobs = L->reduce_jobs.size();
+      L->tail_split = true;
+      if (need_colsum) {   // on the layer's stream, behind the input gradient enqueued above
+        Scratch ws;
+        FL_TRY(ws.get(colsum_ws_floats(M, N) * sizeof(float), st));
+        FL_HIP(timed(FL_K_COLSUM, 0, (double)M * N * e, st,
+                     [&] { return launch_colsum_stage1(dt, gy, M, N, ws.f32(), st); }));
+        FL_TRY(reduce_later(L, ps, true, ws.b, colsum_stage1_rows(M), (size_t)N, (size_t)N, 1,
+                            L->grads[kLinear[lin].b], nullptr, nullptr));
+      }
+    }
     FL_TRY(side_work(ps));
     // (the second stages stay collected until the end of the pass: one launch there measured better than a
     // launch after every operator, 0.408 against 0.413 ms per step on the BERT-base shape)
@@ -1199,6 +1267,16 @@ int backward_impl(fl_layer *L, const fl_layer_params_t *params, const void *dY, 
   // the events of a fork cost the host more than tiny kernels take: small problems stay on one stream
   L->side = g_overlap && (long)L->M * L->cfg.d_model >= (1l << 18) ? side_stream() : nullptr;
   L->forks = 0;
+  L->tail_node = -1;
+  L->tail_split = false;
+  // (not with a deferred join: the layer's stream then goes straight on with the next layer's backward
+  // pass, and work moved onto it delays that chain -- measured +1.2 % on the 12-layer stack)
+  if (L->side && !L->defer_join)
+    for (size_t i = 0; i < tp.nodes.size(); ++i)
+      if (tp.nodes[i].backward == linear_backward) {   // first recorded = last replayed
+        L->tail_node = (int)i;
+        break;
+      }
   int rc = tp.replay_reverse(L);
   if (!rc && !L->pending_side.empty()) {  // no later operator forked: fork now
     hipEvent_t ev;
@@ -1212,10 +1290,12 @@ int backward_impl(fl_layer *L, const fl_layer_params_t *params, const void *dY, 
     L->reduce_jobs.clear();
     for (Buf *&b : L->reduce_bufs) buf_unref(b);
     L->reduce_bufs.clear();
+    L->reduce_job_main.clear();
     L->reduce_from_main = false;
     L->reduce_has_side = false;
+    L->tail_split = false;
   } else {
-    rc = reduce_flush(L);
+    rc = L->tail_split && L->side ? reduce_flush_split(L) : reduce_flush(L);
   }
   const bool landed = rc == 0 && tp.slots[L->slot_x].grad == dX;
   const int jrc = side_join(L, rc != 0, L->defer_join);
@@ -1387,6 +1467,7 @@ fl_status_t fl_layer_destroy(fl_layer_t *layer) {
   if (layer->join_event) hipEventDestroy(layer->join_event);
   if (layer->attn_join_event) hipEventDestroy(layer->attn_join_event);
   if (layer->caller_read_event) hipEventDestroy(layer->caller_read_event);
+  if (layer->tail_event) hipEventDestroy(layer->tail_event);
   delete layer;
   return FL_OK;
   FL_GUARD_END
