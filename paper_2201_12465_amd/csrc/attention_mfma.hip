@@ -256,7 +256,7 @@ __global__ __launch_bounds__(NT, fwd_waves(DH, DROP)) void attn_fwd_mfma(const b
         s[r] = (key < len && (!CAUSAL || key <= q)) ? s[r] * c : -INFINITY;
         mloc = fmaxf(mloc, s[r]);
       }
-      mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+      mloc = half_pair_max(mloc);
       // The reference maximum m moves only when a block's maximum exceeds it by more than RESCALE_SLACK
       // (in units of log2): probabilities are then at most 2^RESCALE_SLACK instead of 1, which changes
       // neither O / l nor the log-sum-exp, and the accumulators are rescaled only in the blocks where some
@@ -270,7 +270,7 @@ __global__ __launch_bounds__(NT, fwd_waves(DH, DROP)) void attn_fwd_mfma(const b
         s[r] = exp2_raw(s[r] - mnew);
         rs += s[r];
       }
-      rs += __shfl_xor(rs, 32, 64);
+      rs = half_pair_sum(rs);
       const bool rescale = !LAZY || __any(moved);    // wave-uniform
       const float corr = (LAZY && !moved) ? 1.f : exp2_raw(m - mnew);
       l = l * corr + rs;   // the softmax denominator ignores dropout
@@ -355,7 +355,7 @@ __global__ __launch_bounds__(NT, dq_waves(DH, DROP)) void attn_bwd_dq_mfma(const
 #pragma unroll
     for (int e = 0; e < 8; ++e) dl += static_cast<float>(dof[kk][e]) * static_cast<float>(of[e]);
   }
-  dl += __shfl_xor(dl, 32, 64);
+  dl = half_pair_sum(dl);
   const size_t st_idx = ((size_t)b * H + hd) * Tn + (qok ? q : 0);
   const float L2 = qok ? lse[st_idx] * LOG2E : 0.f;
   if (qok && h2 == 0) delta[st_idx] = dl;

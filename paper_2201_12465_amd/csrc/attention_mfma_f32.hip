@@ -125,7 +125,7 @@ __global__ __launch_bounds__(NT) void attn_fwd_mfma_f32(const float *__restrict_
         s[r] = (key < len && (!CAUSAL || key <= q)) ? s[r] * c : -INFINITY;
         mloc = fmaxf(mloc, s[r]);
       }
-      mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+      mloc = half_pair_max(mloc);
       const float mnew = fmaxf(m, mloc);
       float rs = 0.f;
 #pragma unroll
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(NT) void attn_fwd_mfma_f32(const float *__restrict_
         s[r] = exp2f(s[r] - mnew);
         rs += s[r];
       }
-      rs += __shfl_xor(rs, 32, 64);
+      rs = half_pair_sum(rs);
       const float corr = exp2f(m - mnew);
       l = l * corr + rs;   // the softmax denominator ignores dropout
       m = mnew;
@@ -200,7 +200,7 @@ __global__ __launch_bounds__(NT) void attn_bwd_dq_mfma_f32(const float *__restri
 #pragma unroll
     for (int kk = 0; kk < DH / 2; ++kk) dl += dof[kk] * of[kk];
   }
-  dl += __shfl_xor(dl, 32, 64);
+  dl = half_pair_sum(dl);
   const size_t st_idx = ((size_t)b * H + hd) * Tn + (qok ? q : 0);
   const float L2 = qok ? lse[st_idx] * LOG2E : 0.f;
   if (qok && h2 == 0) delta[st_idx] = dl;

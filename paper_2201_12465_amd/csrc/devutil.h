@@ -71,6 +71,28 @@ template <int CTRL> __device__ __forceinline__ float dpp_lane(float v) {
 __device__ __forceinline__ float lane_value(float v, int lane) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
 }
+// The value of lane l and the value of lane l ^ 32, in the vector ALU (a shuffle goes through LDS and
+// costs its round trip).  v_permlane32_swap exchanges the upper half of one register with the lower half
+// of another; given the same value twice, one register ends up with the lower half's values in both of its
+// halves and the other with the upper half's: any symmetric combination of the two is the pair's result.
+// (Inline assembly: through the compiler's builtin the two results of one value given twice came back
+// as one and the same register.  The two wait states in front cover a vector-ALU write of either operand
+// by the instruction just before.)
+__device__ __forceinline__ void half_pair(float v, float &a, float &b) {
+  a = v;
+  b = v;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ float half_pair_sum(float v) {
+  float a, b;
+  half_pair(v, a, b);
+  return a + b;
+}
+__device__ __forceinline__ float half_pair_max(float v) {
+  float a, b;
+  half_pair(v, a, b);
+  return fmaxf(a, b);
+}
 __device__ __forceinline__ float wave_sum(float v) {
   v += dpp_lane<0xB1>(v);
   v += dpp_lane<0x4E>(v);
