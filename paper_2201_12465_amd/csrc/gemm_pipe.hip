@@ -316,9 +316,12 @@ int gemm_pipe_pick_variant(bool a_kc, bool b_kc, int M, int N, int K) {
     // against 51)
     if (tiles >= 160 && 100 * tiles >= (rounds == 1 ? 74 : 90) * rounds * 256) return 7;
   }
-  // few tiles and a long k-loop (FFN2): one workgroup per CU; three stages and two k-groups of
-  // wavefronts per tile keep more loads in flight (35 -> 32 us)
-  if ((long)((M + 127) / 128) * ((N + 127) / 128) <= 256 && K >= 2048) return 9;
+  // at most one 128x128 tile per CU: three stages and two k-groups of wavefronts per tile (eight wavefronts on
+  // the CU instead of four) keep more loads in flight.  Long k-loops (FFN2: 35 -> 32 us), and short ones as
+  // well: the 4096 x 768 x 768 problems of the attention projection, whole steps on the BERT-base shape
+  // 0.3835 -> 0.3756 ms (four stages, or one k-group with three stages: 0.379 / 0.380).  With more tiles than
+  // CUs the two-workgroups-per-CU variant is ahead (speech shape, 378 tiles: 0.765 against 0.835 ms).
+  if ((long)((M + 127) / 128) * ((N + 127) / 128) <= 256) return 9;
   return 0;
 }
 
