@@ -186,12 +186,13 @@ __global__ __launch_bounds__(NT, fwd_waves(DH, DROP)) void attn_fwd_mfma(const b
   __shared__ __attribute__((aligned(16))) bf16_t sK[TILE * KS];
   __shared__ __attribute__((aligned(16))) bf16_t sV[TILE * VS];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5;
-  const int b = blockIdx.z, hd = blockIdx.y;
+  const AttnBlock blk = attn_block();
+  const int b = blk.b, hd = blk.hd, rb = blk.rb;
   const int D = H * dh;
   const size_t ld = (size_t)3 * D;
   const int len = lengths ? min(max(lengths[b], 1), Tn) : Tn;  // a length outside 1..T is treated as the nearest valid one
   const bf16_t *base = qkv + (size_t)b * Tn * ld + hd * dh;
-  const int q = blockIdx.x * ROWS_WG + wave * 32 + (lane & 31);
+  const int q = rb * ROWS_WG + wave * 32 + (lane & 31);
   const bf16_t *qrow = q < Tn ? base + (size_t)q * ld : nullptr;
   bf16x8_t qf[NK];
 #pragma unroll
@@ -207,8 +208,8 @@ __global__ __launch_bounds__(NT, fwd_waves(DH, DROP)) void attn_fwd_mfma(const b
   // With the causal mask the workgroup needs keys up to its last query only, and a wavefront keys up
   // to the last of its 32 queries.  Wavefront rows and key blocks are both aligned to 32, so every key
   // block a wavefront visits holds at least one allowed key for each of its queries.
-  const int kend = CAUSAL ? min(len, (int)(blockIdx.x * ROWS_WG + ROWS_WG)) : len;
-  const int wend = CAUSAL ? min(len, (int)(blockIdx.x * ROWS_WG + wave * 32 + 32)) : len;
+  const int kend = CAUSAL ? min(len, (int)(rb * ROWS_WG + ROWS_WG)) : len;
+  const int wend = CAUSAL ? min(len, (int)(rb * ROWS_WG + wave * 32 + 32)) : len;
   TileRegs<DH> tk, tv;
   tk.load(base + D, ld, min(TILE, Tn), dh);
   tv.load(base + 2 * D, ld, min(TILE, Tn), dh);
@@ -335,12 +336,13 @@ __global__ __launch_bounds__(NT, dq_waves(DH, DROP)) void attn_bwd_dq_mfma(const
   constexpr int TBATCH = DH <= 64 ? 1 : NB % 2 == 0 ? 2 : 3;   // K^T fragment pairs of a batch
   static_assert(NK % KBATCH == 0 && NB % TBATCH == 0, "batches must divide the head size");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5;
-  const int b = blockIdx.z, hd = blockIdx.y;
+  const AttnBlock blk = attn_block();
+  const int b = blk.b, hd = blk.hd, rb = blk.rb;
   const int D = H * dh;
   const size_t ld = (size_t)3 * D;
   const int len = lengths ? min(max(lengths[b], 1), Tn) : Tn;  // a length outside 1..T is treated as the nearest valid one
   const bf16_t *base = qkv + (size_t)b * Tn * ld + hd * dh;
-  const int q = blockIdx.x * ROWS_WG + wave * 32 + (lane & 31);
+  const int q = rb * ROWS_WG + wave * 32 + (lane & 31);
   const bool qok = q < Tn;
   const bf16_t *qrow = qok ? base + (size_t)q * ld : nullptr;
   const bf16_t *dorow = qok ? dout + ((size_t)b * Tn + q) * D + hd * dh : nullptr;
@@ -366,8 +368,8 @@ __global__ __launch_bounds__(NT, dq_waves(DH, DROP)) void attn_bwd_dq_mfma(const
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
 
-  const int kend = CAUSAL ? min(len, (int)(blockIdx.x * ROWS_WG + ROWS_WG)) : len;       // as in the forward kernel
-  const int wend = CAUSAL ? min(len, (int)(blockIdx.x * ROWS_WG + wave * 32 + 32)) : len;
+  const int kend = CAUSAL ? min(len, (int)(rb * ROWS_WG + ROWS_WG)) : len;       // as in the forward kernel
+  const int wend = CAUSAL ? min(len, (int)(rb * ROWS_WG + wave * 32 + 32)) : len;
   TileRegs<DH> tk, tv;
   tk.load(base + D, ld, min(TILE, Tn), dh);
   tv.load(base + 2 * D, ld, min(TILE, Tn), dh);
@@ -486,12 +488,13 @@ __global__ __launch_bounds__(NT, dkv_waves(DH)) void attn_bwd_dkv_mfma(const bf1
   constexpr int TBATCH = DH <= 64 ? 1 : (NB % 3 == 0 && DH < 192) ? 3 : 2;   // transposed dO / Q fragment pairs in flight
   static_assert(NK % KBATCH == 0 && NB % TBATCH == 0, "batches must divide the head size");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5;
-  const int b = blockIdx.z, hd = blockIdx.y;
+  const AttnBlock blk = attn_block();
+  const int b = blk.b, hd = blk.hd, rb = blk.rb;
   const int D = H * dh;
   const size_t ld = (size_t)3 * D;
   const int len = lengths ? min(max(lengths[b], 1), Tn) : Tn;  // a length outside 1..T is treated as the nearest valid one
   const bf16_t *base = qkv + (size_t)b * Tn * ld + hd * dh;
-  const int key = blockIdx.x * ROWS_WG + wave * 32 + (lane & 31);
+  const int key = rb * ROWS_WG + wave * 32 + (lane & 31);
   const bool kok = key < Tn;
   const bf16_t *krow = kok ? base + (size_t)key * ld + D : nullptr;
   const bf16_t *vrow = kok ? base + (size_t)key * ld + 2 * D : nullptr;
@@ -512,7 +515,7 @@ __global__ __launch_bounds__(NT, dkv_waves(DH)) void attn_bwd_dkv_mfma(const bf1
       if constexpr (DO_DV) dv[i][r] = 0.f;
     }
   // a workgroup whose keys are all masked only writes zeros
-  const bool wg_live = blockIdx.x * ROWS_WG < len;
+  const bool wg_live = rb * ROWS_WG < len;
   const size_t stat0 = ((size_t)b * H + hd) * Tn;
   const bf16_t *dobase = dout + (size_t)b * Tn * D + hd * dh;
 
@@ -530,8 +533,8 @@ __global__ __launch_bounds__(NT, dkv_waves(DH)) void attn_bwd_dkv_mfma(const bf1
   };
   // with the causal mask only queries at or after a key see it: start at the tile of the workgroup's
   // first key (ROWS_WG is a multiple of TILE) and let a wavefront skip query blocks before its keys
-  const int qbeg = CAUSAL ? (int)(blockIdx.x * ROWS_WG) : 0;
-  const int wkey0 = blockIdx.x * ROWS_WG + wave * 32;
+  const int qbeg = CAUSAL ? (int)(rb * ROWS_WG) : 0;
+  const int wkey0 = rb * ROWS_WG + wave * 32;
   if (wg_live) load_tile(qbeg);
   for (int q0 = qbeg; wg_live && q0 < Tn; q0 += TILE) {
     __syncthreads();

@@ -81,12 +81,13 @@ __global__ __launch_bounds__(NT) void attn_fwd_mfma_f32(const float *__restrict_
   __shared__ __attribute__((aligned(16))) float sK[TILE * ST];
   __shared__ __attribute__((aligned(16))) float sV[TILE * ST];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5, l32 = lane & 31;
-  const int b = blockIdx.z, hd = blockIdx.y;
+  const AttnBlock blk = attn_block();
+  const int b = blk.b, hd = blk.hd, rb = blk.rb;
   const int D = H * dh;
   const size_t ld = (size_t)3 * D;
   const int len = lengths ? min(max(lengths[b], 1), Tn) : Tn;  // a length outside 1..T is treated as the nearest valid one
   const float *base = qkv + (size_t)b * Tn * ld + hd * dh;
-  const int q = blockIdx.x * ROWS_WG + wave * 32 + l32;
+  const int q = rb * ROWS_WG + wave * 32 + l32;
   float qf[DH / 2];
   own_row<DH>(q < Tn ? base + (size_t)q * ld : nullptr, h2, dh, qf);
   const float c = scale * LOG2E;
@@ -96,8 +97,8 @@ __global__ __launch_bounds__(NT) void attn_fwd_mfma_f32(const float *__restrict_
   for (int i = 0; i < NB; ++i) zero16(oacc[i]);
 
   // causal: the workgroup needs keys up to its last query, a wavefront up to the last of its 32 queries
-  const int kend = CAUSAL ? min(len, (int)(blockIdx.x * ROWS_WG + ROWS_WG)) : len;
-  const int wend = CAUSAL ? min(len, (int)(blockIdx.x * ROWS_WG + wave * 32 + 32)) : len;
+  const int kend = CAUSAL ? min(len, (int)(rb * ROWS_WG + ROWS_WG)) : len;
+  const int wend = CAUSAL ? min(len, (int)(rb * ROWS_WG + wave * 32 + 32)) : len;
   TileRegsF<DH> tk, tv;
   tk.load(base + D, ld, min(TILE, Tn), dh);
   tv.load(base + 2 * D, ld, min(TILE, Tn), dh);
@@ -183,12 +184,13 @@ __global__ __launch_bounds__(NT) void attn_bwd_dq_mfma_f32(const float *__restri
   __shared__ __attribute__((aligned(16))) float sK[TILE * ST];
   __shared__ __attribute__((aligned(16))) float sV[TILE * ST];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5, l32 = lane & 31;
-  const int b = blockIdx.z, hd = blockIdx.y;
+  const AttnBlock blk = attn_block();
+  const int b = blk.b, hd = blk.hd, rb = blk.rb;
   const int D = H * dh;
   const size_t ld = (size_t)3 * D;
   const int len = lengths ? min(max(lengths[b], 1), Tn) : Tn;  // a length outside 1..T is treated as the nearest valid one
   const float *base = qkv + (size_t)b * Tn * ld + hd * dh;
-  const int q = blockIdx.x * ROWS_WG + wave * 32 + l32;
+  const int q = rb * ROWS_WG + wave * 32 + l32;
   const bool qok = q < Tn;
   float qf[DH / 2], dof[DH / 2];
   own_row<DH>(qok ? base + (size_t)q * ld : nullptr, h2, dh, qf);
@@ -209,8 +211,8 @@ __global__ __launch_bounds__(NT) void attn_bwd_dq_mfma_f32(const float *__restri
 #pragma unroll
   for (int i = 0; i < NB; ++i) zero16(acc[i]);
 
-  const int kend = CAUSAL ? min(len, (int)(blockIdx.x * ROWS_WG + ROWS_WG)) : len;       // as in the forward kernel
-  const int wend = CAUSAL ? min(len, (int)(blockIdx.x * ROWS_WG + wave * 32 + 32)) : len;
+  const int kend = CAUSAL ? min(len, (int)(rb * ROWS_WG + ROWS_WG)) : len;       // as in the forward kernel
+  const int wend = CAUSAL ? min(len, (int)(rb * ROWS_WG + wave * 32 + 32)) : len;
   TileRegsF<DH> tk, tv;
   tk.load(base + D, ld, min(TILE, Tn), dh);
   tv.load(base + 2 * D, ld, min(TILE, Tn), dh);
@@ -284,12 +286,13 @@ __global__ __launch_bounds__(NT) void attn_bwd_dkv_mfma_f32(const float *__restr
   __shared__ __attribute__((aligned(16))) float sDO[TILE * ST];
   __shared__ float sL[TILE], sDl[TILE];   // lse*log2(e) and delta of the tile's queries
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5, l32 = lane & 31;
-  const int b = blockIdx.z, hd = blockIdx.y;
+  const AttnBlock blk = attn_block();
+  const int b = blk.b, hd = blk.hd, rb = blk.rb;
   const int D = H * dh;
   const size_t ld = (size_t)3 * D;
   const int len = lengths ? min(max(lengths[b], 1), Tn) : Tn;  // a length outside 1..T is treated as the nearest valid one
   const float *base = qkv + (size_t)b * Tn * ld + hd * dh;
-  const int key = blockIdx.x * ROWS_WG + wave * 32 + l32;
+  const int key = rb * ROWS_WG + wave * 32 + l32;
   const bool kok = key < Tn;
   float kf[DH / 2], vf[DH / 2];
   own_row<DH>(kok ? base + (size_t)key * ld + D : nullptr, h2, dh, kf);
@@ -302,7 +305,7 @@ __global__ __launch_bounds__(NT) void attn_bwd_dkv_mfma_f32(const float *__restr
     zero16(dk[i]);
     zero16(dv[i]);
   }
-  const bool wg_live = blockIdx.x * ROWS_WG < len;   // a workgroup whose keys are all masked only writes zeros
+  const bool wg_live = rb * ROWS_WG < len;   // a workgroup whose keys are all masked only writes zeros
   const size_t stat0 = ((size_t)b * H + hd) * Tn;
   const float *dobase = dout + (size_t)b * Tn * D + hd * dh;
 
@@ -319,8 +322,8 @@ __global__ __launch_bounds__(NT) void attn_bwd_dkv_mfma_f32(const float *__restr
     }
   };
   // causal: only queries at or after a key see it (ROWS_WG is a multiple of TILE)
-  const int qbeg = CAUSAL ? (int)(blockIdx.x * ROWS_WG) : 0;
-  const int wkey0 = blockIdx.x * ROWS_WG + wave * 32;
+  const int qbeg = CAUSAL ? (int)(rb * ROWS_WG) : 0;
+  const int wkey0 = rb * ROWS_WG + wave * 32;
   if (wg_live) load_tile(qbeg);
   for (int q0 = qbeg; wg_live && q0 < Tn; q0 += TILE) {
     __syncthreads();

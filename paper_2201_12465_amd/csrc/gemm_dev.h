@@ -164,10 +164,7 @@ __device__ __forceinline__ void gemm_staged_epilogue(const GemmDev &p, const f32
 }
 
 // The 8 XCDs receive workgroup ids round-robin; give each a contiguous range of tiles.
-__device__ __forceinline__ int xcd_tile_order(int bid, int nb) {
-  const int xcd = bid & 7, idx = bid >> 3, per = nb >> 3, rem = nb & 7;
-  return (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + idx;
-}
+__device__ __forceinline__ int xcd_tile_order(int bid, int nb) { return xcd_contiguous_order(bid, nb); }
 
 // Work item (k-range `split`, tile (tm, tn)) of workgroup `bid` of a one-dimensional grid of
 // splits * tiles_m * tiles_n workgroups.  Each XCD has its own L2 and takes a contiguous range of an
