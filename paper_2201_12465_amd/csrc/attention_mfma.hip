@@ -129,13 +129,14 @@ __device__ __forceinline__ bf16x8_t pack8(const f32x16_t &v, int s) {
 // issues the global reads (into registers); store() writes them to one or two LDS tiles.  The
 // kernels load tile t+1 right after storing tile t, so the reads are in flight during the MFMAs.
 // Rows >= nvalid are zero.
-template <int DH> struct TileRegs {
-  static constexpr int CPR = DH / 8, N = TILE * CPR / NT;  // 16-byte chunks per row, per thread
+template <int DH, int NTH = NT> struct TileRegs {
+  static constexpr int CPR = DH / 8, N = TILE * CPR / NTH;  // 16-byte chunks per row, per thread
+  static_assert(TILE * CPR % NTH == 0, "a tile is a whole number of 16-byte chunks per thread");
   uint4 r[N];
   __device__ __forceinline__ void load(const bf16_t *src, size_t ld, int nvalid, int dh) {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      const int c = threadIdx.x + NT * i, row = c / CPR, ch = c % CPR;
+      const int c = threadIdx.x + NTH * i, row = c / CPR, ch = c % CPR;
       r[i] = row < nvalid && ch * 8 < dh ? *reinterpret_cast<const uint4 *>(src + (size_t)row * ld + ch * 8)
                                          : make_uint4(0, 0, 0, 0);
     }
@@ -143,7 +144,7 @@ template <int DH> struct TileRegs {
   __device__ __forceinline__ void store(bf16_t *dst0, int stride0, bf16_t *dst1, int stride1) const {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      const int c = threadIdx.x + NT * i, row = c / CPR, ch = c % CPR;
+      const int c = threadIdx.x + NTH * i, row = c / CPR, ch = c % CPR;
       *reinterpret_cast<uint4 *>(dst0 + row * stride0 + ch * 8) = r[i];
       if (dst1) *reinterpret_cast<uint4 *>(dst1 + row * stride1 + ch * 8) = r[i];
     }
@@ -165,27 +166,39 @@ __device__ __forceinline__ int acc_row(int r, int h) { return (r >> 2) * 8 + h *
 // T = 1000: 150 -> 99 us).
 // dK and dV in one pass up to head size 192 (rolled, that fits the register file); above, two passes.
 constexpr bool dkv_two_passes(int dh) { return dh > 192; }
+// key groups of the forward kernel (see attn_fwd_mfma): large heads, where one group leaves one wavefront per SIMD
+constexpr int fwd_key_groups(int dh, bool drop) { return dh > 128 && dh <= 192 ? 2 : 1; }   // head size 256 does not fit 256 registers
 constexpr int fwd_waves(int dh, bool drop) { return dh <= 64 ? (drop ? 3 : 4) : dh <= 128 ? 2 : 1; }
 constexpr int dq_waves(int dh, bool drop) { return dh <= 64 ? (drop ? 2 : 3) : dh <= 96 ? 2 : dh <= 128 ? (drop ? 1 : 2) : 1; }
 constexpr int dkv_waves(int dh) { return dh <= 64 ? 2 : 1; }
 
 // ------------------------------------------------------------------------------------------ forward
-template <int DH, bool CAUSAL, bool DROP>
-__global__ __launch_bounds__(NT, fwd_waves(DH, DROP)) void attn_fwd_mfma(const bf16_t *__restrict__ qkv, const int32_t *__restrict__ lengths,
+// KG = 2: eight wavefronts; wavefronts w and w + 4 own the same 32 queries and take the first / second 32-key
+// block of every tile, each with its own running maximum, denominator and output accumulators, which group 0
+// merges at the end (the usual rescaling to the common maximum).  For large heads this puts two wavefronts
+// on every SIMD -- each within 256 registers -- so that one's softmax arithmetic and LDS waits run under the
+// other's MFMAs, with the same LDS traffic per key as four wavefronts that walk both blocks.
+template <int DH, bool CAUSAL, bool DROP, int KG = 1>
+__global__ __launch_bounds__(NT * KG, KG > 1 ? 1 : fwd_waves(DH, DROP)) void attn_fwd_mfma(const bf16_t *__restrict__ qkv, const int32_t *__restrict__ lengths,
                                                     DropSpec drop, int Tn, int H, int dh, float scale,
                                                     bf16_t *__restrict__ o, float *__restrict__ lse) {
   constexpr int KS = kc_stride(DH), VS = tr_stride(DH), NK = DH / 16, NB = DH / 32;
   // K fragments in flight at one time (4 registers each); small heads run several wavefronts per SIMD
   // instead and have no registers to spare
-  constexpr int KBATCH = DH <= 64 ? 1 : DH > 192 ? NK / 2 : NK;
+  constexpr int KBATCH = DH <= 64 ? 1 : KG > 1 ? 4 : DH > 192 ? NK / 2 : NK;
   static_assert(NK % KBATCH == 0 && (KBATCH == 1 || KBATCH % 2 == 0), "K fragments are pinned in pairs");
   constexpr bool LAZY = DH > 64;   // rescale the output accumulators only when a row's reference maximum moves
   // V^T fragments requested BEFORE the softmax arithmetic of a block, so that their LDS round trip runs
   // under it (48 registers at head size 192; the largest head has none to spare)
-  constexpr int VEARLY = DH <= 64 || DH > 192 ? 0 : NB;
-  __shared__ __attribute__((aligned(16))) bf16_t sK[TILE * KS];
-  __shared__ __attribute__((aligned(16))) bf16_t sV[TILE * VS];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, h2 = lane >> 5;
+  constexpr int VEARLY = DH <= 64 || DH > 192 || KG > 1 ? 0 : NB;
+  // K tile, V tile.  KG > 1: two such stages (and the merge at the end reuses them) -- a wavefront that is done
+  // with tile t stores its part of tile t+1 into the other stage while the others still compute, and one
+  // barrier per tile is enough.
+  constexpr int STG = KG > 1 ? 2 : 1, STAGE = TILE * (KS + VS);
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t *const smem = reinterpret_cast<bf16_t *>(smem_raw);
+  const int lane = threadIdx.x & 63, h2 = lane >> 5;
+  const int wave = (threadIdx.x >> 6) % 4, kgrp = (threadIdx.x >> 6) / 4;   // position among the query rows, key block
   const AttnBlock blk = attn_block();
   const int b = blk.b, hd = blk.hd, rb = blk.rb;
   const int D = H * dh;
@@ -210,20 +223,30 @@ __global__ __launch_bounds__(NT, fwd_waves(DH, DROP)) void attn_fwd_mfma(const b
   // block a wavefront visits holds at least one allowed key for each of its queries.
   const int kend = CAUSAL ? min(len, (int)(rb * ROWS_WG + ROWS_WG)) : len;
   const int wend = CAUSAL ? min(len, (int)(rb * ROWS_WG + wave * 32 + 32)) : len;
-  TileRegs<DH> tk, tv;
+  TileRegs<DH, NT * KG> tk, tv;
   tk.load(base + D, ld, min(TILE, Tn), dh);
   tv.load(base + 2 * D, ld, min(TILE, Tn), dh);
-  for (int k0 = 0; k0 < kend; k0 += TILE) {
+  auto load_tile = [&](int kt) {   // issue the global reads of the tile that starts at key kt
+    tk.load(base + (size_t)kt * ld + D, ld, min(TILE, Tn - kt), dh);
+    tv.load(base + (size_t)kt * ld + 2 * D, ld, min(TILE, Tn - kt), dh);
+  };
+  if constexpr (STG == 2) {
+    tk.store(smem, KS, nullptr, 0);
+    tv.store(smem + TILE * KS, VS, nullptr, 0);
     __syncthreads();
-    tk.store(sK, KS, nullptr, 0);
-    tv.store(sV, VS, nullptr, 0);
-    __syncthreads();
-    if (k0 + TILE < kend) {
-      tk.load(base + (size_t)(k0 + TILE) * ld + D, ld, min(TILE, Tn - k0 - TILE), dh);
-      tv.load(base + (size_t)(k0 + TILE) * ld + 2 * D, ld, min(TILE, Tn - k0 - TILE), dh);
+    if (TILE < kend) load_tile(TILE);
+  }
+  for (int k0 = 0, it = 0; k0 < kend; k0 += TILE, ++it) {
+    bf16_t *const sK = smem + (STG == 2 ? (it & 1) * STAGE : 0), *const sV = sK + TILE * KS;
+    if constexpr (STG == 1) {
+      __syncthreads();
+      tk.store(sK, KS, nullptr, 0);
+      tv.store(sV, VS, nullptr, 0);
+      __syncthreads();
+      if (k0 + TILE < kend) load_tile(k0 + TILE);
     }
 #pragma unroll (DH >= 192 ? 1 : 2)
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = (KG > 1 ? kgrp : 0); kb < (KG > 1 ? kgrp + 1 : 2); ++kb) {
       if (k0 + kb * 32 >= wend) break;
       f32x16_t s;
 #pragma unroll
@@ -250,14 +273,21 @@ __global__ __launch_bounds__(NT, fwd_waves(DH, DROP)) void attn_fwd_mfma(const b
           for (int st = 0; st < 2; ++st) vt[db][st] = tr_frag(sV, VS, db * 32, kb * 32 + 16 * st, lane);
         issue_fence();
       }
+      // Masked scores become -inf; a block wholly inside the sequence (and, with the causal mask, wholly at or
+      // before the wavefront's first query) has none, which is the common case and a wavefront-uniform test.
+      // The scale is applied inside the exponent's fused multiply-add, so the maximum is taken over raw scores.
+      const int kbase = k0 + kb * 32;
+      if (!(kbase + 32 <= len && (!CAUSAL || kbase + 31 <= (int)(rb * ROWS_WG + wave * 32)))) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = kbase + acc_row(r, h2);
+          if (!(key < len && (!CAUSAL || key <= q))) s[r] = -INFINITY;
+        }
+      }
       float mloc = -INFINITY;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = k0 + kb * 32 + acc_row(r, h2);
-        s[r] = (key < len && (!CAUSAL || key <= q)) ? s[r] * c : -INFINITY;
-        mloc = fmaxf(mloc, s[r]);
-      }
-      mloc = half_pair_max(mloc);
+      for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, s[r]);
+      mloc = half_pair_max(mloc) * c;   // c > 0
       // The reference maximum m moves only when a block's maximum exceeds it by more than RESCALE_SLACK
       // (in units of log2): probabilities are then at most 2^RESCALE_SLACK instead of 1, which changes
       // neither O / l nor the log-sum-exp, and the accumulators are rescaled only in the blocks where some
@@ -268,7 +298,7 @@ __global__ __launch_bounds__(NT, fwd_waves(DH, DROP)) void attn_fwd_mfma(const b
       float rs = 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        s[r] = exp2_raw(s[r] - mnew);
+        s[r] = exp2_raw(fmaf(s[r], c, -mnew));   // -inf stays -inf: mnew is finite (every visited block has an allowed key per query)
         rs += s[r];
       }
       rs = half_pair_sum(rs);
@@ -304,6 +334,55 @@ __global__ __launch_bounds__(NT, fwd_waves(DH, DROP)) void attn_fwd_mfma(const b
               db < VEARLY ? vt[db][st] : tr_frag(sV, VS, db * 32, kb * 32 + 16 * st, lane), pf[st], oacc[db], 0, 0, 0);
       }
     }
+    if constexpr (STG == 2) {
+      // the other stage was last read in the previous pass, which every wavefront left through the barrier below
+      if (k0 + TILE < kend) {
+        bf16_t *const nK = smem + ((it + 1) & 1) * STAGE;
+        tk.store(nK, KS, nullptr, 0);
+        tv.store(nK + TILE * KS, VS, nullptr, 0);
+      }
+      __syncthreads();
+      if (k0 + 2 * TILE < kend) load_tile(k0 + 2 * TILE);
+    }
+  }
+  if constexpr (KG > 1) {
+    // group 1 parks (m, l) and its accumulators, CH 32-column blocks at a time, in the K/V tiles' LDS
+    // ([wave][register][lane]: lane-contiguous); group 0 folds them in.  Group 0 has seen key 0, so its
+    // maximum is finite; a group 1 that saw no block has m = -inf, l = 0 and weight 2^(-inf) = 0.
+    float *red = reinterpret_cast<float *>(smem);
+    constexpr int FLOATS = STG * STAGE / 2, STATS = 4 * 2 * 64;
+    constexpr int CH = (FLOATS - STATS) / (4 * 16 * 64) < NB ? (FLOATS - STATS) / (4 * 16 * 64) : NB;
+    static_assert(CH >= 1, "the tiles' LDS holds at least one accumulator block per wavefront");
+    float *stat = red + 4 * CH * 16 * 64 + wave * 128 + lane;
+    float *blk0 = red + wave * CH * 16 * 64 + lane;
+    float a0 = 1.f, a1 = 0.f;
+#pragma unroll
+    for (int d0 = 0; d0 < NB; d0 += CH) {
+      __syncthreads();   // the tiles (first pass) or the previous chunk are no longer being read
+      if (kgrp == 1) {
+        if (d0 == 0) stat[0] = m, stat[64] = l;
+#pragma unroll
+        for (int db = d0; db < NB && db < d0 + CH; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) blk0[((db - d0) * 16 + r) * 64] = oacc[db][r];
+      }
+      __syncthreads();
+      if (kgrp == 0) {
+        if (d0 == 0) {
+          const float m1 = stat[0], l1 = stat[64];
+          const float mstar = fmaxf(m, m1);
+          a0 = exp2_raw(m - mstar);
+          a1 = exp2_raw(m1 - mstar);
+          l = l * a0 + l1 * a1;
+          m = mstar;
+        }
+#pragma unroll
+        for (int db = d0; db < NB && db < d0 + CH; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[db][r] = oacc[db][r] * a0 + blk0[((db - d0) * 16 + r) * 64] * a1;
+      }
+    }
+    if (kgrp != 0) return;   // no barrier follows
   }
   if (q < Tn) {
     const float inv = 1.0f / l;
@@ -676,8 +755,20 @@ template <int DH, bool CAUSAL, bool DROP>
 hipError_t fwd_t(const void *qkv, const int32_t *lengths, const DropSpec &drop, int B, int T, int H, int dh, float scale,
                  void *o, float *lse, hipStream_t s) {
   dim3 grid((T + ROWS_WG - 1) / ROWS_WG, H, B);
-  hipLaunchKernelGGL((attn_fwd_mfma<DH, CAUSAL, DROP>), grid, dim3(NT), 0, s, static_cast<const bf16_t *>(qkv), lengths,
-                     drop, T, H, dh, scale, static_cast<bf16_t *>(o), lse);
+  constexpr int KG = fwd_key_groups(DH, DROP);
+  constexpr size_t lds = (size_t)(KG > 1 ? 2 : 1) * TILE * (kc_stride(DH) + tr_stride(DH)) * sizeof(bf16_t);
+  static_assert(lds <= 160 * 1024, "the tiles fit in LDS");
+  if (lds > 64 * 1024) {
+    static bool raised = false;   // allow more than the default 64 KiB of dynamic LDS, once
+    if (!raised) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_fwd_mfma<DH, CAUSAL, DROP, KG>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+      raised = true;
+    }
+  }
+  hipLaunchKernelGGL((attn_fwd_mfma<DH, CAUSAL, DROP, KG>), grid, dim3(NT * KG), lds, s, static_cast<const bf16_t *>(qkv),
+                     lengths, drop, T, H, dh, scale, static_cast<bf16_t *>(o), lse);
   return hipGetLastError();
 }
 
