@@ -14,7 +14,8 @@
 //   ds_read_b64_tr_b16 for k-major tiles) touch every bank once per 32 lanes.
 // * Rows past the end of an operand are clamped to the last valid row (their products land in
 //   output rows/columns that are never stored), so no lane ever reads out of bounds.
-// * 256 threads = 4 wavefronts in a 2x2 grid over a BM x BN tile; each wavefront owns
+// * 256 threads = 4 wavefronts in a 2x2 grid over a BM x BN tile (other grids: see the instances in
+//   launch_layout); each wavefront owns
 //   (BM/2) x (BN/2) = TM x TN MFMA tiles of 32x32 (v_mfma_f32_32x32x16_bf16), issued as
 //   D = B_frag x A_frag so that a lane ends with four consecutive n of one m.
 #include "devutil.h"
@@ -269,6 +270,9 @@ hipError_t launch_layout(const GemmDev &d, int splits, int variant, hipStream_t 
     case 6: return launch_cfg<AKC, BKC, 256, 128, 3, 4, 2>(d, splits, s);
     case 8: return launch_cfg<AKC, BKC, 128, 128, 2, 2, 2, 2>(d, splits, s);
     case 9: return launch_cfg<AKC, BKC, 128, 128, 3, 2, 2, 2>(d, splits, s);
+    case 10:  // 160 rows: the same restriction for a k-major A operand
+      if constexpr (AKC) return launch_cfg<AKC, BKC, 160, 128, 2, 1, 4>(d, splits, s);
+      else return hipErrorInvalidValue;
     case 7:  // 192 columns: the k-major swizzle needs a power-of-two row length, so k-contiguous operands only
       if constexpr (AKC && BKC) return launch_cfg<AKC, BKC, 256, 192, 2, 4, 2>(d, splits, s);
       else return hipErrorInvalidValue;
@@ -286,14 +290,14 @@ bool gemm_pipe_eligible(const GemmArgs &a, int kps) {
 }
 
 void gemm_pipe_tile(int variant, int *bm, int *bn) {
-  static const int t[10][2] = {{128, 128}, {128, 128}, {256, 128}, {256, 128}, {256, 256}, {256, 256}, {256, 128}, {256, 192}, {128, 128}, {128, 128}};
+  static const int t[11][2] = {{128, 128}, {128, 128}, {256, 128}, {256, 128}, {256, 256}, {256, 256}, {256, 128}, {256, 192}, {128, 128}, {128, 128}, {160, 128}};
   *bm = t[variant][0];
   *bn = t[variant][1];
 }
 
 int gemm_pipe_pick_variant(bool a_kc, bool b_kc, int M, int N, int K) {
   const int forced = forced_gemm_pipe_variant();
-  if (forced != -1) return forced == 7 && !(a_kc && b_kc) ? -2 : forced;
+  if (forced != -1) return (forced == 7 && !(a_kc && b_kc)) || (forced == 10 && !a_kc) ? -2 : forced;
   (void)K;
   // Measured inside the layer (whole training steps, same box, libraries alternating), since a loop over one
   // launch flatters whatever profits most from warm caches.
@@ -303,8 +307,17 @@ int gemm_pipe_pick_variant(bool a_kc, bool b_kc, int M, int N, int K) {
   // 0.799 -> 0.779, 12.03 -> 11.68 ms for dy^T x; 12.07 -> 11.75 ms for dy W); the variants with three
   // stages or two wavefront groups per tile hold more LDS and slow the kernels they run beside.
   if (!a_kc && !b_kc) return 0;
-  if (a_kc && !b_kc) return 0;
+  // More 128x128 tiles than the chip holds at two workgroups per CU, but not with 160x128 tiles: one round
+  // instead of one and a bit (12608 x 768 outputs: 594 tiles against 474; dy W at k = 3072 / 2304 / 768 alone:
+  // 83 -> 66, 64 -> 51, 28 -> 22 us).
+  const long slots = 512, tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
+  const bool one_round_160 = tiles128 > slots && (long)((M + 159) / 160) * ((N + 127) / 128) <= slots;
+  if (a_kc && !b_kc) return one_round_160 ? 10 : 0;
   if (!(a_kc && b_kc)) return -2;
+  // the same for k-contiguous operands, ahead of one 75-78 %-full round of 256x192 tiles (ViT stack, libraries
+  // alternating: 10.64 ms per step -> 10.58 with the rule for dy W alone -> 10.46 with both; BERT-base shape,
+  // where it takes the fused projection: 0.3703 -> 0.3682 ms)
+  if (one_round_160) return 10;
   // Both operands k-contiguous:
   // 256x192 tiles on 8 wavefronts halve the L1 and LDS traffic per flop and win when they fill the
   // chip in whole rounds (one workgroup per CU); otherwise 128x128 / 2 stages, two workgroups per CU.

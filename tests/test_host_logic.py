@@ -370,15 +370,20 @@ def test_kernel_selection_rules():
     lib = b.test_lib()
     D, F = 768, 3072
     nt = lambda M, N, K: lib.fl_test_gemm_variant(1, 1, M, N, K)
-    # BERT-base-shaped layer (M = 4096): wide outputs fill the chip in one round of 256x192 tiles; narrow
+    # BERT-base-shaped layer (M = 4096): the widest output fills the chip in one round of 256x192 tiles; the
+    # fused projection (576 tiles of 128x128 for 512 places) runs 468 tiles of 160x128 in one round; narrow
     # outputs (at most one 128x128 tile per CU) run three stages and two k-groups of wavefronts per tile
-    assert [nt(4096, 3 * D, D), nt(4096, D, D), nt(4096, F, D), nt(4096, D, F), nt(4096, D, 3 * D)] == [7, 9, 7, 9, 9]
-    # ViT-shaped stack (M = 12608): 3.1 rounds of 256x192 tiles are not worth it, one round for N = 768 is
-    assert [nt(12608, 3 * D, D), nt(12608, D, D), nt(12608, F, D), nt(12608, D, F)] == [0, 7, 0, 7]
+    assert [nt(4096, 3 * D, D), nt(4096, D, D), nt(4096, F, D), nt(4096, D, F), nt(4096, D, 3 * D)] == [10, 9, 7, 9, 9]
+    # ViT-shaped stack (M = 12608): 3.1 rounds of 256x192 tiles are not worth it; N = 768 has 594 tiles of
+    # 128x128 for 512 places and runs 474 tiles of 160x128 in one round
+    assert [nt(12608, 3 * D, D), nt(12608, D, D), nt(12608, F, D), nt(12608, D, F)] == [0, 10, 0, 10]
     # speech-shaped layer (M = 8000): two full rounds are
     assert nt(8000, F, D) == 7 and nt(8000, D, F) == 0
-    # operands that are not contiguous along k (dy W without transposed weights, dy^T x): 128x128 tiles, 2 stages
-    assert lib.fl_test_gemm_variant(1, 0, 12608, D, F) == 0 and lib.fl_test_gemm_variant(0, 0, D, F, 4096) == 0
+    # operands that are not contiguous along k (dy W without transposed weights, dy^T x): 128x128 tiles, 2 stages,
+    # or the 160x128 tiles where they turn one round and a bit into one
+    assert lib.fl_test_gemm_variant(1, 0, 12608, F, D) == 0 and lib.fl_test_gemm_variant(0, 0, D, F, 4096) == 0
+    assert [lib.fl_test_gemm_variant(1, 0, 12608, D, k) for k in (F, D, 3 * D)] == [10, 10, 10]
+    assert lib.fl_test_gemm_variant(1, 0, 8000, D, F) == 0 and lib.fl_test_gemm_variant(0, 0, D, 12608, 4096) == 0
     # weight gradients of the BERT-base layer: about 430 workgroups
     splits = lambda M, N, K: lib.fl_test_gemm_splits(b.FL_BF16, M, N, K)
     assert [splits(D, F, 4096), splits(F, D, 4096), splits(D, D, 4096), splits(3 * D, D, 4096)] == [3, 3, 6, 4]
