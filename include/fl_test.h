@@ -34,10 +34,12 @@ int32_t fl_test_gemm_time(int32_t dtype, int32_t a_kc, int32_t b_kc, const void 
                           void *hip_stream);
 int32_t fl_test_gemm_splits(int32_t dtype, int32_t M, int32_t N, int32_t K);
 /* Host-side selection rules (no GPU work): the pipelined bf16 kernel's tile variant for a problem
- * (-2 = the register-staged kernel; operand flags as in fl_test_gemm), whether an fp32 output runs on
+ * (-2 = the register-staged kernel; operand flags as in fl_test_gemm; _forward: y = x W^T as the forward
+ * pass launches it, with the chip to itself), whether an fp32 output runs on
  * the 32 x 32-tile kernel, and which attention kernels serve a head size (0 general, 1 bf16 matrix-core,
  * 2 fp32 matrix-core). */
 int32_t fl_test_gemm_variant(int32_t a_kc, int32_t b_kc, int32_t M, int32_t N, int32_t K);
+int32_t fl_test_gemm_variant_forward(int32_t M, int32_t N, int32_t K);
 int32_t fl_test_gemm_f32_small(int32_t M, int32_t N);
 int32_t fl_test_attention_path(int32_t dtype, int32_t dh);
 /* Tile/stage variant of the pipelined bf16 GEMM: -1 automatic, 0..3 forced, -2 use the plain kernel. */

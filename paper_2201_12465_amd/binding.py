@@ -126,6 +126,7 @@ def _signatures():
         "fl_test_copy": (i32, [vp, vp, u64, vp]),
         "fl_test_mfma_probe": (i32, [i32, i32, i32, vp, C.POINTER(C.c_double), vp]),
         "fl_test_gemm_variant": (i32, [i32, i32, i32, i32, i32]),
+        "fl_test_gemm_variant_forward": (i32, [i32, i32, i32]),
         "fl_test_gemm_f32_small": (i32, [i32, i32]),
         "fl_test_attention_path": (i32, [i32, i32]),
         "fl_test_transpose_bf16": (i32, [i32, vp, vp, vp, vp, vp]),

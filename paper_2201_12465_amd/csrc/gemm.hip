@@ -286,7 +286,7 @@ hipError_t launch_gemm(int dt, const GemmArgs &a, hipStream_t stream) {
   // every k-range must be non-empty, or its partial slab would stay unwritten
   if ((long)(splits - 1) * kps >= a.K) return hipErrorInvalidValue;
   if (dt == DT_BF16 && gemm_pipe_eligible(a, kps)) {
-    int variant = gemm_pipe_pick_variant(a.a_kc, a.b_kc, a.M, a.N, a.K);
+    int variant = gemm_pipe_pick_variant(a.a_kc, a.b_kc, a.M, a.N, a.K, a.alone);
     if (variant > 0 && d.drop_where) variant = 0;  // the dropout steps exist in the 128x128 / 2-stage instance only,
     if (d.drop_where && !(a.a_kc && a.b_kc)) variant = -2;  // and there for k-contiguous operands only
     if (variant >= 0) return launch_gemm_bf16_pipe(a, &d, splits, variant, stream);

@@ -273,6 +273,9 @@ hipError_t launch_layout(const GemmDev &d, int splits, int variant, hipStream_t 
     case 10:  // 160 rows: the same restriction for a k-major A operand
       if constexpr (AKC) return launch_cfg<AKC, BKC, 160, 128, 2, 1, 4>(d, splits, s);
       else return hipErrorInvalidValue;
+    case 11:  // 96 rows: likewise
+      if constexpr (AKC) return launch_cfg<AKC, BKC, 96, 128, 2, 1, 4>(d, splits, s);
+      else return hipErrorInvalidValue;
     case 7:  // 192 columns: the k-major swizzle needs a power-of-two row length, so k-contiguous operands only
       if constexpr (AKC && BKC) return launch_cfg<AKC, BKC, 256, 192, 2, 4, 2>(d, splits, s);
       else return hipErrorInvalidValue;
@@ -290,14 +293,14 @@ bool gemm_pipe_eligible(const GemmArgs &a, int kps) {
 }
 
 void gemm_pipe_tile(int variant, int *bm, int *bn) {
-  static const int t[11][2] = {{128, 128}, {128, 128}, {256, 128}, {256, 128}, {256, 256}, {256, 256}, {256, 128}, {256, 192}, {128, 128}, {128, 128}, {160, 128}};
+  static const int t[12][2] = {{128, 128}, {128, 128}, {256, 128}, {256, 128}, {256, 256}, {256, 256}, {256, 128}, {256, 192}, {128, 128}, {128, 128}, {160, 128}, {96, 128}};
   *bm = t[variant][0];
   *bn = t[variant][1];
 }
 
-int gemm_pipe_pick_variant(bool a_kc, bool b_kc, int M, int N, int K) {
+int gemm_pipe_pick_variant(bool a_kc, bool b_kc, int M, int N, int K, bool alone) {
   const int forced = forced_gemm_pipe_variant();
-  if (forced != -1) return (forced == 7 && !(a_kc && b_kc)) || (forced == 10 && !a_kc) ? -2 : forced;
+  if (forced != -1) return (forced == 7 && !(a_kc && b_kc)) || ((forced == 10 || forced == 11) && !a_kc) ? -2 : forced;
   (void)K;
   // Measured inside the layer (whole training steps, same box, libraries alternating), since a loop over one
   // launch flatters whatever profits most from warm caches.
@@ -312,7 +315,13 @@ int gemm_pipe_pick_variant(bool a_kc, bool b_kc, int M, int N, int K) {
   // 83 -> 66, 64 -> 51, 28 -> 22 us).
   const long slots = 512, tiles128 = (long)((M + 127) / 128) * ((N + 127) / 128);
   const bool one_round_160 = tiles128 > slots && (long)((M + 159) / 160) * ((N + 127) / 128) <= slots;
-  if (a_kc && !b_kc) return one_round_160 ? 10 : 0;
+  // One round of 128x128 tiles that leaves a quarter of the places empty, where 96x128 tiles fill them (8000 x 768
+  // outputs: 378 tiles against 504; on their own 57 -> 48, 42 -> 38, 20 -> 17.5 us at k = 3072 / 2304 / 768).  Only with
+  // more tiles than CUs (below that the two-k-group variant is ahead), and only for a launch that has the chip to
+  // itself: in the backward pass the places that 128x128 tiles leave empty take the weight-gradient workgroups of
+  // the other lane, and whole steps of the speech shape are slower with the rule there (0.725 -> 0.738 ms).
+  const bool one_round_96 = alone && tiles128 > 256 && 5 * tiles128 <= 4 * slots && (long)((M + 95) / 96) * ((N + 127) / 128) <= slots;
+  if (a_kc && !b_kc) return one_round_160 ? 10 : one_round_96 ? 11 : 0;
   if (!(a_kc && b_kc)) return -2;
   // the same for k-contiguous operands, ahead of one 75-78 %-full round of 256x192 tiles (ViT stack, libraries
   // alternating: 10.64 ms per step -> 10.58 with the rule for dy W alone -> 10.46 with both; BERT-base shape,
@@ -335,7 +344,7 @@ int gemm_pipe_pick_variant(bool a_kc, bool b_kc, int M, int N, int K) {
   // 0.3835 -> 0.3756 ms (four stages, or one k-group with three stages: 0.379 / 0.380).  With more tiles than
   // CUs the two-workgroups-per-CU variant is ahead (speech shape, 378 tiles: 0.765 against 0.835 ms).
   if ((long)((M + 127) / 128) * ((N + 127) / 128) <= 256) return 9;
-  return 0;
+  return one_round_96 ? 11 : 0;
 }
 
 hipError_t launch_gemm_bf16_pipe(const GemmArgs &a, const void *dev, int splits, int variant, hipStream_t s) {

@@ -34,6 +34,7 @@ struct GemmArgs {
   void *C = nullptr;
   int M = 0, N = 0, K = 0, lda = 0, ldb = 0, ldc = 0;
   bool a_kc = true, b_kc = true;
+  bool alone = false;  // nothing else is expected on the chip beside this launch (the forward pass): tiles that fill every place
   const void *bias = nullptr, *residual = nullptr, *aux = nullptr;
   void *preact = nullptr;
   int act = 0, dact = 0;
@@ -65,7 +66,7 @@ hipError_t launch_gemm_f32_small(const GemmArgs &a, const void *gemm_dev, int sp
 
 // The pipelined bf16 kernel (gemm_pipe.hip); launch_gemm uses it whenever the problem is eligible.
 bool gemm_pipe_eligible(const GemmArgs &a, int k_per_split);
-int gemm_pipe_pick_variant(bool a_kc, bool b_kc, int M, int N, int K);  // < 0: use the kernel in gemm.hip
+int gemm_pipe_pick_variant(bool a_kc, bool b_kc, int M, int N, int K, bool alone = false);  // < 0: use the kernel in gemm.hip
 hipError_t launch_gemm_bf16_pipe(const GemmArgs &a, const void *gemm_dev, int splits, int variant, hipStream_t s);
 
 // out_s[n] = sum_p partial[p*stride + s*seglen + n]  for s < nseg (<= 3), n < seglen;

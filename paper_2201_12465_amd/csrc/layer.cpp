@@ -961,6 +961,7 @@ int op_linear(fl_layer *L, int lin, int xslot, int rslot, int act, int K, int N,
   a.A = tp.slots[xslot].value; a.lda = K; a.a_kc = true;
   a.B = L->params[kLinear[lin].w]; a.ldb = K; a.b_kc = true;
   a.M = M; a.N = N; a.K = K; a.C = y; a.ldc = N;
+  a.alone = true;   // the forward pass runs one kernel at a time
   a.bias = L->params[kLinear[lin].b];
   a.act = act;
   if (rslot >= 0) a.residual = tp.slots[rslot].value;

@@ -91,7 +91,10 @@ void fl_test_gemm_force_variant(int32_t v) { gemm_pipe_force_variant(v); }
 void fl_test_gemm_force_tile_height(int32_t tmw) { gemm_force_tile_height(tmw); }
 
 int32_t fl_test_gemm_variant(int32_t a_kc, int32_t b_kc, int32_t M, int32_t N, int32_t K) {
-  return gemm_pipe_pick_variant(a_kc != 0, b_kc != 0, M, N, K);
+  return gemm_pipe_pick_variant(a_kc != 0, b_kc != 0, M, N, K, false);
+}
+int32_t fl_test_gemm_variant_forward(int32_t M, int32_t N, int32_t K) {
+  return gemm_pipe_pick_variant(true, true, M, N, K, true);
 }
 int32_t fl_test_gemm_f32_small(int32_t M, int32_t N) { return gemm_f32_small_applies(M, N) ? 1 : 0; }
 int32_t fl_test_attention_path(int32_t dtype, int32_t dh) {

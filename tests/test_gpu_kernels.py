@@ -97,7 +97,7 @@ def test_gemm_tile_heights(dtype, mode, tmw, shape):
     assert rel_err(to_np(dC), ref) <= _tol(dtype), (dtype, mode, tmw, shape)
 
 
-@pytest.mark.parametrize("variant", [-2, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
+@pytest.mark.parametrize("variant", [-2, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11])
 @pytest.mark.parametrize("mode", ["nt", "nn", "tn"])
 @pytest.mark.parametrize("shape", [(304, 264, 192), (520, 392, 128), (8, 8, 64), (1000, 776, 640)])
 def test_gemm_bf16_pipelined_variants(variant, mode, shape):
@@ -171,7 +171,7 @@ def test_gemm_backward_epilogue(dtype, dact):
     assert rel_err(to_np(dC), ref) <= _tol(dtype)
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11])
 def test_gemm_epilogues_on_every_pipelined_variant(variant):
     """Bias, pre-activation copy, GELU and residual (forward form), and skip + GELU' (backward form), through
     the staged epilogue of every tile shape of the pipelined kernel; ragged M and N, several tiles."""

@@ -377,8 +377,12 @@ def test_kernel_selection_rules():
     # ViT-shaped stack (M = 12608): 3.1 rounds of 256x192 tiles are not worth it; N = 768 has 594 tiles of
     # 128x128 for 512 places and runs 474 tiles of 160x128 in one round
     assert [nt(12608, 3 * D, D), nt(12608, D, D), nt(12608, F, D), nt(12608, D, F)] == [0, 10, 0, 10]
-    # speech-shaped layer (M = 8000): two full rounds are
+    # speech-shaped layer (M = 8000): two full rounds are; the 378 tiles of an N = 768 output become 504 tiles of
+    # 96x128 in the forward pass, where nothing else would use the places they leave empty
     assert nt(8000, F, D) == 7 and nt(8000, D, F) == 0
+    fwd = lib.fl_test_gemm_variant_forward
+    assert [fwd(8000, D, F), fwd(8000, D, D), fwd(8000, F, D), fwd(8000, 3 * D, D)] == [11, 11, 7, 0]
+    assert [fwd(4096, 3 * D, D), fwd(4096, D, D), fwd(4096, F, D), fwd(12608, D, F)] == [10, 9, 7, 10]
     # operands that are not contiguous along k (dy W without transposed weights, dy^T x): 128x128 tiles, 2 stages,
     # or the 160x128 tiles where they turn one round and a bit into one
     assert lib.fl_test_gemm_variant(1, 0, 12608, F, D) == 0 and lib.fl_test_gemm_variant(0, 0, D, F, 4096) == 0
