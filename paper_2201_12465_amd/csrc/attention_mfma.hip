@@ -510,13 +510,18 @@ __global__ __launch_bounds__(NT, dq_waves(DH, DROP)) void attn_bwd_dq_mfma(const
           for (int e = 0; e < 4; ++e) dp[g * 4 + e] *= kp[e];
         }
       }
+      // masked scores become -inf (probability 2^-inf = 0) only in blocks that reach the sequence end or the
+      // diagonal: a wavefront-uniform test, as in the forward kernel
+      const int kbase = k0 + kb * 32;
+      if (!(kbase + 32 <= len && (!CAUSAL || kbase + 31 <= (int)(rb * ROWS_WG + wave * 32)))) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = k0 + kb * 32 + acc_row(r, h2);
-        const float e = exp2_raw(s[r] * c - L2);
-        const float p = (key < len && (!CAUSAL || key <= q)) ? e : 0.f;
-        s[r] = p * (dp[r] - dl);   // dS^T
+        for (int r = 0; r < 16; ++r) {
+          const int key = kbase + acc_row(r, h2);
+          if (!(key < len && (!CAUSAL || key <= q))) s[r] = -INFINITY;
+        }
       }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] = exp2_raw(fmaf(s[r], c, -L2)) * (dp[r] - dl);   // dS^T
       const bf16x8_t dsf[2] = {pack8(s, 0), pack8(s, 1)};
       pipelined<NB / TBATCH>(
           load_t,
