@@ -358,6 +358,11 @@ ATTN_CASES = [  # B, T, H, dh, lengths
     (2, 70, 1, 256, [70, 33]),
     (2, 75, 2, 48, [75, 9]),      # head sizes between the multiples of 32: padded kernel instances
     (1, 45, 1, 112, None),
+    # head sizes 129..192 (bf16 forward: two key groups of wavefronts per query block, merged at the end):
+    (2, 30, 1, 192, [30, 7]),     # less than one 32-key block: the second group sees no key at all
+    (2, 64, 2, 192, [64, 33]),    # exactly one tile; one key for the second group
+    (1, 130, 1, 160, [97]),       # padded instance, an odd number of tiles
+    (2, 257, 1, 192, [257, 128]), # a last tile of one key; a length on a tile boundary
 ]
 
 
@@ -375,6 +380,14 @@ def test_attention_forward_backward(dtype, case, causal, p_drop):
         _attention_case(b, dtype, case, causal, p_drop)
     finally:
         b.lib().fl_test_attention_force_general(0)
+
+
+@pytest.mark.parametrize("causal,p_drop", [(False, 0.0), (True, 0.0), (False, 0.2), (True, 0.35)])
+def test_attention_forward_large_head_with_a_sequence_of_one_key(causal, p_drop):
+    """Forward only (output and log-sum-exp against the oracle): with one key and dropout the reference gradient
+    is exactly 0 and the kernels return the rounding noise of the stored output, see
+    test_one_kernel_attention_backward_agrees_with_the_two_kernel_path."""
+    _attention_case(_lib(), "bf16", (2, 30, 1, 192, [30, 1]), causal, p_drop, check_backward=False)
 
 
 ATTN_ONE_KERNEL_BWD_CASES = [  # head size 64 and T <= 224: the one-kernel backward (2, 4, 6 or 8 wavefronts)
