@@ -90,7 +90,7 @@ __device__ __forceinline__ bf16x8_t frag(const unsigned char *stage, int r0, int
 // groups of wavefronts work on the same tile, group g taking the g-th part of every k-tile, and their
 // accumulators are added through LDS at the end.  For outputs with few tiles (one workgroup per CU)
 // this puts two wavefronts on every SIMD, so that one's LDS reads overlap the other's MFMAs.
-template <bool AKC, bool BKC, int BM, int BN, int NS, int WM, int WN, bool DROP, int KG>
+template <bool AKC, bool BKC, int BM, int BN, int NS, int WM, int WN, bool DROP, int KG, int EPI = EPI_FULL>
 __global__ __launch_bounds__(WM *WN *KG * 64) void gemm_bf16_pipe(GemmDev p) {
   constexpr int NW = WM * WN * KG;
   constexpr int KKS = KT / 16 / KG;  // 16-wide k-steps of a k-tile per group
@@ -217,10 +217,10 @@ __global__ __launch_bounds__(WM *WN *KG * 64) void gemm_bf16_pipe(GemmDev p) {
     if (kg > 0) return;  // no barrier follows: group 0 finishes alone
   }
   float *cw = reinterpret_cast<float *>(smem) + (size_t)wpos * 32 * (TN * 32 + 4);
-  gemm_staged_epilogue<bf16_t, TM, TN, DROP>(p, acc, cw, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane);
+  gemm_staged_epilogue<bf16_t, TM, TN, DROP, EPI>(p, acc, cw, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane);
 }
 
-template <bool AKC, bool BKC, int BM, int BN, int NS, int WM, int WN, bool DROP, int KG>
+template <bool AKC, bool BKC, int BM, int BN, int NS, int WM, int WN, bool DROP, int KG, int EPI = EPI_FULL>
 hipError_t launch_cfg_d(GemmDev d, int splits, hipStream_t s) {
   constexpr size_t stage_lds = (size_t)NS * (BM + BN) * 128;
   constexpr size_t epi_lds = (size_t)WM * WN * 32 * (BN / WN + 4) * sizeof(float);
@@ -228,7 +228,7 @@ hipError_t launch_cfg_d(GemmDev d, int splits, hipStream_t s) {
   constexpr size_t lds0 = stage_lds > epi_lds ? stage_lds : epi_lds;
   constexpr size_t lds = lds0 > red_lds ? lds0 : red_lds;
   static_assert(lds <= 160 * 1024, "stages do not fit in LDS");
-  auto kern = gemm_bf16_pipe<AKC, BKC, BM, BN, NS, WM, WN, DROP, KG>;
+  auto kern = gemm_bf16_pipe<AKC, BKC, BM, BN, NS, WM, WN, DROP, KG, EPI>;
   if (lds > 64 * 1024) {
     static bool raised = false;
     if (!raised) {
@@ -254,6 +254,14 @@ hipError_t launch_cfg(const GemmDev &d, int splits, hipStream_t s) {
       return launch_cfg_d<AKC, BKC, BM, BN, NS, WM, WN, true, KG>(d, splits, s);
     else
       return hipErrorInvalidValue;
+  }
+  // the instances the layer runs on carry only the epilogue steps of their launch (see gemm_epi_kind)
+  constexpr bool specialised = (BM == 128 && BN == 128 && WM == 2 && WN == 2 && ((NS == 2 && KG == 1) || (NS == 3 && KG == 2))) ||
+                               (BM == 256 && BN == 192) || (BN == 128 && (BM == 160 || BM == 96));
+  if constexpr (specialised) {
+    const int kind = gemm_epi_kind(d.partial != nullptr, d.act, d.dact);
+    if (kind == EPI_PARTIAL) return launch_cfg_d<AKC, BKC, BM, BN, NS, WM, WN, false, KG, EPI_PARTIAL>(d, splits, s);
+    if (kind == EPI_LIGHT) return launch_cfg_d<AKC, BKC, BM, BN, NS, WM, WN, false, KG, EPI_LIGHT>(d, splits, s);
   }
   return launch_cfg_d<AKC, BKC, BM, BN, NS, WM, WN, false, KG>(d, splits, s);
 }
