@@ -41,11 +41,14 @@ template <> struct Oct<float> {
 // straight-line code that every workgroup walks once (the epilogue is unrolled over a wavefront's 32-row blocks
 // and passes) is fetched all the same, and the GELU / GELU' evaluations are most of it: a plain 4096 x 768 x 768
 // GEMM is 0.6-1.4 us shorter without them.
-constexpr int EPI_PARTIAL = 0;  // fp32 partial sums of a k-range only
-constexpr int EPI_LIGHT = 1;    // everything but GELU and its derivative
+constexpr int EPI_PARTIAL = 0;   // fp32 partial sums of a k-range only
+constexpr int EPI_LIGHT = 1;     // everything but GELU and its derivative
 constexpr int EPI_FULL = 2;
+constexpr int EPI_GELU_FWD = 3;  // GELU as the activation, no activation derivative
+constexpr int EPI_GELU_BWD = 4;  // GELU' as the activation derivative, no activation
 __host__ __device__ constexpr int gemm_epi_kind(bool partial, int act, int dact) {
-  return partial ? EPI_PARTIAL : (act == 2 || dact == 2) ? EPI_FULL : EPI_LIGHT;
+  return partial ? EPI_PARTIAL
+                 : act == 2 ? (dact ? EPI_FULL : EPI_GELU_FWD) : dact == 2 ? (act ? EPI_FULL : EPI_GELU_BWD) : EPI_LIGHT;
 }
 
 // PRE: the eight residual / aux values were already loaded by the caller (pre_res, pre_aux; bf16 only).
@@ -62,12 +65,12 @@ __device__ __forceinline__ void gemm_epilogue_oct(const GemmDev &p, int m, int n
 #pragma unroll
   for (int e = 0; e < 8; ++e) v[e] += bias8[e];  // zeros without a bias
   if (p.preact) Oct<T>::store(static_cast<T *>(p.preact) + off, v);
-  if (p.act == 1) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
-  } else if (EPI == EPI_FULL && p.act == 2) {
+  if (EPI == EPI_GELU_FWD || (EPI == EPI_FULL && p.act == 2)) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
+  } else if (EPI != EPI_GELU_BWD && p.act == 1) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
   }
   if (DROP && p.drop_where == 1) {
     float k0[4], k1[4];
@@ -86,14 +89,14 @@ __device__ __forceinline__ void gemm_epilogue_oct(const GemmDev &p, int m, int n
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] += t[e];
   }
-  if (p.dact) {
+  if (EPI != EPI_GELU_FWD && p.dact) {
     if constexpr (PRE) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) t[e] = static_cast<float>(pre_aux[e]);
     } else {
       Oct<T>::load(static_cast<const T *>(p.aux) + off, t);
     }
-    if (EPI != EPI_FULL || p.dact == 1) {
+    if (EPI == EPI_LIGHT || (EPI == EPI_FULL && p.dact == 1)) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[e] = t[e] > 0.f ? v[e] : 0.f;
     } else {

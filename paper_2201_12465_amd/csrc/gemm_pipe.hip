@@ -262,6 +262,8 @@ hipError_t launch_cfg(const GemmDev &d, int splits, hipStream_t s) {
     const int kind = gemm_epi_kind(d.partial != nullptr, d.act, d.dact);
     if (kind == EPI_PARTIAL) return launch_cfg_d<AKC, BKC, BM, BN, NS, WM, WN, false, KG, EPI_PARTIAL>(d, splits, s);
     if (kind == EPI_LIGHT) return launch_cfg_d<AKC, BKC, BM, BN, NS, WM, WN, false, KG, EPI_LIGHT>(d, splits, s);
+    if (kind == EPI_GELU_FWD) return launch_cfg_d<AKC, BKC, BM, BN, NS, WM, WN, false, KG, EPI_GELU_FWD>(d, splits, s);
+    if (kind == EPI_GELU_BWD) return launch_cfg_d<AKC, BKC, BM, BN, NS, WM, WN, false, KG, EPI_GELU_BWD>(d, splits, s);
   }
   return launch_cfg_d<AKC, BKC, BM, BN, NS, WM, WN, false, KG>(d, splits, s);
 }
