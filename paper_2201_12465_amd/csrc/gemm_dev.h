@@ -161,8 +161,9 @@ __device__ __forceinline__ void gemm_staged_epilogue(const GemmDev &p, const f32
       for (int q = 0; q < 4; ++q)
         *reinterpret_cast<float4 *>(cw + (lane & 31) * CS + j * 32 + q * 8 + (lane >> 5) * 4) =
             make_float4(acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
-    // the wave reads what its own lanes wrote: LDS operations of one wave complete in order
-#pragma unroll
+    // the wave reads what its own lanes wrote: LDS operations of one wave complete in order.
+    // Without prefetched operands (register arrays indexed by the pass) the passes stay a loop: less code to fetch.
+#pragma unroll (PRE ? PASSES : 1)
     for (int k = 0; k < PASSES; ++k) {
       const int r = rl + k * RPP;
       const int m = mbase + i * 32 + r;
