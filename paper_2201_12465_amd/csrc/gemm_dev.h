@@ -46,9 +46,12 @@ constexpr int EPI_LIGHT = 1;     // everything but GELU and its derivative
 constexpr int EPI_FULL = 2;
 constexpr int EPI_GELU_FWD = 3;  // GELU as the activation, no activation derivative
 constexpr int EPI_GELU_BWD = 4;  // GELU' as the activation derivative, no activation
-__host__ __device__ constexpr int gemm_epi_kind(bool partial, int act, int dact) {
+constexpr int EPI_PLAIN = 5;     // bias and residual only
+__host__ __device__ constexpr int gemm_epi_kind(bool partial, int act, int dact, bool preact = true) {
   return partial ? EPI_PARTIAL
-                 : act == 2 ? (dact ? EPI_FULL : EPI_GELU_FWD) : dact == 2 ? (act ? EPI_FULL : EPI_GELU_BWD) : EPI_LIGHT;
+         : act == 2 ? (dact ? EPI_FULL : EPI_GELU_FWD)
+         : dact == 2 ? (act ? EPI_FULL : EPI_GELU_BWD)
+         : (act == 0 && dact == 0 && !preact) ? EPI_PLAIN : EPI_LIGHT;
 }
 
 // PRE: the eight residual / aux values were already loaded by the caller (pre_res, pre_aux; bf16 only).
@@ -64,11 +67,11 @@ __device__ __forceinline__ void gemm_epilogue_oct(const GemmDev &p, int m, int n
   float t[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) v[e] += bias8[e];  // zeros without a bias
-  if (p.preact) Oct<T>::store(static_cast<T *>(p.preact) + off, v);
+  if (EPI != EPI_PLAIN && p.preact) Oct<T>::store(static_cast<T *>(p.preact) + off, v);
   if (EPI == EPI_GELU_FWD || (EPI == EPI_FULL && p.act == 2)) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
-  } else if (EPI != EPI_GELU_BWD && p.act == 1) {
+  } else if (EPI != EPI_GELU_BWD && EPI != EPI_PLAIN && p.act == 1) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
   }
@@ -89,7 +92,7 @@ __device__ __forceinline__ void gemm_epilogue_oct(const GemmDev &p, int m, int n
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] += t[e];
   }
-  if (EPI != EPI_GELU_FWD && p.dact) {
+  if (EPI != EPI_GELU_FWD && EPI != EPI_PLAIN && p.dact) {
     if constexpr (PRE) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) t[e] = static_cast<float>(pre_aux[e]);
@@ -139,7 +142,7 @@ __device__ __forceinline__ void gemm_staged_epilogue(const GemmDev &p, const f32
   if (EPI != EPI_PARTIAL && p.bias && !p.partial && lane_ok) Oct<T>::load(static_cast<const T *>(p.bias) + n0, bias8);
   bf16x8_t pre_res[PRE ? TM : 1][PRE ? PASSES : 1], pre_aux[PRE ? TM : 1][PRE ? PASSES : 1];
   if constexpr (PRE) {
-    const bool has_res = p.residual && !p.partial, has_aux = p.dact && !p.partial;
+    const bool has_res = p.residual && !p.partial, has_aux = EPI != EPI_PLAIN && EPI != EPI_GELU_FWD && p.dact && !p.partial;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll

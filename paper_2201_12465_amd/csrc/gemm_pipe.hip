@@ -259,7 +259,8 @@ hipError_t launch_cfg(const GemmDev &d, int splits, hipStream_t s) {
   constexpr bool specialised = (BM == 128 && BN == 128 && WM == 2 && WN == 2 && ((NS == 2 && KG == 1) || (NS == 3 && KG == 2))) ||
                                (BM == 256 && BN == 192) || (BN == 128 && (BM == 160 || BM == 96));
   if constexpr (specialised) {
-    const int kind = gemm_epi_kind(d.partial != nullptr, d.act, d.dact);
+    const int kind = gemm_epi_kind(d.partial != nullptr, d.act, d.dact, d.preact != nullptr);
+    if (kind == EPI_PLAIN) return launch_cfg_d<AKC, BKC, BM, BN, NS, WM, WN, false, KG, EPI_PLAIN>(d, splits, s);
     if (kind == EPI_PARTIAL) return launch_cfg_d<AKC, BKC, BM, BN, NS, WM, WN, false, KG, EPI_PARTIAL>(d, splits, s);
     if (kind == EPI_LIGHT) return launch_cfg_d<AKC, BKC, BM, BN, NS, WM, WN, false, KG, EPI_LIGHT>(d, splits, s);
     if (kind == EPI_GELU_FWD) return launch_cfg_d<AKC, BKC, BM, BN, NS, WM, WN, false, KG, EPI_GELU_FWD>(d, splits, s);
