@@ -174,7 +174,8 @@ def test_gemm_backward_epilogue(dtype, dact):
 @pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11])
 def test_gemm_epilogues_on_every_pipelined_variant(variant):
     """Bias, pre-activation copy, GELU and residual (forward form), and skip + GELU' (backward form), through
-    the staged epilogue of every tile shape of the pipelined kernel; ragged M and N, several tiles."""
+    the staged epilogue of every tile shape of the pipelined kernel; ragged M and N, several tiles.  Then the
+    launches that select the other epilogue kinds of the specialised instances."""
     b = _lib()
     M, N, K = 520, 392, 128
     rng = np.random.default_rng(40 + variant)
@@ -200,6 +201,30 @@ def test_gemm_epilogues_on_every_pipelined_variant(variant):
                                      tr.data_ptr(), 0, None, 2, tu.data_ptr(), 1, None, stream_ptr()))
         torch_mod().cuda.synchronize()
         assert rel_err(to_np(dC), ref_bwd) <= BF16_KERNEL_TOL, variant
+        # the other epilogue kinds of an instance: ReLU forward with and without the pre-activation copy, ReLU'
+        # backward, bias + residual only, bias only
+        ref_relu = orc.act_fwd(u, "relu") + res
+        for with_preact in (True, False):
+            dC, dU = empty_dev((M, N), "bf16"), empty_dev((M, N), "bf16")
+            b.check(b.lib().fl_test_gemm(1, 1, 1, tx.data_ptr(), tW.data_ptr(), dC.data_ptr(), M, N, K, tb.data_ptr(),
+                                         tr.data_ptr(), 1, dU.data_ptr() if with_preact else None, 0, None, 1, None,
+                                         stream_ptr()))
+            torch_mod().cuda.synchronize()
+            assert rel_err(to_np(dC), ref_relu) <= BF16_KERNEL_TOL, (variant, with_preact)
+            if with_preact:
+                assert rel_err(to_np(dU), u) <= BF16_KERNEL_TOL, variant
+        ref_relu_bwd = orc.act_bwd(x.astype(np.float64) @ W.astype(np.float64).T + res, u_saved, "relu")
+        dC = empty_dev((M, N), "bf16")
+        b.check(b.lib().fl_test_gemm(1, 1, 1, tx.data_ptr(), tW.data_ptr(), dC.data_ptr(), M, N, K, None,
+                                     tr.data_ptr(), 0, None, 1, tu.data_ptr(), 1, None, stream_ptr()))
+        torch_mod().cuda.synchronize()
+        assert rel_err(to_np(dC), ref_relu_bwd) <= BF16_KERNEL_TOL, variant
+        for with_res in (True, False):
+            dC = empty_dev((M, N), "bf16")
+            b.check(b.lib().fl_test_gemm(1, 1, 1, tx.data_ptr(), tW.data_ptr(), dC.data_ptr(), M, N, K, tb.data_ptr(),
+                                         tr.data_ptr() if with_res else None, 0, None, 0, None, 1, None, stream_ptr()))
+            torch_mod().cuda.synchronize()
+            assert rel_err(to_np(dC), u + (res if with_res else 0.0)) <= BF16_KERNEL_TOL, (variant, with_res)
     finally:
         b.lib().fl_test_gemm_force_variant(-1)
 
